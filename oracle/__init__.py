@@ -1,0 +1,147 @@
+"""Float64 CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Thin ctypes loader around ``ada_oracle.c`` plus the paper's bookkeeping formulas
+(``oracle.metrics``).  Only the tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the product path never does, and this
+package never imports the product.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+from . import metrics  # noqa: F401  (re-export)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ada_oracle.c")
+_LIB = os.path.join(_HERE, "libada_oracle.so")
+
+CROSS_EARLIER_ONLY = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (about a second).  Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+               "-fno-fast-math", "-ffp-contract=off", _SRC, "-o", tmp, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        c_dp = ctypes.POINTER(ctypes.c_double)
+        c_ip = ctypes.POINTER(ctypes.c_int32)
+        c_u8p = ctypes.POINTER(ctypes.c_uint8)
+        c_i8p = ctypes.POINTER(ctypes.c_int8)
+        c_u64p = ctypes.POINTER(ctypes.c_uint64)
+        lib.ada_oracle_threads.restype = ctypes.c_int
+        lib.ada_oracle_normalize.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_dp, c_dp]
+        lib.ada_oracle_gram.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_dp]
+        lib.ada_oracle_select_full.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                               c_i8p, c_u8p, c_dp, c_ip, c_u64p]
+        lib.ada_oracle_gamma_full_rows.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_ip, ctypes.c_int, c_dp]
+        lib.ada_oracle_cascade_step.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, c_ip,
+                                                ctypes.c_int, ctypes.c_uint, c_i8p, c_ip, c_ip, c_ip, c_ip,
+                                                c_u64p, c_dp]
+        _lib = lib
+    return _lib
+
+
+def _p(a: Optional[np.ndarray], ctype):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _as_f64(X) -> np.ndarray:
+    X = np.ascontiguousarray(np.asarray(X, dtype=np.float64))
+    if X.ndim != 2:
+        raise ValueError("X must be T x d")
+    return X
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError("%s failed with oracle status %d" % (what, rc))
+
+
+def threads() -> int:
+    return int(_load().ada_oracle_threads())
+
+
+def normalize(X):
+    X = _as_f64(X)
+    T, d = X.shape
+    Xhat = np.empty_like(X)
+    norms = np.empty(T, dtype=np.float64)
+    _check(_load().ada_oracle_normalize(_p(X, ctypes.c_double), T, d, _p(Xhat, ctypes.c_double),
+                                        _p(norms, ctypes.c_double)), "normalize")
+    return Xhat, norms
+
+
+def gram(X) -> np.ndarray:
+    X = _as_f64(X)
+    T, d = X.shape
+    G = np.empty((T, T), dtype=np.float64)
+    _check(_load().ada_oracle_gram(_p(X, ctypes.c_double), T, d, _p(G, ctypes.c_double)), "gram")
+    return G
+
+
+def select_full(X, tau: float, greedy: bool = False, force: Optional[Sequence[int]] = None):
+    """Definition "Gram threshold".  Returns dict(mask, idx, gamma, r, gram_ops)."""
+    X = _as_f64(X)
+    T, d = X.shape
+    mask = np.zeros(T, dtype=np.uint8)
+    gamma = np.zeros(T, dtype=np.float64)
+    r = ctypes.c_int32(0)
+    ops = ctypes.c_uint64(0)
+    f = None if force is None else np.ascontiguousarray(np.asarray(force, dtype=np.int8))
+    _check(_load().ada_oracle_select_full(_p(X, ctypes.c_double), T, d, float(tau), int(bool(greedy)),
+                                          _p(f, ctypes.c_int8), _p(mask, ctypes.c_uint8),
+                                          _p(gamma, ctypes.c_double), ctypes.byref(r), ctypes.byref(ops)),
+           "select_full")
+    return dict(mask=mask, idx=np.flatnonzero(mask).astype(np.int32), gamma=gamma, r=int(r.value),
+                gram_ops=int(ops.value))
+
+
+def gamma_full_rows(X, rows) -> np.ndarray:
+    X = _as_f64(X)
+    T, d = X.shape
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
+    out = np.zeros(rows.shape[0], dtype=np.float64)
+    _check(_load().ada_oracle_gamma_full_rows(_p(X, ctypes.c_double), T, d, _p(rows, ctypes.c_int32),
+                                              int(rows.shape[0]), _p(out, ctypes.c_double)), "gamma_full_rows")
+    return out
+
+
+def cascade_step(X, tau: float, prev_idx, flags: int = 0, force: Optional[Sequence[int]] = None):
+    """Algorithm 1.  Returns dict(idx, adds, removes, r_new, gram_ops, gamma)."""
+    X = _as_f64(X)
+    T, d = X.shape
+    prev = np.ascontiguousarray(np.asarray(prev_idx, dtype=np.int32))
+    r = int(prev.shape[0])
+    idx = np.zeros(T, dtype=np.int32)
+    adds = np.zeros(T, dtype=np.int32)
+    removes = np.zeros(max(r, 1), dtype=np.int32)
+    counts = np.zeros(3, dtype=np.int32)
+    ops = ctypes.c_uint64(0)
+    gamma = np.zeros(T, dtype=np.float64)
+    f = None if force is None else np.ascontiguousarray(np.asarray(force, dtype=np.int8))
+    _check(_load().ada_oracle_cascade_step(_p(X, ctypes.c_double), T, d, float(tau), _p(prev, ctypes.c_int32), r,
+                                           int(flags), _p(f, ctypes.c_int8), _p(idx, ctypes.c_int32),
+                                           _p(adds, ctypes.c_int32), _p(removes, ctypes.c_int32),
+                                           _p(counts, ctypes.c_int32), ctypes.byref(ops),
+                                           _p(gamma, ctypes.c_double)), "cascade_step")
+    return dict(idx=idx[:counts[0]].copy(), adds=adds[:counts[1]].copy(), removes=removes[:counts[2]].copy(),
+                r_new=int(counts[0]), gram_ops=int(ops.value), gamma=gamma)

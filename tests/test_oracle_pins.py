@@ -1,0 +1,390 @@
+"""Pins for the float64 oracle: everything here checks the oracle against something
+other than itself -- a library routine (numpy float64 matmul), exact integer
+arithmetic, closed forms, and the invariants the paper's definitions fix.
+None of these tests needs a GPU."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_03110_amd import workloads as wl
+
+
+# ----------------------------------------------------------------------------- helpers
+def numpy_gram(X):
+    """Independent statement of Section 2.1 with numpy's float64 matmul."""
+    X = np.asarray(X, dtype=np.float64)
+    n = np.linalg.norm(X, axis=1, keepdims=True)
+    Xn = np.divide(X, n, out=np.zeros_like(X), where=n > 0)
+    return Xn @ Xn.T
+
+
+def exact_near(X_int, num, den):
+    """near[s][t] <=> |cos(x_s, x_t)| >= num/den, decided in exact integer arithmetic:
+    (x_s . x_t)^2 * den^2 >= num^2 * |x_s|^2 |x_t|^2.  Also returns the smallest relative
+    distance of any pair from equality so callers can reject inputs a float64
+    evaluation could not decide."""
+    T = len(X_int)
+    near = [[False] * T for _ in range(T)]
+    margin = math.inf
+    for s in range(T):
+        for t in range(T):
+            dot = sum(int(a) * int(b) for a, b in zip(X_int[s], X_int[t]))
+            ns = sum(int(a) * int(a) for a in X_int[s])
+            nt = sum(int(b) * int(b) for b in X_int[t])
+            lhs = dot * dot * den * den
+            rhs = num * num * ns * nt
+            near[s][t] = lhs >= rhs
+            if rhs > 0:
+                margin = min(margin, abs(lhs - rhs) / rhs)
+    return near, margin
+
+
+def exact_full(near, T):
+    return [t for t in range(T) if not any(near[s][t] for s in range(t))]
+
+
+def exact_cascade(near, T, R, earlier_only):
+    R = sorted(R)
+    valid = [s for s in R if not any(near[sp][s] for sp in R if sp < s)]
+    new = [t for t in range(T) if t not in R
+           and not any(near[t][s] for s in valid if (s < t or not earlier_only))]
+    idx = sorted(valid + new)
+    removes = [s for s in R if s not in valid]
+    ops = len(R) ** 2 + (T - len(R)) * len(valid)
+    return idx, new, removes, ops
+
+
+def integer_tokens(rng, T, d, n_base):
+    """Integer vectors with a mix of near-parallel and unrelated pairs."""
+    base = rng.integers(-9, 10, size=(n_base, d))
+    base[np.all(base == 0, axis=1)] = 1
+    rows = []
+    for _ in range(T):
+        b = base[rng.integers(0, n_base)]
+        k = int(rng.integers(1, 4)) * (1 if rng.random() < 0.8 else -1)
+        noise = rng.integers(-2, 3, size=d) * (rng.random(d) < 0.5)
+        rows.append(k * 6 * b + noise)
+    return np.array(rows, dtype=np.int64)
+
+
+RATIONAL_TAUS = [((1, 10), (99, 100)), ((3, 10), (91, 100)), ((1, 2), (3, 4)), ((7, 10), (51, 100))]
+
+
+# ----------------------------------------------------------------------------- Section 2.1
+def test_gram_matches_numpy_float64_and_is_a_cosine_matrix():
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((37, 53)) * rng.uniform(0.1, 30.0, size=(37, 1))
+    G = oracle.gram(X)
+    assert np.allclose(G, numpy_gram(X), atol=1e-13, rtol=0)
+    assert np.allclose(G, G.T, atol=1e-15)
+    assert np.allclose(np.diag(G), 1.0, atol=1e-14)
+    assert np.max(np.abs(G)) <= 1.0 + 1e-14
+
+
+def test_normalize_gives_unit_rows_and_reports_norms():
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((9, 17)) * 5.0
+    Xhat, norms = oracle.normalize(X)
+    assert np.allclose(norms, np.linalg.norm(X, axis=1), rtol=1e-15)
+    assert np.allclose(np.linalg.norm(Xhat, axis=1), 1.0, atol=1e-15)
+    assert np.allclose(Xhat * norms[:, None], X, rtol=1e-14, atol=0)
+
+
+def test_scale_invariance():
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((40, 24))
+    X[20:] = X[:20] + 0.01 * rng.standard_normal((20, 24))
+    a = oracle.select_full(X, 0.3)
+    b = oracle.select_full(X * rng.uniform(0.01, 100.0, size=(40, 1)), 0.3)
+    assert np.array_equal(a["mask"], b["mask"])
+    assert np.allclose(a["gamma"], b["gamma"], atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- Definition "Gram threshold"
+def test_gamma_is_strictly_lower_triangular_max_of_abs_gram():
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((61, 29))
+    X[30:] = -X[:31] + 0.05 * rng.standard_normal((31, 29))      # negative correlations matter (|G|)
+    res = oracle.select_full(X, 0.3)
+    A = np.abs(numpy_gram(X))
+    expect = np.array([A[:t, t].max() if t else 0.0 for t in range(61)])
+    assert np.allclose(res["gamma"], expect, atol=1e-13)
+    assert res["gamma"][0] == 0.0
+    assert np.array_equal(res["mask"], (expect < 1 - 0.3 ** 2).astype(np.uint8))
+    assert res["r"] == int(res["mask"].sum())
+
+
+def test_exact_duplicates_leave_only_the_first():
+    rng = np.random.default_rng(4)
+    base = rng.standard_normal((5, 16))
+    order = [0, 1, 0, 2, 1, 1, 3, 0, 4, 4, 2]
+    X = base[order] * rng.uniform(0.5, 2.0, size=(len(order), 1))   # scaled copies are still duplicates
+    res = oracle.select_full(X, 0.1)
+    assert res["idx"].tolist() == [0, 1, 3, 6, 8]
+
+
+def test_mutually_orthogonal_tokens_are_all_representative():
+    Q, _ = np.linalg.qr(np.random.default_rng(5).standard_normal((32, 32)))
+    res = oracle.select_full(Q[:20] * 3.0, 0.1)
+    assert res["r"] == 20 and res["mask"].all()
+    assert np.max(res["gamma"]) < 1e-14
+
+
+def test_first_token_is_always_representative_and_sign_is_ignored():
+    x = np.array([[1.0, 2.0, -3.0]])
+    X = np.vstack([x, -x, 2 * x])
+    res = oracle.select_full(X, 0.5)
+    assert res["mask"].tolist() == [1, 0, 0]
+    assert np.allclose(res["gamma"][1:], 1.0)
+
+
+def test_zero_row_is_representative_and_covers_nobody():
+    X = np.array([[0.0, 0.0], [1.0, 0.0], [0.0, 0.0], [1.0, 1e-9]])
+    res = oracle.select_full(X, 0.1)
+    assert res["mask"].tolist() == [1, 1, 1, 0]
+    assert res["gamma"][2] == 0.0
+
+
+@pytest.mark.parametrize("tau", [0.1, 0.3, 0.6])
+def test_threshold_flips_exactly_at_chord_sqrt2_tau(tau):
+    """cos >= 1 - tau^2  <=>  chord |xhat_s - xhat_t| <= sqrt(2) tau (proof of the
+    depth-persistence proposition): build 2-D pairs from the chord length."""
+    for delta, expect_rep in [(+1e-6, 1), (-1e-6, 0), (+1e-3, 1), (-1e-3, 0)]:
+        chord = math.sqrt(2.0) * tau + delta              # longer chord -> smaller cosine -> representative
+        theta = 2.0 * math.asin(chord / 2.0)
+        X = np.array([[1.0, 0.0], [math.cos(theta), math.sin(theta)]]) * 7.0
+        res = oracle.select_full(X, tau)
+        assert res["mask"].tolist() == [1, expect_rep]
+        assert abs(res["gamma"][1] - (1.0 - chord * chord / 2.0)) < 1e-12
+
+
+def test_tie_at_threshold_is_redundant():
+    # tau = 1/2 gives the threshold 0.75 exactly in binary; x = e_1 and y = (3,2,1,1,1) (|y| = 4) give
+    # cos = 3/4 with every intermediate exactly representable, so gamma == threshold: strict "<" fails.
+    X = np.array([[1.0, 0, 0, 0, 0], [3.0, 2, 1, 1, 1]])
+    res = oracle.select_full(X, 0.5)
+    assert res["gamma"][1] == 0.75
+    assert res["mask"].tolist() == [1, 0]
+    assert oracle.cascade_step(X, 0.5, [0])["idx"].tolist() == [0]
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("tau_q,thr_q", RATIONAL_TAUS)
+def test_full_selection_agrees_with_exact_integer_brute_force(seed, tau_q, thr_q):
+    rng = np.random.default_rng(100 + seed)
+    T, d = 16, 6
+    Xi = integer_tokens(rng, T, d, n_base=4)
+    near, margin = exact_near(Xi.tolist(), *thr_q)
+    if margin < 1e-9:
+        pytest.skip("a pair sits on the threshold; float64 cannot be required to decide it")
+    res = oracle.select_full(Xi.astype(np.float64), tau_q[0] / tau_q[1])
+    assert res["idx"].tolist() == exact_full(near, T)
+    assert res["gram_ops"] == T * T
+
+
+def test_brute_force_inputs_exercise_both_decisions():
+    """Guard for the brute-force pins: the integer inputs must contain both redundant
+    and representative tokens, or the comparison would be vacuous."""
+    seen = set()
+    for seed in range(6):
+        rng = np.random.default_rng(100 + seed)
+        Xi = integer_tokens(rng, 16, 6, n_base=4)
+        near, _ = exact_near(Xi.tolist(), 99, 100)
+        r = len(exact_full(near, 16))
+        assert 1 < r < 16
+        seen.add(r)
+    assert len(seen) > 1
+
+
+def test_definition_and_greedy_reading_differ_exactly_on_chains():
+    # a ~ b, b ~ c, a !~ c at threshold cos >= 0.91 (tau = 0.3): angles 0, 20, 40 degrees
+    ang = np.deg2rad([0.0, 20.0, 40.0])
+    X = np.stack([np.cos(ang), np.sin(ang)], axis=1)
+    assert math.cos(ang[1]) > 0.91 > math.cos(ang[2])
+    assert oracle.select_full(X, 0.3)["mask"].tolist() == [1, 0, 0]              # Definition: c is covered by b
+    assert oracle.select_full(X, 0.3, greedy=True)["mask"].tolist() == [1, 0, 1]  # greedy covering: c stays
+
+
+def test_clustered_tokens_first_occurrence_of_each_centre_is_selected():
+    w = wl.small(T=300, d=64, K=40, L=1, dtype="f32", seed=11)
+    rng = np.random.default_rng(w.seed(0))
+    # replay the generator's first two draws to learn the assignment (the module draws C then a)
+    _ = rng.standard_normal((w.K, w.d), dtype=np.float32)
+    a = rng.integers(0, w.K, size=w.T)
+    X = wl.as_f64(wl.layer_list(w)[0])
+    res = oracle.select_full(X, w.tau)
+    first = sorted({int(c): t for t, c in reversed(list(enumerate(a)))}.values())
+    assert res["idx"].tolist() == first
+    assert res["r"] == len(set(a.tolist()))
+
+
+def test_gamma_full_rows_matches_whole_selection():
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((50, 12))
+    rows = [0, 1, 7, 49, 20]
+    assert np.array_equal(oracle.gamma_full_rows(X, rows), oracle.select_full(X, 0.2)["gamma"][rows])
+
+
+def test_force_overrides_only_the_named_tokens():
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((12, 5))
+    free = oracle.select_full(X, 0.3)
+    force = -np.ones(12, dtype=np.int8)
+    force[3] = 1 - free["mask"][3]
+    forced = oracle.select_full(X, 0.3, force=force)
+    diff = np.flatnonzero(forced["mask"] != free["mask"])
+    assert diff.tolist() == [3]
+    assert np.array_equal(forced["gamma"], free["gamma"])
+
+
+def test_argument_errors():
+    X = np.ones((4, 3))
+    for tau in (0.0, 1.0, -0.1, 1.5, float("nan")):
+        with pytest.raises(ValueError):
+            oracle.select_full(X, tau)
+        with pytest.raises(ValueError):
+            oracle.cascade_step(X, tau, [0])
+    for prev in ([], [1, 1], [2, 1], [0, 4], [-1, 2], [0, 1, 2, 3, 3]):
+        with pytest.raises(ValueError):
+            oracle.cascade_step(X, 0.1, prev)
+
+
+# ----------------------------------------------------------------------------- Algorithm 1
+@pytest.mark.parametrize("earlier_only", [False, True])
+@pytest.mark.parametrize("seed", range(3))
+def test_cascade_agrees_with_exact_brute_force_for_every_inherited_subset(seed, earlier_only):
+    rng = np.random.default_rng(200 + seed)
+    T, d = 10, 5
+    Xi = integer_tokens(rng, T, d, n_base=3)
+    (tn, td), thr_q = RATIONAL_TAUS[seed % 2]
+    near, margin = exact_near(Xi.tolist(), *thr_q)
+    if margin < 1e-9:
+        pytest.skip("a pair sits on the threshold")
+    X = Xi.astype(np.float64)
+    flags = oracle.CROSS_EARLIER_ONLY if earlier_only else 0
+    n_changed = 0
+    for bits in range(1, 2 ** T):
+        R = [t for t in range(T) if bits >> t & 1]
+        idx, new, removes, ops = exact_cascade(near, T, R, earlier_only)
+        res = oracle.cascade_step(X, tn / td, R, flags=flags)
+        assert res["idx"].tolist() == idx, R
+        assert res["adds"].tolist() == new, R
+        assert res["removes"].tolist() == removes, R
+        assert res["gram_ops"] == ops, R
+        n_changed += bool(new or removes)
+    assert n_changed > 100            # the sweep is not vacuous
+
+
+def test_cascade_sampled_subsets_T16():
+    rng = np.random.default_rng(300)
+    T, d = 16, 6
+    Xi = integer_tokens(rng, T, d, n_base=4)
+    near, margin = exact_near(Xi.tolist(), 91, 100)
+    assert margin >= 1e-9
+    for _ in range(400):
+        R = sorted(rng.choice(T, size=int(rng.integers(1, T + 1)), replace=False).tolist())
+        for eo in (False, True):
+            idx, new, removes, ops = exact_cascade(near, T, R, eo)
+            res = oracle.cascade_step(Xi.astype(np.float64), 0.3, R, flags=int(eo))
+            assert (res["idx"].tolist(), res["adds"].tolist(), res["removes"].tolist(), res["gram_ops"]) == \
+                   (idx, new, removes, ops)
+
+
+def test_cascade_gamma_is_rep_max_for_inherited_and_cross_max_for_the_rest():
+    rng = np.random.default_rng(12)
+    T = 40
+    X = rng.standard_normal((T, 9))
+    X[25:] = X[:15] * 2.0 + 0.02 * rng.standard_normal((15, 9))
+    R = sorted(rng.choice(T, size=14, replace=False).tolist())
+    tau = 0.3
+    res = oracle.cascade_step(X, tau, R)
+    A = np.abs(numpy_gram(X))
+    thr = 1 - tau * tau
+    g_rep = {s: max([A[sp, s] for sp in R if sp < s], default=0.0) for s in R}
+    valid = [s for s in R if g_rep[s] < thr]
+    for t in range(T):
+        want = g_rep[t] if t in R else max([A[t, s] for s in valid], default=0.0)
+        assert abs(res["gamma"][t] - want) < 1e-13
+
+
+def test_cascade_invariants_on_clustered_layers():
+    w = wl.small(T=400, d=96, K=50, L=6, dtype="f32", seed=21, p=0.08)
+    Xs = [wl.as_f64(x) for x in wl.layer_list(w)]
+    R = oracle.select_full(Xs[0], w.tau)["idx"]
+    total_changes = 0
+    for X in Xs[1:]:
+        for flags in (0, oracle.CROSS_EARLIER_ONLY):
+            res = oracle.cascade_step(X, w.tau, R, flags=flags)
+            full = oracle.select_full(X, w.tau)
+            assert res["idx"][0] == R[0] == 0 or R[0] in res["idx"]           # smallest inherited index survives
+            assert res["r_new"] == len(R) - len(res["removes"]) + len(res["adds"])
+            assert set(res["removes"]) <= set(R.tolist())
+            assert not (set(res["adds"]) & set(R.tolist()))
+            assert np.all(np.diff(res["idx"]) > 0)
+            r_valid = len(R) - len(res["removes"])
+            assert res["gram_ops"] == len(R) ** 2 + (w.T - len(R)) * r_valid
+            missing = set(full["idx"].tolist()) - set(res["idx"].tolist())
+            if flags:   # strict superset (superset proposition, with the comparison set restricted to earlier tokens)
+                assert not missing
+            else:       # as printed: a missing independent representative duplicates a LATER cascade representative
+                A = np.abs(numpy_gram(X))
+                for t in missing:
+                    later = [s for s in res["idx"] if s > t and A[t, s] >= 1 - w.tau ** 2]
+                    assert later
+        res = oracle.cascade_step(X, w.tau, R)
+        total_changes += len(res["adds"]) + len(res["removes"])
+        R = res["idx"]
+    assert total_changes > 0
+
+
+def test_cascade_from_the_same_layers_full_selection_changes_nothing_on_cliques():
+    w = wl.small(T=256, d=48, K=30, L=1, dtype="f32", seed=31)
+    X = wl.as_f64(wl.layer_list(w)[0])
+    full = oracle.select_full(X, w.tau)
+    res = oracle.cascade_step(X, w.tau, full["idx"])
+    assert res["idx"].tolist() == full["idx"].tolist()
+    assert len(res["adds"]) == 0 and len(res["removes"]) == 0
+    assert res["gram_ops"] == w.T * full["r"]                 # eq. (6): r^2 + (T-r) r = T r when nothing is removed
+
+
+def test_cascade_on_a_chain_adds_exactly_the_uncovered_tail():
+    ang = np.deg2rad([0.0, 20.0, 40.0])
+    X = np.stack([np.cos(ang), np.sin(ang)], axis=1)
+    full = oracle.select_full(X, 0.3)
+    assert full["idx"].tolist() == [0]
+    res = oracle.cascade_step(X, 0.3, full["idx"])
+    assert res["adds"].tolist() == [2] and res["removes"].tolist() == [] and res["idx"].tolist() == [0, 2]
+
+
+def test_cascade_removed_representative_still_counts_against_later_ones_and_is_not_readded():
+    # inherited {0,1,2}: 1 duplicates 0, 2 duplicates 1 only through the chain 0~1~2 with 0 !~ 2.
+    ang = np.deg2rad([0.0, 20.0, 40.0, 90.0])
+    X = np.stack([np.cos(ang), np.sin(ang)], axis=1)
+    res = oracle.cascade_step(X, 0.3, [0, 1, 2])
+    assert res["removes"].tolist() == [1, 2]          # step 4 maxes over all inherited, also the removed token 1
+    assert res["adds"].tolist() == [3]                # token 3 is orthogonal to token 0
+    assert res["idx"].tolist() == [0, 3]              # token 2 is uncovered but was inherited: not reconsidered
+    assert res["gram_ops"] == 9 + 1 * 1
+
+
+def test_cascade_unordered_and_earlier_only_cross_step_differ_on_a_later_duplicate():
+    # token 0 unrelated, token 1 = non-inherited duplicate of the LATER inherited token 2
+    X = np.array([[1.0, 0, 0], [0, 1.0, 0], [0, 1.0, 1e-6]])
+    a = oracle.cascade_step(X, 0.1, [0, 2])
+    b = oracle.cascade_step(X, 0.1, [0, 2], flags=oracle.CROSS_EARLIER_ONLY)
+    assert a["idx"].tolist() == [0, 2] and a["adds"].tolist() == []
+    assert b["idx"].tolist() == [0, 1, 2] and b["adds"].tolist() == [1]
+
+
+def test_cascade_extreme_set_sizes():
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal((20, 30))
+    X[10:] = X[:10]
+    one = oracle.cascade_step(X, 0.1, [0])                      # r = 1: only the copy of token 0 is covered
+    assert one["idx"].tolist() == [t for t in range(20) if t != 10] and one["removes"].tolist() == []
+    assert one["gram_ops"] == 1 + 19
+    every = oracle.cascade_step(X, 0.1, list(range(20)))        # r = T: the cross step is empty
+    assert every["idx"].tolist() == list(range(10)) and every["removes"].tolist() == list(range(10, 20))
+    assert every["gram_ops"] == 400
