@@ -31,8 +31,9 @@ def test_bf16_values_widen_exactly():
 
 
 def test_relative_scale_makes_same_centre_tokens_redundant_and_literal_does_not():
-    rel = wl.small(T=200, d=128, K=20, L=1, dtype="f32", seed=5)
-    lit = wl.small(T=200, d=128, K=20, L=1, dtype="f32", seed=5, scale="literal")
+    # literal noise energy d * 0.004^2 must exceed tau^2 = 0.01 for same-centre cosines to drop below 0.99
+    rel = wl.small(T=200, d=2048, K=20, L=1, dtype="f32", seed=5)
+    lit = wl.small(T=200, d=2048, K=20, L=1, dtype="f32", seed=5, scale="literal")
     r_rel = oracle.select_full(wl.as_f64(wl.layer_list(rel)[0]), rel.tau)["r"]
     r_lit = oracle.select_full(wl.as_f64(wl.layer_list(lit)[0]), lit.tau)["r"]
     assert r_rel <= 20
