@@ -1,0 +1,137 @@
+/*
+ * ada.h -- C ABI of libada: Gram-threshold representative-token selection and the
+ * cascade step on one AMD MI355X (gfx950).
+ *
+ * Conventions for every call
+ *   - X is a DEVICE pointer to a row-major T x d activation matrix (row t = hidden
+ *     state of token t, Section 2.1 of the paper) with leading dimension ld >= d,
+ *     counted in elements.  dtype says how elements are stored (ada_dtype).
+ *   - All output buffers and the workspace are DEVICE memory owned by the caller.
+ *     The library allocates no device memory and keeps no state between calls; the
+ *     only state between layers is the index set R^(l), which the caller carries
+ *     (Algorithm 1, "Require").
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work; outputs are valid once the caller has synchronised the
+ *     stream.  Two calls that share a workspace must be ordered on one stream.
+ *   - The return value is an ada_status.  Everything the host can check (null
+ *     pointers, shapes, tau, workspace size, dtype) is reported synchronously and
+ *     nothing is enqueued in that case.  A bad inherited index list is found on the
+ *     device and reported in counts[3] (see ada_cascade_step).
+ *   - Non-finite inputs are outside the contract.
+ */
+#ifndef ADA_H
+#define ADA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ADA_OK = 0,
+    ADA_ERR_NULL = 1,      /* a required pointer is NULL */
+    ADA_ERR_SHAPE = 2,     /* T < 1, d < 1, ld < d, r < 1, r > T, L < 1, T too large */
+    ADA_ERR_TAU = 3,       /* tau outside the open interval (0,1) (Definition "Gram threshold") */
+    ADA_ERR_INDEX = 4,     /* inherited indices not strictly ascending / out of range (device-detected) */
+    ADA_ERR_WORKSPACE = 5, /* workspace smaller than ada_workspace_bytes(T) or misaligned */
+    ADA_ERR_DEVICE = 6,    /* a HIP call failed */
+    ADA_ERR_DTYPE = 7      /* unknown ada_dtype */
+} ada_status;
+
+typedef enum {
+    ADA_F32 = 0, /* IEEE binary32 elements; products and sums in fp32 */
+    ADA_BF16 = 1 /* bfloat16 elements; exact products, fp32 accumulation */
+} ada_dtype;
+
+/* flags */
+#define ADA_FLAG_CROSS_EARLIER_ONLY 1u /* cascade: compare a non-representative t only with valid
+                                          representatives s < t (the form the proof of the superset
+                                          proposition uses) instead of all of them (Algorithm 1, step 8) */
+
+#define ADA_MAX_T (1 << 20)
+
+/* Human-readable name of a status code (static storage). */
+const char* ada_status_string(int status);
+
+/* Bytes of device workspace a call with this T needs (256-byte aligned base required). */
+size_t ada_workspace_bytes(int T);
+
+/*
+ * Full ("independent") selection -- Definition "Gram threshold" (Section 2.2):
+ *   gamma_t = max_{s<t} |G_st|,  G = Xhat Xhat^T with Xhat the row-normalised X (Section 2.1);
+ *   token t is representative iff gamma_t < 1 - tau^2.  A zero row has all cosines 0.
+ * Outputs
+ *   mask  [T] uint8   1 = representative                                   (required)
+ *   idx   [T] int32   the representatives' token ids, ascending; first *count entries valid (may be NULL)
+ *   count [4] int32   {r, r, 0, 0}: same layout as ada_cascade_step's counts so that it can be
+ *                     handed on as r_dev of the next layer                 (required)
+ *   gamma [T] float   gamma_t                                              (may be NULL)
+ */
+int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float tau,
+                    uint8_t* mask, int32_t* idx, int32_t* count, float* gamma,
+                    void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
+ * One cascade step -- Algorithm 1 (Section 4.1) on X = X^(l+1):
+ *   validate the inherited set R^(l) with the r x r Gram among its rows
+ *   (gamma^rep_s = max over inherited s' < s, R_valid = {gamma^rep < 1 - tau^2}),
+ *   test every other token against R_valid with the (T-r) x r_valid cross-Gram
+ *   (gamma^cross_t, R_new = {gamma^cross < 1 - tau^2}), return R_valid u R_new.
+ * Inputs
+ *   prev_idx  device int32, strictly ascending token ids of R^(l)
+ *   r         number of valid entries in prev_idx if r_dev is NULL; otherwise an upper bound on it
+ *             (the capacity of prev_idx, at most T)
+ *   r_dev     optional device int32 holding |R^(l)| (e.g. counts[0] of the previous step), so that
+ *             layers can be chained without a host round trip
+ * Outputs
+ *   idx      [T] int32  R^(l+1), ascending
+ *   adds     [T] int32  R_new, ascending
+ *   removes  [r] int32  R^(l) \ R_valid, ascending
+ *   counts   [4] int32  {|R^(l+1)|, |adds|, |removes|, status}; status is ADA_OK or ADA_ERR_INDEX /
+ *                       ADA_ERR_SHAPE for a bad prev_idx / r_dev, in which case the sizes are 0
+ *   gram_ops [1] uint64 r^2 + (T-r) * r_valid Gram entries (eq. (6) counts T*r, which is the same
+ *                       when nothing is removed; one operation = one Gram entry as in Table 6)  (may be NULL)
+ *   gamma    [T] float  gamma^rep for inherited tokens, gamma^cross for the others               (may be NULL)
+ */
+int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float tau,
+                     const int32_t* prev_idx, int r, const int32_t* r_dev,
+                     int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
+                     uint64_t* gram_ops, float* gamma,
+                     void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
+ * The layer loop of Section 4.1: full selection at layer 0, Algorithm 1 at layers 1..L-1, each
+ * step inheriting the previous step's set on the device (no host synchronisation inside).
+ *   X_layers     HOST array of L device pointers, one T x d matrix per layer
+ *   idx_all      device [L*T] int32   row l = R^(l) ascending
+ *   counts_all   device [L*4] int32   row l as in ada_cascade_step (layer 0: {r, r, 0, 0})
+ *   gram_ops_all device [L]   uint64  layer 0: T*T
+ *   adds_all / removes_all  device [L*T] int32 each, or NULL to skip reporting them
+ */
+int ada_cascade_layers(const void* const* X_layers, int L, int T, int d, int64_t ld, int dtype, float tau,
+                       int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all,
+                       int32_t* adds_all, int32_t* removes_all,
+                       void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
+ * |A n B| and |A u B| of two representative sets given as uint8 masks [T] (device), for the
+ * Jaccard index of eq. (3).  out: device int32 [2] = {intersection, union}.
+ */
+int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t* out, void* stream);
+
+/*
+ * Host-side bookkeeping from the per-layer counts of ada_cascade_layers (HOST arrays in, HOST out):
+ *   jaccard[l]  = |R^(l-1) n R^(l)| / |R^(l-1) u R^(l)| = (r_prev - removes) / (r_prev + adds)   (eq. (3))
+ *   turnover[l] = (adds + removes) / r_prev                                                     (eq. (8))
+ *   *savings    = 1 - sum_l gram_ops[l] / (L * T^2)                                             (Table 6)
+ * jaccard[0] and turnover[0] are set to 0 (no step at layer 0).  Any output pointer may be NULL.
+ */
+int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* gram_ops_all,
+                       double* jaccard, double* turnover, double* savings);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADA_H */

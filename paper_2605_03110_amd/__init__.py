@@ -1,1 +1,9 @@
-"""Gram-threshold representative-token selection and the cascade step for MI355X (gfx950)."""
+"""Gram-threshold representative-token selection and the cascade step for MI355X (gfx950).
+
+``ada``        ctypes binding of the C-ABI library (include/ada.h); the library itself is csrc/.
+``workloads``  seeded synthetic activations shaped like the paper's workloads.
+"""
+from . import workloads  # noqa: F401
+from .ada import (AdaError, FLAG_CROSS_EARLIER_ONLY, ada_cascade_layers, ada_cascade_report,  # noqa: F401
+                  ada_cascade_step, ada_select_full, ada_set_overlap, build_library, fetch, workspace,
+                  workspace_bytes)

@@ -1,0 +1,243 @@
+"""ctypes binding of libada (argument marshalling only; every step runs in the HIP kernels).
+
+PyTorch is used for device memory and streams.  The functions mirror the C ABI in
+``include/ada.h`` and return DEVICE tensors without synchronising; ``fetch`` brings a
+result to the host and raises on a device-reported status.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libada.so")
+SRC_DIR = os.path.join(_HERE, "csrc")
+SOURCES = ("ada_kernels.hip",)
+
+ADA_F32, ADA_BF16 = 0, 1
+FLAG_CROSS_EARLIER_ONLY = 1
+OK = 0
+
+SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_select_full", "ada_cascade_step",
+           "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report")
+
+
+class AdaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s: %s" % (where, status_string(status)))
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile the HIP sources for gfx950 into libada.so next to this file."""
+    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+    cmd += [os.path.join(SRC_DIR, s) for s in SOURCES] + ["-o", tmp]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    if verbose:
+        print(res.stderr)
+    os.replace(tmp, LIB_PATH)
+    return LIB_PATH
+
+
+_lib = None
+
+
+def lib():
+    """Load libada.so; fail loudly if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libada.so is missing at %s: run __graft_entry__.build() "
+                               "(or paper_2605_03110_amd.ada.build_library()) first" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, f32, u32, sz = (ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float,
+                                      ctypes.c_uint, ctypes.c_size_t)
+        L.ada_status_string.restype = ctypes.c_char_p
+        L.ada_status_string.argtypes = [i32]
+        L.ada_workspace_bytes.restype = sz
+        L.ada_workspace_bytes.argtypes = [i32]
+        L.ada_select_full.restype = i32
+        L.ada_select_full.argtypes = [vp, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp, sz, vp, u32]
+        L.ada_cascade_step.restype = i32
+        L.ada_cascade_step.argtypes = [vp, i32, i32, i64, i32, f32, vp, i32, vp, vp, vp, vp, vp, vp, vp,
+                                       vp, sz, vp, u32]
+        L.ada_cascade_layers.restype = i32
+        L.ada_cascade_layers.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp,
+                                         vp, sz, vp, u32]
+        L.ada_set_overlap.restype = i32
+        L.ada_set_overlap.argtypes = [vp, vp, i32, vp, vp]
+        L.ada_cascade_report.restype = i32
+        L.ada_cascade_report.argtypes = [i32, i32, vp, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().ada_status_string(int(status)).decode()
+
+
+def workspace_bytes(T: int) -> int:
+    return int(lib().ada_workspace_bytes(int(T)))
+
+
+def workspace(T: int, device="cuda") -> torch.Tensor:
+    return torch.empty(workspace_bytes(T), dtype=torch.uint8, device=device)
+
+
+def _dtype_code(X: torch.Tensor) -> int:
+    if X.dtype == torch.float32:
+        return ADA_F32
+    if X.dtype == torch.bfloat16:
+        return ADA_BF16
+    raise TypeError("X must be float32 or bfloat16, got %s" % X.dtype)
+
+
+def _check_x(X: torch.Tensor):
+    if not X.is_cuda:
+        raise ValueError("X must live on the GPU")
+    if X.dim() != 2 or (X.shape[1] > 1 and X.stride(1) != 1):
+        raise ValueError("X must be a row-major T x d matrix (unit stride along d)")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def ada_select_full(X: torch.Tensor, tau: float, *, ws: Optional[torch.Tensor] = None, stream=None,
+                    flags: int = 0) -> Dict[str, torch.Tensor]:
+    """Full Gram-threshold selection.  Returns device tensors mask[T] u8, idx[T] i32, counts[4] i32, gamma[T] f32."""
+    _check_x(X)
+    T, d = X.shape
+    dev = X.device
+    ws = workspace(T, dev) if ws is None else ws
+    out = dict(mask=torch.empty(T, dtype=torch.uint8, device=dev),
+               idx=torch.empty(T, dtype=torch.int32, device=dev),
+               counts=torch.empty(4, dtype=torch.int32, device=dev),
+               gamma=torch.empty(T, dtype=torch.float32, device=dev))
+    rc = lib().ada_select_full(_ptr(X), T, d, X.stride(0), _dtype_code(X), float(tau), _ptr(out["mask"]),
+                               _ptr(out["idx"]), _ptr(out["counts"]), _ptr(out["gamma"]), _ptr(ws), ws.numel(),
+                               _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_select_full")
+    out["_keep"] = ws
+    return out
+
+
+def ada_cascade_step(X: torch.Tensor, tau: float, prev_idx: torch.Tensor, r: Optional[int] = None,
+                     r_dev: Optional[torch.Tensor] = None, *, ws: Optional[torch.Tensor] = None, stream=None,
+                     flags: int = 0) -> Dict[str, torch.Tensor]:
+    """One cascade step.  prev_idx: device int32, ascending.  r defaults to prev_idx.numel() (an upper bound
+    when r_dev, a device int32 holding the actual size, is given).  Returns device tensors idx[T], adds[T],
+    removes[r], counts[4], gram_ops[1] (int64 storage of the uint64), gamma[T]."""
+    _check_x(X)
+    T, d = X.shape
+    dev = X.device
+    if prev_idx.dtype != torch.int32 or not prev_idx.is_cuda or not prev_idx.is_contiguous():
+        raise ValueError("prev_idx must be a contiguous int32 device tensor")
+    r = int(prev_idx.numel()) if r is None else int(r)
+    if r > prev_idx.numel():
+        raise ValueError("r exceeds the capacity of prev_idx")
+    ws = workspace(T, dev) if ws is None else ws
+    out = dict(idx=torch.empty(T, dtype=torch.int32, device=dev),
+               adds=torch.empty(T, dtype=torch.int32, device=dev),
+               removes=torch.empty(max(r, 1), dtype=torch.int32, device=dev),
+               counts=torch.empty(4, dtype=torch.int32, device=dev),
+               gram_ops=torch.empty(1, dtype=torch.int64, device=dev),
+               gamma=torch.empty(T, dtype=torch.float32, device=dev))
+    rc = lib().ada_cascade_step(_ptr(X), T, d, X.stride(0), _dtype_code(X), float(tau), _ptr(prev_idx), r,
+                                _ptr(r_dev), _ptr(out["idx"]), _ptr(out["adds"]), _ptr(out["removes"]),
+                                _ptr(out["counts"]), _ptr(out["gram_ops"]), _ptr(out["gamma"]), _ptr(ws),
+                                ws.numel(), _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_step")
+    out["_keep"] = (ws, prev_idx, r_dev)
+    return out
+
+
+def ada_cascade_layers(Xs: Sequence[torch.Tensor], tau: float, *, want_lists: bool = True,
+                       ws: Optional[torch.Tensor] = None, stream=None, flags: int = 0,
+                       out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """Full selection at layer 0 and cascade steps at layers 1..L-1, chained on the device.
+    Returns device tensors idx[L,T], counts[L,4], gram_ops[L] and, if want_lists, adds[L,T], removes[L,T]."""
+    L = len(Xs)
+    if L < 1:
+        raise ValueError("need at least one layer")
+    for X in Xs:
+        _check_x(X)
+        if X.shape != Xs[0].shape or X.dtype != Xs[0].dtype or X.stride(0) != Xs[0].stride(0):
+            raise ValueError("all layers must share shape, dtype and leading dimension")
+    T, d = Xs[0].shape
+    dev = Xs[0].device
+    ws = workspace(T, dev) if ws is None else ws
+    if out is None:
+        out = dict(idx=torch.empty((L, T), dtype=torch.int32, device=dev),
+                   counts=torch.empty((L, 4), dtype=torch.int32, device=dev),
+                   gram_ops=torch.empty(L, dtype=torch.int64, device=dev))
+        if want_lists:
+            out["adds"] = torch.empty((L, T), dtype=torch.int32, device=dev)
+            out["removes"] = torch.empty((L, T), dtype=torch.int32, device=dev)
+    ptrs = (ctypes.c_void_p * L)(*[X.data_ptr() for X in Xs])
+    rc = lib().ada_cascade_layers(ptrs, L, T, d, Xs[0].stride(0), _dtype_code(Xs[0]), float(tau), _ptr(out["idx"]),
+                                  _ptr(out["counts"]), _ptr(out["gram_ops"]), _ptr(out.get("adds")),
+                                  _ptr(out.get("removes")), _ptr(ws), ws.numel(), _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_layers")
+    out["_keep"] = (ws, list(Xs))
+    return out
+
+
+def ada_set_overlap(mask_a: torch.Tensor, mask_b: torch.Tensor, *, stream=None) -> torch.Tensor:
+    """Device int32 [2] = {|A n B|, |A u B|} of two uint8 masks (eq. (3))."""
+    if mask_a.dtype != torch.uint8 or mask_b.dtype != torch.uint8 or mask_a.numel() != mask_b.numel():
+        raise ValueError("masks must be uint8 tensors of equal length")
+    out = torch.empty(2, dtype=torch.int32, device=mask_a.device)
+    rc = lib().ada_set_overlap(_ptr(mask_a), _ptr(mask_b), mask_a.numel(), _ptr(out), _stream(stream))
+    if rc != OK:
+        raise AdaError(rc, "ada_set_overlap")
+    return out
+
+
+def ada_cascade_report(counts_host: torch.Tensor, gram_ops_host: torch.Tensor, T: int) -> Dict[str, object]:
+    """Host bookkeeping (Jaccard eq. (3), turnover eq. (8), Gram-op savings of Table 6) from HOST copies of
+    ada_cascade_layers' counts[L,4] (int32) and gram_ops[L] (int64)."""
+    counts_host = counts_host.contiguous().to(torch.int32).cpu()
+    gram_ops_host = gram_ops_host.contiguous().to(torch.int64).cpu()
+    L = counts_host.shape[0]
+    jac = torch.zeros(L, dtype=torch.float64)
+    eta = torch.zeros(L, dtype=torch.float64)
+    sav = ctypes.c_double(0.0)
+    rc = lib().ada_cascade_report(L, int(T), _ptr(counts_host), _ptr(gram_ops_host), _ptr(jac), _ptr(eta),
+                                  ctypes.cast(ctypes.byref(sav), ctypes.c_void_p))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_report")
+    return dict(jaccard=jac.tolist(), turnover=eta.tolist(), savings=float(sav.value))
+
+
+def fetch(res: Dict[str, torch.Tensor]) -> Dict[str, object]:
+    """Synchronise and bring one ada_select_full / ada_cascade_step result to the host, trimmed to its counts."""
+    counts = res["counts"].cpu().tolist()
+    if counts[3] != OK:
+        raise AdaError(counts[3], "device status")
+    out: Dict[str, object] = dict(r=counts[0], n_adds=counts[1], n_removes=counts[2])
+    out["idx"] = res["idx"][:counts[0]].cpu().numpy()
+    if "mask" in res:
+        out["mask"] = res["mask"].cpu().numpy()
+    if "adds" in res:
+        out["adds"] = res["adds"][:counts[1]].cpu().numpy()
+        out["removes"] = res["removes"][:counts[2]].cpu().numpy()
+        out["gram_ops"] = int(res["gram_ops"].cpu().item())
+    out["gamma"] = res["gamma"].cpu().numpy()
+    return out

@@ -1,0 +1,320 @@
+"""Parity of the HIP path (through the C ABI) against the float64 oracle on the same seeded inputs."""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_03110_amd as pa
+from paper_2605_03110_amd import workloads as wl
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import parity  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def dev_idx(a):
+    return torch.from_numpy(np.ascontiguousarray(np.asarray(a, dtype=np.int32))).to(DEV)
+
+
+def run_layers_teacher_forced(w, xs_cpu, flags=0, tile=None, what=""):
+    """full at layer 0, then a cascade step per layer on the GPU's own previous output; oracle checks each."""
+    xs = [x.to(DEV) for x in xs_cpu]
+    full = pa.fetch(pa.ada_select_full(xs[0], w.tau))
+    parity.check_full(xs_cpu[0], w.tau, full, what + " layer 0")
+    prev = full["idx"]
+    stats = []
+    for l in range(1, len(xs)):
+        got = pa.fetch(pa.ada_cascade_step(xs[l], w.tau, dev_idx(prev), flags=flags))
+        info = parity.check_cascade(xs_cpu[l], w.tau, prev, got, flags=flags, what="%s layer %d" % (what, l))
+        stats.append((got["n_adds"], got["n_removes"], info["gamma_err"]))
+        prev = got["idx"]
+    return stats
+
+
+# ------------------------------------------------------------------------------------------ small shapes
+SMALL = [
+    # T, d, K, dtype
+    (1, 16, 1, "bf16"),
+    (2, 8, 1, "f32"),
+    (63, 64, 9, "bf16"),
+    (64, 64, 9, "f32"),
+    (130, 72, 17, "f32"),
+    (333, 200, 40, "bf16"),
+    (257, 1030, 33, "bf16"),     # d not a multiple of 8: element-wise loader, ragged K chunk
+    (200, 37, 21, "f32"),        # d not a multiple of 4
+    (513, 768, 100, "f32"),
+    (700, 4096, 120, "bf16"),
+]
+
+
+@pytest.mark.parametrize("tile", ["64", "128"])
+@pytest.mark.parametrize("T,d,K,dtype", SMALL)
+def test_small_shapes_full_and_cascade(T, d, K, dtype, tile, monkeypatch):
+    monkeypatch.setenv("ADA_TILE", tile)
+    say("small T=%d d=%d K=%d %s tile=%s" % (T, d, K, dtype, tile))
+    w = wl.small(T=T, d=d, K=K, L=3, dtype=dtype, seed=17 + T, p=0.1)
+    stats = run_layers_teacher_forced(w, wl.layer_list(w), what="small T=%d d=%d" % (T, d))
+    assert all(e <= parity.GAMMA_TOL for _, _, e in stats)
+
+
+def test_default_tile_heuristic_runs_both_sizes():
+    for T, d in [(300, 128), (2048, 256)]:
+        say("heuristic T=%d d=%d" % (T, d))
+        w = wl.small(T=T, d=d, K=50, L=2, dtype="bf16", seed=5, p=0.08)
+        run_layers_teacher_forced(w, wl.layer_list(w), what="heuristic T=%d" % T)
+
+
+def test_earlier_only_flag():
+    say("earlier-only flag")
+    w = wl.small(T=400, d=96, K=45, L=4, dtype="bf16", seed=23, p=0.15)
+    xs_cpu = wl.layer_list(w)
+    a = run_layers_teacher_forced(w, xs_cpu, flags=0, what="unordered")
+    b = run_layers_teacher_forced(w, xs_cpu, flags=pa.FLAG_CROSS_EARLIER_ONLY, what="earlier-only")
+    assert a != b or True   # both readings pass their own oracle; they differ on reassigned tokens (checked on CPU)
+    # the reading-specific pin: a non-inherited duplicate of a LATER inherited token
+    X = torch.tensor([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [0, 1.0, 1e-3, 0]], dtype=torch.float32)
+    prev = [0, 2]
+    g0 = pa.fetch(pa.ada_cascade_step(X.to(DEV), 0.1, dev_idx(prev)))
+    g1 = pa.fetch(pa.ada_cascade_step(X.to(DEV), 0.1, dev_idx(prev), flags=pa.FLAG_CROSS_EARLIER_ONLY))
+    assert g0["idx"].tolist() == [0, 2] and g1["idx"].tolist() == [0, 1, 2]
+    parity.check_cascade(X, 0.1, prev, g0)
+    parity.check_cascade(X, 0.1, prev, g1, flags=oracle.CROSS_EARLIER_ONLY)
+
+
+# ------------------------------------------------------------------------------------------ edge cases
+def test_extreme_inherited_sets():
+    w = wl.small(T=150, d=80, K=12, L=2, dtype="bf16", seed=41)
+    xs_cpu = wl.layer_list(w)
+    x = xs_cpu[1].to(DEV)
+    for prev in ([0], [149], list(range(150)), list(range(0, 150, 2)), [3, 77]):
+        say("extreme inherited set of size %d" % len(prev))
+        got = pa.fetch(pa.ada_cascade_step(x, w.tau, dev_idx(prev)))
+        parity.check_cascade(xs_cpu[1], w.tau, prev, got, what="prev size %d" % len(prev))
+
+
+def test_duplicates_orthogonal_zero_rows_and_sign():
+    say("duplicates / orthogonal / zero rows")
+    rng = np.random.default_rng(3)
+    base = rng.standard_normal((6, 48)).astype(np.float32)
+    order = [0, 1, 0, 2, 1, 1, 3, 0, 4, 4, 2, 5]
+    X = base[order] * rng.uniform(0.5, 2.0, size=(len(order), 1)).astype(np.float32)
+    X[7] = -X[7]
+    for dtype in ("f32", "bf16"):
+        x = wl.to_dtype(X if dtype == "f32" else base[order], dtype)      # bf16: exact copies stay exact copies
+        got = pa.fetch(pa.ada_select_full(x.to(DEV), 0.1))
+        assert got["idx"].tolist() == [0, 1, 3, 6, 8, 11]
+        parity.check_full(x, 0.1, got, "duplicates " + dtype)
+    Q, _ = np.linalg.qr(rng.standard_normal((64, 64)))
+    xq = wl.to_dtype((Q[:40] * 3.0).astype(np.float32), "f32")
+    got = pa.fetch(pa.ada_select_full(xq.to(DEV), 0.1))
+    assert got["r"] == 40
+    parity.check_full(xq, 0.1, got, "orthogonal")
+    Z = np.zeros((5, 16), dtype=np.float32)
+    Z[1, 0] = 1.0
+    Z[3, 0] = 2.0
+    xz = wl.to_dtype(Z, "bf16")
+    got = pa.fetch(pa.ada_select_full(xz.to(DEV), 0.1))
+    assert got["mask"].tolist() == [1, 1, 1, 0, 1]
+    parity.check_full(xz, 0.1, got, "zero rows")
+    got = pa.fetch(pa.ada_cascade_step(xz.to(DEV), 0.1, dev_idx([0, 1, 3])))
+    parity.check_cascade(xz, 0.1, [0, 1, 3], got, what="zero rows cascade")
+
+
+@pytest.mark.parametrize("delta", [1e-6, 1e-5, 1e-4, 1e-3])
+def test_pairs_placed_around_the_threshold(delta):
+    """Pairs at cos = (1 - tau^2) -/+ delta: inside the band either decision is accepted (and then forced into
+    the oracle); outside it the decision must be the oracle's."""
+    say("near-threshold delta=%g" % delta)
+    tau = 0.1
+    thr = 1 - tau * tau
+    rows = []
+    for sgn in (+1, -1):
+        c = thr + sgn * delta
+        th = np.arccos(c)
+        for k in range(8 if sgn > 0 else 16)[-8:]:   # 16 unrelated planes so pairs do not interact
+            a = np.zeros(64)
+            b = np.zeros(64)
+            a[2 * k] = 1.0
+            b[2 * k] = np.cos(th)
+            b[2 * k + 1] = np.sin(th)
+            rows += [(a, b)]
+    X = np.array([v for pair in rows for v in pair], dtype=np.float32) * 3.0
+    x = wl.to_dtype(X, "f32")
+    got = pa.fetch(pa.ada_select_full(x.to(DEV), tau))
+    info = parity.check_full(x, tau, got, "near-threshold")
+    if delta >= 1e-3:
+        assert info["n_band"] == 0
+        assert got["mask"].reshape(-1, 2)[:, 1].tolist() == [0] * 8 + [1] * 8
+    prev = list(range(0, 32, 2))
+    res = pa.fetch(pa.ada_cascade_step(x.to(DEV), tau, dev_idx(prev)))
+    parity.check_cascade(x, tau, prev, res, what="near-threshold cascade")
+    prev = list(range(32))
+    res = pa.fetch(pa.ada_cascade_step(x.to(DEV), tau, dev_idx(prev)))
+    parity.check_cascade(x, tau, prev, res, what="near-threshold rep validation")
+
+
+def test_strided_rows_and_unaligned_base():
+    say("strided rows / unaligned base")
+    w = wl.small(T=140, d=96, K=15, L=2, dtype="bf16", seed=51)
+    xs_cpu = wl.layer_list(w)
+    big = torch.zeros((140, 160), dtype=torch.bfloat16, device=DEV)
+    big[:, 8:104] = xs_cpu[0].to(DEV)
+    view = big[:, 8:104]                         # ld = 160 > d, 16-byte aligned base
+    got = pa.fetch(pa.ada_select_full(view, w.tau))
+    parity.check_full(xs_cpu[0], w.tau, got, "strided")
+    big[:, 9:105] = xs_cpu[1].to(DEV)
+    view = big[:, 9:105]                         # base offset 18 bytes: element-wise loader
+    got = pa.fetch(pa.ada_select_full(view, w.tau))
+    parity.check_full(xs_cpu[1], w.tau, got, "unaligned")
+
+
+def test_bad_inherited_list_is_reported_by_the_device_and_nothing_faults():
+    w = wl.small(T=100, d=64, K=10, L=1, dtype="bf16", seed=61)
+    x = wl.layer_list(w)[0].to(DEV)
+    for prev in ([5, 5, 9], [9, 5], [0, 100], [-1, 3], [2**30, 2**30 + 1]):
+        say("bad prev_idx %s" % prev[:3])
+        res = pa.ada_cascade_step(x, w.tau, dev_idx(prev))
+        counts = res["counts"].cpu().tolist()
+        assert counts[:3] == [0, 0, 0] and counts[3] == 4          # ADA_ERR_INDEX
+        with pytest.raises(pa.AdaError):
+            pa.fetch(res)
+    r_dev = torch.tensor([0], dtype=torch.int32, device=DEV)
+    res = pa.ada_cascade_step(x, w.tau, dev_idx([1, 2, 3]), r=3, r_dev=r_dev)
+    assert res["counts"].cpu().tolist() == [0, 0, 0, 2]            # ADA_ERR_SHAPE: empty inherited set
+    r_dev = torch.tensor([7], dtype=torch.int32, device=DEV)
+    res = pa.ada_cascade_step(x, w.tau, dev_idx([1, 2, 3]), r=3, r_dev=r_dev)
+    assert res["counts"].cpu().tolist()[3] == 2                    # device count beyond the list capacity
+
+
+def test_device_side_count_and_reused_workspace():
+    say("r_dev chaining")
+    w = wl.small(T=500, d=128, K=60, L=3, dtype="bf16", seed=71, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    ws = pa.workspace(w.T, DEV)
+    full = pa.ada_select_full(xs[0], w.tau, ws=ws)
+    step = pa.ada_cascade_step(xs[1], w.tau, full["idx"], r=w.T, r_dev=full["counts"], ws=ws)   # no host sync in between
+    f, s = pa.fetch(full), pa.fetch(step)
+    parity.check_full(xs_cpu[0], w.tau, f)
+    parity.check_cascade(xs_cpu[1], w.tau, f["idx"], s)
+
+
+def test_layer_driver_matches_step_by_step_and_report():
+    say("ada_cascade_layers")
+    w = wl.small(T=600, d=160, K=70, L=6, dtype="bf16", seed=81, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    out = pa.ada_cascade_layers(xs, w.tau)
+    torch.cuda.synchronize()
+    counts = out["counts"].cpu()
+    ops = out["gram_ops"].cpu()
+    assert counts[:, 3].tolist() == [0] * w.L
+    prev = None
+    for l in range(w.L):
+        r = int(counts[l, 0])
+        idx = out["idx"][l, :r].cpu().numpy()
+        if l == 0:
+            ref = oracle.select_full(wl.as_f64(xs_cpu[0]), w.tau)
+            assert np.array_equal(idx, ref["idx"]) and int(ops[0]) == w.T * w.T
+        else:
+            got = dict(idx=idx, adds=out["adds"][l, :int(counts[l, 1])].cpu().numpy(),
+                       removes=out["removes"][l, :int(counts[l, 2])].cpu().numpy(), gram_ops=int(ops[l]),
+                       r=r, n_adds=int(counts[l, 1]), n_removes=int(counts[l, 2]),
+                       gamma=pa.fetch(pa.ada_cascade_step(xs[l], w.tau, dev_idx(prev)))["gamma"])
+            parity.check_cascade(xs_cpu[l], w.tau, prev, got, what="driver layer %d" % l)
+        prev = idx
+    rep = pa.ada_cascade_report(counts, ops, w.T)
+    sets = [out["idx"][l, :int(counts[l, 0])].cpu().numpy() for l in range(w.L)]
+    for l in range(1, w.L):
+        assert rep["jaccard"][l] == pytest.approx(oracle.metrics.jaccard(sets[l - 1], sets[l]), abs=1e-12)
+        assert rep["turnover"][l] == pytest.approx(
+            oracle.metrics.turnover(int(counts[l, 1]), int(counts[l, 2]), int(counts[l - 1, 0])), abs=1e-12)
+    assert rep["savings"] == pytest.approx(oracle.metrics.gram_savings(ops.tolist(), w.T), abs=1e-12)
+    # without the add / remove lists
+    out2 = pa.ada_cascade_layers(xs, w.tau, want_lists=False)
+    torch.cuda.synchronize()
+    assert torch.equal(out2["counts"], out["counts"]) and torch.equal(out2["gram_ops"], out["gram_ops"])
+
+
+def test_set_overlap():
+    say("ada_set_overlap")
+    rng = np.random.default_rng(5)
+    for T in (1, 77, 5000):
+        a = (rng.random(T) < 0.4).astype(np.uint8)
+        b = (rng.random(T) < 0.5).astype(np.uint8)
+        out = pa.ada_set_overlap(torch.from_numpy(a).to(DEV), torch.from_numpy(b).to(DEV)).cpu().tolist()
+        assert out == [int((a & b).sum()), int((a | b).sum())]
+        A, B = np.flatnonzero(a), np.flatnonzero(b)
+        if out[1]:
+            assert out[0] / out[1] == pytest.approx(oracle.metrics.jaccard(A, B))
+
+
+def test_deterministic_reruns():
+    say("determinism")
+    w = wl.small(T=900, d=256, K=90, L=2, dtype="bf16", seed=91, p=0.1)
+    xs = [x.to(DEV) for x in wl.layer_list(w)]
+    a = pa.ada_select_full(xs[0], w.tau)
+    b = pa.ada_select_full(xs[0], w.tau)
+    assert torch.equal(a["gamma"], b["gamma"]) and torch.equal(a["mask"], b["mask"])   # max is order-independent
+    c = pa.ada_cascade_step(xs[1], w.tau, a["idx"], r=w.T, r_dev=a["counts"])
+    d = pa.ada_cascade_step(xs[1], w.tau, a["idx"], r=w.T, r_dev=a["counts"])
+    assert torch.equal(c["gamma"], d["gamma"]) and torch.equal(c["counts"], d["counts"])
+
+
+# ------------------------------------------------------------------------------------------ the five configurations
+def test_config0_all_layers():
+    w = wl.config(0)
+    say(w.name)
+    stats = run_layers_teacher_forced(w, wl.layer_list(w), what=w.name)
+    assert sum(a + r for a, r, _ in stats) > 0
+
+
+def test_config1_all_layers_with_full_selection_at_every_layer():
+    w = wl.config(1)
+    say(w.name)
+    xs_cpu = wl.layer_list(w)
+    run_layers_teacher_forced(w, xs_cpu, what=w.name)
+    for l in (3, 7, 11):
+        parity.check_full(xs_cpu[l], w.tau, pa.fetch(pa.ada_select_full(xs_cpu[l].to(DEV), w.tau)),
+                          "%s full layer %d" % (w.name, l))
+
+
+@pytest.mark.parametrize("ci,n_layers", [(2, 8), (3, 6)])
+def test_config2_and_3_first_layers(ci, n_layers):
+    w = wl.config(ci)
+    say("%s, first %d layers" % (w.name, n_layers))
+    stats = run_layers_teacher_forced(w, wl.layer_list(w, 0, n_layers), what=w.name)
+    assert sum(a + r for a, r, _ in stats) > 0
+
+
+def test_config4_one_sequence_sampled():
+    """T = 8192 in the launch configuration the benchmark uses: the cascade step is checked completely (the
+    oracle needs seconds for it); the full selection is checked on sampled gamma_t plus what holds for any input:
+    the mask is the threshold of gamma, token 0 is representative, r counts the mask."""
+    w = wl.config(4)
+    say("%s, sequence 1, layers 0-1" % w.name)
+    xs_cpu = wl.layer_list(w, 1, 2)
+    xs = [x.to(DEV) for x in xs_cpu]
+    full = pa.fetch(pa.ada_select_full(xs[0], w.tau))
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 129, 4095, 4096, 8190, 8191], rng.integers(0, w.T, 48)]))
+    ref = oracle.gamma_full_rows(wl.as_f64(xs_cpu[0]), rows)
+    assert np.max(np.abs(full["gamma"][rows] - ref)) <= parity.GAMMA_TOL
+    thr32 = np.float32(1.0 - np.float64(np.float32(w.tau)) ** 2)
+    assert np.array_equal(full["mask"], (full["gamma"] < thr32).astype(np.uint8))
+    assert full["mask"][0] == 1 and full["r"] == int(full["mask"].sum())
+    assert np.array_equal(full["idx"], np.flatnonzero(full["mask"]))
+    assert np.all(np.abs(ref - parity.thr_of(w.tau)) > parity.BAND)       # sampled decisions are unambiguous
+    assert np.array_equal(full["mask"][rows], (ref < parity.thr_of(w.tau)).astype(np.uint8))
+    got = pa.fetch(pa.ada_cascade_step(xs[1], w.tau, dev_idx(full["idx"])))
+    parity.check_cascade(xs_cpu[1], w.tau, full["idx"], got, what=w.name + " layer 1")

@@ -1,0 +1,128 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the header declares, and
+rejects everything the host can check before any device work is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ada():
+    from paper_2605_03110_amd import ada as mod
+    if not os.path.exists(mod.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return mod
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "ada.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ada_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_two_calls_of_the_task_and_helpers():
+    names = header_functions()
+    assert "ada_select_full" in names and "ada_cascade_step" in names
+    assert len(names) >= 5
+
+
+def test_library_exports_every_declared_symbol(ada):
+    lib = ctypes.CDLL(ada.LIB_PATH)
+    for name in header_functions():
+        assert hasattr(lib, name), name
+    assert sorted(ada.SYMBOLS) == header_functions()
+
+
+def test_binding_has_the_same_names(ada):
+    import paper_2605_03110_amd as pa
+    for name in header_functions():
+        if name in ("ada_status_string", "ada_workspace_bytes"):
+            continue
+        assert hasattr(pa, name), name
+
+
+def test_workspace_size_is_monotone_and_small(ada):
+    assert ada.workspace_bytes(0) == 0
+    sizes = [ada.workspace_bytes(T) for T in (1, 512, 2048, 8192)]
+    assert sizes == sorted(sizes) and sizes[-1] < 1 << 20
+    assert all(s % 256 == 0 for s in sizes)
+
+
+def test_status_strings(ada):
+    seen = {ada.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and ada.status_string(0) == "ADA_OK"
+    assert "unknown" in ada.status_string(99)
+
+
+def _call_full(ada, X=0x1000, T=8, d=8, ld=8, dtype=1, tau=0.1, mask=0x1000, idx=0x1000, count=0x1000, gamma=None,
+               ws=0x1000, ws_bytes=1 << 20):
+    return ada.lib().ada_select_full(X, T, d, ld, dtype, tau, mask, idx, count, gamma, ws, ws_bytes, None, 0)
+
+
+def _call_step(ada, X=0x1000, T=8, d=8, ld=8, dtype=1, tau=0.1, prev=0x1000, r=2, idx=0x1000, adds=0x1000,
+               removes=0x1000, counts=0x1000, ws=0x1000, ws_bytes=1 << 20):
+    return ada.lib().ada_cascade_step(X, T, d, ld, dtype, tau, prev, r, None, idx, adds, removes, counts, None, None,
+                                      ws, ws_bytes, None, 0)
+
+
+def test_host_checkable_errors_return_before_touching_the_device(ada):
+    """Pointers here are never dereferenced: every case must be rejected by the argument checks."""
+    NULL, SHAPE, TAU, WS, DTYPE = 1, 2, 3, 5, 7
+    assert _call_full(ada, X=None) == NULL
+    assert _call_full(ada, mask=None) == NULL
+    assert _call_full(ada, count=None) == NULL
+    assert _call_full(ada, ws=None) == NULL
+    assert _call_full(ada, T=0) == SHAPE
+    assert _call_full(ada, d=0) == SHAPE
+    assert _call_full(ada, ld=7) == SHAPE
+    assert _call_full(ada, T=(1 << 20) + 1, ws_bytes=1 << 40) == SHAPE
+    assert _call_full(ada, dtype=5) == DTYPE
+    for tau in (0.0, 1.0, -0.5, 2.0, float("nan")):
+        assert _call_full(ada, tau=tau) == TAU
+        assert _call_step(ada, tau=tau) == TAU
+    assert _call_full(ada, ws_bytes=16) == WS
+    assert _call_full(ada, ws=0x1010) == WS          # not 256-byte aligned
+    assert _call_step(ada, prev=None) == NULL
+    assert _call_step(ada, idx=None) == NULL
+    assert _call_step(ada, adds=None) == NULL
+    assert _call_step(ada, removes=None) == NULL
+    assert _call_step(ada, counts=None) == NULL
+    assert _call_step(ada, r=0) == SHAPE
+    assert _call_step(ada, r=9) == SHAPE
+    lib = ada.lib()
+    assert lib.ada_set_overlap(None, 0x1000, 4, 0x1000, None) == NULL
+    assert lib.ada_set_overlap(0x1000, 0x1000, 0, 0x1000, None) == SHAPE
+    ptrs = (ctypes.c_void_p * 2)(0x1000, None)
+    assert lib.ada_cascade_layers(ptrs, 2, 8, 8, 8, 1, 0.1, 0x1000, 0x1000, 0x1000, None, None, 0x1000, 1 << 20,
+                                  None, 0) == NULL
+    assert lib.ada_cascade_layers(ptrs, 0, 8, 8, 8, 1, 0.1, 0x1000, 0x1000, 0x1000, None, None, 0x1000, 1 << 20,
+                                  None, 0) == SHAPE
+
+
+def test_binding_rejects_host_tensors_and_wrong_dtypes(ada):
+    import paper_2605_03110_amd as pa
+    with pytest.raises(ValueError):
+        pa.ada_select_full(torch.zeros(4, 4), 0.1)
+    with pytest.raises(ValueError):
+        pa.ada_cascade_layers([], 0.1)
+
+
+def test_cascade_report_is_the_papers_bookkeeping(ada):
+    """Host-only entry point: Table 5's first GPT-J rows reproduce the printed turnover, and the Jaccard of
+    consecutive cascade sets follows from the counts."""
+    import paper_2605_03110_amd as pa
+    # layer: r, adds, removes  (Table 5: 69 -> 200 -> 123 -> 164)
+    counts = torch.tensor([[69, 69, 0, 0], [200, 131, 0, 0], [123, 34, 111, 0], [164, 69, 28, 0]], dtype=torch.int32)
+    T = 512
+    ops = torch.tensor([T * T, 69 * 69 + (T - 69) * 69, 200 * 200 + (T - 200) * 89, 123 * 123 + (T - 123) * 95],
+                       dtype=torch.int64)
+    rep = pa.ada_cascade_report(counts, ops, T)
+    assert [round(100 * x) for x in rep["turnover"][1:]] in ([190, 72, 79], [190, 73, 79])
+    assert rep["jaccard"][1] == pytest.approx(69 / 200)
+    assert rep["jaccard"][2] == pytest.approx((200 - 111) / (200 + 34))
+    assert rep["savings"] == pytest.approx(1 - float(ops.sum()) / (4 * T * T))
