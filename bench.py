@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the cascade-selection hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic sequence: full Gram-threshold selection at
+layer 0 and a cascade step at each of the layers 1..L-1 (Section 4.1), all chained on the device through
+ada_cascade_layers with inputs already resident in HBM.  The workload is the benchmark's configs[2]
+(GPT-J-shaped: T=2048, d=4096, 28 layers, bf16, tau=0.1, 400 centres), the configuration the metric is
+quoted on.  The 28 layer buffers (448 MiB) exceed the 256 MB Infinity Cache, so each layer's X comes from
+HBM when the step reaches it.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def cpu_baseline(w, xs_cpu, n_cascade=3):
+    """The float64 oracle, as it stands, on a bounded sample of the same workload: layer 0 (full selection)
+    and the first n_cascade cascade layers; the pass rate is extrapolated as L / (t_full + (L-1) * mean t_casc)."""
+    import oracle
+    from paper_2605_03110_amd import workloads as wl
+    t0 = time.perf_counter()
+    full = oracle.select_full(wl.as_f64(xs_cpu[0]), w.tau)
+    t_full = time.perf_counter() - t0
+    prev = full["idx"]
+    t_c = []
+    for l in range(1, 1 + n_cascade):
+        X = wl.as_f64(xs_cpu[l])
+        t0 = time.perf_counter()
+        res = oracle.cascade_step(X, w.tau, prev)
+        t_c.append(time.perf_counter() - t0)
+        prev = res["idx"]
+    mean_c = sum(t_c) / len(t_c)
+    return dict(value=w.L / (t_full + (w.L - 1) * mean_c), unit="layers/s", cores=oracle.threads(), kind="oracle",
+                sample="float64 C oracle (OpenMP) on layer 0 (full, %.2f s) and layers 1-%d (cascade, mean %.2f s) of the "
+                       "same sequence; extrapolated to the %d-layer pass" % (t_full, n_cascade, mean_c, w.L),
+                t_full_s=t_full, t_cascade_s=mean_c)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="index into BASELINE.json configs (default 2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the full-selection timing and the profiled pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
+              "in this library: see DESIGN.md, 'How the path would shard')" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import __graft_entry__
+    __graft_entry__.ensure_built()
+    import paper_2605_03110_amd as pa
+    from paper_2605_03110_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = wl.config(args.config)
+    T, d, L = w.T, w.d, w.L
+    esz = 2 if w.dtype == "bf16" else 4
+
+    xs_cpu = wl.layer_list(w, 0)
+    xs = [x.to(dev) for x in xs_cpu]
+    ws = pa.workspace(T, dev)
+    out = dict(idx=torch.empty((L, T), dtype=torch.int32, device=dev),
+               counts=torch.empty((L, 4), dtype=torch.int32, device=dev),
+               gram_ops=torch.empty(L, dtype=torch.int64, device=dev))
+    stream = torch.cuda.current_stream()
+
+    def step():
+        pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    layers_per_s = L * args.steps / elapsed
+
+    counts = out["counts"].cpu()
+    ops = out["gram_ops"].cpu()
+    assert counts[:, 3].tolist() == [0] * L, "device status reported an error"
+    rep = pa.ada_cascade_report(counts, ops, T)
+    r_per_layer = counts[:, 0].tolist()
+    r_prev_mean = sum(r_per_layer[:-1]) / max(L - 1, 1)
+
+    result = {
+        "metric": "cascade_select_layers_per_s", "value": layers_per_s, "unit": "layers/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: T=%d d=%d L=%d %s tau=%.2f, %d centres, noise %.3g, drift %.3g, %.0f%% reassigned "
+                               "per layer (%s scale), full selection at layer 0 + cascade at layers 1..%d"
+                               % (w.name, T, d, L, w.dtype, w.tau, w.K, w.sigma_n, w.sigma_c, 100 * w.p, w.scale, L - 1),
+                   "T": T, "d": d, "layers": L, "batch": 1},
+        "tokens_per_s": layers_per_s * T,
+        "method_stats": {"gram_op_savings": rep["savings"], "mean_jaccard_cascade": sum(rep["jaccard"][1:]) / (L - 1),
+                         "mean_turnover": sum(rep["turnover"][1:]) / (L - 1), "r_layer0": r_per_layer[0],
+                         "mean_r_cascade": sum(r_per_layer[1:]) / (L - 1),
+                         "paper_context": "paper: 22-63% savings, mean Jaccard 0.83-0.94 at T=512, tau=0.30, real "
+                                          "activations, MI300X"},
+    }
+
+    # ---- per-kernel durations from HIP events on the launch stream, over a pass identical to the timed one
+    kern = None
+    if not args.no_extras:
+        pa.ada_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        prof_elapsed = time.perf_counter() - t0
+        kern = pa.ada_profile_collect()
+        pa.ada_profile_enable(False)
+        avg_us = {k: (1e3 * v["ms"] / v["launches"] if v["launches"] else None) for k, v in kern.items()}
+        cross_s = 1e-6 * avg_us["gram_cross"]
+        # algorithmic bytes of one cross-Gram launch: every row of X once (the T-r tested rows streamed, the r
+        # inherited rows as the resident operand) = T*d*e bytes; O(T) outputs neglected
+        cross_bytes = T * d * esz
+        r_valid_mean = r_prev_mean   # upper estimate of r_valid for the flop count
+        cross_flops = 2.0 * d * (T - r_prev_mean) * r_valid_mean
+        result["roofline"] = {"bound": "hbm", "kernel": "k_gram (cross-Gram, cascade steps 6-9)",
+                              "achieved": cross_bytes / cross_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": cross_bytes / cross_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                              "avg_launch_us": avg_us["gram_cross"], "bytes_per_launch": cross_bytes,
+                              "mfma_tflops": cross_flops / cross_s / 1e12,
+                              "mfma_frac": cross_flops / cross_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        result["kernel_avg_us"] = avg_us
+        result["ms_per_step_with_events"] = 1e3 * prof_elapsed / args.steps
+
+        # ---- the full T x T selection at every layer (the comparison path), same buffers
+        fo = [pa.ada_select_full(xs[0], w.tau, ws=ws) for _ in range(2)]
+        torch.cuda.synchronize()
+        masks = torch.empty((L, T), dtype=torch.uint8, device=dev)
+        idxb = torch.empty(T, dtype=torch.int32, device=dev)
+        cnt = torch.empty(4, dtype=torch.int32, device=dev)
+        import ctypes
+        lib = pa.ada.lib()
+
+        def full_pass():
+            for l in range(L):
+                rc = lib.ada_select_full(ctypes.c_void_p(xs[l].data_ptr()), T, d, xs[l].stride(0),
+                                         pa.ada._dtype_code(xs[l]), float(w.tau), ctypes.c_void_p(masks[l].data_ptr()),
+                                         ctypes.c_void_p(idxb.data_ptr()), ctypes.c_void_p(cnt.data_ptr()), None,
+                                         ctypes.c_void_p(ws.data_ptr()), ws.numel(), ctypes.c_void_p(stream.cuda_stream), 0)
+                assert rc == 0
+        full_pass()
+        torch.cuda.synchronize()
+        n_full = max(1, args.steps // 4)
+        pa.ada_profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(n_full):
+            full_pass()
+        torch.cuda.synchronize()
+        full_elapsed = time.perf_counter() - t0
+        kf = pa.ada_profile_collect()
+        pa.ada_profile_enable(False)
+        full_us = 1e3 * kf["gram_full"]["ms"] / kf["gram_full"]["launches"]
+        tri_flops = float(T) * (T - 1) * d            # strict lower triangle: T(T-1)/2 entries * 2d flops
+        jac = []
+        for l in range(1, L):
+            o = pa.ada_set_overlap(masks[l - 1], masks[l]).cpu().tolist()
+            jac.append(o[0] / o[1])
+        result["full_select"] = {"layers_per_s": L * n_full / full_elapsed,
+                                 "roofline": {"bound": "mfma", "kernel": "k_gram (full lower-triangular Gram)",
+                                              "achieved": tri_flops / (1e-6 * full_us) / 1e12,
+                                              "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                              "frac": tri_flops / (1e-6 * full_us) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                              "avg_launch_us": full_us, "flops_per_launch": tri_flops},
+                                 "mean_jaccard_independent": sum(jac) / len(jac)}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, xs_cpu)
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

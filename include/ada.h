@@ -131,6 +131,18 @@ int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t
 int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* gram_ops_all,
                        double* jaccard, double* turnover, double* savings);
 
+/*
+ * Measurement aid (not part of the method).  While enabled, every kernel the library launches is bracketed by
+ * two HIP events recorded on the stream it is launched on.  ada_profile_collect waits for them and returns,
+ * per kernel class, the summed elapsed milliseconds and the number of launches since the last collect
+ * (HOST arrays of ADA_K_COUNT entries), then forgets them.  Event pairs include the launch gap in front of the
+ * kernel, so these figures are upper bounds of the durations a kernel trace reports.
+ */
+enum { ADA_K_NORM_PREP = 0, ADA_K_GRAM_FULL = 1, ADA_K_GRAM_REP = 2, ADA_K_GRAM_CROSS = 3, ADA_K_UPDATE = 4,
+       ADA_K_COUNT = 5 };
+int ada_profile_enable(int on);
+int ada_profile_collect(double* ms_sum, int* launches);
+
 #ifdef __cplusplus
 }
 #endif

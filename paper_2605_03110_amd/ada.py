@@ -23,7 +23,10 @@ FLAG_CROSS_EARLIER_ONLY = 1
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_select_full", "ada_cascade_step",
-           "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report")
+           "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
+           "ada_profile_collect")
+
+KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update")
 
 
 class AdaError(RuntimeError):
@@ -76,6 +79,10 @@ def lib():
         L.ada_set_overlap.argtypes = [vp, vp, i32, vp, vp]
         L.ada_cascade_report.restype = i32
         L.ada_cascade_report.argtypes = [i32, i32, vp, vp, vp, vp, vp]
+        L.ada_profile_enable.restype = i32
+        L.ada_profile_enable.argtypes = [i32]
+        L.ada_profile_collect.restype = i32
+        L.ada_profile_collect.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -224,6 +231,21 @@ def ada_cascade_report(counts_host: torch.Tensor, gram_ops_host: torch.Tensor, T
     if rc != OK:
         raise AdaError(rc, "ada_cascade_report")
     return dict(jaccard=jac.tolist(), turnover=eta.tolist(), savings=float(sav.value))
+
+
+def ada_profile_enable(on: bool) -> None:
+    lib().ada_profile_enable(int(bool(on)))
+
+
+def ada_profile_collect() -> Dict[str, Dict[str, float]]:
+    """Per kernel class: summed event-pair milliseconds and launch count since the last collect."""
+    n = len(KERNEL_CLASSES)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int * n)()
+    rc = lib().ada_profile_collect(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(cnt, ctypes.c_void_p))
+    if rc != OK:
+        raise AdaError(rc, "ada_profile_collect")
+    return {k: dict(ms=float(ms[i]), launches=int(cnt[i])) for i, k in enumerate(KERNEL_CLASSES)}
 
 
 def fetch(res: Dict[str, torch.Tensor]) -> Dict[str, object]:

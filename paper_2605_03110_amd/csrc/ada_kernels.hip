@@ -23,6 +23,7 @@
 #include <math.h>
 #include <stdlib.h>
 #include <mutex>
+#include <vector>
 
 #include "../../include/ada.h"
 
@@ -70,21 +71,35 @@ template <> __device__ inline float to_f32<float>(float v) { return v; }
 template <> __device__ inline float to_f32<uint16_t>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 
 // One 16-byte piece of a row starting at element e0; elements at or beyond d read as zero.
+// The aligned form is split in two so that loads can run ahead of their use: fetch_piece issues a branch-free
+// load from an address clamped into the row (a run of them stays in one basic block, which lets the compiler keep
+// several chunks in flight with counted waits), finish_piece zeroes an out-of-range piece when it is consumed.
+// The element-wise form does both in fetch_piece.
 template <typename In, bool ALIGNED>
-__device__ inline u32x4 load_piece(const In* row, int e0, int d) {
+__device__ inline u32x4 fetch_piece(const In* row, int e0, int d) {
     constexpr int EPP = 16 / (int)sizeof(In);
-    u32x4 out = {0u, 0u, 0u, 0u};
     if (ALIGNED) {
-        if (e0 < d) out = *reinterpret_cast<const u32x4*>(row + e0);
+        const int e = min(e0, d - EPP);                     // d is a positive multiple of EPP here
+        return *reinterpret_cast<const u32x4*>(row + e);
     } else {
         union { u32x4 v; In e[EPP]; } u;
-        u.v = out;
+        u.v = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < EPP; ++i)
             if (e0 + i < d) u.e[i] = row[e0 + i];
-        out = u.v;
+        return u.v;
     }
-    return out;
+}
+
+template <bool ALIGNED>
+__device__ inline u32x4 finish_piece(u32x4 v, int e0, int d) {
+    if (ALIGNED && e0 >= d) v = u32x4{0u, 0u, 0u, 0u};
+    return v;
+}
+
+template <typename In, bool ALIGNED>
+__device__ inline u32x4 load_piece(const In* row, int e0, int d) {
+    return finish_piece<ALIGNED>(fetch_piece<In, ALIGNED>(row, e0, d), e0, d);
 }
 
 template <typename In>
@@ -233,31 +248,66 @@ template <> struct Mfma<float> {
 // 16-byte fragment reads of 8 consecutive rows touch all 32 banks.
 __device__ inline int lds_off(int row, int piece) { return row * 128 + ((piece ^ (row & 7)) << 4); }
 
+// Tile geometry.  A workgroup of 4 wavefronts owns a B x B tile ("against" rows s x tested rows t) over all of K.
+//   B = 128: the waves form a 2 x 2 grid of 64 x 64 sub-tiles (2 x 2 MFMA blocks each).
+//   B = 64 : every wave computes the whole 64 x 64 tile for one quarter of each K chunk (k-split inside the
+//            workgroup, same LDS traffic per MFMA as the 128 case); the four partial tiles are summed through LDS
+//            in a fixed order before the epilogue, so results do not depend on scheduling.
+// K advances in chunks of 128 bytes per row.  Global loads run D chunks ahead of the MFMAs in registers and pass
+// through a double-buffered LDS stage.
+template <int B> struct TileGeom {
+    static constexpr bool KSPLIT = (B == 64);
+    static constexpr int D = KSPLIT ? 4 : 2;                 // prefetch depth in chunks (even)
+    static constexpr int ROWS = 2 * B;                       // "against" rows first, then tested rows
+    static constexpr int LPT = ROWS / 32;                    // 16-byte pieces each thread moves per chunk
+    static constexpr int STAGE = ROWS * 128;                 // bytes per LDS stage
+    static constexpr int META = 4 * B * 4;                   // s_tok, t_tok, s_scale, t_scale
+    static constexpr int RED = KSPLIT ? 4 * 4 * 16 * 64 * 4 : 0;   // cross-wave reduction scratch (aliases the stages)
+    static constexpr int LDS = META + (2 * STAGE > RED ? 2 * STAGE : RED);
+};
+
+// max over the 16 accumulator rows this lane holds of |acc| * scale[s], optionally masked by token order
+__device__ inline float block_max(const f32x16& v, const float* s_scale, const int* s_tok, int s_row0, int half,
+                                  bool need_order, int ttok) {
+    float m = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int sl = s_row0 + (i & 3) + 4 * half + 8 * (i >> 2);   // MFMA 32x32 accumulator row of register i
+        float x = fabsf(v[i]) * s_scale[sl];
+        if (need_order && !(s_tok[sl] < ttok)) x = 0.f;
+        m = fmaxf(m, x);
+    }
+    return m;
+}
+
+__device__ inline void publish_max(float m, float tscale, int ttok, int half, uint32_t* gamma_bits) {
+    m *= tscale;
+    m = fmaxf(m, __shfl_xor(m, 32, 64));                       // the two lane halves hold different s rows
+    // non-negative floats order like their bit patterns, so an integer atomicMax is an exact, order-independent max
+    if (half == 0 && ttok >= 0 && m > 0.f) atomicMax(gamma_bits + ttok, __float_as_uint(m));
+}
+
 template <typename In, int B, bool ALIGNED>
 __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, const int32_t* listT, int s0, int t0,
                                  int nS, int nT, bool need_order, char* lds) {
+    using G = TileGeom<B>;
     constexpr int EPP = 16 / (int)sizeof(In);
     constexpr int EPC = 8 * EPP;
-    constexpr int ROWS = 2 * B;          // "against" rows first, then tested rows
-    constexpr int LPT = ROWS / 32;       // pieces each thread moves per chunk
-    constexpr int STAGE = ROWS * 128;
-    constexpr int WB = B / 2;            // wave tile edge (2 x 2 waves)
-    constexpr int NB = WB / 32;          // 32x32 MFMA blocks per wave per edge
+    constexpr int LPT = G::LPT, D = G::D;
 
-    char* buf0 = lds;
-    char* buf1 = lds + STAGE;
-    int* s_tok = reinterpret_cast<int*>(lds + 2 * STAGE);
+    int* s_tok = reinterpret_cast<int*>(lds);
     int* t_tok = s_tok + B;
     float* s_scale = reinterpret_cast<float*>(t_tok + B);
     float* t_scale = s_scale + B;
+    char* buf0 = lds + G::META;
+    char* buf1 = buf0 + G::STAGE;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
-    const int ws = wave >> 1, wt = wave & 1;
     const In* X = reinterpret_cast<const In*>(p.X);
 
     // per-row metadata of the tile
-    for (int i = tid; i < ROWS; i += 256) {
+    for (int i = tid; i < G::ROWS; i += 256) {
         const bool isS = i < B;
         const int li = isS ? s0 + i : t0 + (i - B);
         const int n = isS ? nS : nT;
@@ -277,7 +327,7 @@ __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, cons
         }
     }
 
-    // the rows this thread stages
+    // the rows this thread stages: 8 consecutive lanes fetch one row's 128-byte chunk
     const int pc = tid & 7, rb = tid >> 3;
     const In* rowp[LPT];
     int woff[LPT];
@@ -288,21 +338,21 @@ __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, cons
         const int li = isS ? s0 + row : t0 + (row - B);
         const int n = isS ? nS : nT;
         const int32_t* list = isS ? listS : listT;
-        const int lc = li < n ? li : n - 1;
+        const int lc = li < n ? li : n - 1;        // rows past the end re-read the last row; their results are masked
         int tok = list ? list[lc] : lc;
         tok = min(max(tok, 0), p.T - 1);
         rowp[j] = X + (size_t)tok * (size_t)p.ld;
         woff[j] = lds_off(row, pc);
     }
 
-    const int nk = (p.d + EPC - 1) / EPC;
-    u32x4 pre[LPT];
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) pre[j] = load_piece<In, ALIGNED>(rowp[j], pc * EPP, p.d);
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) *reinterpret_cast<u32x4*>(buf0 + woff[j]) = pre[j];
-    __syncthreads();
+    constexpr int NB = G::KSPLIT ? 2 : (B / 2) / 32;   // MFMA blocks per wave per edge
+    constexpr int WB = G::KSPLIT ? B : B / 2;          // wave tile edge
+    constexpr int KS = G::KSPLIT ? 1 : 4;              // 16-element k-steps this wave runs per chunk
+    const int ws = G::KSPLIT ? 0 : (wave >> 1), wt = G::KSPLIT ? 0 : (wave & 1);
+    const int nk = (p.d + EPC - 1) / EPC;              // run as a multiple of D; the surplus chunks are all zero
 
+    u32x4 pre[D][LPT];                                 // global prefetch: D chunks in flight per thread
+    u32x4 fa[2][KS][NB], fb[2][KS][NB];                // MFMA operand fragments, double-buffered
     f32x16 acc[NB][NB];
 #pragma unroll
     for (int a = 0; a < NB; ++a)
@@ -311,57 +361,120 @@ __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, cons
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    for (int kc = 0; kc < nk; ++kc) {
-        const bool more = kc + 1 < nk;
-        if (more) {
+    auto fetch = [&](int set, int kc) {
 #pragma unroll
-            for (int j = 0; j < LPT; ++j) pre[j] = load_piece<In, ALIGNED>(rowp[j], (kc + 1) * EPC + pc * EPP, p.d);
+        for (int j = 0; j < LPT; ++j) pre[set][j] = fetch_piece<In, ALIGNED>(rowp[j], kc * EPC + pc * EPP, p.d);
+    };
+    auto store = [&](char* stage, int set, int kc) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j)
+            *reinterpret_cast<u32x4*>(stage + woff[j]) = finish_piece<ALIGNED>(pre[set][j], kc * EPC + pc * EPP, p.d);
+    };
+    auto read_frags = [&](const char* stage, int f) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int piece = (G::KSPLIT ? 2 * wave : 2 * ks) + half;
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+                fa[f][ks][a] = *reinterpret_cast<const u32x4*>(stage + lds_off(ws * WB + a * 32 + l32, piece));
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                fb[f][ks][b] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + wt * WB + b * 32 + l32, piece));
         }
-        const char* cur = (kc & 1) ? buf1 : buf0;
+    };
+    auto mma = [&](int f) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int piece = 2 * ks + half;
-            u32x4 fa[NB], fb[NB];
-#pragma unroll
-            for (int a = 0; a < NB; ++a) fa[a] = *reinterpret_cast<const u32x4*>(cur + lds_off(ws * WB + a * 32 + l32, piece));
-#pragma unroll
-            for (int b = 0; b < NB; ++b) fb[b] = *reinterpret_cast<const u32x4*>(cur + lds_off(B + wt * WB + b * 32 + l32, piece));
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int a = 0; a < NB; ++a)
 #pragma unroll
-                for (int b = 0; b < NB; ++b) Mfma<In>::run(acc[a][b], fa[a], fb[b]);
-        }
-        if (more) {
-            char* nxt = (kc & 1) ? buf0 : buf1;
+                for (int b = 0; b < NB; ++b) Mfma<In>::run(acc[a][b], fa[f][ks][a], fb[f][ks][b]);
+    };
+
+    // Software pipeline.  In iteration k the workgroup, after one barrier,
+    //   reads the fragments of chunk k+1 from LDS stage (k+1)&1           (used by the MFMAs of iteration k+1)
+    //   writes chunk k+2 from its prefetch registers into LDS stage k&1   (its global loads were issued D iterations ago)
+    //   issues the global loads of chunk k+2+D into the registers just freed
+    //   runs the MFMAs of chunk k on fragments read one iteration earlier,
+    // so no instruction waits on a memory operation issued in the same iteration.  sched_barrier keeps the
+    // program order of the loads, which is what lets the waits be counted (vmcnt) instead of draining.
 #pragma unroll
-            for (int j = 0; j < LPT; ++j) *reinterpret_cast<u32x4*>(nxt + woff[j]) = pre[j];
+    for (int s = 0; s < D; ++s) {
+        fetch(s, s);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    store(buf0, 0, 0);
+    fetch(0, D);
+    __builtin_amdgcn_sched_barrier(0);
+    store(buf1, 1, 1);
+    fetch(1, D + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    read_frags(buf0, 0);
+    for (int kc0 = 0; kc0 < nk; kc0 += D) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) {                        // D is even: stages, fragment buffers and sets are static
+            const int k = kc0 + s;
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            read_frags((s & 1) ? buf0 : buf1, (s + 1) & 1);
+            store((s & 1) ? buf1 : buf0, (s + 2) % D, k + 2);
+            fetch((s + 2) % D, k + 2 + D);
+            mma(s & 1);
         }
-        __syncthreads();
     }
 
-    // epilogue: lane holds column n = l32 (tested token) and rows m = (i & 3) + 4 * half + 8 * (i >> 2)
+    // epilogue: a lane holds tested column n = l32 and 16 of the 32 "against" rows of each MFMA block
     uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
+    if (G::KSPLIT) {
+        // sum the four K-quarter partial tiles in wave order 0,1,2,3; wave w finishes block w = (a, b) = (w >> 1, w & 1)
+        float* red = reinterpret_cast<float*>(buf0);          // [src wave][block][register][lane]
+        __syncthreads();                                      // all waves are done reading the stages
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int nl = wt * WB + b * 32 + l32;
-        const int ttok = t_tok[nl];
-        float m = 0.f;
+        for (int blk = 0; blk < 4; ++blk)
+            if (blk != wave) {
 #pragma unroll
-        for (int a = 0; a < NB; ++a) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int sl = ws * WB + a * 32 + (i & 3) + 4 * half + 8 * (i >> 2);
-                float v = fabsf(acc[a][b][i]) * s_scale[sl];
-                if (need_order && !(s_tok[sl] < ttok)) v = 0.f;
-                m = fmaxf(m, v);
+                for (int i = 0; i < 16; ++i) red[((wave * 4 + blk) * 16 + i) * 64 + lane] = acc[blk >> 1][blk & 1][i];
             }
+        __syncthreads();
+        f32x16 own;
+        switch (wave) {
+            case 0: own = acc[0][0]; break;
+            case 1: own = acc[0][1]; break;
+            case 2: own = acc[1][0]; break;
+            default: own = acc[1][1]; break;
         }
-        m *= t_scale[nl];
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
-        if (half == 0 && ttok >= 0 && m > 0.f) atomicMax(gamma_bits + ttok, __float_as_uint(m));
+        f32x16 tot;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float v = 0.f;
+#pragma unroll
+            for (int src = 0; src < 4; ++src)
+                v += (src == wave) ? own[i] : red[((src * 4 + wave) * 16 + i) * 64 + lane];
+            tot[i] = v;
+        }
+        const int a = wave >> 1, b = wave & 1;
+        const int nl = b * 32 + l32;
+        const int ttok = t_tok[nl];
+        const float m = block_max(tot, s_scale, s_tok, a * 32, half, need_order, ttok);
+        publish_max(m, t_scale[nl], ttok, half, gamma_bits);
+    } else {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int nl = wt * WB + b * 32 + l32;
+            const int ttok = t_tok[nl];
+            float m = 0.f;
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+                m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WB + a * 32, half, need_order, ttok));
+            publish_max(m, t_scale[nl], ttok, half, gamma_bits);
+        }
     }
 }
 
+// Grid: a multiple of 8 workgroups.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2, so
+// XCD x = blockIdx % 8 takes the contiguous tile range [x * per, (x + 1) * per): tiles that share operand rows run
+// on one L2.  Tiles are numbered with the "against" block fastest.
 template <typename In, int B, bool ALIGNED>
 __global__ __launch_bounds__(256) void k_gram(GramParams p) {
     extern __shared__ __align__(16) char lds[];
@@ -382,7 +495,11 @@ __global__ __launch_bounds__(256) void k_gram(GramParams p) {
     const long long nbS = (nS + B - 1) / B, nbT = (nT + B - 1) / B;
     const bool tri = p.mode != MODE_CROSS;
     const long long ntiles = tri ? nbT * (nbT + 1) / 2 : nbS * nbT;
-    for (long long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const long long per = (ntiles + 7) / 8;
+    const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
+    for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
+        const long long tile = xcd * per + slot;
+        if (tile >= ntiles) break;
         int tb, sb;
         if (tri) {
             tb = (int)((sqrtf(8.f * (float)tile + 1.f) - 1.f) * 0.5f);
@@ -485,7 +602,32 @@ __global__ __launch_bounds__(1024) void k_overlap(const uint8_t* a, const uint8_
 // ------------------------------------------------------------------------------------------------
 // host side
 
-template <int B> constexpr int gram_lds_bytes() { return 2 * (2 * B) * 128 + 4 * B * 4; }
+// Measurement aid: when enabled, every kernel launch is bracketed by two HIP events recorded on the stream the
+// kernel is launched on; ada_profile_collect() turns them into per-kernel-class totals.
+struct ProfRecord { int cls; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof;
+std::mutex g_prof_mu;
+
+struct ProfScope {
+    hipStream_t st;
+    bool on;
+    ProfRecord rec;
+    ProfScope(int cls, hipStream_t s) : st(s), on(g_prof_on) {
+        if (!on) return;
+        rec.cls = cls;
+        if (hipEventCreate(&rec.a) != hipSuccess || hipEventCreate(&rec.b) != hipSuccess) { on = false; return; }
+        (void)hipEventRecord(rec.a, st);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(rec.b, st);
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof.push_back(rec);
+    }
+};
+
+template <int B> constexpr int gram_lds_bytes() { return TileGeom<B>::LDS; }
 
 template <typename In, int B, bool ALIGNED>
 hipError_t launch_gram(const GramParams& p, long long tiles_upper, hipStream_t st) {
@@ -498,7 +640,8 @@ hipError_t launch_gram(const GramParams& p, long long tiles_upper, hipStream_t s
     });
     if (attr_err != hipSuccess) return attr_err;
     if (tiles_upper < 1) return hipSuccess;
-    const unsigned grid = (unsigned)(tiles_upper < 65535 ? tiles_upper : 65535);
+    const unsigned grid = (unsigned)((tiles_upper < 65528 ? tiles_upper : 65528) + 7) / 8 * 8;   // multiple of 8 (XCDs)
+    ProfScope ps(p.mode == MODE_FULL ? ADA_K_GRAM_FULL : p.mode == MODE_REP ? ADA_K_GRAM_REP : ADA_K_GRAM_CROSS, st);
     hipLaunchKernelGGL((k_gram<In, B, ALIGNED>), dim3(grid), dim3(256), lds, st, p);
     return hipGetLastError();
 }
@@ -515,10 +658,12 @@ int tile_override() {
     return (v == 64 || v == 128) ? v : 0;
 }
 
-// nS_upper / nT_upper: host-known upper bounds of the list lengths (the kernel reads the actual ones)
+// nS_upper / nT_upper: host-known upper bounds of the list lengths (the kernel reads the actual ones).
+// 128-tiles need half the operand traffic per flop but only pay off when they still fill the chip; with sizes
+// known only on the device (exact == false) the 64-tile, which suits every skinny cascade shape, is used.
 template <typename In, bool ALIGNED>
-hipError_t launch_gram_any(const GramParams& p, int nS_upper, int nT_upper, hipStream_t st) {
-    int B = tiles_for(p.mode, nS_upper, nT_upper, 128) >= 192 ? 128 : 64;
+hipError_t launch_gram_any(const GramParams& p, int nS_upper, int nT_upper, bool exact, hipStream_t st) {
+    int B = (exact && tiles_for(p.mode, nS_upper, nT_upper, 128) >= 192) ? 128 : 64;
     if (int o = tile_override()) B = o;
     if (B == 128) return launch_gram<In, 128, ALIGNED>(p, tiles_for(p.mode, nS_upper, nT_upper, 128), st);
     return launch_gram<In, 64, ALIGNED>(p, tiles_for(p.mode, nS_upper, nT_upper, 64), st);
@@ -528,9 +673,16 @@ template <typename In, bool ALIGNED>
 hipError_t launch_norm_prep(const void* X, long long ld, int T, int d, float* gamma, const Workspace& w,
                             const PrepParams& prep, hipStream_t st) {
     const int nb = (T + 3) / 4;
+    ProfScope ps(ADA_K_NORM_PREP, st);
     hipLaunchKernelGGL((k_norm_prep<In, ALIGNED>), dim3(nb + (prep.enabled ? 1 : 0)), dim3(256), 0, st,
                        reinterpret_cast<const In*>(X), ld, T, d, w.inv_norm, gamma, w, prep, nb);
     return hipGetLastError();
+}
+
+int launch_update(const UpdateParams& u, hipStream_t st) {
+    ProfScope ps(ADA_K_UPDATE, st);
+    hipLaunchKernelGGL(k_update, dim3(1), dim3(1024), 0, st, u);
+    return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
 template <typename In_, bool A_> struct Variant { using In = In_; static constexpr bool aligned = A_; };
@@ -569,13 +721,12 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
         using V = decltype(v);
         hipError_t e1 = launch_norm_prep<typename V::In, V::aligned>(X, ld, T, d, g, w, prep, st);
         if (e1 != hipSuccess) return e1;
-        return launch_gram_any<typename V::In, V::aligned>(p, T, T, st);
+        return launch_gram_any<typename V::In, V::aligned>(p, T, T, true, st);
     });
     if (e != hipSuccess) return ADA_ERR_DEVICE;
     const UpdateParams u = {g, nullptr, nullptr, T, thr, mask, idx, nullptr, nullptr, counts,
                             reinterpret_cast<unsigned long long*>(gram_ops)};
-    hipLaunchKernelGGL(k_update, dim3(1), dim3(1024), 0, st, u);
-    return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+    return launch_update(u, st);
 }
 
 // Algorithm 1.  Arguments checked by the caller; adds / removes / gram_ops / gamma may be NULL.
@@ -598,17 +749,16 @@ int run_cascade(const void* X, int T, int d, long long ld, int dtype, float tau,
         hipError_t e1 = launch_norm_prep<typename V::In, V::aligned>(X, ld, T, d, g, w, prep, st);
         if (e1 != hipSuccess) return e1;
         // steps 3-5: r x r Gram among the inherited rows, strict lower triangle in token order
-        e1 = launch_gram_any<typename V::In, V::aligned>(rep, nS_up, nS_up, st);
+        e1 = launch_gram_any<typename V::In, V::aligned>(rep, nS_up, nS_up, r_dev == nullptr, st);
         if (e1 != hipSuccess || nT_up < 1) return e1;
         // steps 6-9: every other token against the valid representatives
-        return launch_gram_any<typename V::In, V::aligned>(cross, nS_up, nT_up, st);
+        return launch_gram_any<typename V::In, V::aligned>(cross, nS_up, nT_up, r_dev == nullptr, st);
     });
     if (e != hipSuccess) return ADA_ERR_DEVICE;
     // step 10 and the bookkeeping of eq. (6) / eq. (8)
     const UpdateParams u = {g, w.is_rep, w.meta, T, thr, nullptr, idx, adds, removes, counts,
                             reinterpret_cast<unsigned long long*>(gram_ops)};
-    hipLaunchKernelGGL(k_update, dim3(1), dim3(1024), 0, st, u);
-    return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+    return launch_update(u, st);
 }
 
 }  // namespace
@@ -677,6 +827,28 @@ int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t
     if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
     hipLaunchKernelGGL(k_overlap, dim3(1), dim3(1024), 0, (hipStream_t)stream, mask_a, mask_b, T, out);
     return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+}
+
+int ada_profile_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = on != 0;
+    return ADA_OK;
+}
+
+int ada_profile_collect(double* ms_sum, int* launches) {
+    if (!ms_sum || !launches) return ADA_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (int k = 0; k < ADA_K_COUNT; ++k) { ms_sum[k] = 0.0; launches[k] = 0; }
+    int rc = ADA_OK;
+    for (ProfRecord& r : g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) rc = ADA_ERR_DEVICE;
+        else { ms_sum[r.cls] += (double)ms; launches[r.cls] += 1; }
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_prof.clear();
+    return rc;
 }
 
 int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* gram_ops_all, double* jaccard,
