@@ -130,18 +130,17 @@ def main():
         kern = pa.ada_profile_collect()
         pa.ada_profile_enable(False)
         avg_us = {k: (1e3 * v["ms"] / v["launches"] if v["launches"] else None) for k, v in kern.items()}
-        cross_s = 1e-6 * avg_us["gram_cross"]
-        # algorithmic bytes of one cross-Gram launch: every row of X once (the T-r tested rows streamed, the r
-        # inherited rows as the resident operand) = T*d*e bytes; O(T) outputs neglected
-        cross_bytes = T * d * esz
-        r_valid_mean = r_prev_mean   # upper estimate of r_valid for the flop count
-        cross_flops = 2.0 * d * (T - r_prev_mean) * r_valid_mean
-        result["roofline"] = {"bound": "hbm", "kernel": "k_gram (cross-Gram, cascade steps 6-9)",
-                              "achieved": cross_bytes / cross_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": cross_bytes / cross_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
-                              "avg_launch_us": avg_us["gram_cross"], "bytes_per_launch": cross_bytes,
-                              "mfma_tflops": cross_flops / cross_s / 1e12,
-                              "mfma_frac": cross_flops / cross_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        casc_s = 1e-6 * avg_us["cascade_fused"]
+        # algorithmic bytes of one cascade launch: every row of X once (all T rows are tested rows, the r inherited
+        # rows are also the resident operand) = T*d*e bytes; the O(T*r/8) hit words and O(T) outputs are neglected
+        casc_bytes = T * d * esz
+        casc_flops = 2.0 * d * T * r_prev_mean            # T x r Gram entries of eq. (6), 2d flops each
+        result["roofline"] = {"bound": "hbm", "kernel": "k_cascade_fused (Algorithm 1 in one launch)",
+                              "achieved": casc_bytes / casc_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": casc_bytes / casc_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                              "avg_launch_us": avg_us["cascade_fused"], "bytes_per_launch": casc_bytes,
+                              "mfma_tflops": casc_flops / casc_s / 1e12,
+                              "mfma_frac": casc_flops / casc_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
         result["kernel_avg_us"] = avg_us
         result["ms_per_step_with_events"] = 1e3 * prof_elapsed / args.steps
 

@@ -50,6 +50,10 @@ typedef enum {
                                           representatives s < t (the form the proof of the superset
                                           proposition uses) instead of all of them (Algorithm 1, step 8) */
 
+#define ADA_FLAG_TWO_PASS 2u           /* cascade: run the r x r Gram and the cross-Gram as separate launches instead of
+                                          the one-launch form.  Sets, counts and gram_ops are identical; only the optional
+                                          gamma output differs (see ada_cascade_step) */
+
 #define ADA_MAX_T (1 << 20)
 
 /* Human-readable name of a status code (static storage). */
@@ -57,6 +61,13 @@ const char* ada_status_string(int status);
 
 /* Bytes of device workspace a call with this T needs (256-byte aligned base required). */
 size_t ada_workspace_bytes(int T);
+
+/*
+ * Zero-fills a workspace (one small kernel on the stream).  A workspace must be zero-filled once, by this call or
+ * by any memset, before its first use; every library call leaves it ready for the next one.  If a call is
+ * abandoned part-way (device error), initialise it again.
+ */
+int ada_workspace_init(void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Full ("independent") selection -- Definition "Gram threshold" (Section 2.2):
@@ -93,7 +104,12 @@ int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float ta
  *                       ADA_ERR_SHAPE for a bad prev_idx / r_dev, in which case the sizes are 0
  *   gram_ops [1] uint64 r^2 + (T-r) * r_valid Gram entries (eq. (6) counts T*r, which is the same
  *                       when nothing is removed; one operation = one Gram entry as in Table 6)  (may be NULL)
- *   gamma    [T] float  gamma^rep for inherited tokens, gamma^cross for the others               (may be NULL)
+ *   gamma    [T] float  (may be NULL) for an inherited token gamma^rep; for any other token the largest |cosine|
+ *                       against ALL inherited representatives (>= gamma^cross, equal to it unless the nearest one was
+ *                       removed) -- the one-launch form decides validity after the products.  With ADA_FLAG_TWO_PASS
+ *                       it is the exact gamma^cross of step 8.  (With ADA_FLAG_CROSS_EARLIER_ONLY only earlier
+ *                       representatives enter either maximum.)
+ * The one-launch form is used for T <= 16384; larger T always takes the two-launch form.
  */
 int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float tau,
                      const int32_t* prev_idx, int r, const int32_t* r_dev,
@@ -139,7 +155,7 @@ int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* 
  * kernel, so these figures are upper bounds of the durations a kernel trace reports.
  */
 enum { ADA_K_NORM_PREP = 0, ADA_K_GRAM_FULL = 1, ADA_K_GRAM_REP = 2, ADA_K_GRAM_CROSS = 3, ADA_K_UPDATE = 4,
-       ADA_K_COUNT = 5 };
+       ADA_K_CASCADE_FUSED = 5, ADA_K_COUNT = 6 };
 int ada_profile_enable(int on);
 int ada_profile_collect(double* ms_sum, int* launches);
 

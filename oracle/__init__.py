@@ -55,7 +55,7 @@ def _load():
         lib.ada_oracle_gamma_full_rows.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_ip, ctypes.c_int, c_dp]
         lib.ada_oracle_cascade_step.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, c_ip,
                                                 ctypes.c_int, ctypes.c_uint, c_i8p, c_ip, c_ip, c_ip, c_ip,
-                                                c_u64p, c_dp]
+                                                c_u64p, c_dp, c_dp]
         _lib = lib
     return _lib
 
@@ -126,7 +126,7 @@ def gamma_full_rows(X, rows) -> np.ndarray:
 
 
 def cascade_step(X, tau: float, prev_idx, flags: int = 0, force: Optional[Sequence[int]] = None):
-    """Algorithm 1.  Returns dict(idx, adds, removes, r_new, gram_ops, gamma)."""
+    """Algorithm 1.  Returns dict(idx, adds, removes, r_new, gram_ops, gamma, gamma_all)."""
     X = _as_f64(X)
     T, d = X.shape
     prev = np.ascontiguousarray(np.asarray(prev_idx, dtype=np.int32))
@@ -137,11 +137,13 @@ def cascade_step(X, tau: float, prev_idx, flags: int = 0, force: Optional[Sequen
     counts = np.zeros(3, dtype=np.int32)
     ops = ctypes.c_uint64(0)
     gamma = np.zeros(T, dtype=np.float64)
+    gamma_all = np.zeros(T, dtype=np.float64)
     f = None if force is None else np.ascontiguousarray(np.asarray(force, dtype=np.int8))
     _check(_load().ada_oracle_cascade_step(_p(X, ctypes.c_double), T, d, float(tau), _p(prev, ctypes.c_int32), r,
                                            int(flags), _p(f, ctypes.c_int8), _p(idx, ctypes.c_int32),
                                            _p(adds, ctypes.c_int32), _p(removes, ctypes.c_int32),
                                            _p(counts, ctypes.c_int32), ctypes.byref(ops),
-                                           _p(gamma, ctypes.c_double)), "cascade_step")
+                                           _p(gamma, ctypes.c_double), _p(gamma_all, ctypes.c_double)),
+           "cascade_step")
     return dict(idx=idx[:counts[0]].copy(), adds=adds[:counts[1]].copy(), removes=removes[:counts[2]].copy(),
-                r_new=int(counts[0]), gram_ops=int(ops.value), gamma=gamma)
+                r_new=int(counts[0]), gram_ops=int(ops.value), gamma=gamma, gamma_all=gamma_all)

@@ -186,10 +186,14 @@ int ada_oracle_gamma_full_rows(const double* X, int T, int d, const int32_t* row
  * Outputs (caller-allocated): idx[T] ascending R^(l+1); adds[T]; removes[r];
  *   counts[3] = {|R^(l+1)|, |adds|, |removes|}; gram_ops (reading R6);
  *   gamma[T] (optional): gamma^rep for inherited tokens, gamma^cross for the others.
+ *   gamma_all[T] (optional): as gamma, but for a non-inherited token the max runs over ALL inherited
+ *   representatives instead of the valid ones only (an auxiliary quantity: the cross-Gram row maximum before step 5's
+ *   validity is applied; it never enters a decision).
  */
 int ada_oracle_cascade_step(const double* X, int T, int d, double tau, const int32_t* prev_idx, int r,
                             unsigned flags, const int8_t* force, int32_t* idx, int32_t* adds,
-                            int32_t* removes, int32_t* counts, uint64_t* gram_ops, double* gamma) {
+                            int32_t* removes, int32_t* counts, uint64_t* gram_ops, double* gamma,
+                            double* gamma_all) {
     if (!X || !prev_idx || !idx || !adds || !removes || !counts || T < 1 || d < 1) return ADA_ORACLE_ERR_ARG;
     if (!(tau > 0.0 && tau < 1.0)) return ADA_ORACLE_ERR_ARG;
     if (r < 1 || r > T) return ADA_ORACLE_ERR_ARG;
@@ -202,11 +206,12 @@ int ada_oracle_cascade_step(const double* X, int T, int d, double tau, const int
 
     double* Xhat = (double*)malloc((size_t)T * d * sizeof(double));
     double* g = (double*)calloc((size_t)T, sizeof(double));
+    double* g_all = (double*)calloc((size_t)T, sizeof(double));
     uint8_t* inherited = (uint8_t*)calloc((size_t)T, 1);
     uint8_t* valid = (uint8_t*)calloc((size_t)r, 1);
     uint8_t* is_new = (uint8_t*)calloc((size_t)T, 1);
-    if (!Xhat || !g || !inherited || !valid || !is_new) {
-        free(Xhat); free(g); free(inherited); free(valid); free(is_new);
+    if (!Xhat || !g || !g_all || !inherited || !valid || !is_new) {
+        free(Xhat); free(g); free(g_all); free(inherited); free(valid); free(is_new);
         return ADA_ORACLE_ERR_NOMEM;
     }
 
@@ -224,6 +229,7 @@ int ada_oracle_cascade_step(const double* X, int T, int d, double tau, const int
             if (c > m) m = c;
         }
         g[prev_idx[j]] = m;
+        g_all[prev_idx[j]] = m;
     }
     /* step 5: R_valid */
     int r_valid = 0;
@@ -236,14 +242,16 @@ int ada_oracle_cascade_step(const double* X, int T, int d, double tau, const int
 #pragma omp parallel for schedule(dynamic, 8)
     for (int t = 0; t < T; ++t) {
         if (inherited[t]) continue;
-        double m = 0.0;
+        double m = 0.0, m_all = 0.0;
         for (int j = 0; j < r; ++j) {
-            if (!valid[j]) continue;
             if (earlier_only && prev_idx[j] >= t) continue;
             double c = fabs(gram_entry(Xhat, d, t, prev_idx[j]));
+            if (c > m_all) m_all = c;               /* auxiliary: before validity */
+            if (!valid[j]) continue;
             if (c > m) m = c;
         }
         g[t] = m;
+        g_all[t] = m_all;
     }
     /* step 9: R_new */
     for (int t = 0; t < T; ++t)
@@ -264,7 +272,8 @@ int ada_oracle_cascade_step(const double* X, int T, int d, double tau, const int
     /* reading R6: entries Algorithm 1 forms -- r x r among the inherited, (T-r) x r_valid across */
     if (gram_ops) *gram_ops = (uint64_t)r * (uint64_t)r + (uint64_t)(T - r) * (uint64_t)r_valid;
     if (gamma) memcpy(gamma, g, (size_t)T * sizeof(double));
+    if (gamma_all) memcpy(gamma_all, g_all, (size_t)T * sizeof(double));
 
-    free(Xhat); free(g); free(inherited); free(valid); free(is_new);
+    free(Xhat); free(g); free(g_all); free(inherited); free(valid); free(is_new);
     return ADA_ORACLE_OK;
 }

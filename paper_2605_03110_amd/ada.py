@@ -20,13 +20,14 @@ SOURCES = ("ada_kernels.hip",)
 
 ADA_F32, ADA_BF16 = 0, 1
 FLAG_CROSS_EARLIER_ONLY = 1
+FLAG_TWO_PASS = 2
 OK = 0
 
-SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_select_full", "ada_cascade_step",
+SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
            "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect")
 
-KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update")
+KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused")
 
 
 class AdaError(RuntimeError):
@@ -67,6 +68,8 @@ def lib():
         L.ada_status_string.argtypes = [i32]
         L.ada_workspace_bytes.restype = sz
         L.ada_workspace_bytes.argtypes = [i32]
+        L.ada_workspace_init.restype = i32
+        L.ada_workspace_init.argtypes = [vp, sz, vp]
         L.ada_select_full.restype = i32
         L.ada_select_full.argtypes = [vp, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp, sz, vp, u32]
         L.ada_cascade_step.restype = i32
@@ -96,7 +99,14 @@ def workspace_bytes(T: int) -> int:
 
 
 def workspace(T: int, device="cuda") -> torch.Tensor:
-    return torch.empty(workspace_bytes(T), dtype=torch.uint8, device=device)
+    """A zero-filled workspace (the library needs it zeroed before first use and keeps it ready afterwards)."""
+    return torch.zeros(workspace_bytes(T), dtype=torch.uint8, device=device)
+
+
+def ada_workspace_init(ws: torch.Tensor, *, stream=None) -> None:
+    rc = lib().ada_workspace_init(_ptr(ws), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise AdaError(rc, "ada_workspace_init")
 
 
 def _dtype_code(X: torch.Tensor) -> int:

@@ -1,0 +1,489 @@
+// Fused cascade step (Algorithm 1) in ONE launch.  Included by ada_kernels.hip inside its anonymous namespace.
+//
+// Work: every token t (tested, MFMA N side) against every inherited representative s (MFMA M side): the T x r
+// entries eq. (6) counts.  A workgroup owns a 64 x 64 tile over all of K and, per tile,
+//   * streams the 128 rows through LDS once, accumulating the raw dot products on MFMA and, from the same
+//     registers, each row's sum of squares (Algorithm 1 step 1 costs no extra pass over X);
+//   * turns the accumulators into cosines and records, per tested token, one 32-bit word of "hits"
+//     (|cos| >= 1 - tau^2) per 32 representatives.  For an inherited token only earlier representatives count
+//     (steps 3-4); for any other token all of them do (steps 7-8), or only earlier ones with the earlier-only flag.
+// Validity of a representative (step 5) is "no hit in its own row"; a non-inherited token is new (step 9) iff it has
+// no hit on a VALID representative.  Both are resolved from the hit words by the workgroup that finishes last
+// (ticket counter, no waiting), which also compacts R_valid u R_new (step 10) and writes the counts.
+// Deferring validity this way lets the r x r and the (T-r) x r products run as one batch of tiles.
+//
+// K is split over KG groups of 4 wavefronts (chunk c goes to group c % KG); inside a group each wavefront takes one
+// 16-element k-step of the chunk for the whole tile.  Partial tiles are summed through LDS in a fixed order.
+
+#ifdef ADA_PHASE_CLOCKS
+__device__ unsigned long long g_phase_clk[64];
+#define ADA_CLK(i) do { if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) g_phase_clk[i] = clock64(); } while (0)
+#define ADA_CLK_LAST(i) do { if (threadIdx.x == 0) g_phase_clk[i] = clock64(); } while (0)
+#else
+#define ADA_CLK(i) do { } while (0)
+#define ADA_CLK_LAST(i) do { } while (0)
+#endif
+
+struct FusedParams {
+    const void* X;
+    long long ld;
+    int T, d;
+    const int32_t* prev_idx;
+    const int32_t* r_dev;    // optional device count
+    int r_host;              // count, or capacity of prev_idx when r_dev is given
+    float thr;
+    int earlier_only;
+    uint32_t* hits;          // [W][T] word-major: word w of token t covers inherited representatives 32w .. 32w+31
+    int W;                   // hit words per token (covers r_host)
+    float* gamma;            // optional, zero on entry: max |cos| over the columns that count for the token
+    int32_t* ticket;         // zero on entry, zero again on exit
+    int32_t* idx;
+    int32_t* adds;           // may be NULL
+    int32_t* removes;        // may be NULL
+    int32_t* counts;         // [4]
+    unsigned long long* gram_ops;   // may be NULL
+};
+
+template <int KG> struct FusedGeom {
+    static constexpr int THREADS = 256 * KG;
+    static constexpr int D = 4;                           // prefetch depth (steps of one group), even
+    static constexpr int LPT = 4;                         // 16-byte pieces per thread per chunk
+    static constexpr int STAGE = 128 * 128;               // one chunk of 128 rows
+    static constexpr int OFF_STOK = 0;                    // int[64]   token id of each "against" row (INT_MAX: none)
+    static constexpr int OFF_REPF = 256;                  // int[64]   tested token is inherited
+    static constexpr int OFF_SS = 512;                    // float[KG][128] partial sums of squares
+    static constexpr int OFF_SCALE = OFF_SS + KG * 512;   // float[128] 1/norm (0 for rows that do not exist)
+    static constexpr int OFF_SCAN = OFF_SCALE + 512;      // int[3][32] scan scratch of the update phase
+    static constexpr int META = OFF_SCAN + 512;
+    static constexpr int BODY = 65536;                    // stages (KG * 2 * 16 KB) / reduction scratch / valid mask
+    static constexpr int LDS = META + BODY;
+};
+
+template <typename In> __device__ inline float piece_sumsq_fast(u32x4 v);
+template <> __device__ inline float piece_sumsq_fast<float>(u32x4 v) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { const float f = __uint_as_float(v[i]); s = fmaf(f, f, s); }
+    return s;
+}
+template <> __device__ inline float piece_sumsq_fast<uint16_t>(u32x4 v) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    // two exact bf16 products added in fp32 per instruction; the four words are named one by one on purpose
+    const uint32_t w0 = v[0], w1 = v[1], w2 = v[2], w3 = v[3];
+    const bf16x2 x0 = __builtin_bit_cast(bf16x2, w0), x1 = __builtin_bit_cast(bf16x2, w1);
+    const bf16x2 x2 = __builtin_bit_cast(bf16x2, w2), x3 = __builtin_bit_cast(bf16x2, w3);
+    float s = __builtin_amdgcn_fdot2_f32_bf16(x0, x0, 0.f, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(x1, x1, s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(x2, x2, s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(x3, x3, s, false);
+    return s;
+}
+
+template <typename In, bool ALIGNED, int KG>
+__device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, int sb, char* lds) {
+    using G = FusedGeom<KG>;
+    constexpr int B = 64;
+    constexpr int EPP = 16 / (int)sizeof(In);
+    constexpr int EPC = 8 * EPP;
+    constexpr int LPT = G::LPT, D = G::D, NB = 2;
+
+    int* s_tok = reinterpret_cast<int*>(lds + G::OFF_STOK);
+    int* repf = reinterpret_cast<int*>(lds + G::OFF_REPF);
+    float* ssq = reinterpret_cast<float*>(lds + G::OFF_SS);
+    float* scale = reinterpret_cast<float*>(lds + G::OFF_SCALE);
+    char* body = lds + G::META;
+
+    const int tid = threadIdx.x, t256 = tid & 255;
+    // wave-uniform values are pinned to scalar registers so that code selected by them branches, not predicates
+    const int g = __builtin_amdgcn_readfirstlane(tid >> 8);
+    const int wave = __builtin_amdgcn_readfirstlane(t256 >> 6);
+    const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    char* buf0 = body + g * 2 * G::STAGE;
+    char* buf1 = buf0 + G::STAGE;
+    const In* X = reinterpret_cast<const In*>(p.X);
+
+    ADA_CLK(1);
+    if (tid < B) {
+        const int li = s0 + tid;
+        const bool ok = li < r;
+        int tok = p.prev_idx[ok ? li : r - 1];
+        tok = min(max(tok, 0), p.T - 1);
+        s_tok[tid] = ok ? tok : INT_MAX;
+        repf[tid] = 0;
+    }
+    __syncthreads();
+    for (int j = tid; j < r; j += G::THREADS) {          // which tested tokens of this tile are inherited
+        const unsigned q = (unsigned)(p.prev_idx[j] - t0);
+        if (q < (unsigned)B) repf[q] = 1;
+    }
+
+    const int pc = t256 & 7, rb = t256 >> 3;
+    const In* rowp[LPT];
+    int woff[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int row = rb + 32 * j;                     // rows 0..63: representatives, 64..127: tested tokens
+        int tok;
+        if (row < B) {
+            const int li = s0 + row;
+            tok = p.prev_idx[li < r ? li : r - 1];
+            tok = min(max(tok, 0), p.T - 1);
+        } else {
+            tok = min(t0 + row - B, p.T - 1);
+        }
+        rowp[j] = X + (size_t)tok * (size_t)p.ld;
+        woff[j] = lds_off(row, pc);
+    }
+
+    const int nk = (p.d + EPC - 1) / EPC;
+    const int nsteps = (nk + KG - 1) / KG;               // steps of this group; step k handles chunk k * KG + g
+    u32x4 pre[D][LPT];
+    u32x4 fa[2][NB], fb[2][NB];
+    f32x16 acc[NB][NB];
+    float ss[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) ss[j] = 0.f;
+#pragma unroll
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    auto fetch = [&](int set, int k) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j)
+            pre[set][j] = fetch_piece<In, ALIGNED>(rowp[j], (k * KG + g) * EPC + pc * EPP, p.d);
+    };
+    auto store = [&](char* stage, int set, int k) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            const u32x4 v = finish_piece<ALIGNED>(pre[set][j], (k * KG + g) * EPC + pc * EPP, p.d);
+            *reinterpret_cast<u32x4*>(stage + woff[j]) = v;
+            ss[j] += piece_sumsq_fast<In>(v);            // Section 2.1: ||x||^2 from the registers already in hand
+        }
+    };
+    auto read_frags = [&](const char* stage, int f) {
+        const int piece = 2 * wave + half;               // this wave's k-step of the chunk
+#pragma unroll
+        for (int a = 0; a < NB; ++a) fa[f][a] = *reinterpret_cast<const u32x4*>(stage + lds_off(a * 32 + l32, piece));
+#pragma unroll
+        for (int b = 0; b < NB; ++b) fb[f][b] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + b * 32 + l32, piece));
+    };
+    auto mma = [&](int f) {
+#pragma unroll
+        for (int a = 0; a < NB; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) Mfma<In>::run(acc[a][b], fa[f][a], fb[f][b]);
+    };
+
+    // software pipeline: see gram_tile; steps past the end handle all-zero chunks
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+        fetch(s, s);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    store(buf0, 0, 0);
+    fetch(0, D);
+    __builtin_amdgcn_sched_barrier(0);
+    store(buf1, 1, 1);
+    fetch(1, D + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    ADA_CLK(2);
+    __syncthreads();
+    ADA_CLK(3);
+    read_frags(buf0, 0);
+    for (int k0 = 0; k0 < nsteps; k0 += D) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) {
+            const int k = k0 + s;
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            read_frags((s & 1) ? buf0 : buf1, (s + 1) & 1);
+            store((s & 1) ? buf1 : buf0, (s + 2) % D, k + 2);
+            fetch((s + 2) % D, k + 2 + D);
+            mma(s & 1);
+        }
+    }
+
+    ADA_CLK(4);
+    // ---- norms: 8 consecutive lanes staged one row
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        float v = ss[j];
+        v += __shfl_xor(v, 1, 64);
+        v += __shfl_xor(v, 2, 64);
+        v += __shfl_xor(v, 4, 64);
+        ss[j] = v;
+    }
+    __syncthreads();                                      // every wave is done with the stages
+    ADA_CLK(16);
+    if (pc == 0) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) ssq[g * 128 + rb + 32 * j] = ss[j];
+    }
+    // partial tiles travel through LDS as 16-byte vectors: slot ((wave * 4 + block) * 4 + q) * 64 + lane holds
+    // accumulator registers 4q .. 4q+3 of that block (consecutive lanes, consecutive 16 bytes: conflict-free)
+    f32x4* red = reinterpret_cast<f32x4*>(body);
+    auto put = [&](int slot_wave) {
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x16& v = acc[blk >> 1][blk & 1];
+                red[((slot_wave * 4 + blk) * 4 + q) * 64 + lane] = f32x4{v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
+            }
+    };
+    if (KG == 2 && g == 1) put(wave);
+    __syncthreads();
+    ADA_CLK(17);
+    if (tid < 2 * B) {
+        float tot = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < KG; ++gg) tot += ssq[gg * 128 + tid];
+        float sc = tot > 0.f ? 1.0f / sqrtf(tot) : 0.f;   // a zero row normalises to zero: all its cosines are 0
+        if (tid < B ? (s_tok[tid] == INT_MAX) : (t0 + tid - B >= p.T)) sc = 0.f;
+        scale[tid] = sc;
+    }
+    if (KG == 2 && g == 0) {
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 o = red[((wave * 4 + blk) * 4 + q) * 64 + lane];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[blk >> 1][blk & 1][4 * q + e] += o[e];
+            }
+    }
+    __syncthreads();
+    ADA_CLK(18);
+    if (g == 0) put(wave);                                // every wave publishes all four blocks, its own included
+    __syncthreads();
+    ADA_CLK(19);
+    if (g == 0) {
+        // wave w finishes block (a, b) = (w >> 1, w & 1): sum the four k-step partials in wave order
+        const int a = wave >> 1, b = wave & 1;
+        const int nl = b * 32 + l32;
+        const int t = t0 + nl;
+        f32x4 part[4][4];
+#pragma unroll
+        for (int src = 0; src < 4; ++src)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) part[src][q] = red[((src * 4 + wave) * 4 + q) * 64 + lane];
+        // accumulator register 4q+e of a 32x32 MFMA block is row 8q + 4*half + e: four consecutive rows per q
+        f32x4 sc4[4];
+        i32x4 tk4[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            sc4[q] = *reinterpret_cast<const f32x4*>(scale + a * 32 + 8 * q + 4 * half);
+            tk4[q] = *reinterpret_cast<const i32x4*>(s_tok + a * 32 + 8 * q + 4 * half);
+        }
+        const float tsc = scale[B + nl];
+        const bool ordered = repf[nl] != 0 || p.earlier_only;   // only earlier representatives count
+        uint32_t bits = 0u;
+        float m = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = ((part[0][q][e] + part[1][q][e]) + part[2][q][e]) + part[3][q][e];
+                float c = (fabsf(v) * sc4[q][e]) * tsc;
+                if (ordered && !(tk4[q][e] < t)) c = 0.f;
+                if (c >= p.thr) bits |= 1u << (8 * q + 4 * half + e);
+                m = fmaxf(m, c);
+            }
+        bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        if (half == 0 && t < p.T) {
+            p.hits[(size_t)(sb * 2 + a) * p.T + t] = bits;        // word-major: 32 lanes store 32 consecutive words
+            if (p.gamma && m > 0.f) atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
+        }
+    }
+    ADA_CLK(5);
+}
+
+// exclusive prefix sum of one 64-bit value per thread over the workgroup (three 21-bit counters ride in one scan)
+__device__ inline unsigned long long block_exclusive_scan64(unsigned long long v, unsigned long long* total,
+                                                            unsigned long long* wave_tot /* >= 17 words of LDS */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    unsigned long long inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned lo = __shfl_up((unsigned)inc, o, 64), hi = __shfl_up((unsigned)(inc >> 32), o, 64);
+        if (lane >= o) inc += ((unsigned long long)hi << 32) | lo;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long run = 0;
+        for (int w = 0; w < nw; ++w) { const unsigned long long t = wave_tot[w]; wave_tot[w] = run; run += t; }
+        wave_tot[16] = run;
+    }
+    __syncthreads();
+    *total = wave_tot[16];
+    return wave_tot[wave] + inc - v;
+}
+
+// Algorithm 1 steps 5, 9, 10 and the bookkeeping, from the hit words (run by one workgroup).
+// Per-token state lives in LDS (T <= FUSED_MAX_T bytes): bit 0 = inherited, bit 1 = kept.  The hit table is
+// word-major (hits[w * T + t]), so a thread that owns token t reads its words with loads that are coalesced across
+// the workgroup, independent of each other and branch-free (indices are clamped, results masked): a whole batch is
+// in flight before the first use.
+template <int THREADS>
+__device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, char* lds, int* scan_scratch) {
+    constexpr int TU = 4, WU = 15;                      // tokens x words fetched per batch by one thread (< 64 loads)
+    const int tid = threadIdx.x;
+    const int T = p.T;
+    uint8_t* flag = reinterpret_cast<uint8_t*>(lds);                         // [T]
+    uint32_t* vmask = reinterpret_cast<uint32_t*>(lds + FUSED_MAX_T);        // one bit per inherited representative: valid
+    const int Wa = r_ok ? (r + 31) >> 5 : 0;            // hit words in use per token
+    for (int t = tid; t < T; t += THREADS) flag[t] = 2;                      // not inherited, kept unless covered
+    for (int w = tid; w < Wa; w += THREADS) vmask[w] = 0u;
+    __syncthreads();
+    ADA_CLK_LAST(10);
+    // step 5: an inherited representative with a hit from an earlier inherited one is removed.  The list is checked
+    // on the way (strictly ascending token ids in range); token ids are clamped so that a bad list cannot fault.
+    int ok = 1;
+    if (r_ok) {
+        for (int jb = tid; jb < r; jb += THREADS * TU) {
+            int tok[TU];
+            uint32_t any[TU];
+#pragma unroll
+            for (int u = 0; u < TU; ++u) {
+                const int j = min(jb + u * THREADS, r - 1);
+                const int q = p.prev_idx[j], qp = p.prev_idx[max(j - 1, 0)];
+                if (q < 0 || q >= T || (j > 0 && !(qp < q))) ok = 0;
+                tok[u] = min(max(q, 0), T - 1);
+                any[u] = 0u;
+            }
+            for (int w0 = 0; w0 < Wa; w0 += WU) {
+                uint32_t x[TU][WU];
+#pragma unroll
+                for (int u = 0; u < TU; ++u)
+#pragma unroll
+                    for (int v = 0; v < WU; ++v) x[u][v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + tok[u]];
+#pragma unroll
+                for (int u = 0; u < TU; ++u)
+#pragma unroll
+                    for (int v = 0; v < WU; ++v) any[u] |= (w0 + v < Wa) ? x[u][v] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < TU; ++u)
+                if (jb + u * THREADS < r) flag[tok[u]] = any[u] ? 1 : 3;
+        }
+    }
+    ok = __syncthreads_and(ok);
+    const int status = !r_ok ? ADA_ERR_SHAPE : (!ok ? ADA_ERR_INDEX : ADA_OK);
+    if (status != ADA_OK) {
+        if (tid == 0) {
+            p.counts[0] = 0; p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = status;
+            if (p.gram_ops) *p.gram_ops = 0ull;
+            *p.ticket = 0;
+        }
+        return;
+    }
+    ADA_CLK_LAST(11);
+    for (int j = tid; j < r; j += THREADS)
+        if (flag[p.prev_idx[j]] == 3) atomicOr(&vmask[j >> 5], 1u << (j & 31));
+    __syncthreads();
+    ADA_CLK_LAST(12);
+    // step 9: any other token with a hit on a VALID representative is covered
+    for (int tb = tid; tb < T; tb += THREADS * TU) {
+        uint32_t any[TU];
+#pragma unroll
+        for (int u = 0; u < TU; ++u) any[u] = 0u;
+        for (int w0 = 0; w0 < Wa; w0 += WU) {
+            uint32_t x[TU][WU];
+#pragma unroll
+            for (int u = 0; u < TU; ++u)
+#pragma unroll
+                for (int v = 0; v < WU; ++v)
+                    x[u][v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + min(tb + u * THREADS, T - 1)];
+#pragma unroll
+            for (int v = 0; v < WU; ++v) {
+                const uint32_t vm = (w0 + v < Wa) ? vmask[w0 + v] : 0u;
+#pragma unroll
+                for (int u = 0; u < TU; ++u) any[u] |= x[u][v] & vm;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < TU; ++u) {
+            const int t = tb + u * THREADS;
+            if (t < T && flag[t] == 2 && any[u]) flag[t] = 0;
+        }
+    }
+    __syncthreads();
+    ADA_CLK_LAST(13);
+    const int chunk = (T + THREADS - 1) / THREADS;
+    const int lo = min(T, tid * chunk), hi = min(T, lo + chunk);
+    unsigned long long c = 0;                            // kept | added << 21 | removed << 42
+    for (int t = lo; t < hi; ++t) {
+        const unsigned f = flag[t];
+        c += (unsigned long long)((f >> 1) & 1u) | ((unsigned long long)(f == 2u) << 21) |
+             ((unsigned long long)(f == 1u) << 42);
+    }
+    unsigned long long tot;
+    const unsigned long long o = block_exclusive_scan64(c, &tot, reinterpret_cast<unsigned long long*>(scan_scratch));
+    int o_idx = (int)(o & 0x1FFFFF), o_add = (int)((o >> 21) & 0x1FFFFF), o_rem = (int)((o >> 42) & 0x1FFFFF);
+    const int n_idx = (int)(tot & 0x1FFFFF), n_add = (int)((tot >> 21) & 0x1FFFFF), n_rem = (int)((tot >> 42) & 0x1FFFFF);
+    ADA_CLK_LAST(14);
+    for (int t = lo; t < hi; ++t) {                     // step 10
+        const int f = flag[t];
+        if (f & 2) p.idx[o_idx++] = t;
+        if (f == 2) { if (p.adds) p.adds[o_add] = t; ++o_add; }
+        if (f == 1) { if (p.removes) p.removes[o_rem] = t; ++o_rem; }
+    }
+    if (tid == 0) {
+        p.counts[0] = n_idx; p.counts[1] = n_add; p.counts[2] = n_rem; p.counts[3] = ADA_OK;
+        if (p.gram_ops) {
+            const unsigned long long TT = (unsigned long long)T, rr = (unsigned long long)r;
+            *p.gram_ops = rr * rr + (TT - rr) * (unsigned long long)(r - n_rem);   // entries Algorithm 1 needs
+        }
+        *p.ticket = 0;                                    // leave the workspace ready for the next call
+    }
+}
+
+// Grid: a multiple of 8 workgroups (see k_gram for the XCD-aware tile ranges); tiles with the representative
+// block fastest, so one XCD's L2 serves a contiguous range of tested rows.
+template <typename In, bool ALIGNED, int KG>
+__global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
+    extern __shared__ __align__(16) char lds[];
+    using G = FusedGeom<KG>;
+    __shared__ int s_last;
+    ADA_CLK(0);
+    const int r = p.r_dev ? *p.r_dev : p.r_host;
+    const bool r_ok = r >= 1 && r <= p.r_host && r <= p.T;
+    bool worked = false;
+    if (r_ok) {
+        const long long nbS = (r + 63) / 64, nbT = (p.T + 63) / 64;
+        const long long ntiles = nbS * nbT;
+        const long long per = (ntiles + 7) / 8;
+        const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
+        for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
+            const long long tile = xcd * per + slot;
+            if (tile >= ntiles) break;
+            const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
+            fused_tile<In, ALIGNED, KG>(p, r, sb * 64, tb * 64, sb, lds);
+            worked = true;
+            __syncthreads();
+        }
+    }
+    // The workgroup that takes the last ticket finishes the step.  A workgroup that stored hit words makes them
+    // visible device-wide first: every thread waits for its own stores, then ONE thread issues the release (an L2
+    // write-back is a per-cache operation, so one per workgroup is enough and thousands would serialise).
+    ADA_CLK(6);
+    if (worked) __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this thread's stores have left the CU
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (worked) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        s_last = (atomicAdd(p.ticket, 1) == (int)gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    ADA_CLK(7);
+    if (!s_last) return;
+    ADA_CLK_LAST(8);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");       // see the other workgroups' hit words, not stale lines
+    ADA_CLK_LAST(9);
+    fused_update<G::THREADS>(p, r, r_ok, lds + G::META, reinterpret_cast<int*>(lds + G::OFF_SCAN));
+    ADA_CLK_LAST(15);
+}

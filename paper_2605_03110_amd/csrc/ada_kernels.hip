@@ -32,23 +32,32 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 enum { MODE_FULL = 0, MODE_REP = 1, MODE_CROSS = 2 };
-enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_WORDS = 8 };
+enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_TICKET = 4, META_WORDS = 8 };
+
+// The one-launch cascade step keeps one hit word per token and per 32 inherited representatives; beyond this T
+// the table would dominate the workspace and the two-launch path is used instead.
+constexpr int FUSED_MAX_T = 16384;
 
 struct Workspace {
     float* inv_norm;     // [T]
     float* gamma;        // [T]
     int32_t* nonrep_idx; // [T]
     uint8_t* is_rep;     // [T]
-    int32_t* meta;       // [META_WORDS]
+    int32_t* meta;       // [META_WORDS]; meta[META_TICKET] is zero between calls
+    uint32_t* hits;      // [T][hit_words(T)] (only for T <= FUSED_MAX_T)
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int hit_words(int r_cap) { return 2 * ((r_cap + 63) / 64); }
 
 inline size_t ws_bytes_for(int T) {
     size_t t4 = align_up((size_t)T * 4, 256), t1 = align_up((size_t)T, 256);
-    return t4 * 3 + t1 + 256;
+    size_t hits = T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0;
+    return t4 * 3 + t1 + 256 + hits;
 }
 
 inline Workspace carve(void* ws, int T) {
@@ -59,7 +68,8 @@ inline Workspace carve(void* ws, int T) {
     w.gamma = (float*)p; p += t4;
     w.nonrep_idx = (int32_t*)p; p += t4;
     w.is_rep = (uint8_t*)p; p += t1;
-    w.meta = (int32_t*)p;
+    w.meta = (int32_t*)p; p += 256;
+    w.hits = (uint32_t*)p;
     return w;
 }
 
@@ -302,7 +312,8 @@ __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, cons
     char* buf0 = lds + G::META;
     char* buf1 = buf0 + G::STAGE;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: code selected by it branches, not predicates
     const int l32 = lane & 31, half = lane >> 5;
     const In* X = reinterpret_cast<const In*>(p.X);
 
@@ -599,6 +610,12 @@ __global__ __launch_bounds__(1024) void k_overlap(const uint8_t* a, const uint8_
     if (threadIdx.x == 0) { out[0] = ti; out[1] = tu; }
 }
 
+__global__ __launch_bounds__(256) void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
+}
+
+#include "ada_fused.hpp"
+
 // ------------------------------------------------------------------------------------------------
 // host side
 
@@ -729,10 +746,70 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
     return launch_update(u, st);
 }
 
-// Algorithm 1.  Arguments checked by the caller; adds / removes / gram_ops / gamma may be NULL.
+hipError_t fill_u32(void* p, size_t n_words, uint32_t v, hipStream_t st) {
+    if (n_words == 0) return hipSuccess;
+    const unsigned grid = (unsigned)((n_words + 255) / 256 < 2048 ? (n_words + 255) / 256 : 2048);
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid), dim3(256), 0, st, (uint32_t*)p, n_words, v);
+    return hipGetLastError();
+}
+
+template <typename In, bool ALIGNED, int KG>
+hipError_t launch_fused(const FusedParams& p, hipStream_t st) {
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    constexpr int lds = FusedGeom<KG>::LDS;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cascade_fused<In, ALIGNED, KG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    long long tiles = (long long)((p.r_host + 63) / 64) * ((p.T + 63) / 64);
+    // Workgroups loop over tiles, so any grid is correct.  With the set size known only on the device the bound
+    // r_host = T would launch mostly idle workgroups, and dispatching those is not free: cap at two per CU.
+    const long long cap = p.r_dev ? 512 : 2048;
+    if (tiles > cap) tiles = cap;
+    const unsigned grid = (unsigned)(tiles + 7) / 8 * 8;             // multiple of 8 (XCDs)
+    ProfScope ps(ADA_K_CASCADE_FUSED, st);
+    hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG>), dim3(grid), dim3(256 * KG), lds, st, p);
+    return hipGetLastError();
+}
+
+int kgroups_override() {
+    const char* e = getenv("ADA_KGROUPS");
+    if (!e) return 0;
+    const int v = atoi(e);
+    return (v == 1 || v == 2) ? v : 0;
+}
+
+// Algorithm 1 in one launch (ada_fused.hpp).  gamma, if given, receives for an inherited token gamma^rep and for any
+// other token the max over ALL inherited representatives (validity is resolved after the products).
+int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, float tau, const int32_t* prev_idx, int r,
+                      const int32_t* r_dev, int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
+                      uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st, unsigned flags) {
+    const Workspace w = carve(ws, T);
+    if (gamma && fill_u32(gamma, (size_t)T, 0u, st) != hipSuccess) return ADA_ERR_DEVICE;
+    const FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
+                           (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
+                           w.meta + META_TICKET, idx, adds, removes, counts,
+                           reinterpret_cast<unsigned long long*>(gram_ops)};
+    int kg = 2;
+    if (int o = kgroups_override()) kg = o;
+    hipError_t e = dispatch(dtype, X, ld, d, [&](auto v) {
+        using V = decltype(v);
+        return kg == 2 ? launch_fused<typename V::In, V::aligned, 2>(p, st)
+                       : launch_fused<typename V::In, V::aligned, 1>(p, st);
+    });
+    return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+}
+
+// Algorithm 1 in separate launches (norms + lists, r x r Gram, cross-Gram against the valid representatives, update):
+// gamma holds the exact gamma^cross of step 8.  Arguments checked by the caller; adds / removes / gram_ops / gamma may be NULL.
 int run_cascade(const void* X, int T, int d, long long ld, int dtype, float tau, const int32_t* prev_idx, int r,
                 const int32_t* r_dev, int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
                 uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st, unsigned flags) {
+    if (!(flags & ADA_FLAG_TWO_PASS) && T <= FUSED_MAX_T)
+        return run_cascade_fused(X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops,
+                                 gamma, ws, st, flags);
     const Workspace w = carve(ws, T);
     float* g = gamma ? gamma : w.gamma;
     const float thr = threshold_of(tau);
@@ -783,6 +860,12 @@ const char* ada_status_string(int status) {
 }
 
 size_t ada_workspace_bytes(int T) { return (T < 1 || T > ADA_MAX_T) ? 0 : ws_bytes_for(T); }
+
+int ada_workspace_init(void* ws, size_t ws_bytes, void* stream) {
+    if (!ws) return ADA_ERR_NULL;
+    if (((uintptr_t)ws % 256) != 0 || ws_bytes % 4 != 0) return ADA_ERR_WORKSPACE;
+    return fill_u32(ws, ws_bytes / 4, 0u, (hipStream_t)stream) == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+}
 
 int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float tau, uint8_t* mask, int32_t* idx,
                     int32_t* count, float* gamma, void* ws, size_t ws_bytes, void* stream, unsigned flags) {
@@ -850,6 +933,12 @@ int ada_profile_collect(double* ms_sum, int* launches) {
     g_prof.clear();
     return rc;
 }
+
+#ifdef ADA_PHASE_CLOCKS
+int ada_debug_phase_clocks(unsigned long long* out) {   // development builds only
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_clk), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : 6;
+}
+#endif
 
 int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* gram_ops_all, double* jaccard,
                        double* turnover, double* savings) {

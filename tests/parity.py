@@ -40,8 +40,10 @@ def check_full(x_cpu, tau, got, what=""):
     return dict(ref=ref, gamma_err=err, n_band=int(band.sum()))
 
 
-def check_cascade(x_cpu, tau, prev_idx, got, flags=0, what=""):
-    """got: ada.fetch() of ada_cascade_step on the same prev_idx."""
+def check_cascade(x_cpu, tau, prev_idx, got, flags=0, what="", two_pass=False):
+    """got: ada.fetch() of ada_cascade_step on the same prev_idx.  two_pass says which gamma the call reports for
+    non-inherited tokens: the exact gamma^cross (two-launch form) or the row maximum over all inherited
+    representatives (one-launch form); decisions are checked the same way for both."""
     X = wl.as_f64(x_cpu)
     T = X.shape[0]
     prev_idx = np.asarray(prev_idx, dtype=np.int32)
@@ -56,7 +58,8 @@ def check_cascade(x_cpu, tau, prev_idx, got, flags=0, what=""):
             break
         force[band] = in_gpu[band]
         ref = oracle.cascade_step(X, tau, prev_idx, flags=flags, force=force)
-    err = float(np.max(np.abs(got["gamma"].astype(np.float64) - ref["gamma"])))
+    ref_gamma = ref["gamma"] if two_pass else ref["gamma_all"]
+    err = float(np.max(np.abs(got["gamma"].astype(np.float64) - ref_gamma)))
     assert err <= GAMMA_TOL, "%s gamma error %.3g" % (what, err)
     for k in ("idx", "adds", "removes"):
         assert np.array_equal(got[k], ref[k]), "%s %s differs: gpu %s... oracle %s..." % (

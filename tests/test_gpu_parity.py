@@ -26,7 +26,19 @@ def dev_idx(a):
     return torch.from_numpy(np.ascontiguousarray(np.asarray(a, dtype=np.int32))).to(DEV)
 
 
-def run_layers_teacher_forced(w, xs_cpu, flags=0, tile=None, what=""):
+def oflags(flags):
+    """library flags -> oracle flags (the oracle knows only the cross-step reading)"""
+    return oracle.CROSS_EARLIER_ONLY if flags & pa.FLAG_CROSS_EARLIER_ONLY else 0
+
+
+def step_and_check(x_dev, x_cpu, tau, prev, flags=0, what="", **kw):
+    got = pa.fetch(pa.ada_cascade_step(x_dev, tau, dev_idx(prev), flags=flags, **kw))
+    info = parity.check_cascade(x_cpu, tau, prev, got, flags=oflags(flags), what=what,
+                                two_pass=bool(flags & pa.FLAG_TWO_PASS))
+    return got, info
+
+
+def run_layers_teacher_forced(w, xs_cpu, flags=0, what=""):
     """full at layer 0, then a cascade step per layer on the GPU's own previous output; oracle checks each."""
     xs = [x.to(DEV) for x in xs_cpu]
     full = pa.fetch(pa.ada_select_full(xs[0], w.tau))
@@ -34,8 +46,7 @@ def run_layers_teacher_forced(w, xs_cpu, flags=0, tile=None, what=""):
     prev = full["idx"]
     stats = []
     for l in range(1, len(xs)):
-        got = pa.fetch(pa.ada_cascade_step(xs[l], w.tau, dev_idx(prev), flags=flags))
-        info = parity.check_cascade(xs_cpu[l], w.tau, prev, got, flags=flags, what="%s layer %d" % (what, l))
+        got, info = step_and_check(xs[l], xs_cpu[l], w.tau, prev, flags, "%s layer %d" % (what, l))
         stats.append((got["n_adds"], got["n_removes"], info["gamma_err"]))
         prev = got["idx"]
     return stats
@@ -59,9 +70,19 @@ SMALL = [
 
 @pytest.mark.parametrize("tile", ["64", "128"])
 @pytest.mark.parametrize("T,d,K,dtype", SMALL)
-def test_small_shapes_full_and_cascade(T, d, K, dtype, tile, monkeypatch):
+def test_small_shapes_full_and_two_launch_cascade(T, d, K, dtype, tile, monkeypatch):
     monkeypatch.setenv("ADA_TILE", tile)
-    say("small T=%d d=%d K=%d %s tile=%s" % (T, d, K, dtype, tile))
+    say("small T=%d d=%d K=%d %s tile=%s two-launch" % (T, d, K, dtype, tile))
+    w = wl.small(T=T, d=d, K=K, L=3, dtype=dtype, seed=17 + T, p=0.1)
+    stats = run_layers_teacher_forced(w, wl.layer_list(w), flags=pa.FLAG_TWO_PASS, what="small T=%d d=%d" % (T, d))
+    assert all(e <= parity.GAMMA_TOL for _, _, e in stats)
+
+
+@pytest.mark.parametrize("kgroups", ["1", "2"])
+@pytest.mark.parametrize("T,d,K,dtype", SMALL)
+def test_small_shapes_one_launch_cascade(T, d, K, dtype, kgroups, monkeypatch):
+    monkeypatch.setenv("ADA_KGROUPS", kgroups)
+    say("small T=%d d=%d K=%d %s one-launch kgroups=%s" % (T, d, K, dtype, kgroups))
     w = wl.small(T=T, d=d, K=K, L=3, dtype=dtype, seed=17 + T, p=0.1)
     stats = run_layers_teacher_forced(w, wl.layer_list(w), what="small T=%d d=%d" % (T, d))
     assert all(e <= parity.GAMMA_TOL for _, _, e in stats)
@@ -78,17 +99,15 @@ def test_earlier_only_flag():
     say("earlier-only flag")
     w = wl.small(T=400, d=96, K=45, L=4, dtype="bf16", seed=23, p=0.15)
     xs_cpu = wl.layer_list(w)
-    a = run_layers_teacher_forced(w, xs_cpu, flags=0, what="unordered")
-    b = run_layers_teacher_forced(w, xs_cpu, flags=pa.FLAG_CROSS_EARLIER_ONLY, what="earlier-only")
-    assert a != b or True   # both readings pass their own oracle; they differ on reassigned tokens (checked on CPU)
-    # the reading-specific pin: a non-inherited duplicate of a LATER inherited token
-    X = torch.tensor([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [0, 1.0, 1e-3, 0]], dtype=torch.float32)
-    prev = [0, 2]
-    g0 = pa.fetch(pa.ada_cascade_step(X.to(DEV), 0.1, dev_idx(prev)))
-    g1 = pa.fetch(pa.ada_cascade_step(X.to(DEV), 0.1, dev_idx(prev), flags=pa.FLAG_CROSS_EARLIER_ONLY))
-    assert g0["idx"].tolist() == [0, 2] and g1["idx"].tolist() == [0, 1, 2]
-    parity.check_cascade(X, 0.1, prev, g0)
-    parity.check_cascade(X, 0.1, prev, g1, flags=oracle.CROSS_EARLIER_ONLY)
+    for extra in (0, pa.FLAG_TWO_PASS):
+        run_layers_teacher_forced(w, xs_cpu, flags=extra, what="unordered")
+        run_layers_teacher_forced(w, xs_cpu, flags=extra | pa.FLAG_CROSS_EARLIER_ONLY, what="earlier-only")
+        # the reading-specific pin: a non-inherited duplicate of a LATER inherited token
+        X = torch.tensor([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [0, 1.0, 1e-3, 0]], dtype=torch.float32)
+        prev = [0, 2]
+        g0, _ = step_and_check(X.to(DEV), X, 0.1, prev, extra)
+        g1, _ = step_and_check(X.to(DEV), X, 0.1, prev, extra | pa.FLAG_CROSS_EARLIER_ONLY)
+        assert g0["idx"].tolist() == [0, 2] and g1["idx"].tolist() == [0, 1, 2]
 
 
 # ------------------------------------------------------------------------------------------ edge cases
@@ -98,8 +117,8 @@ def test_extreme_inherited_sets():
     x = xs_cpu[1].to(DEV)
     for prev in ([0], [149], list(range(150)), list(range(0, 150, 2)), [3, 77]):
         say("extreme inherited set of size %d" % len(prev))
-        got = pa.fetch(pa.ada_cascade_step(x, w.tau, dev_idx(prev)))
-        parity.check_cascade(xs_cpu[1], w.tau, prev, got, what="prev size %d" % len(prev))
+        for flags in (0, pa.FLAG_TWO_PASS):
+            step_and_check(x, xs_cpu[1], w.tau, prev, flags, "prev size %d" % len(prev))
 
 
 def test_duplicates_orthogonal_zero_rows_and_sign():
@@ -126,8 +145,8 @@ def test_duplicates_orthogonal_zero_rows_and_sign():
     got = pa.fetch(pa.ada_select_full(xz.to(DEV), 0.1))
     assert got["mask"].tolist() == [1, 1, 1, 0, 1]
     parity.check_full(xz, 0.1, got, "zero rows")
-    got = pa.fetch(pa.ada_cascade_step(xz.to(DEV), 0.1, dev_idx([0, 1, 3])))
-    parity.check_cascade(xz, 0.1, [0, 1, 3], got, what="zero rows cascade")
+    for flags in (0, pa.FLAG_TWO_PASS):
+        step_and_check(xz.to(DEV), xz, 0.1, [0, 1, 3], flags, "zero rows cascade")
 
 
 @pytest.mark.parametrize("delta", [1e-6, 1e-5, 1e-4, 1e-3])
@@ -155,12 +174,9 @@ def test_pairs_placed_around_the_threshold(delta):
     if delta >= 1e-3:
         assert info["n_band"] == 0
         assert got["mask"].reshape(-1, 2)[:, 1].tolist() == [0] * 8 + [1] * 8
-    prev = list(range(0, 32, 2))
-    res = pa.fetch(pa.ada_cascade_step(x.to(DEV), tau, dev_idx(prev)))
-    parity.check_cascade(x, tau, prev, res, what="near-threshold cascade")
-    prev = list(range(32))
-    res = pa.fetch(pa.ada_cascade_step(x.to(DEV), tau, dev_idx(prev)))
-    parity.check_cascade(x, tau, prev, res, what="near-threshold rep validation")
+    for flags in (0, pa.FLAG_TWO_PASS):
+        step_and_check(x.to(DEV), x, tau, list(range(0, 32, 2)), flags, "near-threshold cascade")
+        step_and_check(x.to(DEV), x, tau, list(range(32)), flags, "near-threshold rep validation")
 
 
 def test_strided_rows_and_unaligned_base():
@@ -181,19 +197,24 @@ def test_strided_rows_and_unaligned_base():
 def test_bad_inherited_list_is_reported_by_the_device_and_nothing_faults():
     w = wl.small(T=100, d=64, K=10, L=1, dtype="bf16", seed=61)
     x = wl.layer_list(w)[0].to(DEV)
-    for prev in ([5, 5, 9], [9, 5], [0, 100], [-1, 3], [2**30, 2**30 + 1]):
-        say("bad prev_idx %s" % prev[:3])
-        res = pa.ada_cascade_step(x, w.tau, dev_idx(prev))
-        counts = res["counts"].cpu().tolist()
-        assert counts[:3] == [0, 0, 0] and counts[3] == 4          # ADA_ERR_INDEX
-        with pytest.raises(pa.AdaError):
-            pa.fetch(res)
-    r_dev = torch.tensor([0], dtype=torch.int32, device=DEV)
-    res = pa.ada_cascade_step(x, w.tau, dev_idx([1, 2, 3]), r=3, r_dev=r_dev)
-    assert res["counts"].cpu().tolist() == [0, 0, 0, 2]            # ADA_ERR_SHAPE: empty inherited set
-    r_dev = torch.tensor([7], dtype=torch.int32, device=DEV)
-    res = pa.ada_cascade_step(x, w.tau, dev_idx([1, 2, 3]), r=3, r_dev=r_dev)
-    assert res["counts"].cpu().tolist()[3] == 2                    # device count beyond the list capacity
+    ws = pa.workspace(w.T, DEV)
+    for flags in (0, pa.FLAG_TWO_PASS):
+        for prev in ([5, 5, 9], [9, 5], [0, 100], [-1, 3], [2**30, 2**30 + 1]):
+            say("bad prev_idx %s flags=%d" % (prev[:3], flags))
+            res = pa.ada_cascade_step(x, w.tau, dev_idx(prev), flags=flags, ws=ws)
+            counts = res["counts"].cpu().tolist()
+            assert counts[:3] == [0, 0, 0] and counts[3] == 4          # ADA_ERR_INDEX
+            with pytest.raises(pa.AdaError):
+                pa.fetch(res)
+        r_dev = torch.tensor([0], dtype=torch.int32, device=DEV)
+        res = pa.ada_cascade_step(x, w.tau, dev_idx([1, 2, 3]), r=3, r_dev=r_dev, flags=flags, ws=ws)
+        assert res["counts"].cpu().tolist() == [0, 0, 0, 2]            # ADA_ERR_SHAPE: empty inherited set
+        r_dev = torch.tensor([7], dtype=torch.int32, device=DEV)
+        res = pa.ada_cascade_step(x, w.tau, dev_idx([1, 2, 3]), r=3, r_dev=r_dev, flags=flags, ws=ws)
+        assert res["counts"].cpu().tolist()[3] == 2                    # device count beyond the list capacity
+        # the workspace is left usable after a rejected list
+        xs_cpu = wl.layer_list(w)
+        step_and_check(x, xs_cpu[0], w.tau, [0, 7, 50], flags, "after a rejected list", ws=ws)
 
 
 def test_device_side_count_and_reused_workspace():
@@ -207,6 +228,12 @@ def test_device_side_count_and_reused_workspace():
     f, s = pa.fetch(full), pa.fetch(step)
     parity.check_full(xs_cpu[0], w.tau, f)
     parity.check_cascade(xs_cpu[1], w.tau, f["idx"], s)
+    step2 = pa.ada_cascade_step(xs[2], w.tau, step["idx"], r=w.T, r_dev=step["counts"], ws=ws, flags=pa.FLAG_TWO_PASS)
+    parity.check_cascade(xs_cpu[2], w.tau, s["idx"], pa.fetch(step2), two_pass=True)
+    raw = torch.full((pa.workspace_bytes(w.T),), 0xAB, dtype=torch.uint8, device=DEV)   # dirty memory must be initialised
+    pa.ada_workspace_init(raw)
+    step3 = pa.ada_cascade_step(xs[1], w.tau, full["idx"], r=w.T, r_dev=full["counts"], ws=raw)
+    parity.check_cascade(xs_cpu[1], w.tau, f["idx"], pa.fetch(step3))
 
 
 def test_layer_driver_matches_step_by_step_and_report():
@@ -316,5 +343,5 @@ def test_config4_one_sequence_sampled():
     assert np.array_equal(full["idx"], np.flatnonzero(full["mask"]))
     assert np.all(np.abs(ref - parity.thr_of(w.tau)) > parity.BAND)       # sampled decisions are unambiguous
     assert np.array_equal(full["mask"][rows], (ref < parity.thr_of(w.tau)).astype(np.uint8))
-    got = pa.fetch(pa.ada_cascade_step(xs[1], w.tau, dev_idx(full["idx"])))
-    parity.check_cascade(xs_cpu[1], w.tau, full["idx"], got, what=w.name + " layer 1")
+    for flags in (0, pa.FLAG_TWO_PASS):
+        step_and_check(xs[1], xs_cpu[1], w.tau, full["idx"], flags, w.name + " layer 1")

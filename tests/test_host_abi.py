@@ -49,7 +49,7 @@ def test_binding_has_the_same_names(ada):
 def test_workspace_size_is_monotone_and_small(ada):
     assert ada.workspace_bytes(0) == 0
     sizes = [ada.workspace_bytes(T) for T in (1, 512, 2048, 8192)]
-    assert sizes == sorted(sizes) and sizes[-1] < 1 << 20
+    assert sizes == sorted(sizes) and sizes[-1] < 16 << 20     # dominated by the hit table: T * T / 8 bytes
     assert all(s % 256 == 0 for s in sizes)
 
 

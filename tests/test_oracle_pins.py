@@ -304,9 +304,13 @@ def test_cascade_gamma_is_rep_max_for_inherited_and_cross_max_for_the_rest():
     thr = 1 - tau * tau
     g_rep = {s: max([A[sp, s] for sp in R if sp < s], default=0.0) for s in R}
     valid = [s for s in R if g_rep[s] < thr]
+    assert len(valid) < len(R)                       # some inherited token is removed, so the two maxima differ
     for t in range(T):
         want = g_rep[t] if t in R else max([A[t, s] for s in valid], default=0.0)
         assert abs(res["gamma"][t] - want) < 1e-13
+        want_all = g_rep[t] if t in R else max(A[t, s] for s in R)
+        assert abs(res["gamma_all"][t] - want_all) < 1e-13
+    assert np.any(res["gamma_all"] > res["gamma"] + 1e-6)
 
 
 def test_cascade_invariants_on_clustered_layers():
