@@ -46,6 +46,31 @@ def cpu_baseline(w, xs_cpu, n_cascade=3):
                 t_full_s=t_full, t_cascade_s=mean_c)
 
 
+def recorded_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload (FETCH_SIZE and
+    WRITE_SIZE scaled by the copy probe), or None if no summary is there."""
+    import re
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read(), flags=re.M)
+    return int(m.group(1)) if m else None
+
+
+def probe(pa, xs, w, ws, out, stream):
+    """Short run for hardware counters: one cascade pass, full selection on four layers, and the 256 MiB copy probe."""
+    import torch
+    pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out, stream=stream)
+    for l in range(4):
+        pa.ada_select_full(xs[l], w.tau, ws=ws, stream=stream)
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=xs[0].device).fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        pa.ada_profile_copy_probe(dst, src, stream=stream)
+    torch.cuda.synchronize()
+    print(json.dumps({"probe": "done", "copy_probe_bytes": 256 << 20}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +79,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into BASELINE.json configs (default 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the full-selection timing and the profiled pass")
+    ap.add_argument("--probe", action="store_true", help="short run for rocprofv3 --pmc (no timing, no JSON result)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
@@ -83,6 +109,10 @@ def main():
 
     def step():
         pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out, stream=stream)
+
+    if args.probe:
+        probe(pa, xs, w, ws, out, stream)
+        return
 
     for _ in range(args.warmup):
         step()
@@ -137,7 +167,8 @@ def main():
         casc_flops = 2.0 * d * T * r_prev_mean            # T x r Gram entries of eq. (6), 2d flops each
         result["roofline"] = {"bound": "hbm", "kernel": "k_cascade_fused (Algorithm 1 in one launch)",
                               "achieved": casc_bytes / casc_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": casc_bytes / casc_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                              "frac": casc_bytes / casc_s / 1e9 / HBM_PEAK_GBS,
+                              "traffic": recorded_traffic("cascade_fused_c%d_pmc.txt" % args.config),
                               "avg_launch_us": avg_us["cascade_fused"], "bytes_per_launch": casc_bytes,
                               "mfma_tflops": casc_flops / casc_s / 1e12,
                               "mfma_frac": casc_flops / casc_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
@@ -182,7 +213,8 @@ def main():
                                               "achieved": tri_flops / (1e-6 * full_us) / 1e12,
                                               "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                               "frac": tri_flops / (1e-6 * full_us) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                                              "avg_launch_us": full_us, "flops_per_launch": tri_flops},
+                                              "avg_launch_us": full_us, "flops_per_launch": tri_flops,
+                                              "traffic": recorded_traffic("gram_full_c%d_pmc.txt" % args.config)},
                                  "mean_jaccard_independent": sum(jac) / len(jac)}
 
     if not args.no_cpu_baseline:

@@ -158,6 +158,9 @@ enum { ADA_K_NORM_PREP = 0, ADA_K_GRAM_FULL = 1, ADA_K_GRAM_REP = 2, ADA_K_GRAM_
        ADA_K_CASCADE_FUSED = 5, ADA_K_COUNT = 6 };
 int ada_profile_enable(int on);
 int ada_profile_collect(double* ms_sum, int* launches);
+/* A plain device-to-device copy kernel (bytes: multiple of 16, both pointers 16-byte aligned): it reads and writes
+ * exactly `bytes`, which is what hardware traffic counters of the library's kernels are scaled against. */
+int ada_profile_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
            "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
-           "ada_profile_collect")
+           "ada_profile_collect", "ada_profile_copy_probe")
 
 KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused")
 
@@ -86,6 +86,8 @@ def lib():
         L.ada_profile_enable.argtypes = [i32]
         L.ada_profile_collect.restype = i32
         L.ada_profile_collect.argtypes = [vp, vp]
+        L.ada_profile_copy_probe.restype = i32
+        L.ada_profile_copy_probe.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -256,6 +258,16 @@ def ada_profile_collect() -> Dict[str, Dict[str, float]]:
     if rc != OK:
         raise AdaError(rc, "ada_profile_collect")
     return {k: dict(ms=float(ms[i]), launches=int(cnt[i])) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def ada_profile_copy_probe(dst: torch.Tensor, src: torch.Tensor, *, stream=None) -> None:
+    """Plain copy kernel of known size (the yardstick for traffic counters)."""
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != n:
+        raise ValueError("dst and src must have the same size in bytes")
+    rc = lib().ada_profile_copy_probe(_ptr(dst), _ptr(src), n, _stream(stream))
+    if rc != OK:
+        raise AdaError(rc, "ada_profile_copy_probe")
 
 
 def fetch(res: Dict[str, torch.Tensor]) -> Dict[str, object]:

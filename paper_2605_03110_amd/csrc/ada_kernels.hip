@@ -614,6 +614,11 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* p, size_t n, uint32_
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
 }
 
+// plain 16-byte copy of known size: the yardstick the HBM-traffic counters are scaled by
+__global__ __launch_bounds__(256) void k_copy_probe(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 #include "ada_fused.hpp"
 
 // ------------------------------------------------------------------------------------------------
@@ -909,6 +914,15 @@ int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t
     if (!mask_a || !mask_b || !out) return ADA_ERR_NULL;
     if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
     hipLaunchKernelGGL(k_overlap, dim3(1), dim3(1024), 0, (hipStream_t)stream, mask_a, mask_b, T, out);
+    return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+}
+
+int ada_profile_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src) return ADA_ERR_NULL;
+    if (bytes % 16 != 0 || ((uintptr_t)dst % 16) != 0 || ((uintptr_t)src % 16) != 0) return ADA_ERR_SHAPE;
+    if (bytes == 0) return ADA_OK;
+    hipLaunchKernelGGL(k_copy_probe, dim3(4096), dim3(256), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src,
+                       bytes / 16);
     return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
