@@ -44,20 +44,27 @@ struct FusedParams {
     unsigned long long* gram_ops;   // may be NULL
 };
 
-template <int KG> struct FusedGeom {
+// DMA = operands go global -> LDS directly (global_load_lds, 16 bytes per lane) through a ring of NS stages per
+// K-group; otherwise they pass through registers (needed when a row chunk can be ragged or unaligned).
+template <int KG, bool DMA> struct FusedGeom {
     static constexpr int THREADS = 256 * KG;
-    static constexpr int D = 4;                           // prefetch depth (steps of one group), even
+    static constexpr int D = 4;                           // register path: prefetch depth (steps of one group), even
+    static constexpr int NS = 4;                          // DMA path: LDS stages per K-group
     static constexpr int LPT = 4;                         // 16-byte pieces per thread per chunk
     static constexpr int STAGE = 128 * 128;               // one chunk of 128 rows
+    static constexpr int NPART = DMA ? 4 * KG : KG;       // partial sums of squares per row
     static constexpr int OFF_STOK = 0;                    // int[64]   token id of each "against" row (INT_MAX: none)
     static constexpr int OFF_REPF = 256;                  // int[64]   tested token is inherited
-    static constexpr int OFF_SS = 512;                    // float[KG][128] partial sums of squares
-    static constexpr int OFF_SCALE = OFF_SS + KG * 512;   // float[128] 1/norm (0 for rows that do not exist)
-    static constexpr int OFF_SCAN = OFF_SCALE + 512;      // int[3][32] scan scratch of the update phase
+    static constexpr int OFF_SS = 512;                    // float[NPART][128] partial sums of squares
+    static constexpr int OFF_SCALE = OFF_SS + NPART * 512;   // float[128] 1/norm (0 for rows that do not exist)
+    static constexpr int OFF_SCAN = OFF_SCALE + 512;      // scan scratch of the update phase
     static constexpr int META = OFF_SCAN + 512;
-    static constexpr int BODY = 65536;                    // stages (KG * 2 * 16 KB) / reduction scratch / valid mask
+    static constexpr int RING = DMA ? KG * NS * STAGE : KG * 2 * STAGE;
+    static constexpr int BODY = RING > 65536 ? RING : 65536;   // stages / reduction scratch (64 KB) / update state
     static constexpr int LDS = META + BODY;
 };
+
+constexpr int waitcnt_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only (gfx9 encoding)
 
 template <typename In> __device__ inline float piece_sumsq_fast(u32x4 v);
 template <> __device__ inline float piece_sumsq_fast<float>(u32x4 v) {
@@ -79,9 +86,9 @@ template <> __device__ inline float piece_sumsq_fast<uint16_t>(u32x4 v) {
     return s;
 }
 
-template <typename In, bool ALIGNED, int KG>
+template <typename In, bool ALIGNED, int KG, bool DMA>
 __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, int sb, char* lds) {
-    using G = FusedGeom<KG>;
+    using G = FusedGeom<KG, DMA>;
     constexpr int B = 64;
     constexpr int EPP = 16 / (int)sizeof(In);
     constexpr int EPC = 8 * EPP;
@@ -137,32 +144,14 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
 
     const int nk = (p.d + EPC - 1) / EPC;
     const int nsteps = (nk + KG - 1) / KG;               // steps of this group; step k handles chunk k * KG + g
-    u32x4 pre[D][LPT];
     u32x4 fa[2][NB], fb[2][NB];
     f32x16 acc[NB][NB];
-    float ss[LPT];
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) ss[j] = 0.f;
 #pragma unroll
     for (int a = 0; a < NB; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-    auto fetch = [&](int set, int k) {
-#pragma unroll
-        for (int j = 0; j < LPT; ++j)
-            pre[set][j] = fetch_piece<In, ALIGNED>(rowp[j], (k * KG + g) * EPC + pc * EPP, p.d);
-    };
-    auto store = [&](char* stage, int set, int k) {
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            const u32x4 v = finish_piece<ALIGNED>(pre[set][j], (k * KG + g) * EPC + pc * EPP, p.d);
-            *reinterpret_cast<u32x4*>(stage + woff[j]) = v;
-            ss[j] += piece_sumsq_fast<In>(v);            // Section 2.1: ||x||^2 from the registers already in hand
-        }
-    };
     auto read_frags = [&](const char* stage, int f) {
         const int piece = 2 * wave + half;               // this wave's k-step of the chunk
 #pragma unroll
@@ -177,6 +166,88 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
             for (int b = 0; b < NB; ++b) Mfma<In>::run(acc[a][b], fa[f][a], fb[f][b]);
     };
 
+    if constexpr (DMA) {
+        // ---- operands go straight from global memory into LDS.  One wave instruction moves 64 x 16 bytes to 1 KB of
+        // contiguous LDS = 8 rows of a stage; lane l serves row l / 8, slot l % 8 and therefore fetches piece
+        // (l % 8) ^ (row % 8), which reproduces the XOR-swizzled layout the fragment reads expect.  The waits are
+        // counted by hand (NS - 3 chunks stay in flight across the barrier) and the barrier is the bare instruction:
+        // a fenced barrier would drain the loads.  Chunk indices past the end are clamped, so every step issues the
+        // same number of loads and the counts stay valid; such a chunk is never multiplied.
+        constexpr int NS = G::NS;
+        char* ring = body + g * NS * G::STAGE;
+        const int pcd = pc ^ (rb & 7);
+        float ssa[NB] = {0.f, 0.f}, ssb[NB] = {0.f, 0.f};
+        auto issue = [&](int stage, int k) {
+            const int chunk = min(k * KG + g, nk - 1);
+#pragma unroll
+            for (int j = 0; j < LPT; ++j) {
+                char* dst = ring + stage * G::STAGE + (wave * 8 + 32 * j) * 128;      // wave-uniform
+                __builtin_amdgcn_global_load_lds(
+                    (const void __attribute__((address_space(1)))*)(rowp[j] + chunk * EPC + pcd * EPP),
+                    (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+            }
+        };
+        auto mma_and_norms = [&](int f, int k) {
+            if (k * KG + g < nk) {                       // scalar: a clamped (repeated) chunk is skipped
+                mma(f);
+#pragma unroll
+                for (int a = 0; a < NB; ++a) ssa[a] += piece_sumsq_fast<In>(fa[f][a]);   // Section 2.1: ||x||^2 from the
+#pragma unroll
+                for (int b = 0; b < NB; ++b) ssb[b] += piece_sumsq_fast<In>(fb[f][b]);   // fragments already in hand
+            }
+        };
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue(s, s);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 2) * LPT));
+        ADA_CLK(2);
+        __builtin_amdgcn_s_barrier();
+        ADA_CLK(3);
+        read_frags(ring, 0);
+        for (int k0 = 0; k0 < nsteps; k0 += NS) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {               // NS is even: stage and fragment buffer indices are static
+                const int k = k0 + s;
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 3) * LPT));      // chunk k+1 has landed (this wave's part)
+                __builtin_amdgcn_s_barrier();                               // ... and everybody's; stage (k-1) % NS is free
+                read_frags(ring + ((s + 1) % NS) * G::STAGE, (s + 1) & 1);
+                issue((s + NS - 1) % NS, k + NS - 1);
+                mma_and_norms(s & 1, k);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));        // the surplus loads must land before the ring is reused
+        ADA_CLK(4);
+#pragma unroll
+        for (int a = 0; a < NB; ++a) ssa[a] += __shfl_xor(ssa[a], 32, 64);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) ssb[b] += __shfl_xor(ssb[b], 32, 64);
+        __syncthreads();                                  // every wave is done with the ring
+        ADA_CLK(16);
+        if (half == 0) {
+#pragma unroll
+            for (int a = 0; a < NB; ++a) ssq[(g * 4 + wave) * 128 + a * 32 + l32] = ssa[a];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) ssq[(g * 4 + wave) * 128 + B + b * 32 + l32] = ssb[b];
+        }
+    } else {
+    u32x4 pre[D][LPT];
+    float ss[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) ss[j] = 0.f;
+
+    auto fetch = [&](int set, int k) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j)
+            pre[set][j] = fetch_piece<In, ALIGNED>(rowp[j], (k * KG + g) * EPC + pc * EPP, p.d);
+    };
+    auto store = [&](char* stage, int set, int k) {
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            const u32x4 v = finish_piece<ALIGNED>(pre[set][j], (k * KG + g) * EPC + pc * EPP, p.d);
+            *reinterpret_cast<u32x4*>(stage + woff[j]) = v;
+            ss[j] += piece_sumsq_fast<In>(v);            // Section 2.1: ||x||^2 from the registers already in hand
+        }
+    };
     // software pipeline: see gram_tile; steps past the end handle all-zero chunks
 #pragma unroll
     for (int s = 0; s < D; ++s) {
@@ -222,6 +293,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
 #pragma unroll
         for (int j = 0; j < LPT; ++j) ssq[g * 128 + rb + 32 * j] = ss[j];
     }
+    }
     // partial tiles travel through LDS as 16-byte vectors: slot ((wave * 4 + block) * 4 + q) * 64 + lane holds
     // accumulator registers 4q .. 4q+3 of that block (consecutive lanes, consecutive 16 bytes: conflict-free)
     f32x4* red = reinterpret_cast<f32x4*>(body);
@@ -240,7 +312,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
     if (tid < 2 * B) {
         float tot = 0.f;
 #pragma unroll
-        for (int gg = 0; gg < KG; ++gg) tot += ssq[gg * 128 + tid];
+        for (int part = 0; part < G::NPART; ++part) tot += ssq[part * 128 + tid];
         float sc = tot > 0.f ? 1.0f / sqrtf(tot) : 0.f;   // a zero row normalises to zero: all its cosines are 0
         if (tid < B ? (s_tok[tid] == INT_MAX) : (t0 + tid - B >= p.T)) sc = 0.f;
         scale[tid] = sc;
@@ -445,10 +517,10 @@ __device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, char
 
 // Grid: a multiple of 8 workgroups (see k_gram for the XCD-aware tile ranges); tiles with the representative
 // block fastest, so one XCD's L2 serves a contiguous range of tested rows.
-template <typename In, bool ALIGNED, int KG>
+template <typename In, bool ALIGNED, int KG, bool DMA>
 __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     extern __shared__ __align__(16) char lds[];
-    using G = FusedGeom<KG>;
+    using G = FusedGeom<KG, DMA>;
     __shared__ int s_last;
     ADA_CLK(0);
     const int r = p.r_dev ? *p.r_dev : p.r_host;
@@ -463,7 +535,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
             const long long tile = xcd * per + slot;
             if (tile >= ntiles) break;
             const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
-            fused_tile<In, ALIGNED, KG>(p, r, sb * 64, tb * 64, sb, lds);
+            fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
             worked = true;
             __syncthreads();
         }

@@ -758,13 +758,13 @@ hipError_t fill_u32(void* p, size_t n_words, uint32_t v, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <typename In, bool ALIGNED, int KG>
+template <typename In, bool ALIGNED, int KG, bool DMA>
 hipError_t launch_fused(const FusedParams& p, hipStream_t st) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
-    constexpr int lds = FusedGeom<KG>::LDS;
+    constexpr int lds = FusedGeom<KG, DMA>::LDS;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cascade_fused<In, ALIGNED, KG>),
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cascade_fused<In, ALIGNED, KG, DMA>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     if (attr_err != hipSuccess) return attr_err;
@@ -775,7 +775,7 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st) {
     if (tiles > cap) tiles = cap;
     const unsigned grid = (unsigned)(tiles + 7) / 8 * 8;             // multiple of 8 (XCDs)
     ProfScope ps(ADA_K_CASCADE_FUSED, st);
-    hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG>), dim3(grid), dim3(256 * KG), lds, st, p);
+    hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG, DMA>), dim3(grid), dim3(256 * KG), lds, st, p);
     return hipGetLastError();
 }
 
@@ -799,10 +799,17 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
                            reinterpret_cast<unsigned long long*>(gram_ops)};
     int kg = 2;
     if (int o = kgroups_override()) kg = o;
+    const char* no_dma = getenv("ADA_NO_DMA");
     hipError_t e = dispatch(dtype, X, ld, d, [&](auto v) {
         using V = decltype(v);
-        return kg == 2 ? launch_fused<typename V::In, V::aligned, 2>(p, st)
-                       : launch_fused<typename V::In, V::aligned, 1>(p, st);
+        using In = typename V::In;
+        // direct-to-LDS operand loads need whole, aligned 128-byte row chunks
+        constexpr int epc = 128 / (int)sizeof(In);
+        if constexpr (V::aligned) {
+            if (d % epc == 0 && !(no_dma && no_dma[0] == '1'))
+                return kg == 2 ? launch_fused<In, true, 2, true>(p, st) : launch_fused<In, true, 1, true>(p, st);
+        }
+        return kg == 2 ? launch_fused<In, V::aligned, 2, false>(p, st) : launch_fused<In, V::aligned, 1, false>(p, st);
     });
     return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
