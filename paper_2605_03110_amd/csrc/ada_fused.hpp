@@ -169,13 +169,13 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
     if constexpr (DMA) {
         // ---- operands go straight from global memory into LDS.  One wave instruction moves 64 x 16 bytes to 1 KB of
         // contiguous LDS = 8 rows of a stage; lane l serves row l / 8, slot l % 8 and therefore fetches piece
-        // (l % 8) ^ (row % 8), which reproduces the XOR-swizzled layout the fragment reads expect.  The waits are
+        // (l % 8) ^ lds_swz(row), which reproduces the XOR-swizzled layout the fragment reads expect.  The waits are
         // counted by hand (NS - 3 chunks stay in flight across the barrier) and the barrier is the bare instruction:
         // a fenced barrier would drain the loads.  Chunk indices past the end are clamped, so every step issues the
         // same number of loads and the counts stay valid; such a chunk is never multiplied.
         constexpr int NS = G::NS;
         char* ring = body + g * NS * G::STAGE;
-        const int pcd = pc ^ (rb & 7);
+        const int pcd = pc ^ lds_swz(rb);                 // 32 j leaves bits 0..3 of the row alone
         float ssa[NB] = {0.f, 0.f}, ssb[NB] = {0.f, 0.f};
         auto issue = [&](int stage, int k) {
             const int chunk = min(k * KG + g, nk - 1);

@@ -88,6 +88,17 @@ def test_small_shapes_one_launch_cascade(T, d, K, dtype, kgroups, monkeypatch):
     assert all(e <= parity.GAMMA_TOL for _, _, e in stats)
 
 
+@pytest.mark.parametrize("T,d,K,dtype", [(257, 128, 30, "bf16"), (513, 768, 100, "f32"), (700, 4096, 120, "bf16"),
+                                         (1000, 64, 90, "bf16"), (1, 64, 1, "bf16"), (300, 192, 40, "f32")])
+def test_big_tile_full_selection(T, d, K, dtype, monkeypatch):
+    """The 128 x 256 direct-to-LDS tile of the full selection, forced onto small and ragged shapes."""
+    monkeypatch.setenv("ADA_BIG", "1")
+    say("big tile T=%d d=%d %s" % (T, d, dtype))
+    w = wl.small(T=T, d=d, K=K, L=2, dtype=dtype, seed=29 + T, p=0.1)
+    for x_cpu in wl.layer_list(w):
+        parity.check_full(x_cpu, w.tau, pa.fetch(pa.ada_select_full(x_cpu.to(DEV), w.tau)), "big tile T=%d" % T)
+
+
 def test_default_tile_heuristic_runs_both_sizes():
     for T, d in [(300, 128), (2048, 256)]:
         say("heuristic T=%d d=%d" % (T, d))
