@@ -1,0 +1,231 @@
+// k_gram_dma: the lower-triangular Gram of the full selection (Definition "Gram threshold", Section 2.1) for bf16
+// rows that can be fetched in whole 64-byte pieces.  Included by ada_kernels.hip after the tile helpers.
+//
+// What bounds this kernel is the rate at which a CU can pull operands out of the L2: about 25 bytes per clock per CU
+// when all 256 CUs pull at once (45 when few do), against an MFMA rate that consumes 128 (a + b) bytes per a b / 32
+// clocks for an a x b tile.  A 128 x 256 tile needs 47 B/clk and is L2-bound at half the MFMA rate; 256 x 256 needs 32.
+// So a workgroup is four wavefronts in a 2 x 2 grid, one per SIMD, each holding a 128 x 128 accumulator (256
+// registers), which is the largest square the register file allows.  Operands go global -> LDS directly
+// (global_load_lds, 16 bytes per lane) in half chunks of 32 elements: 512 rows x 64 bytes = 32 KB per stage, a ring of
+// four stages, three half chunks in flight while one is multiplied; waits are counted by hand and the barrier is the
+// bare instruction, because a fenced barrier would drain the loads.
+//
+// Work units.  Off-diagonal 256 x 256 blocks of the triangle are "big" units.  A diagonal 256-block would waste a
+// quarter of its MFMAs on s > t, and 256-blocks quantise badly (T = 8192: 528 blocks on 256 CUs), so each diagonal
+// block is cut into three 128 x 128 "small" units (the same code with 64 x 64 per wave).  For mid-sized T, where
+// 256-blocks cannot fill the chip, the whole triangle is cut into small units.  Units are handed out big first: the
+// first one by workgroup id (a contiguous range per XCD, so neighbours share rows in that XCD's L2), the rest from an
+// atomic counter, which packs the short units into the tail.  The counter pair lives in the workspace and is zero
+// between launches: the last workgroup to leave resets it.
+#pragma once
+
+struct DmaGeom {
+    static constexpr int THREADS = 256, NS = 4;
+    static constexpr int HC = 32;                              // elements per half chunk (64 bytes of bf16)
+    static constexpr int STAGE = 512 * 64;                     // bytes per ring stage at the big tile
+    static constexpr int META = 4 * 256 * 4;                   // s_tok, t_tok, s_scale, t_scale
+    static constexpr int LDS = META + NS * STAGE;              // 132 KB: one workgroup per CU
+};
+
+// s_waitcnt vmcnt(n) lgkmcnt(0): the direct-to-LDS loads are counted, every LDS read of this wave has returned
+constexpr int waitcnt_vm_lgkm0(int n) { return 0x0070 | (n & 15) | ((n >> 4) << 14); }
+
+#ifdef ADA_PHASE_CLOCKS
+#define DMA_CLK(i) do { if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) { const unsigned long long t_ = clock64(); g_phase_clk[(i) + (WM == 128 ? 32 : 48)] += t_ - last_clk; last_clk = t_; } } while (0)
+#else
+#define DMA_CLK(i) do { } while (0)
+#endif
+
+// One WM*2 x WM*2 tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side.
+template <int WM>
+__device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool need_order, char* lds) {
+    using G = DmaGeom;
+    constexpr int BT = 2 * WM, ROWS = 2 * BT, NB = WM / 32, LPT = ROWS / 64, NS = G::NS, HC = G::HC;
+    constexpr int STAGE = ROWS * 64;
+    int* s_tok = reinterpret_cast<int*>(lds);
+    int* t_tok = s_tok + BT;
+    float* s_scale = reinterpret_cast<float*>(t_tok + BT);
+    float* t_scale = s_scale + BT;
+    char* ring = lds + G::META;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int ws = wave >> 1, wt = wave & 1;
+#ifdef ADA_PHASE_CLOCKS
+    unsigned long long last_clk = clock64();
+#endif
+    const int T = p.T;
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
+
+    for (int i = tid; i < ROWS; i += G::THREADS) {
+        const bool isS = i < BT;
+        const int tok = isS ? s0 + i : t0 + (i - BT);
+        const bool ok = tok < T;
+        const float sc = ok ? p.inv_norm[ok ? tok : 0] : 0.f;
+        if (isS) { s_tok[i] = ok ? tok : INT_MAX; s_scale[i] = sc; }
+        else { t_tok[i - BT] = ok ? tok : -1; t_scale[i - BT] = sc; }
+    }
+
+    // Stage layout: rows of 64 bytes = 4 pieces; piece c of row r sits at slot c ^ ((r >> 2) & 3).  Sixteen lanes that
+    // read the same piece of 16 consecutive rows then cover one whole 256-byte bank row (rows with equal r % 4 share
+    // bank columns and get four different slots).  One load instruction fills 1 KB = 16 rows; lane l serves row
+    // l / 4, slot l % 4 and therefore fetches piece (l % 4) ^ ((l / 16) % 4).  Rows past the end re-read row T - 1.
+    const uint16_t* rowp[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int row = (j * 4 + wave) * 16 + (lane >> 2);
+        const int tok = min(row < BT ? s0 + row : t0 + (row - BT), T - 1);
+        rowp[j] = X + (size_t)tok * (size_t)p.ld + (((lane & 3) ^ ((lane >> 4) & 3)) << 3);
+    }
+    const int nh = p.d / HC;
+    auto issue = [&](int stage_off, int h) {
+        const int hc = min(h, nh - 1);                         // surplus issues repeat the last half chunk into a dead stage
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            char* dst = ring + stage_off + (j * 4 + wave) * 1024;               // wave-uniform
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + hc * HC),
+                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+        }
+    };
+
+    f32x16 acc[NB][NB];
+#pragma unroll
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    // lane part of a fragment address for k-step ks of a half chunk: row l32 of a 32-row block, piece 2 ks + half
+    const int lo0 = l32 * 64 + (((0 + half) ^ ((l32 >> 2) & 3)) << 4);
+    const int lo1 = l32 * 64 + (((2 + half) ^ ((l32 >> 2) & 3)) << 4);
+    const char* abase = ring + (ws * WM) * 64;
+    const char* bbase = ring + (BT + wt * WM) * 64;
+    u32x4 fa[2][NB], fb[2][NB];
+    auto read_frags = [&](int set, int stage_off, int ks) {
+        const int lo = ks ? lo1 : lo0;
+#pragma unroll
+        for (int a = 0; a < NB; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(abase + stage_off + a * 2048 + lo);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bbase + stage_off + b * 2048 + lo);
+    };
+    auto mma = [&](int set) {
+#pragma unroll
+        for (int a = 0; a < NB; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) Mfma<uint16_t>::run(acc[a][b], fa[set][a], fb[set][b]);
+    };
+
+    // Half step h multiplies half chunk h (two k-steps of 16).  With one wave per SIMD nothing else hides latency, so
+    // the order is fixed by hand: the fragments of k-step 1 are read while k-step 0 multiplies; then the barrier that
+    // opens half chunk h + 1, the fragment reads of its k-step 0 and the loads of half chunk h + 4 (into the stage
+    // everybody has just left) are issued in the shadow of k-step 1's MFMAs, one load per MFMA.
+    auto step = [&](int cur_off, int nxt_off, int h) {
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, cur_off, 1);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));   // h + 1 has landed; my reads of this stage have returned
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, nxt_off, 0);
+        issue(cur_off, h + 4);
+        mma(1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * NB, 0);  // the LDS reads first
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // then one MFMA ...
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // ... per global load
+        }
+        if constexpr (NB * NB > LPT) __builtin_amdgcn_sched_group_barrier(0x008, NB * NB - LPT, 0);
+    };
+    issue(0 * STAGE, 0);
+    issue(1 * STAGE, 1);
+    issue(2 * STAGE, 2);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));     // half chunk 0 has landed (this wave's part)
+    __builtin_amdgcn_s_barrier();
+    issue(3 * STAGE, 3);
+    read_frags(0, 0, 0);
+    DMA_CLK(0);
+    int h = 0;
+    for (; h + NS < nh; h += NS) {                             // every step here has a successor: no branches inside
+#pragma unroll
+        for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, h + s);
+    }
+    for (; h + 1 < nh; ++h) step((h % NS) * STAGE, ((h + 1) % NS) * STAGE, h);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(1, (h % NS) * STAGE, 1);                        // last half chunk
+    mma(0);
+    mma(1);
+    DMA_CLK(1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
+    __syncthreads();
+    DMA_CLK(2);
+
+    uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int nl = wt * WM + b * 32 + l32;
+        const int ttok = t_tok[nl];
+        float m = 0.f;
+#pragma unroll
+        for (int a = 0; a < NB; ++a)
+            m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WM + a * 32, half, need_order, ttok));
+        publish_max(m, t_scale[nl], ttok, half, gamma_bits);
+    }
+    DMA_CLK(3);
+#ifdef ADA_PHASE_CLOCKS
+    if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) g_phase_clk[(WM == 128 ? 32 : 48) + 8] += 1;
+#endif
+}
+
+struct DmaUnits {
+    long long n_big, n_units;
+    __host__ __device__ DmaUnits(int T, int big_mode) {
+        const long long nb256 = (T + 255) / 256, nb128 = (T + 127) / 128;
+        n_big = big_mode ? nb256 * (nb256 - 1) / 2 : 0;
+        n_units = big_mode ? n_big + 3 * nb256 : nb128 * (nb128 + 1) / 2;
+    }
+};
+
+// largest n with n (n + 1) / 2 <= v
+__device__ inline int tri_row(long long v) {
+    int n = (int)((sqrtf(8.f * (float)v + 1.f) - 1.f) * 0.5f);
+    while ((long long)(n + 1) * (n + 2) / 2 <= v) ++n;
+    while ((long long)n * (n + 1) / 2 > v) --n;
+    return n;
+}
+
+__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* queue) {
+    extern __shared__ __align__(16) char lds[];
+    __shared__ long long s_next;
+    const DmaUnits U(p.T, big_mode);
+    const int G = gridDim.x;
+    long long u = (long long)(blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);     // first unit: contiguous range per XCD
+    while (u < U.n_units) {
+        long long nxt = 0;
+        if (threadIdx.x == 0) nxt = (long long)G + atomicAdd(queue, 1);           // next unit: the reply arrives behind the tile
+        if (u < U.n_big) {
+            const int tb = tri_row(u) + 1;                     // off-diagonal 256-blocks: 0 <= sb < tb
+            const int sb = (int)(u - (long long)tb * (tb - 1) / 2);
+            gram_tile_dma<128>(p, sb * 256, tb * 256, false, lds);
+        } else if (big_mode) {
+            const long long v = u - U.n_big;                   // diagonal 256-block i in three 128 x 128 units
+            const int i = (int)(v / 3), k = (int)(v % 3);
+            const int t0 = (2 * i + (k >= 1)) * 128, s0 = (2 * i + (k == 2)) * 128;
+            if (t0 < p.T) gram_tile_dma<64>(p, s0, t0, k != 1, lds);
+        } else {
+            const int tb = tri_row(u);                         // 128-blocks: 0 <= sb <= tb
+            const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
+            gram_tile_dma<64>(p, sb * 128, tb * 128, sb == tb, lds);
+        }
+        if (threadIdx.x == 0) s_next = nxt;
+        __syncthreads();
+        u = s_next;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        // every workgroup's last fetch precedes its sign-off, so whoever signs off last may clear both counters
+        if (atomicAdd(queue + 1, 1) == G - 1) { atomicExch(queue, 0); atomicExch(queue + 1, 0); }
+    }
+}

@@ -23,6 +23,7 @@
 #include <math.h>
 #include <stdlib.h>
 #include <mutex>
+#include <string>
 #include <vector>
 
 #include "../../include/ada.h"
@@ -36,7 +37,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 enum { MODE_FULL = 0, MODE_REP = 1, MODE_CROSS = 2 };
-enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_TICKET = 4, META_WORDS = 8 };
+enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_TICKET = 4, META_QUEUE = 5 /* and 6 */, META_WORDS = 8 };
 
 // The one-launch cascade step keeps one hit word per token and per 32 inherited representatives; beyond this T
 // the table would dominate the workspace and the two-launch path is used instead.
@@ -47,7 +48,7 @@ struct Workspace {
     float* gamma;        // [T]
     int32_t* nonrep_idx; // [T]
     uint8_t* is_rep;     // [T]
-    int32_t* meta;       // [META_WORDS]; meta[META_TICKET] is zero between calls
+    int32_t* meta;       // [META_WORDS]; meta[META_TICKET] and the META_QUEUE pair are zero between calls
     uint32_t* hits;      // [T][hit_words(T)] (only for T <= FUSED_MAX_T)
 };
 
@@ -531,159 +532,6 @@ __global__ __launch_bounds__(256) void k_gram(GramParams p) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// k_gram_big: the lower-triangular Gram of the full selection for large T, where the work is MFMA-bound.
-// A workgroup of 8 wavefronts (2 x 4 grid of 64 x 64 sub-tiles) owns 128 "against" rows x 256 tested rows; the
-// 384-row K chunks (128 bytes per row) go global -> LDS directly through a 3-stage ring (global_load_lds, counted
-// waits, bare barrier: see ada_fused.hpp).  Per 64-element chunk a workgroup moves 48 KB for 128 MFMAs, which is
-// what the measured CU load path (about 48 B/clk) sustains at full MFMA rate; 64 x 64 or 128 x 128 tiles do not.
-// Needs 16-byte aligned rows and d a multiple of the chunk; other shapes use k_gram.
-struct BigGeom {
-    static constexpr int BS = 128, BT = 256, ROWS = BS + BT, THREADS = 512;
-    static constexpr int NS = 3, LPT = ROWS / 64;          // ring stages; 16-byte pieces per thread per chunk
-    static constexpr int STAGE = ROWS * 128;
-    static constexpr int META = (BS + BT) * 8;               // s_tok, t_tok, s_scale, t_scale
-    static constexpr int LDS = META + NS * STAGE;
-};
-
-constexpr int waitcnt_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only (gfx9 encoding)
-
-template <typename In>
-__device__ inline void gram_tile_big(const GramParams& p, int s0, int t0, bool need_order, char* lds) {
-    using G = BigGeom;
-    constexpr int EPP = 16 / (int)sizeof(In), EPC = 8 * EPP, LPT = G::LPT, NS = G::NS, BS = G::BS, BT = G::BT;
-    int* s_tok = reinterpret_cast<int*>(lds);
-    int* t_tok = s_tok + BS;
-    float* s_scale = reinterpret_cast<float*>(t_tok + BT);
-    float* t_scale = s_scale + BS;
-    char* ring = lds + G::META;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l32 = lane & 31, half = lane >> 5;
-    const int ws = wave >> 2, wt = wave & 3;                 // 2 x 4 wave grid
-    const int T = p.T;
-    const In* X = reinterpret_cast<const In*>(p.X);
-
-    for (int i = tid; i < G::ROWS; i += G::THREADS) {
-        const bool isS = i < BS;
-        const int tok = isS ? s0 + i : t0 + (i - BS);
-        const bool ok = tok < T;
-        const float sc = ok ? p.inv_norm[ok ? tok : 0] : 0.f;
-        if (isS) { s_tok[i] = ok ? tok : INT_MAX; s_scale[i] = sc; }
-        else { t_tok[i - BS] = ok ? tok : -1; t_scale[i - BS] = sc; }
-    }
-
-    // lane l of wave w serves stage rows 8w + l/8 + 64j (slot l%8) and fetches the piece that belongs in that slot
-    const int r8 = lane >> 3;
-    const int pcd = (lane & 7) ^ lds_swz(wave * 8 + r8);        // 64 j leaves bits 0..3 of the row alone
-    const In* rowp[LPT];
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) {
-        const int row = wave * 8 + r8 + 64 * j;
-        const int tok = min(row < BS ? s0 + row : t0 + (row - BS), T - 1);   // rows past the end re-read the last row
-        rowp[j] = X + (size_t)tok * (size_t)p.ld + pcd * EPP;
-    }
-    const int nk = p.d / EPC;
-    auto issue = [&](int stage, int k) {
-        const int chunk = min(k, nk - 1);                    // surplus issues repeat the last chunk into a dead stage
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            char* dst = ring + stage * G::STAGE + (wave * 8 + 64 * j) * 128;   // wave-uniform
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + chunk * EPC),
-                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
-        }
-    };
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-    // Step k: wait for chunk k, barrier, start loading chunk k+2 into the stage chunk k-1 used, multiply chunk k.
-    // Two chunks are in flight while one is multiplied; the eight waves give the scheduler work between LDS reads.
-    issue(0, 0);
-    issue(1, 1);
-    for (int k0 = 0; k0 < nk; k0 += NS) {
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const int k = k0 + s;
-            if (k < nk) {                                    // uniform
-                __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_waitcnt(waitcnt_vmcnt(LPT));   // chunk k has landed (this wave's part); k+1 may be in flight
-                __builtin_amdgcn_s_barrier();                // ... everybody's part; everybody is done with chunk k-1
-                issue((s + 2) % NS, k + 2);
-                const char* cur = ring + s * G::STAGE;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const int piece = 2 * ks + half;
-                    u32x4 fa[2], fb[2];
-#pragma unroll
-                    for (int a = 0; a < 2; ++a)
-                        fa[a] = *reinterpret_cast<const u32x4*>(cur + lds_off(ws * 64 + a * 32 + l32, piece));
-#pragma unroll
-                    for (int b = 0; b < 2; ++b)
-                        fb[b] = *reinterpret_cast<const u32x4*>(cur + lds_off(BS + wt * 64 + b * 32 + l32, piece));
-#pragma unroll
-                    for (int a = 0; a < 2; ++a)
-#pragma unroll
-                        for (int b = 0; b < 2; ++b) Mfma<In>::run(acc[a][b], fa[a], fb[b]);
-                }
-            }
-        }
-    }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vmcnt(0));            // surplus loads land before the ring is reused
-    __syncthreads();
-
-    uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int nl = wt * 64 + b * 32 + l32;
-        const int ttok = t_tok[nl];
-        float m = 0.f;
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-            m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * 64 + a * 32, half, need_order, ttok));
-        publish_max(m, t_scale[nl], ttok, half, gamma_bits);
-    }
-}
-
-// Tiles (tb, sb) with sb <= 2 tb + 1 cover s < t.  They are numbered by "supertiles" of 4 tested-row blocks x 8
-// against-row blocks (32 tiles, lower-triangular in supertile coordinates): the 32 workgroups an XCD runs at a time
-// then share 4 + 8 row blocks through its L2 instead of fetching 32 + 1, which halves the traffic behind the L2.
-// Ids that fall outside the triangle or the matrix are skipped.
-__host__ __device__ inline long long big_tile_ids(int T) {
-    const long long nbT = (T + BigGeom::BT - 1) / BigGeom::BT;
-    const long long nTB = (nbT + 3) / 4;
-    return nTB * (nTB + 1) / 2 * 32;
-}
-
-template <typename In>
-__global__ __launch_bounds__(512) void k_gram_big(GramParams p) {
-    extern __shared__ __align__(16) char lds[];
-    const int nbT = (p.T + BigGeom::BT - 1) / BigGeom::BT, nbS = (p.T + BigGeom::BS - 1) / BigGeom::BS;
-    const long long nids = big_tile_ids(p.T);
-    const long long per = (nids / 32 + 7) / 8 * 32;          // whole supertiles per XCD
-    const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
-    for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
-        const long long id = xcd * per + slot;
-        if (id >= nids) break;
-        const long long u = id >> 5;
-        const int inner = (int)(id & 31);
-        int TB = (int)((sqrtf(8.f * (float)u + 1.f) - 1.f) * 0.5f);
-        while ((long long)(TB + 1) * (TB + 2) / 2 <= u) ++TB;
-        while ((long long)TB * (TB + 1) / 2 > u) --TB;
-        const int SB = (int)(u - (long long)TB * (TB + 1) / 2);
-        const int tb = 4 * TB + (inner >> 3), sb = 8 * SB + (inner & 7);
-        if (tb >= nbT || sb >= nbS || sb > 2 * tb + 1) continue;
-        gram_tile_big<In>(p, sb * BigGeom::BS, tb * BigGeom::BT, sb >= 2 * tb, lds);
-        __syncthreads();
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
 // k_update: threshold + compaction (one workgroup)
 
 struct UpdateParams {
@@ -776,6 +624,7 @@ __global__ __launch_bounds__(256) void k_copy_probe(u32x4* __restrict__ dst, con
 }
 
 #include "ada_fused.hpp"
+#include "ada_gram_dma.hpp"
 
 // ------------------------------------------------------------------------------------------------
 // host side
@@ -836,19 +685,48 @@ int tile_override() {
     return (v == 64 || v == 128) ? v : 0;
 }
 
-template <typename In>
-hipError_t launch_gram_big(const GramParams& p, hipStream_t st) {
+// Makespan of handing the units out big first to G workgroups, in units of one big tile; a small unit was measured at
+// about 0.4 of a big one.
+inline double dma_makespan(int T, int big_mode, int G) {
+    const DmaUnits U(T, big_mode);
+    if (U.n_units > 64LL * G) return ((double)U.n_big + 0.4 * (double)(U.n_units - U.n_big)) / G;
+    std::vector<double> fin(G, 0.0);
+    for (long long u = 0; u < U.n_units; ++u) {
+        int best = 0;
+        for (int g = 1; g < G; ++g) if (fin[g] < fin[best]) best = g;
+        fin[best] += u < U.n_big ? 1.0 : 0.4;
+    }
+    double m = 0.0;
+    for (double f : fin) m = f > m ? f : m;
+    return m;
+}
+
+// mode: 0 = 128 x 128 units everywhere, 1 = 256 x 256 off the diagonal, -1 = whichever hands out better
+hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
+    static int G = 256;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gram_big<In>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, BigGeom::LDS);
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gram_dma),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom::LDS);
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 8)
+            G = cus / 8 * 8;                                   // one workgroup per CU (LDS), whole XCDs
     });
     if (attr_err != hipSuccess) return attr_err;
-    long long tiles = big_tile_ids(p.T);
-    if (tiles > 65528) tiles = 65528;
+    if (mode < 0) {
+        static std::mutex mu;
+        static int last_T = 0, last_mode = 0;
+        std::lock_guard<std::mutex> lock(mu);
+        if (last_T != p.T) {
+            last_mode = dma_makespan(p.T, 1, G) < dma_makespan(p.T, 0, G) ? 1 : 0;
+            last_T = p.T;
+        }
+        mode = last_mode;
+    }
     ProfScope ps(ADA_K_GRAM_FULL, st);
-    hipLaunchKernelGGL((k_gram_big<In>), dim3((unsigned)(tiles + 7) / 8 * 8), dim3(BigGeom::THREADS), BigGeom::LDS, st, p);
+    hipLaunchKernelGGL(k_gram_dma, dim3(G), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue);
     return hipGetLastError();
 }
 
@@ -911,18 +789,20 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
     const float thr = threshold_of(tau);
     const PrepParams prep = {nullptr, nullptr, 0, 0};
     const GramParams p = {X, ld, T, d, nullptr, nullptr, nullptr, w.inv_norm, g, thr, MODE_FULL, 1};
-    const char* big_env = getenv("ADA_BIG");               // development switch: 0 = never, 1 = always (if eligible)
+    const char* path_env = getenv("ADA_GRAM");               // development switch: tile, dma0, dma1
+    const std::string path = path_env ? path_env : "";
     hipError_t e = dispatch(dtype, X, ld, d, [&](auto v) {
         using V = decltype(v);
         using In = typename V::In;
         hipError_t e1 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st);
         if (e1 != hipSuccess) return e1;
         if constexpr (V::aligned) {
-            // the big tile pays off once there are about two tiles per CU; it needs whole 128-byte row chunks
-            const long long nbT = (T + BigGeom::BT - 1) / BigGeom::BT;
-            bool big = d % (128 / (int)sizeof(In)) == 0 && nbT * (nbT + 1) >= 512;
-            if (big_env) big = d % (128 / (int)sizeof(In)) == 0 && big_env[0] == '1';
-            if (big) return launch_gram_big<In>(p, st);
+            if constexpr (sizeof(In) == 2) {
+                // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
+                const bool can = d % DmaGeom::HC == 0;
+                if (can && (path == "dma0" || path == "dma1")) return launch_gram_dma(p, w.meta + META_QUEUE, path == "dma1", st);
+                if (can && path.empty() && T >= 1536) return launch_gram_dma(p, w.meta + META_QUEUE, -1, st);
+            }
         }
         return launch_gram_any<In, V::aligned>(p, T, T, true, st);
     });

@@ -88,15 +88,34 @@ def test_small_shapes_one_launch_cascade(T, d, K, dtype, kgroups, monkeypatch):
     assert all(e <= parity.GAMMA_TOL for _, _, e in stats)
 
 
-@pytest.mark.parametrize("T,d,K,dtype", [(257, 128, 30, "bf16"), (513, 768, 100, "f32"), (700, 4096, 120, "bf16"),
-                                         (1000, 64, 90, "bf16"), (1, 64, 1, "bf16"), (300, 192, 40, "f32")])
-def test_big_tile_full_selection(T, d, K, dtype, monkeypatch):
-    """The 128 x 256 direct-to-LDS tile of the full selection, forced onto small and ragged shapes."""
-    monkeypatch.setenv("ADA_BIG", "1")
-    say("big tile T=%d d=%d %s" % (T, d, dtype))
-    w = wl.small(T=T, d=d, K=K, L=2, dtype=dtype, seed=29 + T, p=0.1)
+@pytest.mark.parametrize("path", ["dma0", "dma1"])
+@pytest.mark.parametrize("T,d,K", [(257, 128, 30), (700, 4096, 120), (1000, 64, 90), (1, 64, 1), (129, 32, 8),
+                                   (1290, 96, 140), (512, 160, 60), (3000, 64, 300), (5500, 32, 400)])
+def test_direct_to_lds_full_selection(T, d, K, path, monkeypatch):
+    """The direct-to-LDS Gram kernel of the full selection, both ways of cutting the triangle into units, forced onto
+    small and ragged shapes (T off the 128 and 256 grids, one to three half chunks, a single token) and onto two
+    shapes with more units than workgroups, where the rest is handed out through the counter in the workspace."""
+    monkeypatch.setenv("ADA_GRAM", path)
+    say("direct-to-LDS %s T=%d d=%d" % (path, T, d))
+    w = wl.small(T=T, d=d, K=K, L=2, dtype="bf16", seed=29 + T, p=0.1)
+    ws = pa.workspace(T, DEV)
     for x_cpu in wl.layer_list(w):
-        parity.check_full(x_cpu, w.tau, pa.fetch(pa.ada_select_full(x_cpu.to(DEV), w.tau)), "big tile T=%d" % T)
+        parity.check_full(x_cpu, w.tau, pa.fetch(pa.ada_select_full(x_cpu.to(DEV), w.tau, ws=ws)), "%s T=%d" % (path, T))
+    # the counters in the workspace (behind three T-word arrays and one T-byte array, each padded to 256 bytes) must
+    # be back at zero for the next launch
+    up = lambda n: (n + 255) // 256 * 256
+    meta = ws[3 * up(4 * T) + up(T):][:32].view(torch.int32).cpu().tolist()
+    assert meta[4:7] == [0, 0, 0]
+
+
+@pytest.mark.parametrize("T,d,K,dtype", [(1600, 64, 200, "bf16"), (1600, 72, 200, "bf16"), (1600, 64, 200, "f32")])
+def test_full_selection_path_choice(T, d, K, dtype):
+    """Default path choice around its boundaries: the direct-to-LDS kernel (bf16, whole 64-byte pieces, T >= 1536)
+    and the register-staged tile kernel next to it (d off the grid, fp32)."""
+    say("path choice T=%d d=%d %s" % (T, d, dtype))
+    w = wl.small(T=T, d=d, K=K, L=1, dtype=dtype, seed=41 + d, p=0.1)
+    x_cpu = wl.layer_list(w)[0]
+    parity.check_full(x_cpu, w.tau, pa.fetch(pa.ada_select_full(x_cpu.to(DEV), w.tau)), "path choice")
 
 
 def test_default_tile_heuristic_runs_both_sizes():
