@@ -110,6 +110,14 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
     const In* X = reinterpret_cast<const In*>(p.X);
 
     ADA_CLK(1);
+    // every list entry this thread needs is requested before anything waits: one trip to memory, not two
+    const int pc = t256 & 7, rb = t256 >> 3;
+    int ptok[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int li = s0 + rb + 32 * j;                 // only used for rows 0..63 (representatives)
+        ptok[j] = p.prev_idx[li < r ? li : r - 1];
+    }
     if (tid < B) {
         const int li = s0 + tid;
         const bool ok = li < r;
@@ -119,29 +127,24 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         repf[tid] = 0;
     }
     __syncthreads();
-    for (int j = tid; j < r; j += G::THREADS) {          // which tested tokens of this tile are inherited
-        const unsigned q = (unsigned)(p.prev_idx[j] - t0);
-        if (q < (unsigned)B) repf[q] = 1;
-    }
+    // which tested tokens of this tile are inherited: a pass over the whole list, run behind the first operand loads
+    // (the flags are not read before the epilogue)
+    auto mark_inherited = [&]() {
+        for (int j = tid; j < r; j += G::THREADS) {
+            const unsigned q = (unsigned)(p.prev_idx[j] - t0);
+            if (q < (unsigned)B) repf[q] = 1;
+        }
+    };
 
-    const int pc = t256 & 7, rb = t256 >> 3;
     const In* rowp[LPT];
     int woff[LPT];
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
         const int row = rb + 32 * j;                     // rows 0..63: representatives, 64..127: tested tokens
-        int tok;
-        if (row < B) {
-            const int li = s0 + row;
-            tok = p.prev_idx[li < r ? li : r - 1];
-            tok = min(max(tok, 0), p.T - 1);
-        } else {
-            tok = min(t0 + row - B, p.T - 1);
-        }
+        const int tok = row < B ? min(max(ptok[j], 0), p.T - 1) : min(t0 + row - B, p.T - 1);
         rowp[j] = X + (size_t)tok * (size_t)p.ld;
         woff[j] = lds_off(row, pc);
     }
-
     const int nk = (p.d + EPC - 1) / EPC;
     const int nsteps = (nk + KG - 1) / KG;               // steps of this group; step k handles chunk k * KG + g
     u32x4 fa[2][NB], fb[2][NB];
@@ -198,7 +201,8 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         };
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) issue(s, s);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 2) * LPT));
+        mark_inherited();                                // its loads are younger than the ring's: the wait below covers stage 0
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
         ADA_CLK(2);
         __builtin_amdgcn_s_barrier();
         ADA_CLK(3);
@@ -254,6 +258,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         fetch(s, s);
         __builtin_amdgcn_sched_barrier(0);
     }
+    mark_inherited();
     store(buf0, 0, 0);
     fetch(0, D);
     __builtin_amdgcn_sched_barrier(0);
@@ -400,48 +405,51 @@ __device__ inline unsigned long long block_exclusive_scan64(unsigned long long v
 // Per-token state lives in LDS (T <= FUSED_MAX_T bytes): bit 0 = inherited, bit 1 = kept.  The hit table is
 // word-major (hits[w * T + t]), so a thread that owns token t reads its words with loads that are coalesced across
 // the workgroup, independent of each other and branch-free (indices are clamped, results masked): a whole batch is
-// in flight before the first use.
+// in flight before the first use.  One CU's load path is what this phase costs, so nothing is fetched twice:
+// the first THREADS list entries arrive in registers (q0 / qp0, loaded before the ticket), representatives take one
+// batch each, and the token pass reads four tokens per 16-byte load when T allows.
 template <int THREADS>
-__device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, char* lds, int* scan_scratch) {
-    constexpr int TU = 4, WU = 15;                      // tokens x words fetched per batch by one thread (< 64 loads)
-    const int tid = threadIdx.x;
+__device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, int q0, int qp0, char* lds, int* scan_scratch) {
+    constexpr int WU = 15;                              // hit words fetched per batch by one thread
+    const int tid = threadIdx.x, lane = tid & 63;
     const int T = p.T;
     uint8_t* flag = reinterpret_cast<uint8_t*>(lds);                         // [T]
     uint32_t* vmask = reinterpret_cast<uint32_t*>(lds + FUSED_MAX_T);        // one bit per inherited representative: valid
     const int Wa = r_ok ? (r + 31) >> 5 : 0;            // hit words in use per token
     for (int t = tid; t < T; t += THREADS) flag[t] = 2;                      // not inherited, kept unless covered
-    for (int w = tid; w < Wa; w += THREADS) vmask[w] = 0u;
+    // the token pass's first batch of hit words does not depend on the validity mask: fetch it now, use it later
+    const bool vec = (T & 3) == 0;
+    const bool have_pre = vec && r_ok && tid < (T >> 2);
+    u32x4 pre[WU];
+#pragma unroll
+    for (int v = 0; v < WU; ++v)
+        pre[v] = have_pre ? *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(v, Wa - 1) * T + 4 * tid) : u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
     ADA_CLK_LAST(10);
     // step 5: an inherited representative with a hit from an earlier inherited one is removed.  The list is checked
     // on the way (strictly ascending token ids in range); token ids are clamped so that a bad list cannot fault.
+    // Lanes of a wave hold 64 consecutive list positions, so a ballot is two words of the validity mask.
     int ok = 1;
     if (r_ok) {
-        for (int jb = tid; jb < r; jb += THREADS * TU) {
-            int tok[TU];
-            uint32_t any[TU];
-#pragma unroll
-            for (int u = 0; u < TU; ++u) {
-                const int j = min(jb + u * THREADS, r - 1);
-                const int q = p.prev_idx[j], qp = p.prev_idx[max(j - 1, 0)];
-                if (q < 0 || q >= T || (j > 0 && !(qp < q))) ok = 0;
-                tok[u] = min(max(q, 0), T - 1);
-                any[u] = 0u;
-            }
+        for (int j = tid; j < r; j += THREADS) {
+            const int q = j < THREADS ? q0 : p.prev_idx[j];
+            const int qp = j < THREADS ? qp0 : p.prev_idx[j - 1];
+            if (q < 0 || q >= T || (j > 0 && !(qp < q))) ok = 0;
+            const int tok = min(max(q, 0), T - 1);
+            uint32_t any = 0u;
             for (int w0 = 0; w0 < Wa; w0 += WU) {
-                uint32_t x[TU][WU];
+                uint32_t x[WU];
 #pragma unroll
-                for (int u = 0; u < TU; ++u)
+                for (int v = 0; v < WU; ++v) x[v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + tok];
 #pragma unroll
-                    for (int v = 0; v < WU; ++v) x[u][v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + tok[u]];
-#pragma unroll
-                for (int u = 0; u < TU; ++u)
-#pragma unroll
-                    for (int v = 0; v < WU; ++v) any[u] |= (w0 + v < Wa) ? x[u][v] : 0u;
+                for (int v = 0; v < WU; ++v) any |= (w0 + v < Wa) ? x[v] : 0u;
             }
-#pragma unroll
-            for (int u = 0; u < TU; ++u)
-                if (jb + u * THREADS < r) flag[tok[u]] = any[u] ? 1 : 3;
+            flag[tok] = any ? 1 : 3;
+            const unsigned long long valid = __ballot(any == 0u);            // lanes past the list are inactive: 0
+            if (lane == 0) {
+                vmask[j >> 5] = (uint32_t)valid;
+                if ((j >> 5) + 1 < Wa) vmask[(j >> 5) + 1] = (uint32_t)(valid >> 32);
+            }
         }
     }
     ok = __syncthreads_and(ok);
@@ -454,34 +462,44 @@ __device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, char
         }
         return;
     }
-    ADA_CLK_LAST(11);
-    for (int j = tid; j < r; j += THREADS)
-        if (flag[p.prev_idx[j]] == 3) atomicOr(&vmask[j >> 5], 1u << (j & 31));
-    __syncthreads();
     ADA_CLK_LAST(12);
     // step 9: any other token with a hit on a VALID representative is covered
-    for (int tb = tid; tb < T; tb += THREADS * TU) {
-        uint32_t any[TU];
+    if (vec) {
+        for (int t4 = tid; t4 < (T >> 2); t4 += THREADS) {                  // tokens 4 t4 .. 4 t4 + 3
+            u32x4 any = {0u, 0u, 0u, 0u};
+            for (int w0 = 0; w0 < Wa; w0 += WU) {
+                u32x4 x[WU];
+                if (t4 == tid && w0 == 0) {                                  // uniform: the batch fetched up front
 #pragma unroll
-        for (int u = 0; u < TU; ++u) any[u] = 0u;
-        for (int w0 = 0; w0 < Wa; w0 += WU) {
-            uint32_t x[TU][WU];
+                    for (int v = 0; v < WU; ++v) x[v] = pre[v];
+                } else {
 #pragma unroll
-            for (int u = 0; u < TU; ++u)
+                    for (int v = 0; v < WU; ++v)
+                        x[v] = *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(w0 + v, Wa - 1) * T + 4 * t4);
+                }
 #pragma unroll
-                for (int v = 0; v < WU; ++v)
-                    x[u][v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + min(tb + u * THREADS, T - 1)];
-#pragma unroll
-            for (int v = 0; v < WU; ++v) {
-                const uint32_t vm = (w0 + v < Wa) ? vmask[w0 + v] : 0u;
-#pragma unroll
-                for (int u = 0; u < TU; ++u) any[u] |= x[u][v] & vm;
+                for (int v = 0; v < WU; ++v) {
+                    const uint32_t vm = (w0 + v < Wa) ? vmask[w0 + v] : 0u;
+                    any |= x[v] & vm;
+                }
             }
-        }
+            uint32_t f4 = *reinterpret_cast<const uint32_t*>(flag + 4 * t4);
 #pragma unroll
-        for (int u = 0; u < TU; ++u) {
-            const int t = tb + u * THREADS;
-            if (t < T && flag[t] == 2 && any[u]) flag[t] = 0;
+            for (int u = 0; u < 4; ++u)
+                if (((f4 >> (8 * u)) & 0xFFu) == 2u && any[u]) f4 &= ~(0xFFu << (8 * u));
+            *reinterpret_cast<uint32_t*>(flag + 4 * t4) = f4;
+        }
+    } else {
+        for (int t = tid; t < T; t += THREADS) {
+            uint32_t any = 0u;
+            for (int w0 = 0; w0 < Wa; w0 += WU) {
+                uint32_t x[WU];
+#pragma unroll
+                for (int v = 0; v < WU; ++v) x[v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + t];
+#pragma unroll
+                for (int v = 0; v < WU; ++v) any |= x[v] & ((w0 + v < Wa) ? vmask[w0 + v] : 0u);
+            }
+            if (flag[t] == 2 && any) flag[t] = 0;
         }
     }
     __syncthreads();
@@ -544,7 +562,11 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     // visible device-wide first: every thread waits for its own stores, then ONE thread issues the release (an L2
     // write-back is a per-cache operation, so one per workgroup is enough and thousands would serialise).
     ADA_CLK(6);
-    if (worked) __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this thread's stores have left the CU
+    // the update phase's first slice of the inherited list: input data, so it can be fetched behind the store drain
+    // (entries below r_host are the caller's memory whatever r turns out to be)
+    const int jq = min((int)threadIdx.x, max(p.r_host, 1) - 1);
+    const int q0 = p.prev_idx[jq], qp0 = p.prev_idx[max(jq - 1, 0)];
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this thread's stores have left the CU
     __syncthreads();
     if (threadIdx.x == 0) {
         if (worked) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
@@ -556,6 +578,6 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     ADA_CLK_LAST(8);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");       // see the other workgroups' hit words, not stale lines
     ADA_CLK_LAST(9);
-    fused_update<G::THREADS>(p, r, r_ok, lds + G::META, reinterpret_cast<int*>(lds + G::OFF_SCAN));
+    fused_update<G::THREADS>(p, r, r_ok, q0, qp0, lds + G::META, reinterpret_cast<int*>(lds + G::OFF_SCAN));
     ADA_CLK_LAST(15);
 }
