@@ -155,12 +155,20 @@ int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* 
  * kernel, so these figures are upper bounds of the durations a kernel trace reports.
  */
 enum { ADA_K_NORM_PREP = 0, ADA_K_GRAM_FULL = 1, ADA_K_GRAM_REP = 2, ADA_K_GRAM_CROSS = 3, ADA_K_UPDATE = 4,
-       ADA_K_CASCADE_FUSED = 5, ADA_K_COUNT = 6 };
+       ADA_K_CASCADE_FUSED = 5, ADA_K_MFMA_PROBE = 6, ADA_K_COUNT = 7 };
 int ada_profile_enable(int on);
 int ada_profile_collect(double* ms_sum, int* launches);
 /* A plain device-to-device copy kernel (bytes: multiple of 16, both pointers 16-byte aligned): it reads and writes
  * exactly `bytes`, which is what hardware traffic counters of the library's kernels are scaled against. */
 int ada_profile_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+/* A kernel that does nothing but bf16 matrix instructions (the 32x32x16 form the Gram kernels use) on pseudo-random
+ * operands held in registers: `workgroups` workgroups of four wavefronts, each wavefront issuing 16 * iters
+ * independent instructions of 32768 flops.  Timed through ada_profile_collect (class ADA_K_MFMA_PROBE) it gives the
+ * matrix rate this device sustains on realistic data, which sits below the published peak when the clock is
+ * power-limited; the Gram kernels' fractions are reported against both.  sink: device, >= workgroups floats
+ * (written only in a case that does not occur; keeps the arithmetic alive).  Returns ADA_ERR_SHAPE for
+ * workgroups < 1, iters < 1 or more than 2^20 of either. */
+int ada_profile_mfma_probe(int workgroups, int iters, float* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,9 +25,9 @@ OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
            "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
-           "ada_profile_collect", "ada_profile_copy_probe")
+           "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe")
 
-KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused")
+KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused", "mfma_probe")
 
 
 class AdaError(RuntimeError):
@@ -88,6 +88,8 @@ def lib():
         L.ada_profile_collect.argtypes = [vp, vp]
         L.ada_profile_copy_probe.restype = i32
         L.ada_profile_copy_probe.argtypes = [vp, vp, sz, vp]
+        L.ada_profile_mfma_probe.restype = i32
+        L.ada_profile_mfma_probe.argtypes = [i32, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -285,3 +287,12 @@ def fetch(res: Dict[str, torch.Tensor]) -> Dict[str, object]:
         out["gram_ops"] = int(res["gram_ops"].cpu().item())
     out["gamma"] = res["gamma"].cpu().numpy()
     return out
+
+
+def ada_profile_mfma_probe(workgroups: int, iters: int, *, device="cuda", stream=None) -> float:
+    """Launch the matrix-instruction-only kernel; returns the flops it performs (time it via ada_profile_collect)."""
+    sink = torch.zeros(int(workgroups), dtype=torch.float32, device=device)
+    rc = lib().ada_profile_mfma_probe(int(workgroups), int(iters), _ptr(sink), _stream(stream))
+    if rc != OK:
+        raise AdaError(rc, "ada_profile_mfma_probe")
+    return float(workgroups) * 4.0 * float(iters) * 16.0 * 32768.0

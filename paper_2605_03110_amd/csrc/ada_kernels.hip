@@ -619,6 +619,41 @@ __global__ __launch_bounds__(256) void k_fill_u32(uint32_t* p, size_t n, uint32_
 }
 
 // plain 16-byte copy of known size: the yardstick the HBM-traffic counters are scaled by
+// two bf16 values with random sign and mantissa, magnitude in [0.5, 1): realistic switching activity, no overflow
+__device__ inline uint32_t probe_bf16x2(uint32_t& s) {
+    s = s * 1664525u + 1013904223u;
+    const uint32_t a = s >> 16;
+    s = s * 1664525u + 1013904223u;
+    const uint32_t b = s >> 16;
+    return ((a & 0x807Fu) | 0x3F00u) | (((b & 0x807Fu) | 0x3F00u) << 16);
+}
+
+__global__ __launch_bounds__(256) void k_mfma_probe(float* sink, int iters) {
+    f32x16 acc[16];
+#pragma unroll
+    for (int a = 0; a < 16; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+    uint32_t seed = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    u32x4 x[4], y[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[q][i] = probe_bf16x2(seed); y[q][i] = probe_bf16x2(seed); }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) Mfma<uint16_t>::run(acc[a * 4 + b], x[a], y[b]);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int a = 0; a < 16; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += acc[a][i];
+    if (sum == 123.456f) sink[blockIdx.x] = sum;           // sums of +-[0.25, 1) products: never this value in practice
+}
+
 __global__ __launch_bounds__(256) void k_copy_probe(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
@@ -991,6 +1026,14 @@ int ada_profile_copy_probe(void* dst, const void* src, size_t bytes, void* strea
     if (bytes == 0) return ADA_OK;
     hipLaunchKernelGGL(k_copy_probe, dim3(4096), dim3(256), 0, (hipStream_t)stream, (u32x4*)dst, (const u32x4*)src,
                        bytes / 16);
+    return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+}
+
+int ada_profile_mfma_probe(int workgroups, int iters, float* sink, void* stream) {
+    if (!sink) return ADA_ERR_NULL;
+    if (workgroups < 1 || iters < 1 || workgroups > (1 << 20) || iters > (1 << 20)) return ADA_ERR_SHAPE;
+    ProfScope ps(ADA_K_MFMA_PROBE, (hipStream_t)stream);
+    hipLaunchKernelGGL(k_mfma_probe, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, sink, iters);
     return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
