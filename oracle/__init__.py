@@ -56,6 +56,7 @@ def _load():
         lib.ada_oracle_cascade_step.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, c_ip,
                                                 ctypes.c_int, ctypes.c_uint, c_i8p, c_ip, c_ip, c_ip, c_ip,
                                                 c_u64p, c_dp, c_dp]
+        lib.ada_oracle_assign_nearest.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_ip, ctypes.c_int, c_ip, c_dp]
         _lib = lib
     return _lib
 
@@ -147,3 +148,15 @@ def cascade_step(X, tau: float, prev_idx, flags: int = 0, force: Optional[Sequen
            "cascade_step")
     return dict(idx=idx[:counts[0]].copy(), adds=adds[:counts[1]].copy(), removes=removes[:counts[2]].copy(),
                 r_new=int(counts[0]), gram_ops=int(ops.value), gamma=gamma, gamma_all=gamma_all)
+
+
+def assign_nearest(X, idx):
+    """Section 2.3: nearest representative of every token.  Returns dict(assign, corr)."""
+    X = _as_f64(X)
+    T, d = X.shape
+    R = np.ascontiguousarray(np.asarray(idx, dtype=np.int32))
+    assign = np.zeros(T, dtype=np.int32)
+    corr = np.zeros(T, dtype=np.float64)
+    _check(_load().ada_oracle_assign_nearest(_p(X, ctypes.c_double), T, d, _p(R, ctypes.c_int32), int(R.shape[0]),
+                                             _p(assign, ctypes.c_int32), _p(corr, ctypes.c_double)), "assign_nearest")
+    return dict(assign=assign, corr=corr)

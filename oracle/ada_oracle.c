@@ -12,6 +12,7 @@
  *   - lower-triangular max correlation, the set R  Definition "Gram threshold" (Section 2.2)
  *   - cascade step ............................... Algorithm 1 (Section 4.1)
  *   - Gram-operation count ....................... eq. (6) and Table 6 (one operation = one Gram entry)
+ *   - nearest-representative assignment .......... Section 2.3 (attention on the representative set)
  *
  * There is no blocking, fusion or reordering: a Gram entry is one left-to-right
  * dot product of two normalised rows in double precision.  The only concession
@@ -34,6 +35,9 @@
  *   R7  strict "<" against 1 - tau^2 evaluated in double; the empty max is 0.
  *   R8  removed representatives are not reconsidered as additions in the same step
  *       (they are not in the complement of the inherited set).
+ *   R14 nearest representative: the maximum of |G_ts| runs over the WHOLE set R handed in (earlier and later
+ *       tokens alike, as Section 2.3 states it); a member of R is its own representative with correlation 1;
+ *       among equal maxima the smallest token id is reported (any of them satisfies the text).
  */
 #include <math.h>
 #include <stdint.h>
@@ -275,5 +279,43 @@ int ada_oracle_cascade_step(const double* X, int T, int d, double tau, const int
     if (gamma_all) memcpy(gamma_all, g_all, (size_t)T * sizeof(double));
 
     free(Xhat); free(g); free(g_all); free(inherited); free(valid); free(is_new);
+    return ADA_ORACLE_OK;
+}
+
+/*
+ * Section 2.3: a token outside R takes the attention output of its nearest representative, the s* in R that
+ * maximises |G_{t s*}| (reading R14).  idx[r]: R as strictly ascending token ids.
+ * Outputs: assign[T] = token id of s*(t) (t itself for t in R); corr[T] (optional) = |G_{t s*}| (1 for t in R).
+ */
+int ada_oracle_assign_nearest(const double* X, int T, int d, const int32_t* idx, int r, int32_t* assign,
+                              double* corr) {
+    if (!X || !idx || !assign || T < 1 || d < 1) return ADA_ORACLE_ERR_ARG;
+    if (r < 1 || r > T) return ADA_ORACLE_ERR_ARG;
+    for (int j = 0; j < r; ++j) {
+        if (idx[j] < 0 || idx[j] >= T) return ADA_ORACLE_ERR_INDEX;
+        if (j > 0 && idx[j] <= idx[j - 1]) return ADA_ORACLE_ERR_INDEX;
+    }
+    double* Xhat = (double*)malloc((size_t)T * d * sizeof(double));
+    uint8_t* in_R = (uint8_t*)calloc((size_t)T, 1);
+    if (!Xhat || !in_R) { free(Xhat); free(in_R); return ADA_ORACLE_ERR_NOMEM; }
+    ada_oracle_normalize(X, T, d, Xhat, NULL);
+    for (int j = 0; j < r; ++j) in_R[idx[j]] = 1;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int t = 0; t < T; ++t) {
+        if (in_R[t]) {
+            assign[t] = t;
+            if (corr) corr[t] = 1.0;
+            continue;
+        }
+        double best = -1.0;
+        int arg = idx[0];
+        for (int j = 0; j < r; ++j) {                 /* ascending token ids: ">" keeps the smallest among equals */
+            double c = fabs(gram_entry(Xhat, d, t, idx[j]));
+            if (c > best) { best = c; arg = idx[j]; }
+        }
+        assign[t] = arg;
+        if (corr) corr[t] = best;
+    }
+    free(Xhat); free(in_R);
     return ADA_ORACLE_OK;
 }

@@ -392,3 +392,92 @@ def test_cascade_extreme_set_sizes():
     every = oracle.cascade_step(X, 0.1, list(range(20)))        # r = T: the cross step is empty
     assert every["idx"].tolist() == list(range(10)) and every["removes"].tolist() == list(range(10, 20))
     assert every["gram_ops"] == 400
+
+
+# ----------------------------------------------------------------------------- Section 2.3: nearest representative
+def exact_argmax_sets(X_int, R):
+    """For every token the set of members of R that maximise cos^2 = (x_t . x_s)^2 / (|x_t|^2 |x_s|^2), compared as
+    exact fractions by cross-multiplication of Python ints (no floating point), and the smallest relative gap between
+    the best and the runner-up so callers can reject inputs float64 could not rank."""
+    T = len(X_int)
+    sq = [sum(int(a) * int(a) for a in row) for row in X_int]
+    out, gap = [], math.inf
+    for t in range(T):
+        cand = []
+        for s in R:
+            dot = sum(int(a) * int(b) for a, b in zip(X_int[t], X_int[s]))
+            cand.append((dot * dot, sq[s], s))              # cos^2 up to the common factor 1 / |x_t|^2
+        best = cand[0]
+        for c in cand[1:]:
+            if c[0] * best[1] > best[0] * c[1]:
+                best = c
+        winners = [c[2] for c in cand if c[0] * best[1] == best[0] * c[1]]
+        for c in cand:
+            if c[2] not in winners and best[0] > 0:
+                gap = min(gap, (best[0] * c[1] - c[0] * best[1]) / (best[0] * c[1]))
+        out.append(winners)
+    return out, gap
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_assignment_agrees_with_exact_integer_argmax(seed):
+    rng = np.random.default_rng(400 + seed)
+    T, d = 18, 5
+    Xi = integer_tokens(rng, T, d, n_base=4)
+    R = sorted(rng.choice(T, size=int(rng.integers(1, 8)), replace=False).tolist())
+    winners, gap = exact_argmax_sets(Xi.tolist(), R)
+    if gap < 1e-9:
+        pytest.skip("a runner-up too close to the maximum for float64 to rank")
+    res = oracle.assign_nearest(Xi.astype(np.float64), R)
+    for t in range(T):
+        if t in R:
+            assert res["assign"][t] == t and res["corr"][t] == 1.0
+        else:
+            assert res["assign"][t] == min(winners[t])       # smallest token id among exact ties (e.g. +x and -x)
+            s = int(res["assign"][t])
+            dot = sum(int(a) * int(b) for a, b in zip(Xi[t], Xi[s]))
+            cos = abs(dot) / math.sqrt(sum(int(a) ** 2 for a in Xi[t]) * sum(int(b) ** 2 for b in Xi[s]))
+            assert res["corr"][t] == pytest.approx(cos, abs=1e-12)
+
+
+def test_assignment_matches_numpy_argmax_of_abs_gram():
+    rng = np.random.default_rng(77)
+    X = rng.standard_normal((120, 24))
+    R = sorted(rng.choice(120, size=17, replace=False).tolist())
+    G = np.abs(numpy_gram(X))[:, R]                          # independent float64 matmul
+    res = oracle.assign_nearest(X, R)
+    others = [t for t in range(120) if t not in R]
+    assert res["assign"][others].tolist() == [R[j] for j in G[others].argmax(axis=1)]
+    assert np.allclose(res["corr"][others], G[others].max(axis=1), atol=1e-13)
+    assert res["assign"][R].tolist() == R
+
+
+def test_assignment_sign_and_later_representatives_count():
+    # token 1 = -token 3 (|G| = 1 with a LATER member of R), token 2 nearer to 0 than to 3
+    X = np.array([[1.0, 0, 0], [0, -2.0, 0], [0.9, 0.1, 0], [0, 1.0, 0], [0, 0, 1.0]])
+    res = oracle.assign_nearest(X, [0, 3])
+    assert res["assign"].tolist() == [0, 3, 0, 3, 0]          # token 4 is orthogonal to both: smallest id among ties
+    assert res["corr"][1] == pytest.approx(1.0) and res["corr"][4] == 0.0
+
+
+def test_assignment_on_clustered_tokens_is_the_own_clusters_representative():
+    w = wl.small(T=300, d=64, K=40, L=1, dtype="f32", seed=11)
+    rng = np.random.default_rng(w.seed(0))
+    _ = rng.standard_normal((w.K, w.d), dtype=np.float32)    # replay the generator: centres, then the assignment
+    a = rng.integers(0, w.K, size=w.T)
+    X = wl.as_f64(wl.layer_list(w)[0])
+    full = oracle.select_full(X, w.tau)
+    res = oracle.assign_nearest(X, full["idx"])
+    first = {}
+    for t, c in enumerate(a):
+        first.setdefault(int(c), t)
+    assert res["assign"].tolist() == [first[int(c)] for c in a]
+    redundant = full["mask"] == 0
+    assert (res["corr"][redundant] >= 1.0 - w.tau ** 2).all()  # a covered token is within the threshold of its own
+
+
+def test_assignment_rejects_bad_sets():
+    X = np.eye(4)
+    for bad in ([], [2, 1], [1, 1], [0, 4], [-1]):
+        with pytest.raises(ValueError):
+            oracle.assign_nearest(X, bad)
