@@ -118,6 +118,28 @@ int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float t
                      void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
+ * Nearest-representative assignment -- Section 2.3 ("Attention on the representative set"): a token outside R
+ * takes the attention output of the member s* of R that maximises |G_{t s*}|.  The maximum runs over the whole
+ * set handed in (earlier and later tokens alike); a member of R is its own representative.  One launch: the
+ * T x r products on the cascade step's tile engine with an arg-max epilogue.
+ * Inputs
+ *   idx    device int32, strictly ascending token ids of R (the idx output of ada_select_full or ada_cascade_step)
+ *   r      number of entries if r_dev is NULL, otherwise an upper bound (capacity of idx, at most T)
+ *   r_dev  optional device int32 holding |R| (e.g. counts[0] of the call that produced idx)
+ * Outputs
+ *   assign [T] int32  token id of s*(t); t itself for t in R.  Among representatives whose |cosine| to t is equal
+ *                     in the fp32 arithmetic of the kernel the smallest token id is taken.
+ *   corr   [T] float  |G_{t s*(t)}|, 1 for t in R                                     (may be NULL)
+ *   info   [4] int32  {T - r (tokens represented by another token), 0, 0, status}; status is ADA_OK, or
+ *                     ADA_ERR_INDEX / ADA_ERR_SHAPE for a bad idx / r_dev, and then assign / corr hold no result
+ * Errors the host can see (null pointers, shapes, workspace) are returned before anything is enqueued.
+ */
+int ada_assign_nearest(const void* X, int T, int d, int64_t ld, int dtype,
+                       const int32_t* idx, int r, const int32_t* r_dev,
+                       int32_t* assign, float* corr, int32_t* info,
+                       void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
  * The layer loop of Section 4.1: full selection at layer 0, Algorithm 1 at layers 1..L-1, each
  * step inheriting the previous step's set on the device (no host synchronisation inside).
  *   X_layers     HOST array of L device pointers, one T x d matrix per layer
@@ -155,7 +177,7 @@ int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* 
  * kernel, so these figures are upper bounds of the durations a kernel trace reports.
  */
 enum { ADA_K_NORM_PREP = 0, ADA_K_GRAM_FULL = 1, ADA_K_GRAM_REP = 2, ADA_K_GRAM_CROSS = 3, ADA_K_UPDATE = 4,
-       ADA_K_CASCADE_FUSED = 5, ADA_K_MFMA_PROBE = 6, ADA_K_COUNT = 7 };
+       ADA_K_CASCADE_FUSED = 5, ADA_K_MFMA_PROBE = 6, ADA_K_ASSIGN = 7, ADA_K_COUNT = 8 };
 int ada_profile_enable(int on);
 int ada_profile_collect(double* ms_sum, int* launches);
 /* A plain device-to-device copy kernel (bytes: multiple of 16, both pointers 16-byte aligned): it reads and writes

@@ -25,9 +25,9 @@ OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
            "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
-           "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe")
+           "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest")
 
-KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused", "mfma_probe")
+KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused", "mfma_probe", "assign")
 
 
 class AdaError(RuntimeError):
@@ -90,6 +90,8 @@ def lib():
         L.ada_profile_copy_probe.argtypes = [vp, vp, sz, vp]
         L.ada_profile_mfma_probe.restype = i32
         L.ada_profile_mfma_probe.argtypes = [i32, i32, vp, vp]
+        L.ada_assign_nearest.restype = i32
+        L.ada_assign_nearest.argtypes = [vp, i32, i32, i64, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp, u32]
         _lib = L
     return _lib
 
@@ -185,6 +187,33 @@ def ada_cascade_step(X: torch.Tensor, tau: float, prev_idx: torch.Tensor, r: Opt
     if rc != OK:
         raise AdaError(rc, "ada_cascade_step")
     out["_keep"] = (ws, prev_idx, r_dev)
+    return out
+
+
+def ada_assign_nearest(X: torch.Tensor, idx: torch.Tensor, r: Optional[int] = None,
+                       r_dev: Optional[torch.Tensor] = None, *, ws: Optional[torch.Tensor] = None, stream=None,
+                       flags: int = 0) -> Dict[str, torch.Tensor]:
+    """Nearest representative of every token (Section 2.3).  idx: device int32, ascending token ids of R; r
+    defaults to idx.numel() (an upper bound when r_dev is given).  Returns device tensors assign[T] (int32),
+    corr[T] (float32) and info[4] = {T - r, 0, 0, status}."""
+    _check_x(X)
+    T, d = X.shape
+    dev = X.device
+    if idx.dtype != torch.int32 or not idx.is_cuda or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous int32 device tensor")
+    r = int(idx.numel()) if r is None else int(r)
+    if r > idx.numel():
+        raise ValueError("r exceeds the capacity of idx")
+    ws = workspace(T, dev) if ws is None else ws
+    out = dict(assign=torch.empty(T, dtype=torch.int32, device=dev),
+               corr=torch.empty(T, dtype=torch.float32, device=dev),
+               info=torch.empty(4, dtype=torch.int32, device=dev))
+    rc = lib().ada_assign_nearest(_ptr(X), T, d, X.stride(0), _dtype_code(X), _ptr(idx), r, _ptr(r_dev),
+                                  _ptr(out["assign"]), _ptr(out["corr"]), _ptr(out["info"]), _ptr(ws), ws.numel(),
+                                  _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_assign_nearest")
+    out["_keep"] = (ws, idx, r_dev)
     return out
 
 

@@ -42,6 +42,11 @@ struct FusedParams {
     int32_t* removes;        // may be NULL
     int32_t* counts;         // [4]
     unsigned long long* gram_ops;   // may be NULL
+    // nearest-representative assignment (Section 2.3) instead of the cascade step: prev_idx is the set R itself
+    int assign_mode;
+    unsigned long long* best;       // [T], zero on entry and on exit: (bits of the max |cos|) << 32 | (INT_MAX - token id)
+    int32_t* assign;                // [T]
+    float* corr;                    // [T], may be NULL
 };
 
 // DMA = operands go global -> LDS directly (global_load_lds, 16 bytes per lane) through a ring of NS stages per
@@ -201,7 +206,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         };
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) issue(s, s);
-        mark_inherited();                                // its loads are younger than the ring's: the wait below covers stage 0
+        if (!p.assign_mode) mark_inherited();            // its loads are younger than the ring's: the wait below covers stage 0
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
         ADA_CLK(2);
         __builtin_amdgcn_s_barrier();
@@ -258,7 +263,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         fetch(s, s);
         __builtin_amdgcn_sched_barrier(0);
     }
-    mark_inherited();
+    if (!p.assign_mode) mark_inherited();
     store(buf0, 0, 0);
     fetch(0, D);
     __builtin_amdgcn_sched_barrier(0);
@@ -356,6 +361,27 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
             tk4[q] = *reinterpret_cast<const i32x4*>(s_tok + a * 32 + 8 * q + 4 * half);
         }
         const float tsc = scale[B + nl];
+        if (p.assign_mode) {                              // uniform
+            // Section 2.3: the largest |cos| over this tile's representatives and who holds it.  A non-negative float
+            // orders like its bit pattern, so (bits << 32 | INT_MAX - token id) under an integer max is an exact,
+            // order-independent arg max that prefers the smaller token id among equals; padding rows (token id
+            // INT_MAX, scale 0) give key 0 and never win.
+            unsigned long long key = 0ull;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float v = ((part[0][q][e] + part[1][q][e]) + part[2][q][e]) + part[3][q][e];
+                    const float c = (fabsf(v) * sc4[q][e]) * tsc;
+                    const unsigned long long k = ((unsigned long long)__float_as_uint(c) << 32) |
+                                                 (unsigned long long)(uint32_t)(INT_MAX - tk4[q][e]);
+                    key = k > key ? k : key;
+                }
+            const unsigned long long other = ((unsigned long long)(uint32_t)__shfl_xor((int)(key >> 32), 32, 64) << 32) |
+                                             (unsigned long long)(uint32_t)__shfl_xor((int)(uint32_t)key, 32, 64);
+            key = other > key ? other : key;
+            if (half == 0 && t < p.T) atomicMax(p.best + t, key);
+        } else {
         const bool ordered = repf[nl] != 0 || p.earlier_only;   // only earlier representatives count
         uint32_t bits = 0u;
         float m = 0.f;
@@ -374,6 +400,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         if (half == 0 && t < p.T) {
             p.hits[(size_t)(sb * 2 + a) * p.T + t] = bits;        // word-major: 32 lanes store 32 consecutive words
             if (p.gamma && m > 0.f) atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
+        }
         }
     }
     ADA_CLK(5);
@@ -533,6 +560,39 @@ __device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, int 
     }
 }
 
+// Section 2.3, last step (run by one workgroup): unpack the per-token arg max, make every member of R its own
+// representative, check the list, and leave the key table zero for the next call.
+// info[0] = tokens represented by another token (T - r), info[3] = status.
+template <int THREADS>
+__device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int q0, int qp0) {
+    const int tid = threadIdx.x;
+    const int T = p.T;
+    for (int t = tid; t < T; t += THREADS) {
+        const unsigned long long key = p.best[t];
+        p.best[t] = 0ull;
+        p.assign[t] = INT_MAX - (int)(uint32_t)key;
+        if (p.corr) p.corr[t] = __uint_as_float((uint32_t)(key >> 32));
+    }
+    int ok = 1;
+    __syncthreads();                                     // fenced: the stores above have completed before a member of R
+    if (r_ok) {                                          // is overwritten with itself by another thread
+        for (int j = tid; j < r; j += THREADS) {
+            const int q = j < THREADS ? q0 : p.prev_idx[j];
+            const int qp = j < THREADS ? qp0 : p.prev_idx[j - 1];
+            if (q < 0 || q >= T || (j > 0 && !(qp < q))) { ok = 0; continue; }
+            p.assign[q] = q;
+            if (p.corr) p.corr[q] = 1.0f;
+        }
+    }
+    ok = __syncthreads_and(ok);
+    if (tid == 0) {
+        const int status = !r_ok ? ADA_ERR_SHAPE : (!ok ? ADA_ERR_INDEX : ADA_OK);
+        p.counts[0] = status == ADA_OK ? T - r : 0;
+        p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = status;
+        *p.ticket = 0;
+    }
+}
+
 // Grid: a multiple of 8 workgroups (see k_gram for the XCD-aware tile ranges); tiles with the representative
 // block fastest, so one XCD's L2 serves a contiguous range of tested rows.
 template <typename In, bool ALIGNED, int KG, bool DMA>
@@ -578,6 +638,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     ADA_CLK_LAST(8);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");       // see the other workgroups' hit words, not stale lines
     ADA_CLK_LAST(9);
-    fused_update<G::THREADS>(p, r, r_ok, q0, qp0, lds + G::META, reinterpret_cast<int*>(lds + G::OFF_SCAN));
+    if (p.assign_mode) assign_finish<G::THREADS>(p, r, r_ok, q0, qp0);
+    else fused_update<G::THREADS>(p, r, r_ok, q0, qp0, lds + G::META, reinterpret_cast<int*>(lds + G::OFF_SCAN));
     ADA_CLK_LAST(15);
 }

@@ -50,6 +50,7 @@ struct Workspace {
     uint8_t* is_rep;     // [T]
     int32_t* meta;       // [META_WORDS]; meta[META_TICKET] and the META_QUEUE pair are zero between calls
     uint32_t* hits;      // [T][hit_words(T)] (only for T <= FUSED_MAX_T)
+    unsigned long long* best;   // [T] arg-max keys of the assignment; zero between calls
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -58,7 +59,7 @@ inline int hit_words(int r_cap) { return 2 * ((r_cap + 63) / 64); }
 inline size_t ws_bytes_for(int T) {
     size_t t4 = align_up((size_t)T * 4, 256), t1 = align_up((size_t)T, 256);
     size_t hits = T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0;
-    return t4 * 3 + t1 + 256 + hits;
+    return t4 * 3 + t1 + 256 + hits + align_up((size_t)T * 8, 256);
 }
 
 inline Workspace carve(void* ws, int T) {
@@ -70,7 +71,8 @@ inline Workspace carve(void* ws, int T) {
     w.nonrep_idx = (int32_t*)p; p += t4;
     w.is_rep = (uint8_t*)p; p += t1;
     w.meta = (int32_t*)p; p += 256;
-    w.hits = (uint32_t*)p;
+    w.hits = (uint32_t*)p; p += T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0;
+    w.best = (unsigned long long*)p;
     return w;
 }
 
@@ -855,7 +857,7 @@ hipError_t fill_u32(void* p, size_t n_words, uint32_t v, hipStream_t st) {
 }
 
 template <typename In, bool ALIGNED, int KG, bool DMA>
-hipError_t launch_fused(const FusedParams& p, hipStream_t st) {
+hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = ADA_K_CASCADE_FUSED) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     constexpr int lds = FusedGeom<KG, DMA>::LDS;
@@ -870,7 +872,7 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st) {
     const long long cap = p.r_dev ? 512 : 2048;
     if (tiles > cap) tiles = cap;
     const unsigned grid = (unsigned)(tiles + 7) / 8 * 8;             // multiple of 8 (XCDs)
-    ProfScope ps(ADA_K_CASCADE_FUSED, st);
+    ProfScope ps(prof_class, st);
     hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG, DMA>), dim3(grid), dim3(256 * KG), lds, st, p);
     return hipGetLastError();
 }
@@ -880,6 +882,27 @@ int kgroups_override() {
     if (!e) return 0;
     const int v = atoi(e);
     return (v == 1 || v == 2) ? v : 0;
+}
+
+// Picks the form of the one-launch kernel: two K-groups unless overridden; direct-to-LDS operand loads when rows come
+// in whole, aligned 128-byte chunks.
+int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_t st) {
+    int kg = 2;
+    if (int o = kgroups_override()) kg = o;
+    const char* no_dma = getenv("ADA_NO_DMA");
+    hipError_t e = dispatch(dtype, p.X, p.ld, p.d, [&](auto v) {
+        using V = decltype(v);
+        using In = typename V::In;
+        constexpr int epc = 128 / (int)sizeof(In);
+        if constexpr (V::aligned) {
+            if (p.d % epc == 0 && !(no_dma && no_dma[0] == '1'))
+                return kg == 2 ? launch_fused<In, true, 2, true>(p, st, prof_class)
+                               : launch_fused<In, true, 1, true>(p, st, prof_class);
+        }
+        return kg == 2 ? launch_fused<In, V::aligned, 2, false>(p, st, prof_class)
+                       : launch_fused<In, V::aligned, 1, false>(p, st, prof_class);
+    });
+    return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
 // Algorithm 1 in one launch (ada_fused.hpp).  gamma, if given, receives for an inherited token gamma^rep and for any
@@ -892,22 +915,17 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
     const FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
                            (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
                            w.meta + META_TICKET, idx, adds, removes, counts,
-                           reinterpret_cast<unsigned long long*>(gram_ops)};
-    int kg = 2;
-    if (int o = kgroups_override()) kg = o;
-    const char* no_dma = getenv("ADA_NO_DMA");
-    hipError_t e = dispatch(dtype, X, ld, d, [&](auto v) {
-        using V = decltype(v);
-        using In = typename V::In;
-        // direct-to-LDS operand loads need whole, aligned 128-byte row chunks
-        constexpr int epc = 128 / (int)sizeof(In);
-        if constexpr (V::aligned) {
-            if (d % epc == 0 && !(no_dma && no_dma[0] == '1'))
-                return kg == 2 ? launch_fused<In, true, 2, true>(p, st) : launch_fused<In, true, 1, true>(p, st);
-        }
-        return kg == 2 ? launch_fused<In, V::aligned, 2, false>(p, st) : launch_fused<In, V::aligned, 1, false>(p, st);
-    });
-    return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr};
+    return launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
+}
+
+// Section 2.3 on the same tile engine: T x r products against the set R, per-token arg max.
+int run_assign(const void* X, int T, int d, long long ld, int dtype, const int32_t* idx, int r, const int32_t* r_dev,
+               int32_t* assign, float* corr, int32_t* info, void* ws, hipStream_t st) {
+    const Workspace w = carve(ws, T);
+    const FusedParams p = {X, ld, T, d, idx, r_dev, r, 2.0f, 0, nullptr, 0, nullptr, w.meta + META_TICKET,
+                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr};
+    return launch_fused_any(p, dtype, ADA_K_ASSIGN, st);
 }
 
 // Algorithm 1 in separate launches (norms + lists, r x r Gram, cross-Gram against the valid representatives, update):
@@ -981,6 +999,16 @@ int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float ta
     if (!mask || !count) return ADA_ERR_NULL;
     if (int e = check_common(X, T, d, ld, dtype, tau, ws, ws_bytes)) return e;
     return run_full(X, T, d, ld, dtype, tau, mask, idx, count, nullptr, gamma, ws, (hipStream_t)stream);
+}
+
+int ada_assign_nearest(const void* X, int T, int d, int64_t ld, int dtype, const int32_t* idx, int r,
+                       const int32_t* r_dev, int32_t* assign, float* corr, int32_t* info, void* ws, size_t ws_bytes,
+                       void* stream, unsigned flags) {
+    (void)flags;
+    if (!idx || !assign || !info) return ADA_ERR_NULL;
+    if (int e = check_common(X, T, d, ld, dtype, 0.5f, ws, ws_bytes)) return e;
+    if (r < 1 || r > T) return ADA_ERR_SHAPE;
+    return run_assign(X, T, d, ld, dtype, idx, r, r_dev, assign, corr, info, ws, (hipStream_t)stream);
 }
 
 int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float tau, const int32_t* prev_idx, int r,

@@ -67,3 +67,29 @@ def check_cascade(x_cpu, tau, prev_idx, got, flags=0, what="", two_pass=False):
     assert got["gram_ops"] == ref["gram_ops"], what
     assert got["r"] == ref["r_new"] and got["n_adds"] == len(ref["adds"]) and got["n_removes"] == len(ref["removes"])
     return dict(ref=ref, gamma_err=err, n_band=int((force >= 0).sum()))
+
+
+def check_assign(x_cpu, idx, got_assign, got_corr, what=""):
+    """Section 2.3.  corr within GAMMA_TOL of the oracle; members of R map to themselves; for every other token
+    the GPU's choice must be a member of R whose float64 |cosine| is within 2*GAMMA_TOL of the float64 maximum
+    (several maximisers can be valid), and must equal the oracle's choice whenever the float64 runner-up is more
+    than 2*GAMMA_TOL below the maximum (then the maximiser is unique at the kernel's accuracy)."""
+    X = wl.as_f64(x_cpu)
+    T = X.shape[0]
+    idx = np.asarray(idx, dtype=np.int32)
+    ref = oracle.assign_nearest(X, idx)
+    err = float(np.max(np.abs(got_corr.astype(np.float64) - ref["corr"])))
+    assert err <= GAMMA_TOL, "%s corr error %.3g" % (what, err)
+    in_R = np.zeros(T, dtype=bool)
+    in_R[idx] = True
+    assert np.array_equal(got_assign[in_R], np.flatnonzero(in_R)), what
+    assert in_R[got_assign].all(), "%s: assigned to a token outside R" % what
+    Xn, _ = oracle.normalize(X)
+    others = np.flatnonzero(~in_R)
+    chosen = np.abs(np.einsum("ij,ij->i", Xn[others], Xn[got_assign[others]]))
+    assert (chosen >= ref["corr"][others] - 2 * GAMMA_TOL).all(), what
+    differ = others[got_assign[others] != ref["assign"][others]]
+    for t in differ:          # only legitimate when another member of R is as close as the oracle's choice
+        c = np.sort(np.abs(Xn[idx] @ Xn[t]))
+        assert c[-1] - c[-2] <= 2 * GAMMA_TOL, "%s token %d: unique maximiser missed" % (what, t)
+    return dict(ref=ref, corr_err=err, n_differ=int(len(differ)))

@@ -375,3 +375,81 @@ def test_config4_one_sequence_sampled():
     assert np.array_equal(full["mask"][rows], (ref < parity.thr_of(w.tau)).astype(np.uint8))
     for flags in (0, pa.FLAG_TWO_PASS):
         step_and_check(xs[1], xs_cpu[1], w.tau, full["idx"], flags, w.name + " layer 1")
+
+
+# ------------------------------------------------------------------------------------------ Section 2.3: assignment
+def assign_and_check(x_cpu, idx, what, **kw):
+    res = pa.ada_assign_nearest(x_cpu.to(DEV), torch.as_tensor(np.asarray(idx, dtype=np.int32)).to(DEV), **kw)
+    info = res["info"].cpu().tolist()
+    assert info[3] == 0 and info[0] == x_cpu.shape[0] - len(idx), what
+    return parity.check_assign(x_cpu, idx, res["assign"].cpu().numpy(), res["corr"].cpu().numpy(), what)
+
+
+@pytest.mark.parametrize("T,d,K,dtype", [(333, 200, 40, "bf16"), (700, 4096, 120, "bf16"), (513, 768, 100, "f32"),
+                                         (1000, 64, 90, "bf16"), (129, 33, 8, "f32"), (1, 64, 1, "bf16")])
+def test_assignment_small_shapes(T, d, K, dtype):
+    """Nearest representatives of the full selection's set and of a cascade step's set, on ragged shapes that take
+    the direct-to-LDS and the register-staged loaders."""
+    say("assign T=%d d=%d %s" % (T, d, dtype))
+    w = wl.small(T=T, d=d, K=K, L=2, dtype=dtype, seed=61 + T, p=0.1)
+    xs = wl.layer_list(w)
+    full = pa.fetch(pa.ada_select_full(xs[0].to(DEV), w.tau))
+    assign_and_check(xs[0], full["idx"], "assign after full T=%d" % T)
+    step = pa.fetch(pa.ada_cascade_step(xs[1].to(DEV), w.tau, torch.as_tensor(full["idx"]).to(DEV)))
+    assign_and_check(xs[1], step["idx"], "assign after cascade T=%d" % T)
+
+
+@pytest.mark.parametrize("kgroups", ["1", "2"])
+def test_assignment_forms_and_device_count(kgroups, monkeypatch):
+    monkeypatch.setenv("ADA_KGROUPS", kgroups)
+    say("assign forms kgroups=%s" % kgroups)
+    w = wl.small(T=600, d=256, K=70, L=1, dtype="bf16", seed=7, p=0.1)
+    x = wl.layer_list(w)[0]
+    out = pa.ada_select_full(x.to(DEV), w.tau)
+    full = pa.fetch(out)
+    # chained on the device: idx buffer of capacity T, size taken from the selection's count
+    res = pa.ada_assign_nearest(x.to(DEV), out["idx"], r=w.T, r_dev=out["counts"])
+    assert res["info"].cpu().tolist() == [w.T - full["r"], 0, 0, 0]
+    parity.check_assign(x, full["idx"], res["assign"].cpu().numpy(), res["corr"].cpu().numpy(), "r_dev")
+
+
+def test_assignment_extremes_signs_and_ties():
+    say("assign extremes")
+    rng = np.random.default_rng(5)
+    X = torch.tensor(rng.standard_normal((96, 48)), dtype=torch.float32)
+    X[40] = -X[3]                      # |G| = 1 with an earlier member, opposite sign
+    X[10] = X[80]                      # duplicate of a LATER member of R
+    X[50] = 0.0                        # zero row: every cosine 0 -> smallest member of R
+    R = [3, 7, 80, 90]
+    got = assign_and_check(X, R, "extremes")
+    a = pa.ada_assign_nearest(X.to(DEV), torch.tensor(R, dtype=torch.int32, device=DEV))["assign"].cpu().tolist()
+    assert a[40] == 3 and a[10] == 80 and a[50] == 3 and got["n_differ"] == 0
+    assign_and_check(X, [0], "single representative")
+    assign_and_check(X, list(range(96)), "everybody is a representative")
+
+
+def test_assignment_rejects_bad_sets_on_the_device_and_leaves_the_workspace_clean():
+    say("assign bad sets")
+    w = wl.small(T=200, d=64, K=20, L=1, dtype="bf16", seed=3)
+    x = wl.layer_list(w)[0]
+    xd = x.to(DEV)
+    ws = pa.workspace(w.T, DEV)
+    for bad in ([5, 4, 9], [0, 0, 1], [0, 300], [-1, 2]):
+        res = pa.ada_assign_nearest(xd, torch.tensor(bad, dtype=torch.int32, device=DEV), ws=ws)
+        assert res["info"].cpu().tolist()[3] == 4, bad            # ADA_ERR_INDEX
+    zero = torch.zeros(1, dtype=torch.int32, device=DEV)
+    res = pa.ada_assign_nearest(xd, torch.tensor([1, 2, 3], dtype=torch.int32, device=DEV), r_dev=zero, ws=ws)
+    assert res["info"].cpu().tolist()[3] == 2                     # ADA_ERR_SHAPE
+    full = pa.fetch(pa.ada_select_full(xd, w.tau, ws=ws))        # the same workspace still serves every call
+    parity.check_full(x, w.tau, full, "after bad sets")
+    res = pa.ada_assign_nearest(xd, torch.as_tensor(full["idx"]).to(DEV), ws=ws)
+    parity.check_assign(x, full["idx"], res["assign"].cpu().numpy(), res["corr"].cpu().numpy(), "after bad sets")
+
+
+def test_assignment_at_config2_size():
+    say("assign config 2")
+    w = wl.config(2)
+    x = next(iter(wl.layers(w, 0, 1)))
+    full = pa.fetch(pa.ada_select_full(x.to(DEV), w.tau))
+    got = assign_and_check(x, full["idx"], "config 2")
+    assert got["n_differ"] == 0                                   # clusters: the maximiser is unique by a wide margin

@@ -95,6 +95,13 @@ def test_host_checkable_errors_return_before_touching_the_device(ada):
     assert _call_step(ada, r=0) == SHAPE
     assert _call_step(ada, r=9) == SHAPE
     lib = ada.lib()
+
+    def assign(X=0x1000, T=8, d=8, ld=8, dtype=1, idx=0x1000, r=2, out=0x1000, info=0x1000, ws=0x1000, nb=1 << 20):
+        return lib.ada_assign_nearest(X, T, d, ld, dtype, idx, r, None, out, None, info, ws, nb, None, 0)
+    assert assign(X=None) == NULL and assign(idx=None) == NULL and assign(out=None) == NULL
+    assert assign(info=None) == NULL and assign(ws=None) == NULL
+    assert assign(r=0) == SHAPE and assign(r=9) == SHAPE and assign(T=0) == SHAPE and assign(ld=7) == SHAPE
+    assert assign(dtype=3) == DTYPE and assign(nb=64) == WS
     assert lib.ada_set_overlap(None, 0x1000, 4, 0x1000, None) == NULL
     assert lib.ada_set_overlap(0x1000, 0x1000, 0, 0x1000, None) == SHAPE
     ptrs = (ctypes.c_void_p * 2)(0x1000, None)
