@@ -238,6 +238,24 @@ def main():
                                               "traffic": recorded_traffic("gram_full_c%d_pmc.txt" % args.config)},
                                  "mean_jaccard_independent": sum(jac) / len(jac)}
 
+        # ---- nearest-representative assignment (Section 2.3) for the last layer's set: T x r products, arg max
+        last = out["idx"][L - 1]
+        for _ in range(2):
+            pa.ada_assign_nearest(xs[L - 1], last, r=T, r_dev=out["counts"][L - 1], ws=ws, stream=stream)
+        torch.cuda.synchronize()
+        pa.ada_profile_enable(True)
+        for l in range(L):                                   # rotate over the layer buffers: operands come from HBM
+            pa.ada_assign_nearest(xs[l], last, r=T, r_dev=out["counts"][L - 1], ws=ws, stream=stream)
+        torch.cuda.synchronize()
+        ka = pa.ada_profile_collect()
+        pa.ada_profile_enable(False)
+        us_a = 1e3 * ka["assign"]["ms"] / ka["assign"]["launches"]
+        result["assign_nearest"] = {"avg_launch_us": us_a, "r": r_per_layer[L - 1],
+                                    "roofline": {"bound": "hbm", "kernel": "k_cascade_fused (arg-max epilogue)",
+                                                 "achieved": casc_bytes / (1e-6 * us_a) / 1e9, "peak": HBM_PEAK_GBS,
+                                                 "unit": "GB/s", "frac": casc_bytes / (1e-6 * us_a) / 1e9 / HBM_PEAK_GBS,
+                                                 "bytes_per_launch": casc_bytes, "traffic": None}}
+
         # ---- the same selection at the long-context shape (configs[4]: T=8192, d=4096, one sequence), where the
         # triangle has enough tiles to fill the chip and the kernel is bound by the matrix pipes
         w4 = wl.config(4)
