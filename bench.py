@@ -168,15 +168,24 @@ def main():
         pa.ada_profile_enable(False)
         avg_us = {k: (1e3 * v["ms"] / v["launches"] if v["launches"] else None) for k, v in kern.items()}
         casc_s = 1e-6 * avg_us["cascade_fused"]
-        # algorithmic bytes of one cascade launch: every row of X once (all T rows are tested rows, the r inherited
-        # rows are also the resident operand) = T*d*e bytes; the O(T*r/8) hit words and O(T) outputs are neglected
-        casc_bytes = T * d * esz
-        casc_flops = 2.0 * d * T * r_prev_mean            # T x r Gram entries of eq. (6), 2d flops each
-        result["roofline"] = {"bound": "hbm", "kernel": "k_cascade_fused (Algorithm 1 in one launch)",
+        # The cascade layers of a pass run in one resident launch (k_cascade_pass) when the shape allows, else one
+        # launch per layer: the units of a launch are the layers it processes.
+        layers_per_launch = (L - 1) * args.steps / kern["cascade_fused"]["launches"]
+        # algorithmic bytes per layer: every row of X once (all T rows are tested rows, the r inherited rows are also
+        # the resident operand) = T*d*e bytes; the O(T*r/8) hit words and O(T) outputs are neglected
+        layer_bytes = T * d * esz
+        casc_bytes = layers_per_launch * layer_bytes
+        casc_flops = layers_per_launch * 2.0 * d * T * r_prev_mean   # T x r Gram entries of eq. (6), 2d flops each
+        traffic_layer = recorded_traffic("cascade_fused_c%d_pmc.txt" % args.config)
+        result["roofline"] = {"bound": "hbm",
+                              "kernel": "k_cascade_pass (Algorithm 1, %g layers per resident launch)" % layers_per_launch
+                                        if layers_per_launch > 1 else "k_cascade_fused (Algorithm 1 in one launch)",
                               "achieved": casc_bytes / casc_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": casc_bytes / casc_s / 1e9 / HBM_PEAK_GBS,
-                              "traffic": recorded_traffic("cascade_fused_c%d_pmc.txt" % args.config),
-                              "avg_launch_us": avg_us["cascade_fused"], "bytes_per_launch": casc_bytes,
+                              "traffic": None if traffic_layer is None else int(traffic_layer * layers_per_launch),
+                              "avg_launch_us": avg_us["cascade_fused"], "layers_per_launch": layers_per_launch,
+                              "us_per_layer": avg_us["cascade_fused"] / layers_per_launch,
+                              "bytes_per_launch": casc_bytes,
                               "mfma_tflops": casc_flops / casc_s / 1e12,
                               "mfma_frac": casc_flops / casc_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
         result["kernel_avg_us"] = avg_us
@@ -215,6 +224,19 @@ def main():
         for l in range(1, L):
             o = pa.ada_set_overlap(masks[l - 1], masks[l]).cpu().tolist()
             jac.append(o[0] / o[1])
+        # ---- the same pass with the cascade layers in one resident launch (ADA_FLAG_RESIDENT_PASS)
+        for _ in range(2):
+            pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out, stream=stream, flags=pa.FLAG_RESIDENT_PASS)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out, stream=stream, flags=pa.FLAG_RESIDENT_PASS)
+        torch.cuda.synchronize()
+        res_elapsed = time.perf_counter() - t0
+        assert out["counts"][:, 3].cpu().tolist() == [0] * L, "resident pass reported an error"
+        result["resident_pass"] = {"ms_per_step": 1e3 * res_elapsed / args.steps,
+                                   "layers_per_s": L * args.steps / res_elapsed}
+
         # ---- what the matrix pipes sustain on this device with realistic operands (the published peak assumes the
         # full boost clock): one workgroup per CU, matrix instructions only
         n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
@@ -252,9 +274,9 @@ def main():
         us_a = 1e3 * ka["assign"]["ms"] / ka["assign"]["launches"]
         result["assign_nearest"] = {"avg_launch_us": us_a, "r": r_per_layer[L - 1],
                                     "roofline": {"bound": "hbm", "kernel": "k_cascade_fused (arg-max epilogue)",
-                                                 "achieved": casc_bytes / (1e-6 * us_a) / 1e9, "peak": HBM_PEAK_GBS,
-                                                 "unit": "GB/s", "frac": casc_bytes / (1e-6 * us_a) / 1e9 / HBM_PEAK_GBS,
-                                                 "bytes_per_launch": casc_bytes, "traffic": None}}
+                                                 "achieved": layer_bytes / (1e-6 * us_a) / 1e9, "peak": HBM_PEAK_GBS,
+                                                 "unit": "GB/s", "frac": layer_bytes / (1e-6 * us_a) / 1e9 / HBM_PEAK_GBS,
+                                                 "bytes_per_launch": layer_bytes, "traffic": None}}
 
         # ---- the same selection at the long-context shape (configs[4]: T=8192, d=4096, one sequence), where the
         # triangle has enough tiles to fill the chip and the kernel is bound by the matrix pipes

@@ -54,6 +54,14 @@ typedef enum {
                                           the one-launch form.  Sets, counts and gram_ops are identical; only the optional
                                           gamma output differs (see ada_cascade_step) */
 
+#define ADA_FLAG_RESIDENT_PASS 4u      /* ada_cascade_layers: run the cascade layers (up to 64 per launch) in ONE launch whose
+                                          workgroups stay resident and hand the set from layer to layer through device memory,
+                                          instead of one launch per layer.  Same results.  It needs every CU of the device for
+                                          itself (one workgroup per CU must be resident at once) and rows in whole, aligned
+                                          128-byte chunks; otherwise the flag is ignored.  The wait between layers is bounded:
+                                          if it runs out, the kernel ends and the unfinished layers report ADA_ERR_DEVICE in
+                                          their counts (initialise the workspace again after that) */
+
 #define ADA_MAX_T (1 << 20)
 
 /* Human-readable name of a status code (static storage). */
@@ -64,8 +72,9 @@ size_t ada_workspace_bytes(int T);
 
 /*
  * Zero-fills a workspace (one small kernel on the stream).  A workspace must be zero-filled once, by this call or
- * by any memset, before its first use; every library call leaves it ready for the next one.  If a call is
- * abandoned part-way (device error), initialise it again.
+ * by any memset, before its first use; every library call leaves it ready for the next one (it holds counters that
+ * the last workgroup of a launch resets).  If a call is abandoned part-way (device error), initialise it again.
+ * Calls that share a workspace must not overlap in time.
  */
 int ada_workspace_init(void* ws, size_t ws_bytes, void* stream);
 

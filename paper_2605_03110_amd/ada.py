@@ -21,6 +21,7 @@ SOURCES = ("ada_kernels.hip",)
 ADA_F32, ADA_BF16 = 0, 1
 FLAG_CROSS_EARLIER_ONLY = 1
 FLAG_TWO_PASS = 2
+FLAG_RESIDENT_PASS = 4
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",

@@ -36,7 +36,7 @@ struct FusedParams {
     uint32_t* hits;          // [W][T] word-major: word w of token t covers inherited representatives 32w .. 32w+31
     int W;                   // hit words per token (covers r_host)
     float* gamma;            // optional, zero on entry: max |cos| over the columns that count for the token
-    int32_t* ticket;         // zero on entry, zero again on exit
+    int32_t* ticket;         // zero on entry, zero again on exit; ticket[TICKET_XCD0 + 32 x] (x < 8): first-level counters
     int32_t* idx;
     int32_t* adds;           // may be NULL
     int32_t* removes;        // may be NULL
@@ -47,7 +47,31 @@ struct FusedParams {
     unsigned long long* best;       // [T], zero on entry and on exit: (bits of the max |cos|) << 32 | (INT_MAX - token id)
     int32_t* assign;                // [T]
     float* corr;                    // [T], may be NULL
+    // the list was written earlier in this same launch by another workgroup (k_cascade_pass): read it past the
+    // caches instead of invalidating them
+    int coherent_list;
 };
+
+// Last-arriver detection in two levels.  Atomics on one address are served one after the other at the memory side
+// (about 25 ns each here), so a single counter taken by 256 workgroups that finish together costs the last of them 6 us.
+// Workgroups first count per XCD (blockIdx % 8: eight counters on separate cache lines); the last of each XCD then
+// takes the device-wide ticket.  Called by one thread; true in exactly one workgroup, after all others have called.
+constexpr int TICKET_XCD0 = 64;                          // ints from the device-wide ticket to the first XCD counter
+__device__ inline bool take_ticket(int32_t* ticket) {
+    const int per = gridDim.x >> 3;                      // grids are multiples of 8
+    if (atomicAdd(ticket + TICKET_XCD0 + 32 * (blockIdx.x & 7), 1) != per - 1) return false;
+    return atomicAdd(ticket, 1) == 7;
+}
+__device__ inline void reset_tickets(int32_t* ticket) {   // by the last arriver: nobody else touches them any more
+    __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+        __hip_atomic_store(ticket + TICKET_XCD0 + 32 * x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline int list_at(const FusedParams& p, int j) {
+    return p.coherent_list ? __hip_atomic_load(p.prev_idx + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : p.prev_idx[j];
+}
 
 // DMA = operands go global -> LDS directly (global_load_lds, 16 bytes per lane) through a ring of NS stages per
 // K-group; otherwise they pass through registers (needed when a row chunk can be ragged or unaligned).
@@ -121,12 +145,12 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
         const int li = s0 + rb + 32 * j;                 // only used for rows 0..63 (representatives)
-        ptok[j] = p.prev_idx[li < r ? li : r - 1];
+        ptok[j] = list_at(p, li < r ? li : r - 1);
     }
     if (tid < B) {
         const int li = s0 + tid;
         const bool ok = li < r;
-        int tok = p.prev_idx[ok ? li : r - 1];
+        int tok = list_at(p, ok ? li : r - 1);
         tok = min(max(tok, 0), p.T - 1);
         s_tok[tid] = ok ? tok : INT_MAX;
         repf[tid] = 0;
@@ -136,7 +160,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
     // (the flags are not read before the epilogue)
     auto mark_inherited = [&]() {
         for (int j = tid; j < r; j += G::THREADS) {
-            const unsigned q = (unsigned)(p.prev_idx[j] - t0);
+            const unsigned q = (unsigned)(list_at(p, j) - t0);
             if (q < (unsigned)B) repf[q] = 1;
         }
     };
@@ -398,7 +422,10 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
         m = fmaxf(m, __shfl_xor(m, 32, 64));
         if (half == 0 && t < p.T) {
-            p.hits[(size_t)(sb * 2 + a) * p.T + t] = bits;        // word-major: 32 lanes store 32 consecutive words
+            // word-major: 32 lanes store 32 consecutive words.  The store is a device-scope atomic (written through
+            // the L2 to where every XCD sees it), so that handing the words over needs no L2 write-back: a write-back
+            // per workgroup serialises on the L2 and was the longest single wait of the step.
+            __hip_atomic_store(p.hits + (size_t)(sb * 2 + a) * p.T + t, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (p.gamma && m > 0.f) atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
         }
         }
@@ -435,8 +462,9 @@ __device__ inline unsigned long long block_exclusive_scan64(unsigned long long v
 // in flight before the first use.  One CU's load path is what this phase costs, so nothing is fetched twice:
 // the first THREADS list entries arrive in registers (q0 / qp0, loaded before the ticket), representatives take one
 // batch each, and the token pass reads four tokens per 16-byte load when T allows.
+// Returns |R^(l+1)| to every thread (0 if the step is rejected).
 template <int THREADS>
-__device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, int q0, int qp0, char* lds, int* scan_scratch) {
+__device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q0, int qp0, char* lds, int* scan_scratch) {
     constexpr int WU = 15;                              // hit words fetched per batch by one thread
     const int tid = threadIdx.x, lane = tid & 63;
     const int T = p.T;
@@ -459,8 +487,8 @@ __device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, int 
     int ok = 1;
     if (r_ok) {
         for (int j = tid; j < r; j += THREADS) {
-            const int q = j < THREADS ? q0 : p.prev_idx[j];
-            const int qp = j < THREADS ? qp0 : p.prev_idx[j - 1];
+            const int q = j < THREADS ? q0 : list_at(p, j);
+            const int qp = j < THREADS ? qp0 : list_at(p, j - 1);
             if (q < 0 || q >= T || (j > 0 && !(qp < q))) ok = 0;
             const int tok = min(max(q, 0), T - 1);
             uint32_t any = 0u;
@@ -485,9 +513,9 @@ __device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, int 
         if (tid == 0) {
             p.counts[0] = 0; p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = status;
             if (p.gram_ops) *p.gram_ops = 0ull;
-            *p.ticket = 0;
+            reset_tickets(p.ticket);
         }
-        return;
+        return 0;
     }
     ADA_CLK_LAST(12);
     // step 9: any other token with a hit on a VALID representative is covered
@@ -556,8 +584,9 @@ __device__ inline void fused_update(const FusedParams& p, int r, bool r_ok, int 
             const unsigned long long TT = (unsigned long long)T, rr = (unsigned long long)r;
             *p.gram_ops = rr * rr + (TT - rr) * (unsigned long long)(r - n_rem);   // entries Algorithm 1 needs
         }
-        *p.ticket = 0;                                    // leave the workspace ready for the next call
+        reset_tickets(p.ticket);                                    // leave the workspace ready for the next call
     }
+    return n_idx;
 }
 
 // Section 2.3, last step (run by one workgroup): unpack the per-token arg max, make every member of R its own
@@ -577,8 +606,8 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
     __syncthreads();                                     // fenced: the stores above have completed before a member of R
     if (r_ok) {                                          // is overwritten with itself by another thread
         for (int j = tid; j < r; j += THREADS) {
-            const int q = j < THREADS ? q0 : p.prev_idx[j];
-            const int qp = j < THREADS ? qp0 : p.prev_idx[j - 1];
+            const int q = j < THREADS ? q0 : list_at(p, j);
+            const int qp = j < THREADS ? qp0 : list_at(p, j - 1);
             if (q < 0 || q >= T || (j > 0 && !(qp < q))) { ok = 0; continue; }
             p.assign[q] = q;
             if (p.corr) p.corr[q] = 1.0f;
@@ -589,7 +618,7 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
         const int status = !r_ok ? ADA_ERR_SHAPE : (!ok ? ADA_ERR_INDEX : ADA_OK);
         p.counts[0] = status == ADA_OK ? T - r : 0;
         p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = status;
-        *p.ticket = 0;
+        reset_tickets(p.ticket);
     }
 }
 
@@ -603,7 +632,6 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     ADA_CLK(0);
     const int r = p.r_dev ? *p.r_dev : p.r_host;
     const bool r_ok = r >= 1 && r <= p.r_host && r <= p.T;
-    bool worked = false;
     if (r_ok) {
         const long long nbS = (r + 63) / 64, nbT = (p.T + 63) / 64;
         const long long ntiles = nbS * nbT;
@@ -614,31 +642,140 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
             if (tile >= ntiles) break;
             const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
             fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
-            worked = true;
             __syncthreads();
         }
     }
-    // The workgroup that takes the last ticket finishes the step.  A workgroup that stored hit words makes them
-    // visible device-wide first: every thread waits for its own stores, then ONE thread issues the release (an L2
-    // write-back is a per-cache operation, so one per workgroup is enough and thousands would serialise).
+    // The workgroup that takes the last ticket finishes the step.  Hit words and row maxima leave the CU as
+    // device-scope atomics (written through the L2), so once every thread's stores are acknowledged (vmcnt(0)) and
+    // the workgroup has met at the barrier, the ticket can be taken: nothing is left in the L2 to write back.
     ADA_CLK(6);
     // the update phase's first slice of the inherited list: input data, so it can be fetched behind the store drain
     // (entries below r_host are the caller's memory whatever r turns out to be)
     const int jq = min((int)threadIdx.x, max(p.r_host, 1) - 1);
-    const int q0 = p.prev_idx[jq], qp0 = p.prev_idx[max(jq - 1, 0)];
+    const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this thread's stores have left the CU
     __syncthreads();
-    if (threadIdx.x == 0) {
-        if (worked) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        s_last = (atomicAdd(p.ticket, 1) == (int)gridDim.x - 1) ? 1 : 0;
-    }
+    if (threadIdx.x == 0) s_last = take_ticket(p.ticket) ? 1 : 0;
     __syncthreads();
     ADA_CLK(7);
     if (!s_last) return;
     ADA_CLK_LAST(8);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");       // see the other workgroups' hit words, not stale lines
+    // see the other workgroups' hit words, not stale lines: one invalidate for the workgroup (the caches it clears
+    // are shared by the CU), then a barrier
+    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();
     ADA_CLK_LAST(9);
     if (p.assign_mode) assign_finish<G::THREADS>(p, r, r_ok, q0, qp0);
     else fused_update<G::THREADS>(p, r, r_ok, q0, qp0, lds + G::META, reinterpret_cast<int*>(lds + G::OFF_SCAN));
     ADA_CLK_LAST(15);
+}
+
+// ------------------------------------------------------------------------------------------------
+// k_cascade_pass: the layer loop of Section 4.1 in ONE launch.  Between two launches of k_cascade_fused the device
+// idles for about 4 us and the new launch starts with a trip to memory for the set size; here the workgroups stay
+// resident and walk through the layers.  A layer's last workgroup (ticket) updates the set as before, then publishes
+// (layers done << 21 | set size) in one word; the others wait for that word before they start the next layer.
+// The grid must be co-resident (one workgroup per CU: the launcher asks for no more workgroups than CUs, and the LDS
+// footprint admits one per CU).  The wait is bounded: a workgroup that does not see the word within spin_limit polls
+// gives up and leaves, the others then run into the same bound, and the layers that were not finished keep the
+// status the launcher wrote into their counts beforehand.  Every wave therefore reaches the end of the kernel.
+constexpr int PASS_MAX_LAYERS = 64;
+
+struct PassParams {
+    FusedParams f;                     // shape, threshold, hit table, ticket; the per-layer pointers are set in the kernel
+    const void* X[PASS_MAX_LAYERS];    // X of the n cascade layers of this launch
+    int n;                             // cascade layers in this launch (1 .. PASS_MAX_LAYERS)
+    int32_t* idx_row0;                 // row of the set inherited by the first layer; layer i writes row i + 1
+    int32_t* counts_row0;              // likewise ([4] per row); counts_row0[0] is the first inherited size
+    unsigned long long* gram_ops_row0; // likewise
+    int32_t* adds_row0;                // row i + 1 for layer i, or NULL
+    int32_t* removes_row0;             // likewise
+    int32_t* epoch;                    // zero on entry and on exit
+    int spin_limit;
+};
+
+#ifdef ADA_PHASE_CLOCKS
+__device__ unsigned long long g_pass_clk[512 * 8];
+#define PASS_CLK(k) do { if (threadIdx.x == 0 && i == 5) g_pass_clk[blockIdx.x * 8 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define PASS_CLK(k) do { } while (0)
+#endif
+
+template <typename In, bool ALIGNED, int KG, bool DMA>
+__global__ __launch_bounds__(256 * KG) void k_cascade_pass(PassParams pp) {
+    extern __shared__ __align__(16) char lds[];
+    using G = FusedGeom<KG, DMA>;
+    __shared__ int s_last, s_word;
+    FusedParams p = pp.f;
+    const int T = p.T;
+    // No cache is invalidated between layers.  X is read-only.  A row of the set is written (and written back) before
+    // anybody reads it and is never read before that, so plain loads are safe when rows do not share cache lines;
+    // otherwise (coherent_list, set by the launcher) the list is read past the caches.
+    for (int i = 0; i < pp.n; ++i) {
+        PASS_CLK(0);
+        // ---- the inherited set: from the previous launch for the first layer, from this launch's previous layer after
+        if (threadIdx.x == 0) {
+            int word;
+            if (i == 0) {
+                word = pp.counts_row0[0] & 0x1FFFFF;
+            } else {
+                word = -1;
+                for (int n = 0; n < pp.spin_limit; ++n) {
+                    const int v = __hip_atomic_load(pp.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((v >> 21) == i) { word = v & 0x1FFFFF; break; }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            }
+            s_word = word;
+        }
+        __syncthreads();
+        const int r = s_word;
+        if (r < 0) break;                                    // uniform: gave up waiting
+        PASS_CLK(1);
+        const size_t row = (size_t)(i + 1) * (size_t)T;
+        p.X = pp.X[i];
+        p.prev_idx = pp.idx_row0 + row - T;
+        p.idx = pp.idx_row0 + row;
+        p.adds = pp.adds_row0 ? pp.adds_row0 + row : nullptr;
+        p.removes = pp.removes_row0 ? pp.removes_row0 + row : nullptr;
+        p.counts = pp.counts_row0 + (size_t)(i + 1) * 4;
+        p.gram_ops = pp.gram_ops_row0 + (i + 1);
+        const bool r_ok = r >= 1 && r <= T;
+        if (r_ok) {
+            const long long nbS = (r + 63) / 64, nbT = (T + 63) / 64;
+            const long long ntiles = nbS * nbT;
+            const long long per = (ntiles + 7) / 8;
+            const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
+            for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
+                const long long tile = xcd * per + slot;
+                if (tile >= ntiles) break;
+                const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
+                fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
+                __syncthreads();
+            }
+        }
+        PASS_CLK(2);
+        const int jq = min((int)threadIdx.x, T - 1);         // the row has T entries whatever r is
+        const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this thread's stores have left the CU
+        __syncthreads();
+        if (threadIdx.x == 0) s_last = take_ticket(p.ticket) ? 1 : 0;
+        __syncthreads();
+        PASS_CLK(3);
+        if (s_last) {                                        // uniform
+            if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            __syncthreads();
+            const int r_new = fused_update<G::THREADS>(p, r, r_ok, q0, qp0, lds + G::META,
+                                                       reinterpret_cast<int*>(lds + G::OFF_SCAN));
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                // the ticket is back at zero and the set is written: hand both over with one release
+                const int word = i + 1 < pp.n ? (((i + 1) << 21) | (r_new & 0x1FFFFF)) : 0;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                __hip_atomic_store(pp.epoch, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            PASS_CLK(4);
+        }
+        __syncthreads();
+    }
 }

@@ -37,7 +37,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 enum { MODE_FULL = 0, MODE_REP = 1, MODE_CROSS = 2 };
-enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_TICKET = 4, META_QUEUE = 5 /* and 6 */, META_WORDS = 8 };
+// meta: 8 words of scalars, then (from word META_TICKET + 64 on, one per 128-byte line) the per-XCD ticket counters
+constexpr size_t META_BYTES = 2048;
+enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_TICKET = 4, META_QUEUE = 5 /* and 6 */, META_EPOCH = 7, META_WORDS = 8 };
 
 // The one-launch cascade step keeps one hit word per token and per 32 inherited representatives; beyond this T
 // the table would dominate the workspace and the two-launch path is used instead.
@@ -48,7 +50,7 @@ struct Workspace {
     float* gamma;        // [T]
     int32_t* nonrep_idx; // [T]
     uint8_t* is_rep;     // [T]
-    int32_t* meta;       // [META_WORDS]; meta[META_TICKET] and the META_QUEUE pair are zero between calls
+    int32_t* meta;       // [META_WORDS]; meta[META_TICKET], the META_QUEUE pair and meta[META_EPOCH] are zero between calls
     uint32_t* hits;      // [T][hit_words(T)] (only for T <= FUSED_MAX_T)
     unsigned long long* best;   // [T] arg-max keys of the assignment; zero between calls
 };
@@ -59,7 +61,7 @@ inline int hit_words(int r_cap) { return 2 * ((r_cap + 63) / 64); }
 inline size_t ws_bytes_for(int T) {
     size_t t4 = align_up((size_t)T * 4, 256), t1 = align_up((size_t)T, 256);
     size_t hits = T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0;
-    return t4 * 3 + t1 + 256 + hits + align_up((size_t)T * 8, 256);
+    return t4 * 3 + t1 + META_BYTES + hits + align_up((size_t)T * 8, 256);
 }
 
 inline Workspace carve(void* ws, int T) {
@@ -70,7 +72,7 @@ inline Workspace carve(void* ws, int T) {
     w.gamma = (float*)p; p += t4;
     w.nonrep_idx = (int32_t*)p; p += t4;
     w.is_rep = (uint8_t*)p; p += t1;
-    w.meta = (int32_t*)p; p += 256;
+    w.meta = (int32_t*)p; p += META_BYTES;
     w.hits = (uint32_t*)p; p += T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0;
     w.best = (unsigned long long*)p;
     return w;
@@ -722,6 +724,19 @@ int tile_override() {
     return (v == 64 || v == 128) ? v : 0;
 }
 
+// Compute units of the current device, rounded down to whole XCDs (at least 8).
+int device_cus() {
+    static std::once_flag once;
+    static int cus = 256;
+    std::call_once(once, [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n >= 8)
+            cus = n / 8 * 8;
+    });
+    return cus;
+}
+
 // Makespan of handing the units out big first to G workgroups, in units of one big tile; a small unit was measured at
 // about 0.4 of a big one.
 inline double dma_makespan(int T, int big_mode, int G) {
@@ -742,16 +757,12 @@ inline double dma_makespan(int T, int big_mode, int G) {
 hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
-    static int G = 256;
     std::call_once(once, [] {
         attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gram_dma),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom::LDS);
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 8)
-            G = cus / 8 * 8;                                   // one workgroup per CU (LDS), whole XCDs
     });
     if (attr_err != hipSuccess) return attr_err;
+    const int G = device_cus();                                // one workgroup per CU (LDS), whole XCDs
     if (mode < 0) {
         static std::mutex mu;
         static int last_T = 0, last_mode = 0;
@@ -915,7 +926,7 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
     const FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
                            (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
                            w.meta + META_TICKET, idx, adds, removes, counts,
-                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr};
+                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0};
     return launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
 }
 
@@ -924,8 +935,72 @@ int run_assign(const void* X, int T, int d, long long ld, int dtype, const int32
                int32_t* assign, float* corr, int32_t* info, void* ws, hipStream_t st) {
     const Workspace w = carve(ws, T);
     const FusedParams p = {X, ld, T, d, idx, r_dev, r, 2.0f, 0, nullptr, 0, nullptr, w.meta + META_TICKET,
-                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr};
+                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr, 0};
     return launch_fused_any(p, dtype, ADA_K_ASSIGN, st);
+}
+
+__global__ void k_fill_status(int32_t* counts, int rows, int status) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < rows * 4) counts[i] = (i & 3) == 3 ? status : 0;
+}
+
+template <typename In, bool ALIGNED, int KG, bool DMA>
+hipError_t launch_pass(const PassParams& pp, hipStream_t st) {
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    constexpr int lds = FusedGeom<KG, DMA>::LDS;
+    static_assert(lds > 80 * 1024, "the pass kernel relies on one workgroup per CU");
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cascade_pass<In, ALIGNED, KG, DMA>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    ProfScope ps(ADA_K_CASCADE_FUSED, st);
+    hipLaunchKernelGGL((k_cascade_pass<In, ALIGNED, KG, DMA>), dim3(device_cus()), dim3(256 * KG), lds, st, pp);
+    return hipGetLastError();
+}
+
+// Layers first .. first + n - 1 (all cascade layers, first >= 1) in one resident launch; see k_cascade_pass.
+// Needs whole, aligned 128-byte row chunks in every layer (the direct-to-LDS form, whose LDS footprint keeps the grid
+// to one workgroup per CU); the caller falls back to one launch per layer otherwise.
+bool pass_eligible(const void* const* X_layers, int L, int T, int d, long long ld, int dtype, unsigned flags) {
+    if (!(flags & ADA_FLAG_RESIDENT_PASS) || (flags & ADA_FLAG_TWO_PASS) || T > FUSED_MAX_T || L < 2) return false;
+    if (getenv("ADA_NO_DMA") || kgroups_override() == 1) return false;
+    const int epc = dtype == ADA_BF16 ? 64 : 32;
+    if (d % epc != 0 || ld % (epc / 8) != 0) return false;
+    for (int l = 0; l < L; ++l)
+        if ((uintptr_t)X_layers[l] % 16 != 0) return false;
+    return true;
+}
+
+int run_cascade_pass(const void* const* X_layers, int first, int n, int T, int d, long long ld, int dtype, float tau,
+                     int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all, int32_t* adds_all,
+                     int32_t* removes_all, void* ws, hipStream_t st, unsigned flags) {
+    const Workspace w = carve(ws, T);
+    PassParams pp;
+    pp.f = {nullptr, ld, T, d, nullptr, nullptr, T, threshold_of(tau), (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0,
+            w.hits, hit_words(T), nullptr, w.meta + META_TICKET, nullptr, nullptr, nullptr, nullptr, nullptr,
+            0, nullptr, nullptr, nullptr, 0};
+    // rows of idx_all that share a 128-byte line with their neighbour could be cached half-written
+    pp.f.coherent_list = ((uintptr_t)idx_all % 128 != 0 || T % 32 != 0) ? 1 : 0;
+    for (int i = 0; i < n; ++i) pp.X[i] = X_layers[first + i];
+    for (int i = n; i < PASS_MAX_LAYERS; ++i) pp.X[i] = nullptr;
+    pp.n = n;
+    const size_t row0 = (size_t)(first - 1);
+    pp.idx_row0 = idx_all + row0 * (size_t)T;
+    pp.counts_row0 = counts_all + row0 * 4;
+    pp.gram_ops_row0 = reinterpret_cast<unsigned long long*>(gram_ops_all) + row0;
+    pp.adds_row0 = adds_all ? adds_all + row0 * (size_t)T : nullptr;
+    pp.removes_row0 = removes_all ? removes_all + row0 * (size_t)T : nullptr;
+    pp.epoch = w.meta + META_EPOCH;
+    pp.spin_limit = 1 << 20;                                 // about a second of polling
+    if (const char* e = getenv("ADA_SPIN_LIMIT")) { const int v = atoi(e); if (v >= 1) pp.spin_limit = v; }
+    // a layer that is never finished (a workgroup gave up waiting) keeps this status
+    hipLaunchKernelGGL(k_fill_status, dim3((n * 4 + 255) / 256), dim3(256), 0, st, pp.counts_row0 + 4, n, (int)ADA_ERR_DEVICE);
+    if (hipGetLastError() != hipSuccess) return ADA_ERR_DEVICE;
+    const hipError_t e = dtype == ADA_BF16 ? launch_pass<uint16_t, true, 2, true>(pp, st)
+                                           : launch_pass<float, true, 2, true>(pp, st);
+    return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
 // Algorithm 1 in separate launches (norms + lists, r x r Gram, cross-Gram against the valid representatives, update):
@@ -1032,6 +1107,14 @@ int ada_cascade_layers(const void* const* X_layers, int L, int T, int d, int64_t
     hipStream_t st = (hipStream_t)stream;
     // layer 0: the full T x T selection; layers >= 1 inherit the previous layer's set on the device (Section 4.1)
     int e = run_full(X_layers[0], T, d, ld, dtype, tau, nullptr, idx_all, counts_all, gram_ops_all, nullptr, ws, st);
+    if (e == ADA_OK && pass_eligible(X_layers, L, T, d, ld, dtype, flags)) {
+        for (int first = 1; first < L && e == ADA_OK; first += PASS_MAX_LAYERS) {
+            const int n = L - first < PASS_MAX_LAYERS ? L - first : PASS_MAX_LAYERS;
+            e = run_cascade_pass(X_layers, first, n, T, d, ld, dtype, tau, idx_all, counts_all, gram_ops_all, adds_all,
+                                 removes_all, ws, st, flags);
+        }
+        return e;
+    }
     for (int l = 1; l < L && e == ADA_OK; ++l) {
         const size_t o = (size_t)l * (size_t)T;
         e = run_cascade(X_layers[l], T, d, ld, dtype, tau, idx_all + o - T, T, counts_all + (size_t)(l - 1) * 4,
@@ -1088,6 +1171,9 @@ int ada_profile_collect(double* ms_sum, int* launches) {
 }
 
 #ifdef ADA_PHASE_CLOCKS
+int ada_debug_pass_clocks(unsigned long long* out) {   // development builds only
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_pass_clk), sizeof(unsigned long long) * 512 * 8) == hipSuccess ? 0 : 6;
+}
 int ada_debug_phase_clocks(unsigned long long* out) {   // development builds only
     return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_clk), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : 6;
 }

@@ -303,6 +303,74 @@ def test_layer_driver_matches_step_by_step_and_report():
     assert torch.equal(out2["counts"], out["counts"]) and torch.equal(out2["gram_ops"], out["gram_ops"])
 
 
+def run_driver(xs, tau, **kw):
+    out = pa.ada_cascade_layers(xs, tau, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def assert_same_driver_output(a, b, L):
+    ca, cb = a["counts"].cpu(), b["counts"].cpu()
+    assert torch.equal(ca, cb) and torch.equal(a["gram_ops"], b["gram_ops"])
+    for l in range(L):
+        r, na, nr = (int(v) for v in ca[l, :3])
+        assert torch.equal(a["idx"][l, :r], b["idx"][l, :r])
+        if l > 0:
+            assert torch.equal(a["adds"][l, :na], b["adds"][l, :na])
+            assert torch.equal(a["removes"][l, :nr], b["removes"][l, :nr])
+
+
+@pytest.mark.parametrize("T,d,K,L,dtype", [(600, 192, 70, 6, "bf16"), (333, 96, 40, 5, "f32"), (130, 64, 20, 70, "bf16")])
+def test_resident_pass_matches_one_launch_per_layer_and_the_oracle(T, d, K, L, dtype, monkeypatch):
+    """The layer loop in one resident launch (rows in whole 128-byte chunks) against the same loop as one launch per
+    layer, and layer by layer against the oracle; L = 70 takes two resident launches."""
+    say("resident pass T=%d d=%d L=%d %s" % (T, d, L, dtype))
+    w = wl.small(T=T, d=d, K=K, L=L, dtype=dtype, seed=17 + L, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    ws = pa.workspace(T, DEV)
+    resident = run_driver(xs, w.tau, ws=ws, flags=pa.FLAG_RESIDENT_PASS)
+    again = run_driver(xs, w.tau, ws=ws, flags=pa.FLAG_RESIDENT_PASS)    # the workspace is left ready
+    chained = run_driver(xs, w.tau, ws=ws)
+    assert resident["counts"][:, 3].cpu().tolist() == [0] * L
+    assert_same_driver_output(resident, chained, L)
+    assert_same_driver_output(resident, again, L)
+    counts = resident["counts"].cpu()
+    prev = resident["idx"][0, :int(counts[0, 0])].cpu().numpy()
+    for l in range(1, min(L, 8)):
+        r, na, nr = (int(v) for v in counts[l, :3])
+        got = dict(idx=resident["idx"][l, :r].cpu().numpy(), adds=resident["adds"][l, :na].cpu().numpy(),
+                   removes=resident["removes"][l, :nr].cpu().numpy(), gram_ops=int(resident["gram_ops"][l]),
+                   r=r, n_adds=na, n_removes=nr,
+                   gamma=pa.fetch(pa.ada_cascade_step(xs[l], w.tau, dev_idx(prev)))["gamma"])
+        parity.check_cascade(xs_cpu[l], w.tau, prev, got, what="resident layer %d" % l)
+        prev = got["idx"]
+
+
+def test_resident_pass_gives_up_cleanly_when_its_wait_is_cut_short(monkeypatch):
+    """The wait between layers is bounded.  With the bound forced to a single poll most workgroups give up at the
+    second layer: every kernel still ends, unfinished layers report ADA_ERR_DEVICE, finished ones are correct, and a
+    re-initialised workspace serves the next call."""
+    say("resident pass, spin limit 1")
+    w = wl.small(T=700, d=128, K=60, L=5, dtype="bf16", seed=19, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    ws = pa.workspace(w.T, DEV)
+    good = run_driver(xs, w.tau, ws=ws)
+    monkeypatch.setenv("ADA_SPIN_LIMIT", "1")
+    cut = run_driver(xs, w.tau, ws=ws, flags=pa.FLAG_RESIDENT_PASS)
+    status = cut["counts"][:, 3].cpu().tolist()
+    assert status[0] == 0 and status[1] == 0 and set(status) <= {0, 6}
+    done = [l for l in range(w.L) if status[l] == 0]
+    assert done == list(range(len(done)))                         # a layer cannot finish after one that did not
+    for l in done:
+        r = int(cut["counts"][l, 0])
+        assert torch.equal(cut["counts"][l], good["counts"][l]) and torch.equal(cut["idx"][l, :r], good["idx"][l, :r])
+    monkeypatch.delenv("ADA_SPIN_LIMIT")
+    pa.ada_workspace_init(ws)
+    assert_same_driver_output(run_driver(xs, w.tau, ws=ws, flags=pa.FLAG_RESIDENT_PASS), good, w.L)
+
+
 def test_set_overlap():
     say("ada_set_overlap")
     rng = np.random.default_rng(5)
