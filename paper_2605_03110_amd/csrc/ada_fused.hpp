@@ -462,12 +462,109 @@ __device__ inline unsigned long long block_exclusive_scan64(unsigned long long v
 // in flight before the first use.  One CU's load path is what this phase costs, so nothing is fetched twice:
 // the first THREADS list entries arrive in registers (q0 / qp0, loaded before the ticket), representatives take one
 // batch each, and the token pass reads four tokens per 16-byte load when T allows.
+// The same steps when one thread can own four consecutive tokens with all their hit words in registers
+// (T % 4 == 0, T <= 4 THREADS, at most WMAX words per token).  The hit words of an inherited token are among the
+// words its owner holds, so validity (step 5) needs no second trip to memory: one batch of 16-byte loads, the list
+// (to learn which tokens are inherited and at which position), then bit operations and one scan.
+template <int THREADS, int WMAX>
+__device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int qp0, char* lds, int* scan_scratch) {
+    const int tid = threadIdx.x;
+    const int T = p.T, T4 = T >> 2;
+    const int Wa = (r + 31) >> 5;
+    uint16_t* pos = reinterpret_cast<uint16_t*>(lds);                        // [T] list position of an inherited token
+    uint32_t* vmask = reinterpret_cast<uint32_t*>(lds + FUSED_MAX_T * 2);    // [Wa] valid bits by list position
+    const bool own = tid < T4;
+    u32x4 x[WMAX];
+#pragma unroll
+    for (int w = 0; w < WMAX; ++w)
+        x[w] = own ? *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(w, Wa - 1) * T + 4 * tid) : u32x4{0u, 0u, 0u, 0u};
+    if (own) *reinterpret_cast<unsigned long long*>(pos + 4 * tid) = ~0ull;  // 0xFFFF: not inherited
+    for (int w = tid; w < Wa; w += THREADS) vmask[w] = 0u;
+    __syncthreads();
+    int ok = 1;
+    for (int j = tid; j < r; j += THREADS) {            // the list: strictly ascending token ids in range
+        const int q = j < THREADS ? q0 : list_at(p, j);
+        const int qp = j < THREADS ? qp0 : list_at(p, j - 1);
+        if (q < 0 || q >= T || (j > 0 && !(qp < q))) ok = 0;
+        else pos[q] = (uint16_t)j;
+    }
+    ok = __syncthreads_and(ok);
+    if (!ok) {
+        if (tid == 0) {
+            p.counts[0] = 0; p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = ADA_ERR_INDEX;
+            if (p.gram_ops) *p.gram_ops = 0ull;
+            reset_tickets(p.ticket);
+        }
+        return 0;
+    }
+    // step 5: an inherited representative with a hit from an earlier inherited one is removed (the tile epilogue
+    // already kept only earlier representatives in an inherited token's words)
+    uint32_t any_all[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int w = 0; w < WMAX; ++w) {
+        const bool in = w < Wa;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) any_all[u] |= in ? x[w][u] : 0u;
+    }
+    int jpos[4];
+    {
+        const unsigned long long pk = own ? *reinterpret_cast<const unsigned long long*>(pos + 4 * tid) : ~0ull;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            jpos[u] = (int)((pk >> (16 * u)) & 0xFFFFu);
+            if (jpos[u] != 0xFFFF && any_all[u] == 0u) atomicOr(&vmask[jpos[u] >> 5], 1u << (jpos[u] & 31));
+        }
+    }
+    __syncthreads();
+    // step 9: any other token with a hit on a VALID representative is covered
+    uint32_t cov[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int w = 0; w < WMAX; ++w) {
+        const uint32_t vm = w < Wa ? vmask[w] : 0u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cov[u] |= x[w][u] & vm;
+    }
+    int st[4];                                           // 3 kept inherited, 1 removed, 2 added, 0 covered
+    unsigned long long c = 0;                            // kept | added << 21 | removed << 42
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const bool inh = jpos[u] != 0xFFFF;
+        st[u] = !own ? 0 : inh ? (any_all[u] == 0u ? 3 : 1) : (cov[u] == 0u ? 2 : 0);
+        c += (unsigned long long)((st[u] >> 1) & 1) | ((unsigned long long)(st[u] == 2) << 21) |
+             ((unsigned long long)(st[u] == 1) << 42);
+    }
+    unsigned long long tot;
+    const unsigned long long o = block_exclusive_scan64(c, &tot, reinterpret_cast<unsigned long long*>(scan_scratch));
+    int o_idx = (int)(o & 0x1FFFFF), o_add = (int)((o >> 21) & 0x1FFFFF), o_rem = (int)((o >> 42) & 0x1FFFFF);
+    const int n_idx = (int)(tot & 0x1FFFFF), n_add = (int)((tot >> 21) & 0x1FFFFF), n_rem = (int)((tot >> 42) & 0x1FFFFF);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {                        // step 10
+        const int t = 4 * tid + u;
+        if (st[u] & 2) p.idx[o_idx++] = t;
+        if (st[u] == 2) { if (p.adds) p.adds[o_add] = t; ++o_add; }
+        if (st[u] == 1) { if (p.removes) p.removes[o_rem] = t; ++o_rem; }
+    }
+    if (tid == 0) {
+        p.counts[0] = n_idx; p.counts[1] = n_add; p.counts[2] = n_rem; p.counts[3] = ADA_OK;
+        if (p.gram_ops) {
+            const unsigned long long TT = (unsigned long long)T, rr = (unsigned long long)r;
+            *p.gram_ops = rr * rr + (TT - rr) * (unsigned long long)(r - n_rem);   // entries Algorithm 1 needs
+        }
+        reset_tickets(p.ticket);
+    }
+    return n_idx;
+}
+
 // Returns |R^(l+1)| to every thread (0 if the step is rejected).
 template <int THREADS>
 __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q0, int qp0, char* lds, int* scan_scratch) {
     constexpr int WU = 15;                              // hit words fetched per batch by one thread
     const int tid = threadIdx.x, lane = tid & 63;
     const int T = p.T;
+    if (r_ok && (T & 3) == 0 && (T >> 2) <= THREADS) {  // uniform
+        if (r <= 16 * 32) return fused_update_fast<THREADS, 16>(p, r, q0, qp0, lds, scan_scratch);
+        if (r <= 32 * 32) return fused_update_fast<THREADS, 32>(p, r, q0, qp0, lds, scan_scratch);
+    }
     uint8_t* flag = reinterpret_cast<uint8_t*>(lds);                         // [T]
     uint32_t* vmask = reinterpret_cast<uint32_t*>(lds + FUSED_MAX_T);        // one bit per inherited representative: valid
     const int Wa = r_ok ? (r + 31) >> 5 : 0;            // hit words in use per token
