@@ -81,7 +81,7 @@ template <int KG, bool DMA> struct FusedGeom {
     static constexpr int NS = 4;                          // DMA path: LDS stages per K-group
     static constexpr int LPT = 4;                         // 16-byte pieces per thread per chunk
     static constexpr int STAGE = 128 * 128;               // one chunk of 128 rows
-    static constexpr int NPART = DMA ? 4 * KG : KG;       // partial sums of squares per row
+    static constexpr int NPART = DMA ? 2 * KG : KG;       // partial sums of squares per row
     static constexpr int OFF_STOK = 0;                    // int[64]   token id of each "against" row (INT_MAX: none)
     static constexpr int OFF_REPF = 256;                  // int[64]   tested token is inherited
     static constexpr int OFF_SS = 512;                    // float[NPART][128] partial sums of squares
@@ -121,7 +121,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
     constexpr int B = 64;
     constexpr int EPP = 16 / (int)sizeof(In);
     constexpr int EPC = 8 * EPP;
-    constexpr int LPT = G::LPT, D = G::D, NB = 2;
+    constexpr int LPT = G::LPT, D = G::D;
 
     int* s_tok = reinterpret_cast<int*>(lds + G::OFF_STOK);
     int* repf = reinterpret_cast<int*>(lds + G::OFF_REPF);
@@ -176,26 +176,27 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
     }
     const int nk = (p.d + EPC - 1) / EPC;
     const int nsteps = (nk + KG - 1) / KG;               // steps of this group; step k handles chunk k * KG + g
-    u32x4 fa[2][NB], fb[2][NB];
-    f32x16 acc[NB][NB];
+    // Wave w of a K-group owns the 32 x 32 block (wa, wb) = (w >> 1, w & 1) of the tile over all four k-steps of each of
+    // the group's chunks, so a block has only one partial sum per K-group and the epilogue needs one small exchange.
+    // Two accumulators (even / odd k-steps) keep two independent MFMA chains in flight.
+    const int wa = wave >> 1, wb = wave & 1;
+    u32x4 fa[2][4], fb[2][4];
+    f32x16 acc[2];
 #pragma unroll
-    for (int a = 0; a < NB; ++a)
+    for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
     auto read_frags = [&](const char* stage, int f) {
-        const int piece = 2 * wave + half;               // this wave's k-step of the chunk
 #pragma unroll
-        for (int a = 0; a < NB; ++a) fa[f][a] = *reinterpret_cast<const u32x4*>(stage + lds_off(a * 32 + l32, piece));
-#pragma unroll
-        for (int b = 0; b < NB; ++b) fb[f][b] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + b * 32 + l32, piece));
+        for (int ks = 0; ks < 4; ++ks) {
+            const int piece = 2 * ks + half;
+            fa[f][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(wa * 32 + l32, piece));
+            fb[f][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + wb * 32 + l32, piece));
+        }
     };
     auto mma = [&](int f) {
 #pragma unroll
-        for (int a = 0; a < NB; ++a)
-#pragma unroll
-            for (int b = 0; b < NB; ++b) Mfma<In>::run(acc[a][b], fa[f][a], fb[f][b]);
+        for (int ks = 0; ks < 4; ++ks) Mfma<In>::run(acc[ks & 1], fa[f][ks], fb[f][ks]);
     };
 
     if constexpr (DMA) {
@@ -208,7 +209,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         constexpr int NS = G::NS;
         char* ring = body + g * NS * G::STAGE;
         const int pcd = pc ^ lds_swz(rb);                 // 32 j leaves bits 0..3 of the row alone
-        float ssa[NB] = {0.f, 0.f}, ssb[NB] = {0.f, 0.f};
+        float ssa = 0.f, ssb = 0.f;
         auto issue = [&](int stage, int k) {
             const int chunk = min(k * KG + g, nk - 1);
 #pragma unroll
@@ -223,9 +224,12 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
             if (k * KG + g < nk) {                       // scalar: a clamped (repeated) chunk is skipped
                 mma(f);
 #pragma unroll
-                for (int a = 0; a < NB; ++a) ssa[a] += piece_sumsq_fast<In>(fa[f][a]);   // Section 2.1: ||x||^2 from the
-#pragma unroll
-                for (int b = 0; b < NB; ++b) ssb[b] += piece_sumsq_fast<In>(fb[f][b]);   // fragments already in hand
+                for (int ks = 0; ks < 2; ++ks) {
+                    // Section 2.1: ||x||^2 from the fragments already in hand.  The two waves that share a block of rows
+                    // split its four k-steps, so every wave sums four fragments per chunk (scalar selects).
+                    ssa += piece_sumsq_fast<In>(wb == 0 ? fa[f][ks] : fa[f][ks + 2]);
+                    ssb += piece_sumsq_fast<In>(wa == 0 ? fb[f][ks] : fb[f][ks + 2]);
+                }
             }
         };
 #pragma unroll
@@ -243,24 +247,20 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
                 __builtin_amdgcn_sched_barrier(0);
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 3) * LPT));      // chunk k+1 has landed (this wave's part)
                 __builtin_amdgcn_s_barrier();                               // ... and everybody's; stage (k-1) % NS is free
+                issue((s + NS - 1) % NS, k + NS - 1);                       // first: the loads are what the loop waits for
                 read_frags(ring + ((s + 1) % NS) * G::STAGE, (s + 1) & 1);
-                issue((s + NS - 1) % NS, k + NS - 1);
                 mma_and_norms(s & 1, k);
             }
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));        // the surplus loads must land before the ring is reused
         ADA_CLK(4);
-#pragma unroll
-        for (int a = 0; a < NB; ++a) ssa[a] += __shfl_xor(ssa[a], 32, 64);
-#pragma unroll
-        for (int b = 0; b < NB; ++b) ssb[b] += __shfl_xor(ssb[b], 32, 64);
+        ssa += __shfl_xor(ssa, 32, 64);                    // the two lane halves hold different k pieces
+        ssb += __shfl_xor(ssb, 32, 64);
         __syncthreads();                                  // every wave is done with the ring
         ADA_CLK(16);
-        if (half == 0) {
-#pragma unroll
-            for (int a = 0; a < NB; ++a) ssq[(g * 4 + wave) * 128 + a * 32 + l32] = ssa[a];
-#pragma unroll
-            for (int b = 0; b < NB; ++b) ssq[(g * 4 + wave) * 128 + B + b * 32 + l32] = ssb[b];
+        if (half == 0) {                                  // two partial sums per row and K-group
+            ssq[(g * 2 + wb) * 128 + wa * 32 + l32] = ssa;
+            ssq[(g * 2 + wa) * 128 + B + wb * 32 + l32] = ssb;
         }
     } else {
     u32x4 pre[D][LPT];
@@ -328,54 +328,41 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         for (int j = 0; j < LPT; ++j) ssq[g * 128 + rb + 32 * j] = ss[j];
     }
     }
-    // partial tiles travel through LDS as 16-byte vectors: slot ((wave * 4 + block) * 4 + q) * 64 + lane holds
-    // accumulator registers 4q .. 4q+3 of that block (consecutive lanes, consecutive 16 bytes: conflict-free)
+    // the second K-group hands its partial blocks over through LDS as 16-byte vectors: slot (wave * 4 + q) * 64 + lane
+    // holds accumulator registers 4q .. 4q+3 (consecutive lanes, consecutive 16 bytes: conflict-free)
+    f32x16 tot;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot[i] = acc[0][i] + acc[1][i];
     f32x4* red = reinterpret_cast<f32x4*>(body);
-    auto put = [&](int slot_wave) {
+    if (KG == 2 && g == 1) {
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x16& v = acc[blk >> 1][blk & 1];
-                red[((slot_wave * 4 + blk) * 4 + q) * 64 + lane] = f32x4{v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]};
-            }
-    };
-    if (KG == 2 && g == 1) put(wave);
+        for (int q = 0; q < 4; ++q) red[(wave * 4 + q) * 64 + lane] = f32x4{tot[4 * q], tot[4 * q + 1], tot[4 * q + 2], tot[4 * q + 3]};
+    }
     __syncthreads();
     ADA_CLK(17);
     if (tid < 2 * B) {
-        float tot = 0.f;
+        float sum = 0.f;
 #pragma unroll
-        for (int part = 0; part < G::NPART; ++part) tot += ssq[part * 128 + tid];
-        float sc = tot > 0.f ? 1.0f / sqrtf(tot) : 0.f;   // a zero row normalises to zero: all its cosines are 0
+        for (int part = 0; part < G::NPART; ++part) sum += ssq[part * 128 + tid];
+        float sc = sum > 0.f ? 1.0f / sqrtf(sum) : 0.f;   // a zero row normalises to zero: all its cosines are 0
         if (tid < B ? (s_tok[tid] == INT_MAX) : (t0 + tid - B >= p.T)) sc = 0.f;
         scale[tid] = sc;
     }
     if (KG == 2 && g == 0) {
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk)
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 o = red[(wave * 4 + q) * 64 + lane];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 o = red[((wave * 4 + blk) * 4 + q) * 64 + lane];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) acc[blk >> 1][blk & 1][4 * q + e] += o[e];
-            }
+            for (int e = 0; e < 4; ++e) tot[4 * q + e] += o[e];
+        }
     }
     __syncthreads();
     ADA_CLK(18);
-    if (g == 0) put(wave);                                // every wave publishes all four blocks, its own included
-    __syncthreads();
     ADA_CLK(19);
     if (g == 0) {
-        // wave w finishes block (a, b) = (w >> 1, w & 1): sum the four k-step partials in wave order
-        const int a = wave >> 1, b = wave & 1;
+        const int a = wa, b = wb;
         const int nl = b * 32 + l32;
         const int t = t0 + nl;
-        f32x4 part[4][4];
-#pragma unroll
-        for (int src = 0; src < 4; ++src)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) part[src][q] = red[((src * 4 + wave) * 4 + q) * 64 + lane];
         // accumulator register 4q+e of a 32x32 MFMA block is row 8q + 4*half + e: four consecutive rows per q
         f32x4 sc4[4];
         i32x4 tk4[4];
@@ -395,7 +382,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float v = ((part[0][q][e] + part[1][q][e]) + part[2][q][e]) + part[3][q][e];
+                    const float v = tot[4 * q + e];
                     const float c = (fabsf(v) * sc4[q][e]) * tsc;
                     const unsigned long long k = ((unsigned long long)__float_as_uint(c) << 32) |
                                                  (unsigned long long)(uint32_t)(INT_MAX - tk4[q][e]);
@@ -413,7 +400,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float v = ((part[0][q][e] + part[1][q][e]) + part[2][q][e]) + part[3][q][e];
+                const float v = tot[4 * q + e];
                 float c = (fabsf(v) * sc4[q][e]) * tsc;
                 if (ordered && !(tk4[q][e] < t)) c = 0.f;
                 if (c >= p.thr) bits |= 1u << (8 * q + 4 * half + e);
