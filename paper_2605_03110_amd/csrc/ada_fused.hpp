@@ -50,6 +50,9 @@ struct FusedParams {
     // the list was written earlier in this same launch by another workgroup (k_cascade_pass): read it past the
     // caches instead of invalidating them
     int coherent_list;
+    // 0: 64 x 64 tiles always; n > 0: 128 x 128 tiles when the step has more than n 64 x 64 tiles (the launcher passes the
+    // CU count: below that the smaller tiles keep more CUs busy, above it the larger ones halve the L2 -> CU traffic)
+    int tile128;
 };
 
 // Last-arriver detection in two levels.  Atomics on one address are served one after the other at the memory side
@@ -90,7 +93,8 @@ template <int KG, bool DMA> struct FusedGeom {
     static constexpr int META = OFF_SCAN + 512;
     static constexpr int RING = DMA ? KG * NS * STAGE : KG * 2 * STAGE;
     static constexpr int BODY = RING > 65536 ? RING : 65536;   // stages / reduction scratch (64 KB) / update state
-    static constexpr int LDS = META + BODY;
+    static constexpr int OFF_BIG = META + BODY;           // metadata of the 128 x 128 tile (two-group direct-to-LDS form)
+    static constexpr int LDS = META + BODY + ((KG == 2 && DMA) ? 8192 : 0);
 };
 
 constexpr int waitcnt_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only (gfx9 encoding)
@@ -113,6 +117,63 @@ template <> __device__ inline float piece_sumsq_fast<uint16_t>(u32x4 v) {
     s = __builtin_amdgcn_fdot2_f32_bf16(x2, x2, s, false);
     s = __builtin_amdgcn_fdot2_f32_bf16(x3, x3, s, false);
     return s;
+}
+
+// Epilogue of one 32 x 32 block (rows: 32 representatives, columns: 32 tested tokens, one token per lane pair):
+// scale the raw dot products to cosines, then either the hit word of Algorithm 1 or the arg-max key of Section 2.3.
+// s_tok32 / scale32: token ids and 1/norm of the block's 32 representative rows; tsc: 1/norm of this lane's token t;
+// word: index of the hit word these 32 representatives fill.
+__device__ inline void finish_block(const FusedParams& p, const f32x16& tot, const int* s_tok32, const float* scale32,
+                                    float tsc, bool ordered, int t, int word, int half) {
+    // accumulator register 4q+e of a 32x32 MFMA block is row 8q + 4*half + e: four consecutive rows per q
+    f32x4 sc4[4];
+    i32x4 tk4[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        sc4[q] = *reinterpret_cast<const f32x4*>(scale32 + 8 * q + 4 * half);
+        tk4[q] = *reinterpret_cast<const i32x4*>(s_tok32 + 8 * q + 4 * half);
+    }
+    if (p.assign_mode) {                              // uniform
+        // Section 2.3: the largest |cos| over this tile's representatives and who holds it.  A non-negative float
+        // orders like its bit pattern, so (bits << 32 | INT_MAX - token id) under an integer max is an exact,
+        // order-independent arg max that prefers the smaller token id among equals; padding rows (token id
+        // INT_MAX, scale 0) give key 0 and never win.
+        unsigned long long key = 0ull;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float c = (fabsf(tot[4 * q + e]) * sc4[q][e]) * tsc;
+                const unsigned long long k = ((unsigned long long)__float_as_uint(c) << 32) |
+                                             (unsigned long long)(uint32_t)(INT_MAX - tk4[q][e]);
+                key = k > key ? k : key;
+            }
+        const unsigned long long other = ((unsigned long long)(uint32_t)__shfl_xor((int)(key >> 32), 32, 64) << 32) |
+                                         (unsigned long long)(uint32_t)__shfl_xor((int)(uint32_t)key, 32, 64);
+        key = other > key ? other : key;
+        if (half == 0 && t < p.T) atomicMax(p.best + t, key);
+        return;
+    }
+    uint32_t bits = 0u;
+    float m = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float c = (fabsf(tot[4 * q + e]) * sc4[q][e]) * tsc;
+            if (ordered && !(tk4[q][e] < t)) c = 0.f;     // only earlier representatives count
+            if (c >= p.thr) bits |= 1u << (8 * q + 4 * half + e);
+            m = fmaxf(m, c);
+        }
+    bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
+    m = fmaxf(m, __shfl_xor(m, 32, 64));
+    if (half == 0 && t < p.T) {
+        // word-major: 32 lanes store 32 consecutive words.  The store is a device-scope atomic (written through
+        // the L2 to where every XCD sees it), so that handing the words over needs no L2 write-back: a write-back
+        // per workgroup serialises on the L2 and was the longest single wait of the step.
+        __hip_atomic_store(p.hits + (size_t)word * p.T + t, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (p.gamma && m > 0.f) atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
+    }
 }
 
 template <typename In, bool ALIGNED, int KG, bool DMA>
@@ -363,61 +424,154 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         const int a = wa, b = wb;
         const int nl = b * 32 + l32;
         const int t = t0 + nl;
-        // accumulator register 4q+e of a 32x32 MFMA block is row 8q + 4*half + e: four consecutive rows per q
-        f32x4 sc4[4];
-        i32x4 tk4[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            sc4[q] = *reinterpret_cast<const f32x4*>(scale + a * 32 + 8 * q + 4 * half);
-            tk4[q] = *reinterpret_cast<const i32x4*>(s_tok + a * 32 + 8 * q + 4 * half);
-        }
-        const float tsc = scale[B + nl];
-        if (p.assign_mode) {                              // uniform
-            // Section 2.3: the largest |cos| over this tile's representatives and who holds it.  A non-negative float
-            // orders like its bit pattern, so (bits << 32 | INT_MAX - token id) under an integer max is an exact,
-            // order-independent arg max that prefers the smaller token id among equals; padding rows (token id
-            // INT_MAX, scale 0) give key 0 and never win.
-            unsigned long long key = 0ull;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float v = tot[4 * q + e];
-                    const float c = (fabsf(v) * sc4[q][e]) * tsc;
-                    const unsigned long long k = ((unsigned long long)__float_as_uint(c) << 32) |
-                                                 (unsigned long long)(uint32_t)(INT_MAX - tk4[q][e]);
-                    key = k > key ? k : key;
-                }
-            const unsigned long long other = ((unsigned long long)(uint32_t)__shfl_xor((int)(key >> 32), 32, 64) << 32) |
-                                             (unsigned long long)(uint32_t)__shfl_xor((int)(uint32_t)key, 32, 64);
-            key = other > key ? other : key;
-            if (half == 0 && t < p.T) atomicMax(p.best + t, key);
-        } else {
-        const bool ordered = repf[nl] != 0 || p.earlier_only;   // only earlier representatives count
-        uint32_t bits = 0u;
-        float m = 0.f;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float v = tot[4 * q + e];
-                float c = (fabsf(v) * sc4[q][e]) * tsc;
-                if (ordered && !(tk4[q][e] < t)) c = 0.f;
-                if (c >= p.thr) bits |= 1u << (8 * q + 4 * half + e);
-                m = fmaxf(m, c);
-            }
-        bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
-        m = fmaxf(m, __shfl_xor(m, 32, 64));
-        if (half == 0 && t < p.T) {
-            // word-major: 32 lanes store 32 consecutive words.  The store is a device-scope atomic (written through
-            // the L2 to where every XCD sees it), so that handing the words over needs no L2 write-back: a write-back
-            // per workgroup serialises on the L2 and was the longest single wait of the step.
-            __hip_atomic_store(p.hits + (size_t)(sb * 2 + a) * p.T + t, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (p.gamma && m > 0.f) atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
-        }
-        }
+        finish_block(p, tot, s_tok + a * 32, scale + a * 32, scale[B + nl], repf[nl] != 0 || p.earlier_only, t,
+                     sb * 2 + a, half);
     }
     ADA_CLK(5);
+}
+
+// The same step on a 128 x 128 tile (8 waves on one chunk at a time, rows in whole aligned 128-byte chunks): half
+// the L2 -> CU bytes per Gram entry of the 64 x 64 tile, for steps with enough tiles to keep every CU busy anyway.
+// Wave w owns the 32-row block wa = w / 2 of the representatives and the two 32-token blocks 2 (w % 2), 2 (w % 2) + 1.
+template <typename In>
+__device__ inline void fused_tile128(const FusedParams& p, int r, int s0, int t0, char* lds) {
+    using G = FusedGeom<2, true>;
+    constexpr int B = 128, EPP = 16 / (int)sizeof(In), EPC = 8 * EPP, LPT = 4, NS = 4, STAGE = 2 * B * 128;
+    static_assert(NS * STAGE <= G::BODY, "ring does not fit");
+    int* s_tok = reinterpret_cast<int*>(lds + G::OFF_BIG);       // [128]
+    int* repf = s_tok + B;                                       // [128]
+    float* ssq = reinterpret_cast<float*>(repf + B);             // [256] sums of squares
+    float* scale = ssq + 2 * B;                                  // [256]
+    char* ring = lds + G::META;
+
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wa = wave >> 1, wp = wave & 1, b0 = 2 * wp;
+    const In* X = reinterpret_cast<const In*>(p.X);
+
+    // lane l of wave w serves stage rows 8 w + l / 8 + 64 j (slot l % 8): j = 0, 1 are representatives, 2, 3 tokens
+    const int r8 = lane >> 3;
+    int ptok[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int li = s0 + wave * 8 + r8 + 64 * j;
+        ptok[j] = list_at(p, li < r ? li : r - 1);
+    }
+    if (tid < B) {
+        const int li = s0 + tid;
+        const bool ok = li < r;
+        int tok = list_at(p, ok ? li : r - 1);
+        tok = min(max(tok, 0), p.T - 1);
+        s_tok[tid] = ok ? tok : INT_MAX;
+        repf[tid] = 0;
+    }
+    __syncthreads();
+    const int pcd = (lane & 7) ^ lds_swz(wave * 8 + r8);          // 64 j leaves bits 0..3 of the row alone
+    const In* rowp[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int row = wave * 8 + r8 + 64 * j;
+        const int tok = j < 2 ? min(max(ptok[j], 0), p.T - 1) : min(t0 + row - B, p.T - 1);
+        rowp[j] = X + (size_t)tok * (size_t)p.ld + pcd * EPP;
+    }
+    const int nk = p.d / EPC;
+    auto issue = [&](int stage, int k) {
+        const int chunk = min(k, nk - 1);                        // surplus issues repeat the last chunk into a dead stage
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            char* dst = ring + stage * STAGE + (wave * 8 + 64 * j) * 128;      // wave-uniform
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + chunk * EPC),
+                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+        }
+    };
+    u32x4 fa[2][4], fb[2][2][4];
+    f32x16 acc[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+    auto read_frags = [&](const char* stage, int f) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int piece = 2 * ks + half;
+            fa[f][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(wa * 32 + l32, piece));
+            fb[f][0][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + b0 * 32 + l32, piece));
+            fb[f][1][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + b0 * 32 + 32 + l32, piece));
+        }
+    };
+    float ssa = 0.f, ssb[2] = {0.f, 0.f};
+    const bool do_a = wa < 2 ? wp == 1 : wp == 0;                // representative block wa: waves (0,1) (1,1) (2,0) (3,0)
+    const bool do_b = wp == 0 ? wa == 0 : wa == 3;               // token blocks 2 wp, 2 wp + 1: waves (0,0) and (3,1)
+    auto mma_and_norms = [&](int f, int k) {
+        if (k < nk) {                                            // scalar: a clamped (repeated) chunk is skipped
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                Mfma<In>::run(acc[0], fa[f][ks], fb[f][0][ks]);
+                Mfma<In>::run(acc[1], fa[f][ks], fb[f][1][ks]);
+            }
+            // Section 2.1: ||x||^2 from the fragments already in hand.  Every block of rows is summed by ONE of the waves
+            // that hold it, chosen so that no wave sums more than eight fragments per chunk.  The choice is a plain
+            // scalar branch around code with fixed registers: selecting fragments by a computed index sends them
+            // through scratch memory, whose loads count in vmcnt and drain the ring.
+            if (do_a) {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) ssa += piece_sumsq_fast<In>(fa[f][ks]);
+            }
+            if (do_b) {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    ssb[0] += piece_sumsq_fast<In>(fb[f][0][ks]);
+                    ssb[1] += piece_sumsq_fast<In>(fb[f][1][ks]);
+                }
+            }
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(s, s);
+    if (!p.assign_mode) {                                        // which tested tokens are inherited (read in the epilogue)
+        for (int j = tid; j < r; j += G::THREADS) {
+            const unsigned q = (unsigned)(list_at(p, j) - t0);
+            if (q < (unsigned)B) repf[q] = 1;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    read_frags(ring, 0);
+    for (int k0 = 0; k0 < nk; k0 += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int k = k0 + s;
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm((NS - 3) * LPT));   // chunk k+1 has landed (this wave's part)
+            __builtin_amdgcn_s_barrier();                            // ... and everybody's; stage (k-1) % NS is free
+            issue((s + NS - 1) % NS, k + NS - 1);
+            read_frags(ring + ((s + 1) % NS) * STAGE, (s + 1) & 1);
+            mma_and_norms(s & 1, k);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));                    // the surplus loads must land before the ring is reused
+    ssa += __shfl_xor(ssa, 32, 64);                               // the two lane halves hold different k pieces
+    ssb[0] += __shfl_xor(ssb[0], 32, 64);
+    ssb[1] += __shfl_xor(ssb[1], 32, 64);
+    __syncthreads();
+    if (half == 0) {
+        if (do_a) ssq[wa * 32 + l32] = ssa;
+        if (do_b) { ssq[B + b0 * 32 + l32] = ssb[0]; ssq[B + b0 * 32 + 32 + l32] = ssb[1]; }
+    }
+    __syncthreads();
+    if (tid < 2 * B) {
+        const float sum = ssq[tid];
+        float sc = sum > 0.f ? 1.0f / sqrtf(sum) : 0.f;           // a zero row normalises to zero: all its cosines are 0
+        if (tid < B ? (s_tok[tid] == INT_MAX) : (t0 + tid - B >= p.T)) sc = 0.f;
+        scale[tid] = sc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int nl = (b0 + c) * 32 + l32;
+        finish_block(p, acc[c], s_tok + wa * 32, scale + wa * 32, scale[B + nl], repf[nl] != 0 || p.earlier_only,
+                     t0 + nl, (s0 >> 5) + wa, half);
+    }
 }
 
 // exclusive prefix sum of one 64-bit value per thread over the workgroup (three 21-bit counters ride in one scan)
@@ -706,6 +860,32 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
     }
 }
 
+// The tiles of one step, dealt to the workgroups in contiguous ranges per XCD (blockIdx % 8), the representative block
+// fastest, so that one XCD's L2 serves a contiguous range of tested rows.
+template <typename In, bool ALIGNED, int KG, bool DMA>
+__device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds) {
+    bool big = false;
+    if constexpr (ALIGNED && KG == 2 && DMA)
+        big = p.tile128 > 0 && (long long)((r + 63) / 64) * ((p.T + 63) / 64) > p.tile128;
+    const int bs = big ? 128 : 64;
+    const long long nbS = (r + bs - 1) / bs, nbT = (p.T + bs - 1) / bs;
+    const long long ntiles = nbS * nbT;
+    const long long per = (ntiles + 7) / 8;
+    const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
+    for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
+        const long long tile = xcd * per + slot;
+        if (tile >= ntiles) break;
+        const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
+        if constexpr (ALIGNED && KG == 2 && DMA) {
+            if (big) fused_tile128<In>(p, r, sb * 128, tb * 128, lds);
+            else fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
+        } else {
+            fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
+        }
+        __syncthreads();
+    }
+}
+
 // Grid: a multiple of 8 workgroups (see k_gram for the XCD-aware tile ranges); tiles with the representative
 // block fastest, so one XCD's L2 serves a contiguous range of tested rows.
 template <typename In, bool ALIGNED, int KG, bool DMA>
@@ -716,19 +896,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     ADA_CLK(0);
     const int r = p.r_dev ? *p.r_dev : p.r_host;
     const bool r_ok = r >= 1 && r <= p.r_host && r <= p.T;
-    if (r_ok) {
-        const long long nbS = (r + 63) / 64, nbT = (p.T + 63) / 64;
-        const long long ntiles = nbS * nbT;
-        const long long per = (ntiles + 7) / 8;
-        const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
-        for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
-            const long long tile = xcd * per + slot;
-            if (tile >= ntiles) break;
-            const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
-            fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
-            __syncthreads();
-        }
-    }
+    if (r_ok) fused_step_tiles<In, ALIGNED, KG, DMA>(p, r, lds);
     // The workgroup that takes the last ticket finishes the step.  Hit words and row maxima leave the CU as
     // device-scope atomics (written through the L2), so once every thread's stores are acknowledged (vmcnt(0)) and
     // the workgroup has met at the barrier, the ticket can be taken: nothing is left in the L2 to write back.
@@ -825,19 +993,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_pass(PassParams pp) {
         p.counts = pp.counts_row0 + (size_t)(i + 1) * 4;
         p.gram_ops = pp.gram_ops_row0 + (i + 1);
         const bool r_ok = r >= 1 && r <= T;
-        if (r_ok) {
-            const long long nbS = (r + 63) / 64, nbT = (T + 63) / 64;
-            const long long ntiles = nbS * nbT;
-            const long long per = (ntiles + 7) / 8;
-            const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
-            for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
-                const long long tile = xcd * per + slot;
-                if (tile >= ntiles) break;
-                const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
-                fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
-                __syncthreads();
-            }
-        }
+        if (r_ok) fused_step_tiles<In, ALIGNED, KG, DMA>(p, r, lds);
         PASS_CLK(2);
         const int jq = min((int)threadIdx.x, T - 1);         // the row has T entries whatever r is
         const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));

@@ -56,7 +56,10 @@ struct Workspace {
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-inline int hit_words(int r_cap) { return 2 * ((r_cap + 63) / 64); }
+inline int hit_words(int r_cap) {                            // whole 64- or 128-row tiles, whichever needs more words
+    const int w64 = 2 * ((r_cap + 63) / 64), w128 = 4 * ((r_cap + 127) / 128);
+    return w64 > w128 ? w64 : w128;
+}
 
 inline size_t ws_bytes_for(int T) {
     size_t t4 = align_up((size_t)T * 4, 256), t1 = align_up((size_t)T, 256);
@@ -895,6 +898,13 @@ int kgroups_override() {
     return (v == 1 || v == 2) ? v : 0;
 }
 
+// Above how many 64 x 64 tiles a step switches to 128 x 128 tiles (0: never): one per CU by default.
+int cascade_tile128() {
+    const char* e = getenv("ADA_CASCADE_TILE");              // development switch: 64 = never, 128 = always
+    if (e) { const int v = atoi(e); if (v == 64) return 0; if (v == 128) return 1; }
+    return device_cus();
+}
+
 // Picks the form of the one-launch kernel: two K-groups unless overridden; direct-to-LDS operand loads when rows come
 // in whole, aligned 128-byte chunks.
 int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_t st) {
@@ -926,7 +936,7 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
     const FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
                            (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
                            w.meta + META_TICKET, idx, adds, removes, counts,
-                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0};
+                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile128()};
     return launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
 }
 
@@ -935,7 +945,7 @@ int run_assign(const void* X, int T, int d, long long ld, int dtype, const int32
                int32_t* assign, float* corr, int32_t* info, void* ws, hipStream_t st) {
     const Workspace w = carve(ws, T);
     const FusedParams p = {X, ld, T, d, idx, r_dev, r, 2.0f, 0, nullptr, 0, nullptr, w.meta + META_TICKET,
-                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr, 0};
+                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr, 0, cascade_tile128()};
     return launch_fused_any(p, dtype, ADA_K_ASSIGN, st);
 }
 
@@ -980,7 +990,7 @@ int run_cascade_pass(const void* const* X_layers, int first, int n, int T, int d
     PassParams pp;
     pp.f = {nullptr, ld, T, d, nullptr, nullptr, T, threshold_of(tau), (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0,
             w.hits, hit_words(T), nullptr, w.meta + META_TICKET, nullptr, nullptr, nullptr, nullptr, nullptr,
-            0, nullptr, nullptr, nullptr, 0};
+            0, nullptr, nullptr, nullptr, 0, cascade_tile128()};
     // rows of idx_all that share a 128-byte line with their neighbour could be cached half-written
     pp.f.coherent_list = ((uintptr_t)idx_all % 128 != 0 || T % 32 != 0) ? 1 : 0;
     for (int i = 0; i < n; ++i) pp.X[i] = X_layers[first + i];
