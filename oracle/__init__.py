@@ -21,6 +21,7 @@ _SRC = os.path.join(_HERE, "ada_oracle.c")
 _LIB = os.path.join(_HERE, "libada_oracle.so")
 
 CROSS_EARLIER_ONLY = 1
+ATTN_CAUSAL = 1
 
 
 def build(force: bool = False) -> str:
@@ -57,6 +58,8 @@ def _load():
                                                 ctypes.c_int, ctypes.c_uint, c_i8p, c_ip, c_ip, c_ip, c_ip,
                                                 c_u64p, c_dp, c_dp]
         lib.ada_oracle_assign_nearest.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_ip, ctypes.c_int, c_ip, c_dp]
+        lib.ada_oracle_attention_compressed.argtypes = [c_dp, c_dp, c_dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, c_ip,
+                                                        ctypes.c_int, c_ip, ctypes.c_uint, c_dp]
         _lib = lib
     return _lib
 
@@ -160,3 +163,22 @@ def assign_nearest(X, idx):
     _check(_load().ada_oracle_assign_nearest(_p(X, ctypes.c_double), T, d, _p(R, ctypes.c_int32), int(R.shape[0]),
                                              _p(assign, ctypes.c_int32), _p(corr, ctypes.c_double)), "assign_nearest")
     return dict(assign=assign, corr=corr)
+
+
+def attention_compressed(Q, K, V, H: int, idx, assign, flags: int = 0) -> np.ndarray:
+    """eq. (1): attention on the representative rows, every token taking its representative's output row.
+    Q, K, V: T x (H * d_h).  Returns out, T x (H * d_h), float64."""
+    Q, K, V = _as_f64(Q), _as_f64(K), _as_f64(V)
+    T, D = Q.shape
+    if K.shape != (T, D) or V.shape != (T, D) or D % int(H) != 0:
+        raise ValueError("Q, K, V must share the shape T x (H * d_h)")
+    R = np.ascontiguousarray(np.asarray(idx, dtype=np.int32))
+    a = np.ascontiguousarray(np.asarray(assign, dtype=np.int32))
+    if a.shape != (T,):
+        raise ValueError("assign must have T entries")
+    out = np.empty((T, D), dtype=np.float64)
+    _check(_load().ada_oracle_attention_compressed(_p(Q, ctypes.c_double), _p(K, ctypes.c_double), _p(V, ctypes.c_double),
+                                                   T, int(H), D // int(H), _p(R, ctypes.c_int32), int(R.shape[0]),
+                                                   _p(a, ctypes.c_int32), int(flags), _p(out, ctypes.c_double)),
+           "attention_compressed")
+    return out

@@ -13,6 +13,7 @@
  *   - cascade step ............................... Algorithm 1 (Section 4.1)
  *   - Gram-operation count ....................... eq. (6) and Table 6 (one operation = one Gram entry)
  *   - nearest-representative assignment .......... Section 2.3 (attention on the representative set)
+ *   - attention on the representative set ........ eq. (1) (Section 2.3)
  *
  * There is no blocking, fusion or reordering: a Gram entry is one left-to-right
  * dot product of two normalised rows in double precision.  The only concession
@@ -35,6 +36,10 @@
  *   R7  strict "<" against 1 - tau^2 evaluated in double; the empty max is 0.
  *   R8  removed representatives are not reconsidered as additions in the same step
  *       (they are not in the complement of the inherited set).
+ *   R15 eq. (1) is a plain softmax over all members of R (no causal mask is printed); ADA_ORACLE_ATTN_CAUSAL
+ *       restricts a representative's keys to members of R that are not later than itself in the sequence, as
+ *       the decoder-only models of Section 6 would.  Heads lie side by side in a row (head h owns columns
+ *       h*d_h .. (h+1)*d_h - 1); every token outside R takes its representative's output row unchanged.
  *   R14 nearest representative: the maximum of |G_ts| runs over the WHOLE set R handed in (earlier and later
  *       tokens alike, as Section 2.3 states it); a member of R is its own representative with correlation 1;
  *       among equal maxima the smallest token id is reported (any of them satisfies the text).
@@ -53,6 +58,7 @@
 #define ADA_ORACLE_ERR_NOMEM 3
 
 #define ADA_ORACLE_CROSS_EARLIER_ONLY 1u
+#define ADA_ORACLE_ATTN_CAUSAL 1u
 
 int ada_oracle_threads(void) {
 #ifdef _OPENMP
@@ -317,5 +323,60 @@ int ada_oracle_assign_nearest(const double* X, int T, int d, const int32_t* idx,
         if (corr) corr[t] = best;
     }
     free(Xhat); free(in_R);
+    return ADA_ORACLE_OK;
+}
+
+/*
+ * eq. (1) (Section 2.3): per head, O_R = softmax(Q_R K_R^T / sqrt(d_h)) V_R on the r representative rows, then every
+ * token t takes the row of its representative assign[t] (reading R15).
+ * Q, K, V: T x (H*d_h) row-major.  idx[r]: R ascending.  assign[T]: members of R (as ada_oracle_assign_nearest returns).
+ * flags: ADA_ORACLE_ATTN_CAUSAL.  out: T x (H*d_h).
+ */
+int ada_oracle_attention_compressed(const double* Q, const double* K, const double* V, int T, int H, int d_h,
+                                    const int32_t* idx, int r, const int32_t* assign, unsigned flags, double* out) {
+    if (!Q || !K || !V || !idx || !assign || !out || T < 1 || H < 1 || d_h < 1) return ADA_ORACLE_ERR_ARG;
+    if (r < 1 || r > T) return ADA_ORACLE_ERR_ARG;
+    for (int j = 0; j < r; ++j) {
+        if (idx[j] < 0 || idx[j] >= T) return ADA_ORACLE_ERR_INDEX;
+        if (j > 0 && idx[j] <= idx[j - 1]) return ADA_ORACLE_ERR_INDEX;
+    }
+    const int causal = (flags & ADA_ORACLE_ATTN_CAUSAL) != 0;
+    const size_t D = (size_t)H * (size_t)d_h;
+    int32_t* pos = (int32_t*)malloc((size_t)T * sizeof(int32_t));      /* position in R, -1 outside */
+    double* O = (double*)malloc((size_t)r * D * sizeof(double));
+    if (!pos || !O) { free(pos); free(O); return ADA_ORACLE_ERR_NOMEM; }
+    for (int t = 0; t < T; ++t) pos[t] = -1;
+    for (int j = 0; j < r; ++j) pos[idx[j]] = j;
+    for (int t = 0; t < T; ++t)
+        if (assign[t] < 0 || assign[t] >= T || pos[assign[t]] < 0) { free(pos); free(O); return ADA_ORACLE_ERR_INDEX; }
+    const double inv_sqrt = 1.0 / sqrt((double)d_h);
+#pragma omp parallel for schedule(dynamic, 4) collapse(2)
+    for (int h = 0; h < H; ++h) {
+        for (int i = 0; i < r; ++i) {
+            double* p = (double*)malloc((size_t)r * sizeof(double));
+            const double* q = Q + (size_t)idx[i] * D + (size_t)h * d_h;
+            const int n = causal ? i + 1 : r;                           /* keys 0 .. n-1 (R is in sequence order) */
+            double m = -INFINITY;
+            for (int j = 0; j < n; ++j) {
+                const double* k = K + (size_t)idx[j] * D + (size_t)h * d_h;
+                double s = 0.0;
+                for (int c = 0; c < d_h; ++c) s += q[c] * k[c];
+                p[j] = s * inv_sqrt;
+                if (p[j] > m) m = p[j];
+            }
+            double z = 0.0;
+            for (int j = 0; j < n; ++j) { p[j] = exp(p[j] - m); z += p[j]; }
+            double* o = O + (size_t)i * D + (size_t)h * d_h;
+            for (int c = 0; c < d_h; ++c) o[c] = 0.0;
+            for (int j = 0; j < n; ++j) {
+                const double w = p[j] / z;
+                const double* v = V + (size_t)idx[j] * D + (size_t)h * d_h;
+                for (int c = 0; c < d_h; ++c) o[c] += w * v[c];
+            }
+            free(p);
+        }
+    }
+    for (int t = 0; t < T; ++t) memcpy(out + (size_t)t * D, O + (size_t)pos[assign[t]] * D, D * sizeof(double));
+    free(pos); free(O);
     return ADA_ORACLE_OK;
 }

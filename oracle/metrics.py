@@ -56,3 +56,8 @@ def selection_cost_independent(L: int, T: int, d: int) -> int:
 def selection_cost_cascade(L: int, T: int, d: int, r_bar: float) -> float:
     """Section 6.6: T d (T + (L-1) r_bar)."""
     return T * d * (T + (L - 1) * r_bar)
+
+
+def attention_cost_compressed(L: int, r: float, d_h: int, heads: int) -> float:
+    """Section 6.6's count for the attention on r representatives: L * 2 r^2 d_h * heads FLOPs."""
+    return float(L) * 2.0 * float(r) ** 2 * float(d_h) * float(heads)

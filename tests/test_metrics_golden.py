@@ -68,6 +68,8 @@ def test_cost_model_and_speedup(golden_dir):
     for L, T, d, r_bar, printed, unit, _ in records(golden_dir, "cost_cascade"):
         got = metrics.selection_cost_cascade(int(L), int(T), int(d), float(r_bar)) / 1e9
         assert got == pytest.approx(float(printed), rel=1e-2)
+    for L, r, dh, heads, printed, unit, _ in records(golden_dir, "cost_attention"):
+        assert metrics.attention_cost_compressed(int(L), float(r), int(dh), int(heads)) / 1e9 == pytest.approx(float(printed), rel=2e-3)
     for L, T, d, r, printed, unit, _ in records(golden_dir, "speedup"):
         assert metrics.selection_speedup(int(T), int(r)) == pytest.approx(float(printed), rel=1e-2)
 

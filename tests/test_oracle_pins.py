@@ -481,3 +481,80 @@ def test_assignment_rejects_bad_sets():
     for bad in ([], [2, 1], [1, 1], [0, 4], [-1]):
         with pytest.raises(ValueError):
             oracle.assign_nearest(X, bad)
+
+
+# ----------------------------------------------------------------------------- eq. (1): attention on the representatives
+def numpy_attention(Q, K, V, H, R, assign, causal=False):
+    """Independent statement of eq. (1) with numpy / scipy routines (float64 matmul, scipy's softmax)."""
+    from scipy.special import softmax
+    T, D = Q.shape
+    dh = D // H
+    R = np.asarray(R)
+    O = np.empty((len(R), D))
+    for h in range(H):
+        c = slice(h * dh, (h + 1) * dh)
+        S = Q[R][:, c] @ K[R][:, c].T / math.sqrt(dh)
+        if causal:
+            S = np.where(np.arange(len(R))[None, :] <= np.arange(len(R))[:, None], S, -np.inf)
+        O[:, c] = softmax(S, axis=1) @ V[R][:, c]
+    return O[np.searchsorted(R, assign)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_matches_numpy_and_scipy_softmax(causal):
+    rng = np.random.default_rng(31)
+    T, H, dh = 90, 3, 8
+    Q, K, V = (rng.standard_normal((T, H * dh)) for _ in range(3))
+    X = rng.standard_normal((T, 16))
+    R = sorted(rng.choice(T, size=23, replace=False).tolist())
+    assign = oracle.assign_nearest(X, R)["assign"]
+    out = oracle.attention_compressed(Q, K, V, H, R, assign, flags=oracle.ATTN_CAUSAL if causal else 0)
+    assert np.allclose(out, numpy_attention(Q, K, V, H, R, assign, causal), rtol=0, atol=1e-12)
+    for t in range(T):                                       # a token carries its representative's row, unchanged
+        assert np.array_equal(out[t], out[assign[t]])
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(32)
+    T, H, dh = 40, 2, 6
+    Q, V = rng.standard_normal((T, H * dh)), rng.standard_normal((T, H * dh))
+    R = [1, 5, 6, 20, 33]
+    assign = np.array([R[t % len(R)] for t in range(T)], dtype=np.int32)
+    assign[R] = R
+    # identical keys: every score in a row is equal -> uniform weights -> the mean of the value rows
+    K = np.tile(rng.standard_normal((1, H * dh)), (T, 1))
+    out = oracle.attention_compressed(Q, K, V, H, R, assign)
+    assert np.allclose(out[R], np.tile(V[R].mean(axis=0), (len(R), 1)), atol=1e-12)
+    # adding one vector to every key shifts each row of scores by a constant: softmax does not move
+    K2 = rng.standard_normal((T, H * dh))
+    a = oracle.attention_compressed(Q, K2, V, H, R, assign)
+    b = oracle.attention_compressed(Q, K2 + rng.standard_normal((1, H * dh)), V, H, R, assign)
+    assert np.allclose(a, b, atol=1e-10)
+    # one key dominating: the output approaches that key's value row; scores are divided by sqrt(d_h)
+    K3 = np.zeros((T, H * dh)); Q3 = np.zeros((T, H * dh))
+    Q3[:, 0] = 1.0; Q3[:, dh] = 1.0
+    K3[R[2], 0] = 80.0 * math.sqrt(dh); K3[R[2], dh] = 80.0 * math.sqrt(dh)
+    out3 = oracle.attention_compressed(Q3, K3, V, H, R, assign)
+    assert np.allclose(out3[R], np.tile(V[R[2]], (len(R), 1)), atol=1e-9)
+    K3[R[2], 0] = math.log(3.0) * math.sqrt(dh); K3[R[2], dh] = 0.0   # head 0: weights 3 : 1 : 1 : 1 : 1
+    out4 = oracle.attention_compressed(Q3, K3, V, H, R, assign)
+    w = np.ones(len(R)); w[2] = 3.0
+    assert np.allclose(out4[R[0], :dh], (w / w.sum()) @ V[R][:, :dh], atol=1e-12)
+    assert np.allclose(out4[R[0], dh:], V[R][:, dh:].mean(axis=0), atol=1e-12)
+    # a single representative: everybody gets its value row; causal: the first representative sees only itself
+    one = oracle.attention_compressed(Q, K2, V, H, [7], np.full(T, 7, dtype=np.int32))
+    assert np.array_equal(one, np.tile(V[7], (T, 1)))
+    c = oracle.attention_compressed(Q, K2, V, H, R, assign, flags=oracle.ATTN_CAUSAL)
+    assert np.allclose(c[R[0]], V[R[0]], atol=1e-15)
+    assert (out.min(axis=0) >= V[R].min(axis=0) - 1e-12).all() and (out.max(axis=0) <= V[R].max(axis=0) + 1e-12).all()
+
+
+def test_attention_rejects_bad_input():
+    Q = np.zeros((6, 4))
+    good = np.array([0, 0, 2, 2, 2, 0], dtype=np.int32)
+    oracle.attention_compressed(Q, Q, Q, 2, [0, 2], good)
+    for R, a in (([2, 0], good), ([0, 2], np.array([0, 1, 2, 2, 2, 0], dtype=np.int32)), ([0, 9], good)):
+        with pytest.raises(ValueError):
+            oracle.attention_compressed(Q, Q, Q, 2, R, a)
+    with pytest.raises(ValueError):
+        oracle.attention_compressed(Q, Q, Q, 3, [0, 2], good)       # 4 columns do not split into 3 heads
