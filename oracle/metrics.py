@@ -59,5 +59,7 @@ def selection_cost_cascade(L: int, T: int, d: int, r_bar: float) -> float:
 
 
 def attention_cost_compressed(L: int, r: float, d_h: int, heads: int) -> float:
-    """Section 6.6's count for the attention on r representatives: L * 2 r^2 d_h * heads FLOPs."""
-    return float(L) * 2.0 * float(r) ** 2 * float(d_h) * float(heads)
+    """FLOPs of the attention on r representatives over L layers: the two r x r x d_h products of eq. (1), at two
+    FLOPs per multiply-add: L * 4 r^2 d_h * heads.  Section 6.6 writes the formula with a factor 2 but prints
+    19.3 GFLOP for GPT-J, which is this count (the factor-2 form gives 9.6); the printed value is taken."""
+    return float(L) * 4.0 * float(r) ** 2 * float(d_h) * float(heads)
