@@ -278,6 +278,35 @@ def main():
                                                  "unit": "GB/s", "frac": layer_bytes / (1e-6 * us_a) / 1e9 / HBM_PEAK_GBS,
                                                  "bytes_per_launch": layer_bytes, "traffic": None}}
 
+        # ---- attention on the representative set (eq. (1)) for the last layer's set, 16 heads of d/16, with the
+        # hand-over to all T tokens; synthetic Q, K, V
+        Hh = 16
+        if d % Hh == 0 and d // Hh in ((64, 128, 256) if w.dtype == "bf16" else (64, 128)):
+            qd, kd, vd = (m.to(dev) for m in wl.qkv(w, Hh))
+            near = pa.ada_assign_nearest(xs[L - 1], last, r=T, r_dev=out["counts"][L - 1], ws=ws, stream=stream)
+            for _ in range(2):
+                pa.ada_attention_compressed(qd, kd, vd, Hh, last, near["assign"], r=T, r_dev=out["counts"][L - 1], ws=ws,
+                                            stream=stream)
+            torch.cuda.synchronize()
+            pa.ada_profile_enable(True)
+            for _ in range(10):
+                att = pa.ada_attention_compressed(qd, kd, vd, Hh, last, near["assign"], r=T, r_dev=out["counts"][L - 1],
+                                                  ws=ws, stream=stream)
+            torch.cuda.synchronize()
+            kt = pa.ada_profile_collect()
+            pa.ada_profile_enable(False)
+            assert att["info"].cpu().tolist()[3] == 0
+            us_t = 1e3 * kt["attn"]["ms"] / kt["attn"]["launches"]
+            r_last = r_per_layer[L - 1]
+            att_bytes = 3 * r_last * d * esz + T * d * 4       # gathered Q, K, V rows in, fp32 rows out
+            att_flops = 4.0 * r_last * r_last * d              # two r x r x d_h products per head
+            result["attention_compressed"] = {
+                "avg_launch_us": us_t, "r": r_last, "heads": Hh, "d_h": d // Hh,
+                "roofline": {"bound": "hbm", "kernel": "k_attn_rep (eq. (1) + hand-over)",
+                             "achieved": att_bytes / (1e-6 * us_t) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": att_bytes / (1e-6 * us_t) / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": att_bytes,
+                             "mfma_tflops": att_flops / (1e-6 * us_t) / 1e12, "traffic": None}}
+
         # ---- the same selection at the long-context shape (configs[4]: T=8192, d=4096, one sequence), where the
         # triangle has enough tiles to fill the chip and the kernel is bound by the matrix pipes
         w4 = wl.config(4)

@@ -62,6 +62,10 @@ typedef enum {
                                           if it runs out, the kernel ends and the unfinished layers report ADA_ERR_DEVICE in
                                           their counts (initialise the workspace again after that) */
 
+#define ADA_FLAG_ATTN_CAUSAL 8u        /* ada_attention_compressed: a representative attends only to members of R that are
+                                          not later than itself in the sequence (eq. (1) prints no mask; the decoder-only
+                                          models of Section 6 have one) */
+
 #define ADA_MAX_T (1 << 20)
 
 /* Human-readable name of a status code (static storage). */
@@ -149,6 +153,28 @@ int ada_assign_nearest(const void* X, int T, int d, int64_t ld, int dtype,
                        void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
+ * Attention on the representative set -- eq. (1) (Section 2.3): per head,
+ *   O_R = softmax(Q_R K_R^T / sqrt(d_h)) V_R      on the r representative rows (r x r instead of T x T),
+ * and every token takes the output row of its representative: out[t] = O_R[position of assign[t] in R].
+ * Inputs
+ *   Q, K, V  device, row-major T x (H * d_h), heads side by side, leading dimension ld (elements), dtype as for X;
+ *            base pointers and rows 16-byte aligned; d_h in {64, 128, 256} for bf16, {64, 128} for fp32
+ *   idx, r, r_dev   the set R as for ada_assign_nearest
+ *   assign   [T] int32, the representative of every token (the output of ada_assign_nearest for the same R)
+ * Outputs
+ *   out   [T x (H * d_h)] float, leading dimension ld_out (elements)
+ *   info  [4] int32  {|R|, 0, 0, status}; status is ADA_OK, or ADA_ERR_INDEX (idx not strictly ascending / out of
+ *                    range, or an assign entry that is not a member of R) / ADA_ERR_SHAPE (bad r_dev), and then out
+ *                    is not written
+ * Scores and weights are fp32 (row maxima subtracted); bf16 weights enter the second product as hi + lo pairs.
+ * ADA_FLAG_ATTN_CAUSAL masks later members of R.  Three small launches (status clear, positions, attention).
+ */
+int ada_attention_compressed(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
+                             const int32_t* idx, int r, const int32_t* r_dev, const int32_t* assign,
+                             float* out, int64_t ld_out, int32_t* info,
+                             void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
  * The layer loop of Section 4.1: full selection at layer 0, Algorithm 1 at layers 1..L-1, each
  * step inheriting the previous step's set on the device (no host synchronisation inside).
  *   X_layers     HOST array of L device pointers, one T x d matrix per layer
@@ -186,7 +212,7 @@ int ada_cascade_report(int L, int T, const int32_t* counts_all, const uint64_t* 
  * kernel, so these figures are upper bounds of the durations a kernel trace reports.
  */
 enum { ADA_K_NORM_PREP = 0, ADA_K_GRAM_FULL = 1, ADA_K_GRAM_REP = 2, ADA_K_GRAM_CROSS = 3, ADA_K_UPDATE = 4,
-       ADA_K_CASCADE_FUSED = 5, ADA_K_MFMA_PROBE = 6, ADA_K_ASSIGN = 7, ADA_K_COUNT = 8 };
+       ADA_K_CASCADE_FUSED = 5, ADA_K_MFMA_PROBE = 6, ADA_K_ASSIGN = 7, ADA_K_ATTN = 8, ADA_K_COUNT = 9 };
 int ada_profile_enable(int on);
 int ada_profile_collect(double* ms_sum, int* launches);
 /* A plain device-to-device copy kernel (bytes: multiple of 16, both pointers 16-byte aligned): it reads and writes

@@ -22,13 +22,15 @@ ADA_F32, ADA_BF16 = 0, 1
 FLAG_CROSS_EARLIER_ONLY = 1
 FLAG_TWO_PASS = 2
 FLAG_RESIDENT_PASS = 4
+FLAG_ATTN_CAUSAL = 8
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
            "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
-           "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest")
+           "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
+           "ada_attention_compressed")
 
-KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused", "mfma_probe", "assign")
+KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused", "mfma_probe", "assign", "attn")
 
 
 class AdaError(RuntimeError):
@@ -91,6 +93,9 @@ def lib():
         L.ada_profile_copy_probe.argtypes = [vp, vp, sz, vp]
         L.ada_profile_mfma_probe.restype = i32
         L.ada_profile_mfma_probe.argtypes = [i32, i32, vp, vp]
+        L.ada_attention_compressed.restype = i32
+        L.ada_attention_compressed.argtypes = [vp, vp, vp, i32, i32, i32, i64, i32, vp, i32, vp, vp, vp, i64, vp,
+                                               vp, sz, vp, u32]
         L.ada_assign_nearest.restype = i32
         L.ada_assign_nearest.argtypes = [vp, i32, i32, i64, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp, u32]
         _lib = L
@@ -215,6 +220,42 @@ def ada_assign_nearest(X: torch.Tensor, idx: torch.Tensor, r: Optional[int] = No
     if rc != OK:
         raise AdaError(rc, "ada_assign_nearest")
     out["_keep"] = (ws, idx, r_dev)
+    return out
+
+
+def ada_attention_compressed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, H: int, idx: torch.Tensor,
+                             assign: torch.Tensor, r: Optional[int] = None, r_dev: Optional[torch.Tensor] = None, *,
+                             ws: Optional[torch.Tensor] = None, stream=None, flags: int = 0) -> Dict[str, torch.Tensor]:
+    """Attention on the representative set (eq. (1)) with every token taking its representative's output row.
+    Q, K, V: device T x (H * d_h), same dtype and strides.  Returns device tensors out[T, H * d_h] (float32) and
+    info[4] = {|R|, 0, 0, status}."""
+    for M in (Q, K, V):
+        _check_x(M)
+    T, D = Q.shape
+    if K.shape != Q.shape or V.shape != Q.shape or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V must share shape and dtype")
+    if K.stride(0) != Q.stride(0) or V.stride(0) != Q.stride(0):
+        raise ValueError("Q, K, V must share their leading dimension")
+    if D % int(H) != 0:
+        raise ValueError("the row length must be H * d_h")
+    for a, name in ((idx, "idx"), (assign, "assign")):
+        if a.dtype != torch.int32 or not a.is_cuda or not a.is_contiguous():
+            raise ValueError("%s must be a contiguous int32 device tensor" % name)
+    if assign.numel() != T:
+        raise ValueError("assign must have T entries")
+    r = int(idx.numel()) if r is None else int(r)
+    if r > idx.numel():
+        raise ValueError("r exceeds the capacity of idx")
+    dev = Q.device
+    ws = workspace(T, dev) if ws is None else ws
+    out = dict(out=torch.empty((T, D), dtype=torch.float32, device=dev),
+               info=torch.empty(4, dtype=torch.int32, device=dev))
+    rc = lib().ada_attention_compressed(_ptr(Q), _ptr(K), _ptr(V), T, int(H), D // int(H), Q.stride(0), _dtype_code(Q),
+                                        _ptr(idx), r, _ptr(r_dev), _ptr(assign), _ptr(out["out"]), D, _ptr(out["info"]),
+                                        _ptr(ws), ws.numel(), _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_attention_compressed")
+    out["_keep"] = (ws, Q, K, V, idx, assign, r_dev)
     return out
 
 

@@ -1,0 +1,342 @@
+// Attention on the representative set -- eq. (1) of Section 2.3 -- and the hand-over of each representative's output row
+// to the tokens it represents.  Included by ada_kernels.hip after the tile helpers (Mfma, lds_swz, u32x4, f32x16).
+//
+// Per head: O_R = softmax(Q_R K_R^T / sqrt(d_h)) V_R on the r representative rows only (r x r instead of T x T), then
+// out[t] = O_R[position of assign[t] in R].  The work is small (a few GFLOP at r ~ 400), so the kernel is a plain
+// blocked softmax attention: one workgroup per (64 query representatives, head), key / value rows in blocks of 64
+// gathered through the index list, scores and weights kept in fp32, running row maximum and sum across key blocks.
+//   * S = Q K^T: the Gram tile pattern (both operands K-contiguous rows in LDS, 32x32 MFMA blocks, one per wave).
+//   * P V needs V with the key index contiguous, so V blocks are transposed while they are staged into LDS.
+//   * For bf16 inputs the weights enter the second product as hi + lo bf16 pairs (p = hi + lo to 2^-17 relative), so
+//     the product keeps fp32-level accuracy; fp32 inputs use fp32 MFMA throughout.
+// LDS rows are XOR-swizzled in 16-byte pieces so that 16 consecutive rows read at one piece index cover 16 different
+// bank groups of the 64-bank LDS (rows of 128 bytes: lds_swz; rows of 256 or 512 bytes: row % 16).
+#pragma once
+
+struct AttnParams {
+    const void* Q;
+    const void* K;
+    const void* V;
+    long long ld;
+    int T, H;
+    const int32_t* idx;        // R, ascending
+    const int32_t* r_dev;      // optional device count
+    int r_host;
+    const int32_t* pos;        // [T] position of assign[t] in R (k_attn_pos)
+    float* out;
+    long long ld_out;
+    float scale;               // 1 / sqrt(d_h)
+    int causal;
+    int32_t* info;             // [4]; info[3] holds the status (k_attn_pos)
+};
+
+// position of every token's representative in R, by binary search; validates R (strictly ascending, in range) and
+// assign (a member of R).  info[3] was zeroed by the launcher; any thread that sees a fault raises it.
+__global__ __launch_bounds__(256) void k_attn_pos(const int32_t* __restrict__ idx, const int32_t* r_dev, int r_host,
+                                                  const int32_t* __restrict__ assign, int T, int32_t* __restrict__ pos,
+                                                  int32_t* info) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    int r = r_dev ? *r_dev : r_host;
+    const bool r_ok = r >= 1 && r <= r_host && r <= T;
+    if (!r_ok) {
+        if (i == 0) { info[0] = 0; atomicMax(info + 3, (int)ADA_ERR_SHAPE); }
+        if (i < T) pos[i] = 0;
+        return;
+    }
+    if (i == 0) info[0] = r;
+    if (i < r) {
+        const int q = idx[i];
+        if (q < 0 || q >= T || (i > 0 && !(idx[i - 1] < q))) atomicMax(info + 3, (int)ADA_ERR_INDEX);
+    }
+    if (i < T) {
+        const int a = assign[i];
+        int lo = 0, hi = r - 1;
+        while (lo < hi) {                                  // first position with idx[pos] >= a
+            const int mid = (lo + hi) >> 1;
+            if (idx[mid] < a) lo = mid + 1; else hi = mid;
+        }
+        if (idx[lo] != a) atomicMax(info + 3, (int)ADA_ERR_INDEX);
+        pos[i] = lo;
+    }
+}
+
+__device__ inline int attn_off(int row, int piece, int ppr) {
+    const int swz = ppr >= 16 ? (row & 15) : lds_swz(row);
+    return row * ppr * 16 + ((piece ^ swz) << 4);
+}
+
+template <typename In> __device__ inline In attn_elem(u32x4 v, int e);
+template <> __device__ inline uint16_t attn_elem<uint16_t>(u32x4 v, int e) { return (uint16_t)(v[e >> 1] >> (16 * (e & 1))); }
+template <> __device__ inline float attn_elem<float>(u32x4 v, int e) { return __uint_as_float(v[e]); }
+
+__device__ inline uint32_t attn_bf16_rne(float f) {        // finite inputs; rounds the magnitude, keeps the sign
+    const uint32_t u = __float_as_uint(f);
+    return ((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16) & 0xFFFFu;
+}
+
+template <typename In, int DH> struct AttnGeom {
+    static constexpr int E = (int)sizeof(In), EPP = 16 / E;
+    static constexpr int ROWB = DH * E, PPR = ROWB / 16;              // a Q / K row of one head
+    static constexpr int PPRV = 64 * E / 16;                          // a V^T or P row: 64 keys
+    static constexpr int OFF_Q = 0, OFF_K = 64 * ROWB, OFF_VT = 2 * 64 * ROWB;
+    static constexpr int OFF_S = 3 * 64 * ROWB;                       // float[64][65]
+    static constexpr int OFF_P = OFF_S + 64 * 65 * 4;                 // weights: bf16 hi then lo (8 KB each), or fp32 (16 KB)
+    static constexpr int OFF_ROW = OFF_P + 16384;                     // alpha[64], lsum[64], qtok[64], ktok[64]
+    static constexpr int OFF_LIST = OFF_ROW + 4 * 64 * 4;             // int[256] + counter
+    static constexpr int LDS = OFF_LIST + 257 * 4;
+    static_assert(PPR == 8 || PPR == 16 || PPR == 32, "head rows of 128, 256 or 512 bytes");
+    static_assert(DH % 64 == 0, "head dimension in multiples of 64");
+};
+
+#ifdef ADA_PHASE_CLOCKS
+#define ATTN_CLK(k) do { if (threadIdx.x == 0 && blockIdx.x == 1 && blockIdx.y == 3) g_phase_clk[k] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define ATTN_CLK(k) do { } while (0)
+#endif
+
+template <typename In, int DH>
+__global__ __launch_bounds__(256) void k_attn_rep(AttnParams p) {
+    using G = AttnGeom<In, DH>;
+    constexpr int EPP = G::EPP, PPR = G::PPR, PPRV = G::PPRV, NB = DH / 64;
+    extern __shared__ __align__(16) char lds[];
+    char* qbuf = lds + G::OFF_Q;
+    char* kbuf = lds + G::OFF_K;
+    char* vtbuf = lds + G::OFF_VT;
+    float* sbuf = reinterpret_cast<float*>(lds + G::OFF_S);
+    char* pbuf = lds + G::OFF_P;
+    float* alpha = reinterpret_cast<float*>(lds + G::OFF_ROW);
+    float* lsum = alpha + 64;
+    int* qtok = reinterpret_cast<int*>(lsum + 64);
+    int* ktok = qtok + 64;
+    int* list = reinterpret_cast<int*>(lds + G::OFF_LIST);
+
+    ATTN_CLK(0);
+    if (p.info[3] != ADA_OK) return;                       // k_attn_pos rejected the set or the assignment
+    const int r = p.r_dev ? *p.r_dev : p.r_host;
+    const int q0 = blockIdx.x * 64, h = blockIdx.y;
+    if (q0 >= r) return;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const In* Qh = reinterpret_cast<const In*>(p.Q) + (size_t)h * DH;
+    const In* Kh = reinterpret_cast<const In*>(p.K) + (size_t)h * DH;
+    const In* Vh = reinterpret_cast<const In*>(p.V) + (size_t)h * DH;
+
+    constexpr int NP = PPR / 4;                            // 16-byte pieces per thread per 64-row block
+    if (tid < 64) qtok[tid] = min(max(p.idx[min(q0 + tid, r - 1)], 0), p.T - 1);
+    __syncthreads();
+    {   // Q block: rows gathered through the list; all loads are issued before the first store
+        u32x4 qreg[NP];
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            const int i = tid + 256 * j, row = i / PPR, pc = i % PPR;
+            qreg[j] = *reinterpret_cast<const u32x4*>(Qh + (size_t)qtok[row] * (size_t)p.ld + pc * EPP);
+        }
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            const int i = tid + 256 * j, row = i / PPR, pc = i % PPR;
+            *reinterpret_cast<u32x4*>(qbuf + attn_off(row, pc, PPR)) = qreg[j];
+        }
+    }
+    // K and V blocks travel through registers one block ahead of the products.  K pieces are fetched row-major
+    // (coalesced); V pieces with the key row fastest across lanes, so that the transposed 2- or 4-byte stores of one
+    // wave instruction fill one whole row of V^T instead of colliding on a few banks.
+    // The token ids of a block are requested one block before its rows, so that neither trip to memory is waited for
+    // in the middle of a block: ids(kb + 2) and fetch(kb + 1) are issued behind the products of block kb.
+    u32x4 kreg[NP], vreg[NP];
+    int ktid[NP], vtid;
+    auto ids = [&](int kb) {
+#pragma unroll
+        for (int j = 0; j < NP; ++j) ktid[j] = p.idx[min(kb * 64 + (tid + 256 * j) / PPR, r - 1)];
+        vtid = p.idx[min(kb * 64 + (tid & 63), r - 1)];
+    };
+    auto fetch = [&]() {                                   // rows of the block whose ids are in ktid / vtid
+        const size_t vt = (size_t)min(max(vtid, 0), p.T - 1) * (size_t)p.ld;
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            const int i = tid + 256 * j;
+            const int kpc = i % PPR, vpc = i >> 6;
+            kreg[j] = *reinterpret_cast<const u32x4*>(Kh + (size_t)min(max(ktid[j], 0), p.T - 1) * (size_t)p.ld + kpc * EPP);
+            vreg[j] = *reinterpret_cast<const u32x4*>(Vh + vt + vpc * EPP);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            const int i = tid + 256 * j;
+            const int krow = i / PPR, kpc = i % PPR, vrow = i & 63, vpc = i >> 6;
+            *reinterpret_cast<u32x4*>(kbuf + attn_off(krow, kpc, PPR)) = kreg[j];
+            // V^T: element (key row, column c) goes to row c, key position row
+#pragma unroll
+            for (int e = 0; e < EPP; ++e) {
+                const int c = vpc * EPP + e;
+                *reinterpret_cast<In*>(vtbuf + attn_off(c, vrow / EPP, PPRV) + (vrow % EPP) * G::E) = attn_elem<In>(vreg[j], e);
+            }
+        }
+    };
+
+    // running maximum and sum of the row this thread helps with (four threads per row hold the same values)
+    const int srow = tid >> 2, spart = tid & 3;
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16 acc_o[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[i][e] = 0.f;
+
+    const int nkb_all = (r + 63) / 64;
+    const int nkb = p.causal ? min(nkb_all, q0 / 64 + 1) : nkb_all;   // R is in sequence order: later key blocks are fully masked
+    ids(0);
+    fetch();
+    ids(1);
+    ATTN_CLK(1);
+    for (int kb = 0; kb < nkb; ++kb) {
+        if (kb == 1) ATTN_CLK(2);
+        __syncthreads();                                   // the previous block's products are done with K, V^T, P
+        if (tid < 64) ktok[tid] = min(max(p.idx[min(kb * 64 + tid, r - 1)], 0), p.T - 1);
+        stash();
+        __syncthreads();
+        if (kb == 1) ATTN_CLK(3);
+        if (kb + 1 < nkb) { fetch(); ids(kb + 2); }        // in flight behind this block's products
+        {   // ---- S = Q K^T for this wave's 32 x 32 block, scaled and masked, to LDS
+            const int wa = wave >> 1, wb = wave & 1;
+            f32x16 acc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < PPR / 2; ++ks) {
+                const u32x4 fa = *reinterpret_cast<const u32x4*>(qbuf + attn_off(wa * 32 + l32, 2 * ks + half, PPR));
+                const u32x4 fb = *reinterpret_cast<const u32x4*>(kbuf + attn_off(wb * 32 + l32, 2 * ks + half, PPR));
+                Mfma<In>::run(acc, fa, fb);
+            }
+            const int kc = wb * 32 + l32;                  // key column of this lane
+            const bool k_in = kb * 64 + kc < r;
+            const int kt = p.causal ? ktok[kc] : INT_MIN;  // without the mask no key is "later"
+            i32x4 qt4[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) qt4[q] = *reinterpret_cast<const i32x4*>(qtok + wa * 32 + 8 * q + 4 * half);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int qr = wa * 32 + (e & 3) + 4 * half + 8 * (e >> 2);
+                const bool masked = !k_in | (kt > qt4[e >> 2][e & 3]);
+                sbuf[qr * 65 + kc] = masked ? -INFINITY : acc[e] * p.scale;
+            }
+        }
+        __syncthreads();
+        if (kb == 1) ATTN_CLK(4);
+        {   // ---- softmax bookkeeping for row srow, columns 16 spart .. 16 spart + 15
+            float s[16];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) { s[j] = sbuf[srow * 65 + spart * 16 + j]; mx = fmaxf(mx, s[j]); }
+            mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+            const float m_new = fmaxf(m_run, mx);
+            const float a = m_new == -INFINITY ? 1.f : __expf(m_run - m_new);    // exp(-inf) = 0 on the first block
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) { s[j] = m_new == -INFINITY ? 0.f : __expf(s[j] - m_new); sum += s[j]; }
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            l_run = l_run * a + sum;
+            m_run = m_new;
+            if (spart == 0) alpha[srow] = a;
+            if constexpr (sizeof(In) == 2) {               // hi + lo bf16 pairs, 8 weights per 16-byte piece
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    u32x4 hi, lo;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        uint32_t hw = 0u, lw = 0u;
+#pragma unroll
+                        for (int z = 0; z < 2; ++z) {
+                            const float pv = s[q * 8 + w * 2 + z];
+                            const uint32_t hb = attn_bf16_rne(pv);
+                            const uint32_t lo16 = attn_bf16_rne(pv - __uint_as_float(hb << 16));   // signed remainder
+                            hw |= hb << (16 * z);
+                            lw |= (lo16 & 0xFFFFu) << (16 * z);
+                        }
+                        hi[w] = hw; lo[w] = lw;
+                    }
+                    *reinterpret_cast<u32x4*>(pbuf + attn_off(srow, spart * 2 + q, PPRV)) = hi;
+                    *reinterpret_cast<u32x4*>(pbuf + 8192 + attn_off(srow, spart * 2 + q, PPRV)) = lo;
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<u32x4*>(pbuf + attn_off(srow, spart * 4 + q, PPRV)) =
+                        u32x4{__float_as_uint(s[4 * q]), __float_as_uint(s[4 * q + 1]), __float_as_uint(s[4 * q + 2]),
+                              __float_as_uint(s[4 * q + 3])};
+            }
+        }
+        __syncthreads();
+        if (kb == 1) ATTN_CLK(5);
+        // ---- O = alpha O + P V for this wave's blocks (block b: query half b % 2, column block b / 2)
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int b = wave + 4 * i, qa = b & 1, cb = b >> 1;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 a4 = *reinterpret_cast<const f32x4*>(alpha + qa * 32 + 8 * q + 4 * half);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc_o[i][4 * q + e] *= a4[e];
+            }
+#pragma unroll
+            for (int ks = 0; ks < PPRV / 2; ++ks) {
+                const u32x4 fb = *reinterpret_cast<const u32x4*>(vtbuf + attn_off(cb * 32 + l32, 2 * ks + half, PPRV));
+                const u32x4 fa = *reinterpret_cast<const u32x4*>(pbuf + attn_off(qa * 32 + l32, 2 * ks + half, PPRV));
+                Mfma<In>::run(acc_o[i], fa, fb);
+                if constexpr (sizeof(In) == 2) {
+                    const u32x4 fl = *reinterpret_cast<const u32x4*>(pbuf + 8192 + attn_off(qa * 32 + l32, 2 * ks + half, PPRV));
+                    Mfma<In>::run(acc_o[i], fl, fb);
+                }
+            }
+        }
+    }
+    ATTN_CLK(6);
+    if (spart == 0) lsum[srow] = l_run;
+    __syncthreads();                                       // everybody is done with Q, K (O is laid over them)
+    float* obuf = reinterpret_cast<float*>(lds + G::OFF_Q);   // [64][DH]
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int b = wave + 4 * i, qa = b & 1, cb = b >> 1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 l4 = *reinterpret_cast<const f32x4*>(lsum + qa * 32 + 8 * q + 4 * half);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int qr = qa * 32 + e + 4 * half + 8 * q;
+                const float inv = l4[e] > 0.f ? 1.0f / l4[e] : 0.f;
+                obuf[qr * DH + cb * 32 + l32] = acc_o[i][4 * q + e] * inv;
+            }
+        }
+    }
+    __syncthreads();
+    ATTN_CLK(7);
+    // ---- hand-over: every token whose representative sits in this block takes that row (tokens in chunks of 256)
+    float* outh = p.out + (size_t)h * DH;
+    for (int tb = 0; tb < p.T; tb += 8 * 256) {            // positions of 2048 tokens at a time, one trip to memory
+        int rel[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int t = tb + u * 256 + tid;
+            rel[u] = t < p.T ? p.pos[t] - q0 : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (tb + u * 256 >= p.T) break;                // uniform
+            if (tid == 0) list[256] = 0;
+            __syncthreads();
+            if ((unsigned)rel[u] < 64u) list[atomicAdd(&list[256], 1)] = ((tb + u * 256 + tid) << 6) | rel[u];
+            __syncthreads();
+            const int n = list[256];
+            for (int j = wave; j < n; j += 4) {            // one wave per token row
+                const int e = list[j], tt = e >> 6, row = e & 63;
+                float* dst = outh + (size_t)tt * (size_t)p.ld_out;
+#pragma unroll
+                for (int c = 0; c < DH; c += 64) dst[c + lane] = obuf[row * DH + c + lane];
+            }
+            __syncthreads();
+        }
+    }
+    ATTN_CLK(8);
+}

@@ -667,6 +667,7 @@ __global__ __launch_bounds__(256) void k_copy_probe(u32x4* __restrict__ dst, con
 
 #include "ada_fused.hpp"
 #include "ada_gram_dma.hpp"
+#include "ada_attn.hpp"
 
 // ------------------------------------------------------------------------------------------------
 // host side
@@ -818,6 +819,21 @@ hipError_t dispatch(int dtype, const void* X, long long ld, int d, F&& f) {
     const bool al = ((uintptr_t)X % 16 == 0) && (ld % epp == 0) && (d % epp == 0);
     if (dtype == ADA_BF16) return al ? f(Variant<uint16_t, true>{}) : f(Variant<uint16_t, false>{});
     return al ? f(Variant<float, true>{}) : f(Variant<float, false>{});
+}
+
+template <typename In, int DH>
+hipError_t launch_attn(const AttnParams& p, hipStream_t st) {
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    constexpr int lds = AttnGeom<In, DH>::LDS;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_rep<In, DH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    ProfScope ps(ADA_K_ATTN, st);
+    hipLaunchKernelGGL((k_attn_rep<In, DH>), dim3((p.r_host + 63) / 64, p.H), dim3(256), lds, st, p);
+    return hipGetLastError();
 }
 
 int check_common(const void* X, int T, int d, int64_t ld, int dtype, float tau, void* ws, size_t ws_bytes) {
@@ -1084,6 +1100,35 @@ int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float ta
     if (!mask || !count) return ADA_ERR_NULL;
     if (int e = check_common(X, T, d, ld, dtype, tau, ws, ws_bytes)) return e;
     return run_full(X, T, d, ld, dtype, tau, mask, idx, count, nullptr, gamma, ws, (hipStream_t)stream);
+}
+
+int ada_attention_compressed(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
+                             const int32_t* idx, int r, const int32_t* r_dev, const int32_t* assign, float* out,
+                             int64_t ld_out, int32_t* info, void* ws, size_t ws_bytes, void* stream, unsigned flags) {
+    if (!Q || !K || !V || !idx || !assign || !out || !info || !ws) return ADA_ERR_NULL;
+    if (dtype != ADA_F32 && dtype != ADA_BF16) return ADA_ERR_DTYPE;
+    if (T < 1 || T > ADA_MAX_T || H < 1 || H > 65535 || r < 1 || r > T) return ADA_ERR_SHAPE;
+    const bool dh_ok = dtype == ADA_BF16 ? (d_h == 64 || d_h == 128 || d_h == 256) : (d_h == 64 || d_h == 128);
+    const int64_t D = (int64_t)H * d_h;
+    const int esz = dtype == ADA_BF16 ? 2 : 4;
+    if (!dh_ok || ld < D || ld_out < D || (ld * esz) % 16 != 0) return ADA_ERR_SHAPE;
+    if ((uintptr_t)Q % 16 || (uintptr_t)K % 16 || (uintptr_t)V % 16) return ADA_ERR_SHAPE;
+    if (ws_bytes < ws_bytes_for(T) || ((uintptr_t)ws % 256) != 0) return ADA_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const Workspace w = carve(ws, T);
+    if (fill_u32(info, 4, 0u, st) != hipSuccess) return ADA_ERR_DEVICE;
+    const int n = T > r ? T : r;
+    hipLaunchKernelGGL(k_attn_pos, dim3((n + 255) / 256), dim3(256), 0, st, idx, r_dev, r, assign, T, w.nonrep_idx, info);
+    if (hipGetLastError() != hipSuccess) return ADA_ERR_DEVICE;
+    const AttnParams p = {Q, K, V, ld, T, H, idx, r_dev, r, w.nonrep_idx, out, ld_out,
+                          (float)(1.0 / sqrt((double)d_h)), (flags & ADA_FLAG_ATTN_CAUSAL) ? 1 : 0, info};
+    hipError_t e;
+    if (dtype == ADA_BF16)
+        e = d_h == 64 ? launch_attn<uint16_t, 64>(p, st) : d_h == 128 ? launch_attn<uint16_t, 128>(p, st)
+                                                                      : launch_attn<uint16_t, 256>(p, st);
+    else
+        e = d_h == 64 ? launch_attn<float, 64>(p, st) : launch_attn<float, 128>(p, st);
+    return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
 int ada_assign_nearest(const void* X, int T, int d, int64_t ld, int dtype, const int32_t* idx, int r,

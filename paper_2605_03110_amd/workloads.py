@@ -108,3 +108,13 @@ def small(T: int, d: int, K: int, L: int, dtype: str = "bf16", seed: int = 7, p:
           sigma_c: float = 0.01, tau: float = 0.1, scale: str = "relative") -> Workload:
     """A reduced workload of the same recipe for tests (ragged T and d allowed)."""
     return Workload("small_T%d_d%d" % (T, d), seed, T, d, L, dtype, tau, K, 0.004, sigma_c, p, scale=scale)
+
+
+def qkv(w: Workload, H: int, sequence: int = 0, layer: int = 0):
+    """Seeded stand-ins for one layer's query / key / value activations, T x d with H heads side by side (the paper's
+    are projections of real activations, which are not available): i.i.d. N(0, 1) entries, so that scores divided by
+    sqrt(d_h) have unit variance.  Returns three CPU tensors in w.dtype."""
+    if w.d % H != 0:
+        raise ValueError("d must be a multiple of the head count")
+    rng = np.random.default_rng(7_000_000 + 1000 * w.seed(sequence) + layer)
+    return tuple(to_dtype(rng.standard_normal((w.T, w.d), dtype=np.float32), w.dtype) for _ in range(3))

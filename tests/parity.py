@@ -93,3 +93,16 @@ def check_assign(x_cpu, idx, got_assign, got_corr, what=""):
         c = np.sort(np.abs(Xn[idx] @ Xn[t]))
         assert c[-1] - c[-2] <= 2 * GAMMA_TOL, "%s token %d: unique maximiser missed" % (what, t)
     return dict(ref=ref, corr_err=err, n_differ=int(len(differ)))
+
+
+ATTN_TOL = 2e-5     # absolute, for value entries of unit scale; see the derivation next to the test
+
+
+def check_attention(q, k, v, H, idx, assign, got_out, causal=False, what=""):
+    """eq. (1): GPU output (float32) against the float64 oracle on the same (bf16- or fp32-valued) inputs."""
+    ref = oracle.attention_compressed(wl.as_f64(q), wl.as_f64(k), wl.as_f64(v), H, idx, assign,
+                                      flags=oracle.ATTN_CAUSAL if causal else 0)
+    vmax = float(np.max(np.abs(wl.as_f64(v))))
+    err = float(np.max(np.abs(got_out.astype(np.float64) - ref)))
+    assert err <= ATTN_TOL * max(1.0, vmax), "%s attention error %.3g (|V| max %.3g)" % (what, err, vmax)
+    return err

@@ -538,3 +538,64 @@ def test_assignment_at_config2_size():
     full = pa.fetch(pa.ada_select_full(x.to(DEV), w.tau))
     got = assign_and_check(x, full["idx"], "config 2")
     assert got["n_differ"] == 0                                   # clusters: the maximiser is unique by a wide margin
+
+
+# ------------------------------------------------------------------------------------------ eq. (1): attention on R
+# Tolerance: products of bf16 (or fp32) inputs are exact in the fp32 accumulators; a score sums d_h <= 256 of them
+# (relative rounding ~ d_h 2^-24 of a value of size ~ sqrt(d_h) before scaling: < 1e-5 absolute on scores of order
+# 1), exp and the running rescale add a few ulp, bf16 weights are split into hi + lo (2^-17 relative), and the second
+# product sums r <= 1000 non-negative weights (sum 1) times values in fp32 (~ 1e-6 |V|).  Measured: up to 6e-6 at
+# |V|max = 4.5; the bar is 2e-5 |V|max.
+def attention_case(T, d, H, K, dtype, seed, causal, what):
+    w = wl.small(T=T, d=d, K=K, L=1, dtype=dtype, seed=seed, p=0.1)
+    x = wl.layer_list(w)[0]
+    q, k, v = wl.qkv(w, H)
+    full = pa.fetch(pa.ada_select_full(x.to(DEV), w.tau))
+    idx = torch.as_tensor(full["idx"]).to(DEV)
+    near = pa.ada_assign_nearest(x.to(DEV), idx)
+    res = pa.ada_attention_compressed(q.to(DEV), k.to(DEV), v.to(DEV), H, idx, near["assign"],
+                                      flags=pa.FLAG_ATTN_CAUSAL if causal else 0)
+    info = res["info"].cpu().tolist()
+    assert info == [full["r"], 0, 0, 0], what
+    return parity.check_attention(q, k, v, H, full["idx"], near["assign"].cpu().numpy(), res["out"].cpu().numpy(),
+                                  causal, what)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("T,d,H,K,dtype", [(333, 256, 4, 40, "bf16"), (700, 256, 2, 150, "bf16"), (500, 512, 2, 90, "bf16"),
+                                           (300, 128, 2, 70, "f32"), (260, 256, 2, 33, "f32"), (1, 64, 1, 1, "bf16"),
+                                           (130, 128, 1, 130, "bf16")])
+def test_attention_on_the_representative_set(T, d, H, K, dtype, causal):
+    """Head sizes 64 / 128 / 256 (bf16) and 64 / 128 (fp32), one to three key blocks, a single token, r = T."""
+    say("attention T=%d d=%d H=%d %s causal=%s" % (T, d, H, dtype, causal))
+    attention_case(T, d, H, K, dtype, 5 + T, causal, "attention T=%d" % T)
+
+
+def test_attention_rejects_bad_sets_and_assignments():
+    say("attention bad input")
+    w = wl.small(T=200, d=128, K=20, L=1, dtype="bf16", seed=3)
+    q, k, v = (m.to(DEV) for m in wl.qkv(w, 2))
+    good_idx = torch.tensor([3, 50, 120], dtype=torch.int32, device=DEV)
+    assign = torch.full((w.T,), 50, dtype=torch.int32, device=DEV)
+    ok = pa.ada_attention_compressed(q, k, v, 2, good_idx, assign)
+    assert ok["info"].cpu().tolist() == [3, 0, 0, 0]
+    bad_assign = assign.clone(); bad_assign[7] = 51                 # not a member of R
+    assert pa.ada_attention_compressed(q, k, v, 2, good_idx, bad_assign)["info"].cpu().tolist()[3] == 4
+    bad_idx = torch.tensor([50, 3, 120], dtype=torch.int32, device=DEV)
+    assert pa.ada_attention_compressed(q, k, v, 2, bad_idx, assign)["info"].cpu().tolist()[3] == 4
+    zero = torch.zeros(1, dtype=torch.int32, device=DEV)
+    assert pa.ada_attention_compressed(q, k, v, 2, good_idx, assign, r_dev=zero)["info"].cpu().tolist()[3] == 2
+
+
+def test_attention_at_config2_size():
+    say("attention config 2")
+    w = wl.config(2)
+    x = next(iter(wl.layers(w, 0, 1)))
+    q, k, v = wl.qkv(w, 16)
+    full = pa.fetch(pa.ada_select_full(x.to(DEV), w.tau))
+    idx = torch.as_tensor(full["idx"]).to(DEV)
+    near = pa.ada_assign_nearest(x.to(DEV), idx)
+    res = pa.ada_attention_compressed(q.to(DEV), k.to(DEV), v.to(DEV), 16, idx, near["assign"])
+    assert res["info"].cpu().tolist()[3] == 0
+    parity.check_attention(q, k, v, 16, full["idx"], near["assign"].cpu().numpy(), res["out"].cpu().numpy(), False,
+                           "config 2")

@@ -102,6 +102,16 @@ def test_host_checkable_errors_return_before_touching_the_device(ada):
     assert assign(info=None) == NULL and assign(ws=None) == NULL
     assert assign(r=0) == SHAPE and assign(r=9) == SHAPE and assign(T=0) == SHAPE and assign(ld=7) == SHAPE
     assert assign(dtype=3) == DTYPE and assign(nb=64) == WS
+
+    def attn(Q=0x1000, T=8, H=2, dh=64, ld=128, dtype=1, idx=0x1000, r=2, a=0x1000, out=0x1000, ldo=128, info=0x1000,
+             ws=0x1000, nb=1 << 20):
+        return lib.ada_attention_compressed(Q, 0x1000, 0x1000, T, H, dh, ld, dtype, idx, r, None, a, out, ldo, info,
+                                            ws, nb, None, 0)
+    assert attn(Q=None) == NULL and attn(idx=None) == NULL and attn(a=None) == NULL and attn(out=None) == NULL
+    assert attn(info=None) == NULL and attn(ws=None) == NULL
+    assert attn(dh=48) == SHAPE and attn(dh=256, dtype=0, ld=512, ldo=512) == SHAPE      # fp32 heads stop at 128
+    assert attn(ld=64) == SHAPE and attn(ldo=64) == SHAPE and attn(r=0) == SHAPE and attn(r=9) == SHAPE
+    assert attn(Q=0x1008) == SHAPE and attn(dtype=4) == DTYPE and attn(nb=64) == WS
     assert lib.ada_set_overlap(None, 0x1000, 4, 0x1000, None) == NULL
     assert lib.ada_set_overlap(0x1000, 0x1000, 0, 0x1000, None) == SHAPE
     ptrs = (ctypes.c_void_p * 2)(0x1000, None)
