@@ -898,8 +898,9 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = A
     if (attr_err != hipSuccess) return attr_err;
     long long tiles = (long long)((p.r_host + 63) / 64) * ((p.T + 63) / 64);
     // Workgroups loop over tiles, so any grid is correct.  With the set size known only on the device the bound
-    // r_host = T would launch mostly idle workgroups, and dispatching those is not free: cap at two per CU.
-    const long long cap = p.r_dev ? 512 : 2048;
+    // r_host = T would launch mostly idle workgroups, and dispatching those is not free: cap at one per CU (the LDS
+    // footprint admits no more at a time anyway).
+    const long long cap = p.r_dev ? device_cus() : 2048;
     if (tiles > cap) tiles = cap;
     const unsigned grid = (unsigned)(tiles + 7) / 8 * 8;             // multiple of 8 (XCDs)
     ProfScope ps(prof_class, st);
