@@ -89,7 +89,7 @@ template <typename In, int DH> struct AttnGeom {
 };
 
 #ifdef ADA_PHASE_CLOCKS
-#define ATTN_CLK(k) do { if (threadIdx.x == 0 && blockIdx.x == 1 && blockIdx.y == 3) g_phase_clk[k] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#define ATTN_CLK(k) do { if (threadIdx.x == 0 && (k) < 8) g_pass_clk[((blockIdx.y * gridDim.x + blockIdx.x) & 511) * 8 + ((k) & 7)] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define ATTN_CLK(k) do { } while (0)
 #endif
@@ -113,10 +113,13 @@ __global__ __launch_bounds__(256) void k_attn_rep(AttnParams p) {
     ATTN_CLK(0);
     if (p.info[3] != ADA_OK) return;                       // k_attn_pos rejected the set or the assignment
     const int r = p.r_dev ? *p.r_dev : p.r_host;
-    const int q0 = blockIdx.x * 64, h = blockIdx.y;
-    if (q0 >= r) return;
+    const int h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // query blocks are dealt round-robin over gridDim.x: with the set size known only on the device the launcher
+    // sizes the grid for the chip, not for the largest possible set (idle workgroups of this LDS size are not free)
+    for (int q0 = blockIdx.x * 64; q0 < r; q0 += gridDim.x * 64) {
+    __syncthreads();                                       // a previous query block's hand-over is done with the LDS
     const In* Qh = reinterpret_cast<const In*>(p.Q) + (size_t)h * DH;
     const In* Kh = reinterpret_cast<const In*>(p.K) + (size_t)h * DH;
     const In* Vh = reinterpret_cast<const In*>(p.V) + (size_t)h * DH;
@@ -222,7 +225,6 @@ __global__ __launch_bounds__(256) void k_attn_rep(AttnParams p) {
             }
         }
         __syncthreads();
-        if (kb == 1) ATTN_CLK(4);
         {   // ---- softmax bookkeeping for row srow, columns 16 spart .. 16 spart + 15
             float s[16];
             float mx = -INFINITY;
@@ -269,7 +271,6 @@ __global__ __launch_bounds__(256) void k_attn_rep(AttnParams p) {
             }
         }
         __syncthreads();
-        if (kb == 1) ATTN_CLK(5);
         // ---- O = alpha O + P V for this wave's blocks (block b: query half b % 2, column block b / 2)
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -338,5 +339,6 @@ __global__ __launch_bounds__(256) void k_attn_rep(AttnParams p) {
             __syncthreads();
         }
     }
-    ATTN_CLK(8);
+    ATTN_CLK(4);
+    }
 }

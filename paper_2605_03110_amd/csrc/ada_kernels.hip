@@ -832,7 +832,12 @@ hipError_t launch_attn(const AttnParams& p, hipStream_t st) {
     });
     if (attr_err != hipSuccess) return attr_err;
     ProfScope ps(ADA_K_ATTN, st);
-    hipLaunchKernelGGL((k_attn_rep<In, DH>), dim3((p.r_host + 63) / 64, p.H), dim3(256), lds, st, p);
+    int gx = (p.r_host + 63) / 64;
+    if (p.r_dev) {                                         // size known on the device only: about one workgroup per CU
+        const int fit = (device_cus() + p.H - 1) / p.H;
+        gx = gx < fit ? gx : fit;
+    }
+    hipLaunchKernelGGL((k_attn_rep<In, DH>), dim3(gx, p.H), dim3(256), lds, st, p);
     return hipGetLastError();
 }
 

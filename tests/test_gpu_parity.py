@@ -571,6 +571,24 @@ def test_attention_on_the_representative_set(T, d, H, K, dtype, causal):
     attention_case(T, d, H, K, dtype, 5 + T, causal, "attention T=%d" % T)
 
 
+def test_attention_with_device_side_set_size_loops_over_query_blocks():
+    """128 heads and the set size on the device: the grid is sized for the chip (two workgroups per head) and each
+    workgroup walks through two of the four query blocks."""
+    say("attention r_dev, looping grid")
+    w = wl.small(T=300, d=8192, K=250, L=1, dtype="bf16", seed=77, p=0.1)
+    x = wl.layer_list(w)[0]
+    q, k, v = wl.qkv(w, 128)
+    sel = pa.ada_select_full(x.to(DEV), w.tau)
+    full = pa.fetch(sel)
+    assert full["r"] > 192
+    near = pa.ada_assign_nearest(x.to(DEV), sel["idx"], r=w.T, r_dev=sel["counts"])
+    res = pa.ada_attention_compressed(q.to(DEV), k.to(DEV), v.to(DEV), 128, sel["idx"], near["assign"], r=w.T,
+                                      r_dev=sel["counts"])
+    assert res["info"].cpu().tolist() == [full["r"], 0, 0, 0]
+    parity.check_attention(q, k, v, 128, full["idx"], near["assign"].cpu().numpy(), res["out"].cpu().numpy(), False,
+                           "looping grid")
+
+
 def test_attention_rejects_bad_sets_and_assignments():
     say("attention bad input")
     w = wl.small(T=200, d=128, K=20, L=1, dtype="bf16", seed=3)
