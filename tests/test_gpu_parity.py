@@ -575,7 +575,7 @@ def test_attention_with_device_side_set_size_loops_over_query_blocks():
     """128 heads and the set size on the device: the grid is sized for the chip (two workgroups per head) and each
     workgroup walks through two of the four query blocks."""
     say("attention r_dev, looping grid")
-    w = wl.small(T=300, d=8192, K=250, L=1, dtype="bf16", seed=77, p=0.1)
+    w = wl.small(T=300, d=8192, K=1000, L=1, dtype="bf16", seed=77, p=0.1)
     x = wl.layer_list(w)[0]
     q, k, v = wl.qkv(w, 128)
     sel = pa.ada_select_full(x.to(DEV), w.tau)
