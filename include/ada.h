@@ -123,6 +123,7 @@ int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float ta
  *                       it is the exact gamma^cross of step 8.  (With ADA_FLAG_CROSS_EARLIER_ONLY only earlier
  *                       representatives enter either maximum.)
  * The one-launch form is used for T <= 16384; larger T always takes the two-launch form.
+ * Output buffers must not overlap the inputs (prev_idx in particular: idx is written while prev_idx is still read).
  */
 int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float tau,
                      const int32_t* prev_idx, int r, const int32_t* r_dev,

@@ -470,6 +470,26 @@ def assign_and_check(x_cpu, idx, what, **kw):
     return parity.check_assign(x_cpu, idx, res["assign"].cpu().numpy(), res["corr"].cpu().numpy(), what)
 
 
+def test_beyond_the_one_launch_limit():
+    """T = 16500 > 16384: the cascade step takes its two-launch form whatever the flags say (exact gamma^cross), the
+    full selection runs on 256 x 256 units, the assignment on the tile engine without a hit table."""
+    w = wl.small(T=16500, d=64, K=300, L=2, dtype="bf16", seed=12, p=0.05)
+    say("T=%d beyond the one-launch limit" % w.T)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    full = pa.fetch(pa.ada_select_full(xs[0], w.tau))
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 16383, 16384, 16499], rng.integers(0, w.T, 200)]))
+    ref = oracle.gamma_full_rows(wl.as_f64(xs_cpu[0]), rows)
+    assert np.max(np.abs(full["gamma"][rows] - ref)) <= parity.GAMMA_TOL
+    clear = np.abs(ref - parity.thr_of(w.tau)) > parity.BAND
+    assert np.array_equal(full["mask"][rows][clear], (ref < parity.thr_of(w.tau)).astype(np.uint8)[clear])
+    assert full["mask"][0] == 1 and np.array_equal(full["idx"], np.flatnonzero(full["mask"]))
+    got = pa.fetch(pa.ada_cascade_step(xs[1], w.tau, dev_idx(full["idx"])))
+    parity.check_cascade(xs_cpu[1], w.tau, full["idx"], got, what="T=16500 step", two_pass=True)
+    assign_and_check(xs_cpu[1], got["idx"], "T=16500 assign")
+
+
 @pytest.mark.parametrize("T,d,K,dtype", [(333, 200, 40, "bf16"), (700, 4096, 120, "bf16"), (513, 768, 100, "f32"),
                                          (1000, 64, 90, "bf16"), (129, 33, 8, "f32"), (1, 64, 1, "bf16")])
 def test_assignment_small_shapes(T, d, K, dtype):
