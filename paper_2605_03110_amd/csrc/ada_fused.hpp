@@ -50,10 +50,32 @@ struct FusedParams {
     // the list was written earlier in this same launch by another workgroup (k_cascade_pass): read it past the
     // caches instead of invalidating them
     int coherent_list;
-    // 0: 64 x 64 tiles always; n > 0: 128 x 128 tiles when the step has more than n 64 x 64 tiles (the launcher passes the
-    // CU count: below that the smaller tiles keep more CUs busy, above it the larger ones halve the L2 -> CU traffic)
-    int tile128;
+    // tile shape of the two-group direct-to-LDS form: n > 0 = choose per step for a chip of n CUs (cascade_tile_shape);
+    // 0, -1, -2 = always shape 0, 1, 2
+    int tile_pick;
 };
+
+// Tile shapes (representatives x tested tokens): 0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128.  A step's cost is taken as
+// rounds x (operand rows per tile + a fixed part worth about 40 rows), rounds = tiles per XCD over workgroups per XCD:
+// operand bytes per Gram entry fall with the tile size, but a tile count below the CU count leaves CUs idle.
+__host__ __device__ inline int tile_rows_r(int shape) { return shape == 2 ? 128 : 64; }
+__host__ __device__ inline int tile_rows_t(int shape) { return shape == 0 ? 64 : 128; }
+__host__ __device__ inline long long tile_count(int r, int T, int shape) {
+    const int br = tile_rows_r(shape), bt = tile_rows_t(shape);
+    return (long long)((r + br - 1) / br) * ((T + bt - 1) / bt);
+}
+__host__ __device__ inline int cascade_tile_shape(int r, int T, int pick) {
+    if (pick <= 0) return -pick;
+    const long long slots = pick >= 8 ? pick / 8 : 1;
+    int best = 0;
+    long long best_cost = 0;
+    for (int shape = 0; shape < 3; ++shape) {
+        const long long per = (tile_count(r, T, shape) + 7) / 8;
+        const long long cost = ((per + slots - 1) / slots) * (tile_rows_r(shape) + tile_rows_t(shape) + 40);
+        if (shape == 0 || cost < best_cost) { best = shape; best_cost = cost; }
+    }
+    return best;
+}
 
 // Last-arriver detection in two levels.  Atomics on one address are served one after the other at the memory side
 // (about 25 ns each here), so a single counter taken by 256 workgroups that finish together costs the last of them 6 us.
@@ -301,7 +323,12 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         __builtin_amdgcn_s_barrier();
         ADA_CLK(3);
         read_frags(ring, 0);
-        for (int k0 = 0; k0 < nsteps; k0 += NS) {
+        // When the steps come in whole blocks of NS, the last block is written out on its own: it issues only the one
+        // chunk that is still missing and lowers its waits accordingly, so no chunk is fetched twice (the clamped
+        // surplus loads of the general form are 3 chunks in every nsteps of L2 -> CU traffic).
+        const bool clean = nsteps % NS == 0;
+        const int nmain = clean ? nsteps - NS : nsteps;
+        for (int k0 = 0; k0 < nmain; k0 += NS) {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {               // NS is even: stage and fragment buffer indices are static
                 const int k = k0 + s;
@@ -313,7 +340,26 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
                 mma_and_norms(s & 1, k);
             }
         }
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));        // the surplus loads must land before the ring is reused
+        if (clean) {
+            static_assert(NS == 4, "the last block is written for four stages");
+            auto last = [&](auto S) {
+                constexpr int s = decltype(S)::value;
+                const int k = nsteps - NS + s;
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (s < NS - 1) {               // chunk k+1 exists: wait for it; chunks k+2 .. nsteps-1 may fly
+                    __builtin_amdgcn_s_waitcnt(waitcnt_vm((s == 0 ? NS - 3 : NS - 2 - s) * LPT));
+                    __builtin_amdgcn_s_barrier();
+                    if constexpr (s == 0) issue(NS - 1, k + NS - 1);
+                    read_frags(ring + ((s + 1) % NS) * G::STAGE, (s + 1) & 1);
+                }
+                mma_and_norms(s & 1, k);
+            };
+            last(std::integral_constant<int, 0>{});
+            last(std::integral_constant<int, 1>{});
+            last(std::integral_constant<int, 2>{});
+            last(std::integral_constant<int, 3>{});
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));        // (general form) surplus loads must land before the ring is reused
         ADA_CLK(4);
         ssa += __shfl_xor(ssa, 32, 64);                    // the two lane halves hold different k pieces
         ssb += __shfl_xor(ssb, 32, 64);
@@ -430,48 +476,55 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
     ADA_CLK(5);
 }
 
-// The same step on a 128 x 128 tile (8 waves on one chunk at a time, rows in whole aligned 128-byte chunks): half
-// the L2 -> CU bytes per Gram entry of the 64 x 64 tile, for steps with enough tiles to keep every CU busy anyway.
-// Wave w owns the 32-row block wa = w / 2 of the representatives and the two 32-token blocks 2 (w % 2), 2 (w % 2) + 1.
-template <typename In>
-__device__ inline void fused_tile128(const FusedParams& p, int r, int s0, int t0, char* lds) {
+// The same step on a wider tile: BR = 32 RB representatives (RB = 2 or 4) against 128 tested tokens, 8 waves on one
+// chunk at a time, rows in whole aligned 128-byte chunks.  Per Gram entry the 128 x 128 tile pulls half and the
+// 64 x 128 tile three quarters of the 64 x 64 tile's L2 -> CU bytes; they pay when the step has enough tiles to keep
+// the CUs busy anyway.  The 32 x 32 blocks are dealt to the waves in row-major order, NBW = RB / 2 token blocks per
+// wave: wave w owns representative block wa = w / WPB and token blocks NBW (w % WPB) ... (WPB = 8 / RB waves share
+// a representative block).
+template <typename In, int RB>
+__device__ inline void fused_tile_wide(const FusedParams& p, int r, int s0, int t0, char* lds) {
     using G = FusedGeom<2, true>;
-    constexpr int B = 128, EPP = 16 / (int)sizeof(In), EPC = 8 * EPP, LPT = 4, NS = 4, STAGE = 2 * B * 128;
+    static_assert(RB == 2 || RB == 4, "64 or 128 representatives per tile");
+    constexpr int BR = 32 * RB, BT = 128, ROWS = BR + BT, EPP = 16 / (int)sizeof(In), EPC = 8 * EPP;
+    constexpr int LPT = ROWS / 64, LR = BR / 64, NS = 4, STAGE = ROWS * 128, NBW = RB / 2, WPB = 8 / RB;
     static_assert(NS * STAGE <= G::BODY, "ring does not fit");
-    int* s_tok = reinterpret_cast<int*>(lds + G::OFF_BIG);       // [128]
-    int* repf = s_tok + B;                                       // [128]
-    float* ssq = reinterpret_cast<float*>(repf + B);             // [256] sums of squares
-    float* scale = ssq + 2 * B;                                  // [256]
+    int* s_tok = reinterpret_cast<int*>(lds + G::OFF_BIG);       // [BR] (room for 128)
+    int* repf = s_tok + 128;                                     // [128]
+    float* ssq = reinterpret_cast<float*>(repf + 128);           // [ROWS] sums of squares (room for 256)
+    float* scale = ssq + 256;                                    // [ROWS]
     char* ring = lds + G::META;
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wa = wave >> 1, wp = wave & 1, b0 = 2 * wp;
+    const int wa = wave / WPB, wp = wave % WPB, b0 = NBW * wp;
     const In* X = reinterpret_cast<const In*>(p.X);
 
-    // lane l of wave w serves stage rows 8 w + l / 8 + 64 j (slot l % 8): j = 0, 1 are representatives, 2, 3 tokens
+    // lane l of wave w serves stage rows 8 w + l / 8 + 64 j (slot l % 8): j < LR are representatives, the rest tokens
     const int r8 = lane >> 3;
-    int ptok[2];
+    int ptok[LR];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < LR; ++j) {
         const int li = s0 + wave * 8 + r8 + 64 * j;
         ptok[j] = list_at(p, li < r ? li : r - 1);
     }
-    if (tid < B) {
+    if (tid < BR) {
         const int li = s0 + tid;
         const bool ok = li < r;
         int tok = list_at(p, ok ? li : r - 1);
         tok = min(max(tok, 0), p.T - 1);
         s_tok[tid] = ok ? tok : INT_MAX;
-        repf[tid] = 0;
     }
+    if (tid < BT) repf[tid] = 0;
     __syncthreads();
     const int pcd = (lane & 7) ^ lds_swz(wave * 8 + r8);          // 64 j leaves bits 0..3 of the row alone
     const In* rowp[LPT];
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
         const int row = wave * 8 + r8 + 64 * j;
-        const int tok = j < 2 ? min(max(ptok[j], 0), p.T - 1) : min(t0 + row - B, p.T - 1);
+        int tok;
+        if (j < LR) tok = min(max(ptok[j < LR ? j : 0], 0), p.T - 1);
+        else tok = min(t0 + row - BR, p.T - 1);
         rowp[j] = X + (size_t)tok * (size_t)p.ld + pcd * EPP;
     }
     const int nk = p.d / EPC;
@@ -484,10 +537,10 @@ __device__ inline void fused_tile128(const FusedParams& p, int r, int s0, int t0
                                              (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
         }
     };
-    u32x4 fa[2][4], fb[2][2][4];
-    f32x16 acc[2];
+    u32x4 fa[2][4], fb[2][NBW][4];
+    f32x16 acc[NBW];
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < NBW; ++c)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
     auto read_frags = [&](const char* stage, int f) {
@@ -495,34 +548,37 @@ __device__ inline void fused_tile128(const FusedParams& p, int r, int s0, int t0
         for (int ks = 0; ks < 4; ++ks) {
             const int piece = 2 * ks + half;
             fa[f][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(wa * 32 + l32, piece));
-            fb[f][0][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + b0 * 32 + l32, piece));
-            fb[f][1][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(B + b0 * 32 + 32 + l32, piece));
+#pragma unroll
+            for (int c = 0; c < NBW; ++c)
+                fb[f][c][ks] = *reinterpret_cast<const u32x4*>(stage + lds_off(BR + (b0 + c) * 32 + l32, piece));
         }
     };
-    float ssa = 0.f, ssb[2] = {0.f, 0.f};
-    const bool do_a = wa < 2 ? wp == 1 : wp == 0;                // representative block wa: waves (0,1) (1,1) (2,0) (3,0)
-    const bool do_b = wp == 0 ? wa == 0 : wa == 3;               // token blocks 2 wp, 2 wp + 1: waves (0,0) and (3,1)
+    float ssa = 0.f, ssb[NBW];
+#pragma unroll
+    for (int c = 0; c < NBW; ++c) ssb[c] = 0.f;
+    // Section 2.1: ||x||^2 from the fragments already in hand.  Every block of rows is summed by ONE of the waves that
+    // hold it, chosen so that no wave sums more than eight fragments per chunk.
+    //   RB = 4: representative block wa by waves (0,1) (1,1) (2,0) (3,0); token blocks 2 wp, 2 wp + 1 by (0,0) and (3,1)
+    //   RB = 2: representative block wa by waves (0,1) and (1,2); token block wp by waves (0,0) (1,1) (0,2) (1,3)
+    const bool do_a = RB == 4 ? (wa < 2 ? wp == 1 : wp == 0) : (wp == wa + 1);
+    const bool do_b = RB == 4 ? (wp == 0 ? wa == 0 : wa == 3) : (wa == (wp & 1));
     auto mma_and_norms = [&](int f, int k) {
         if (k < nk) {                                            // scalar: a clamped (repeated) chunk is skipped
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                Mfma<In>::run(acc[0], fa[f][ks], fb[f][0][ks]);
-                Mfma<In>::run(acc[1], fa[f][ks], fb[f][1][ks]);
-            }
-            // Section 2.1: ||x||^2 from the fragments already in hand.  Every block of rows is summed by ONE of the waves
-            // that hold it, chosen so that no wave sums more than eight fragments per chunk.  The choice is a plain
-            // scalar branch around code with fixed registers: selecting fragments by a computed index sends them
-            // through scratch memory, whose loads count in vmcnt and drain the ring.
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int c = 0; c < NBW; ++c) Mfma<In>::run(acc[c], fa[f][ks], fb[f][c][ks]);
+            // The choice is a plain scalar branch around code with fixed registers: selecting fragments by a computed
+            // index sends them through scratch memory, whose loads count in vmcnt and drain the ring.
             if (do_a) {
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) ssa += piece_sumsq_fast<In>(fa[f][ks]);
             }
             if (do_b) {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    ssb[0] += piece_sumsq_fast<In>(fb[f][0][ks]);
-                    ssb[1] += piece_sumsq_fast<In>(fb[f][1][ks]);
-                }
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int c = 0; c < NBW; ++c) ssb[c] += piece_sumsq_fast<In>(fb[f][c][ks]);
             }
         }
     };
@@ -531,13 +587,15 @@ __device__ inline void fused_tile128(const FusedParams& p, int r, int s0, int t0
     if (!p.assign_mode) {                                        // which tested tokens are inherited (read in the epilogue)
         for (int j = tid; j < r; j += G::THREADS) {
             const unsigned q = (unsigned)(list_at(p, j) - t0);
-            if (q < (unsigned)B) repf[q] = 1;
+            if (q < (unsigned)BT) repf[q] = 1;
         }
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
     read_frags(ring, 0);
-    for (int k0 = 0; k0 < nk; k0 += NS) {
+    const bool clean = nk % NS == 0;                             // see fused_tile: the last block on its own
+    const int nmain = clean ? nk - NS : nk;
+    for (int k0 = 0; k0 < nmain; k0 += NS) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             const int k = k0 + s;
@@ -549,27 +607,49 @@ __device__ inline void fused_tile128(const FusedParams& p, int r, int s0, int t0
             mma_and_norms(s & 1, k);
         }
     }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));                    // the surplus loads must land before the ring is reused
+    if (clean) {
+        static_assert(NS == 4, "the last block is written for four stages");
+        auto last = [&](auto S) {
+            constexpr int s = decltype(S)::value;
+            const int k = nk - NS + s;
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (s < NS - 1) {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm((s == 0 ? NS - 3 : NS - 2 - s) * LPT));
+                __builtin_amdgcn_s_barrier();
+                if constexpr (s == 0) issue(NS - 1, k + NS - 1);
+                read_frags(ring + ((s + 1) % NS) * STAGE, (s + 1) & 1);
+            }
+            mma_and_norms(s & 1, k);
+        };
+        last(std::integral_constant<int, 0>{});
+        last(std::integral_constant<int, 1>{});
+        last(std::integral_constant<int, 2>{});
+        last(std::integral_constant<int, 3>{});
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));                    // (general form) surplus loads must land before the ring is reused
     ssa += __shfl_xor(ssa, 32, 64);                               // the two lane halves hold different k pieces
-    ssb[0] += __shfl_xor(ssb[0], 32, 64);
-    ssb[1] += __shfl_xor(ssb[1], 32, 64);
+#pragma unroll
+    for (int c = 0; c < NBW; ++c) ssb[c] += __shfl_xor(ssb[c], 32, 64);
     __syncthreads();
     if (half == 0) {
         if (do_a) ssq[wa * 32 + l32] = ssa;
-        if (do_b) { ssq[B + b0 * 32 + l32] = ssb[0]; ssq[B + b0 * 32 + 32 + l32] = ssb[1]; }
+        if (do_b) {
+#pragma unroll
+            for (int c = 0; c < NBW; ++c) ssq[BR + (b0 + c) * 32 + l32] = ssb[c];
+        }
     }
     __syncthreads();
-    if (tid < 2 * B) {
+    if (tid < ROWS) {
         const float sum = ssq[tid];
         float sc = sum > 0.f ? 1.0f / sqrtf(sum) : 0.f;           // a zero row normalises to zero: all its cosines are 0
-        if (tid < B ? (s_tok[tid] == INT_MAX) : (t0 + tid - B >= p.T)) sc = 0.f;
+        if (tid < BR ? (s_tok[tid] == INT_MAX) : (t0 + tid - BR >= p.T)) sc = 0.f;
         scale[tid] = sc;
     }
     __syncthreads();
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < NBW; ++c) {
         const int nl = (b0 + c) * 32 + l32;
-        finish_block(p, acc[c], s_tok + wa * 32, scale + wa * 32, scale[B + nl], repf[nl] != 0 || p.earlier_only,
+        finish_block(p, acc[c], s_tok + wa * 32, scale + wa * 32, scale[BR + nl], repf[nl] != 0 || p.earlier_only,
                      t0 + nl, (s0 >> 5) + wa, half);
     }
 }
@@ -864,12 +944,11 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
 // fastest, so that one XCD's L2 serves a contiguous range of tested rows.
 template <typename In, bool ALIGNED, int KG, bool DMA>
 __device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds) {
-    bool big = false;
-    if constexpr (ALIGNED && KG == 2 && DMA)
-        big = p.tile128 > 0 && (long long)((r + 63) / 64) * ((p.T + 63) / 64) > p.tile128;
-    const int bs = big ? 128 : 64;
-    const long long nbS = (r + bs - 1) / bs, nbT = (p.T + bs - 1) / bs;
-    const long long ntiles = nbS * nbT;
+    int shape = 0;
+    if constexpr (ALIGNED && KG == 2 && DMA) shape = cascade_tile_shape(r, p.T, p.tile_pick);
+    const int br = tile_rows_r(shape), bt = tile_rows_t(shape);
+    const long long nbS = (r + br - 1) / br;
+    const long long ntiles = tile_count(r, p.T, shape);
     const long long per = (ntiles + 7) / 8;
     const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
     for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
@@ -877,7 +956,8 @@ __device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds) 
         if (tile >= ntiles) break;
         const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
         if constexpr (ALIGNED && KG == 2 && DMA) {
-            if (big) fused_tile128<In>(p, r, sb * 128, tb * 128, lds);
+            if (shape == 2) fused_tile_wide<In, 4>(p, r, sb * 128, tb * 128, lds);
+            else if (shape == 1) fused_tile_wide<In, 2>(p, r, sb * 64, tb * 128, lds);
             else fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
         } else {
             fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);

@@ -24,6 +24,7 @@
 #include <stdlib.h>
 #include <mutex>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/ada.h"
@@ -901,7 +902,10 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = A
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     if (attr_err != hipSuccess) return attr_err;
-    long long tiles = (long long)((p.r_host + 63) / 64) * ((p.T + 63) / 64);
+    // with the set size known here the tile shape is too (the kernel makes the same choice from the same numbers)
+    int shape = 0;
+    if (ALIGNED && KG == 2 && DMA && !p.r_dev) shape = cascade_tile_shape(p.r_host, p.T, p.tile_pick);
+    long long tiles = tile_count(p.r_host, p.T, shape);
     // Workgroups loop over tiles, so any grid is correct.  With the set size known only on the device the bound
     // r_host = T would launch mostly idle workgroups, and dispatching those is not free: cap at one per CU (the LDS
     // footprint admits no more at a time anyway).
@@ -920,10 +924,15 @@ int kgroups_override() {
     return (v == 1 || v == 2) ? v : 0;
 }
 
-// Above how many 64 x 64 tiles a step switches to 128 x 128 tiles (0: never): one per CU by default.
-int cascade_tile128() {
-    const char* e = getenv("ADA_CASCADE_TILE");              // development switch: 64 = never, 128 = always
-    if (e) { const int v = atoi(e); if (v == 64) return 0; if (v == 128) return 1; }
+// FusedParams::tile_pick: the CU count (automatic choice per step) unless the development switch fixes the shape.
+int cascade_tile_pick() {
+    const char* e = getenv("ADA_CASCADE_TILE");              // 64 = 64 x 64, 64x128 = 64 x 128, 128 = 128 x 128
+    if (e) {
+        const std::string v(e);
+        if (v == "64") return 0;
+        if (v == "64x128") return -1;
+        if (v == "128") return -2;
+    }
     return device_cus();
 }
 
@@ -958,7 +967,7 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
     const FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
                            (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
                            w.meta + META_TICKET, idx, adds, removes, counts,
-                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile128()};
+                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
     return launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
 }
 
@@ -967,7 +976,7 @@ int run_assign(const void* X, int T, int d, long long ld, int dtype, const int32
                int32_t* assign, float* corr, int32_t* info, void* ws, hipStream_t st) {
     const Workspace w = carve(ws, T);
     const FusedParams p = {X, ld, T, d, idx, r_dev, r, 2.0f, 0, nullptr, 0, nullptr, w.meta + META_TICKET,
-                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr, 0, cascade_tile128()};
+                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr, 0, cascade_tile_pick()};
     return launch_fused_any(p, dtype, ADA_K_ASSIGN, st);
 }
 
@@ -1012,7 +1021,7 @@ int run_cascade_pass(const void* const* X_layers, int first, int n, int T, int d
     PassParams pp;
     pp.f = {nullptr, ld, T, d, nullptr, nullptr, T, threshold_of(tau), (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0,
             w.hits, hit_words(T), nullptr, w.meta + META_TICKET, nullptr, nullptr, nullptr, nullptr, nullptr,
-            0, nullptr, nullptr, nullptr, 0, cascade_tile128()};
+            0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
     // rows of idx_all that share a 128-byte line with their neighbour could be cached half-written
     pp.f.coherent_list = ((uintptr_t)idx_all % 128 != 0 || T % 32 != 0) ? 1 : 0;
     for (int i = 0; i < n; ++i) pp.X[i] = X_layers[first + i];

@@ -88,21 +88,22 @@ def test_small_shapes_one_launch_cascade(T, d, K, dtype, kgroups, monkeypatch):
     assert all(e <= parity.GAMMA_TOL for _, _, e in stats)
 
 
+@pytest.mark.parametrize("tile", ["64x128", "128"])
 @pytest.mark.parametrize("T,d,K,dtype", [(1, 64, 1, "bf16"), (130, 64, 17, "bf16"), (333, 192, 40, "bf16"), (300, 96, 40, "f32"),
                                          (700, 4096, 120, "bf16"), (1290, 128, 300, "bf16")])
-def test_small_shapes_one_launch_cascade_on_128_tiles(T, d, K, dtype, monkeypatch):
-    """The 128 x 128 tile of the one-launch cascade (rows in whole aligned 128-byte chunks), forced onto small and
-    ragged shapes; the assignment runs on the same tiles."""
-    monkeypatch.setenv("ADA_CASCADE_TILE", "128")
-    say("small T=%d d=%d K=%d %s one-launch, 128 tiles" % (T, d, K, dtype))
+def test_small_shapes_one_launch_cascade_on_wide_tiles(T, d, K, dtype, tile, monkeypatch):
+    """The 64 x 128 and 128 x 128 tiles of the one-launch cascade (rows in whole aligned 128-byte chunks), forced onto
+    small and ragged shapes; the assignment runs on the same tiles."""
+    monkeypatch.setenv("ADA_CASCADE_TILE", tile)
+    say("small T=%d d=%d K=%d %s one-launch, %s tiles" % (T, d, K, dtype, tile))
     w = wl.small(T=T, d=d, K=K, L=3, dtype=dtype, seed=23 + T, p=0.1)
     xs = wl.layer_list(w)
-    stats = run_layers_teacher_forced(w, xs, what="128 tiles T=%d d=%d" % (T, d))
+    stats = run_layers_teacher_forced(w, xs, what="%s tiles T=%d d=%d" % (tile, T, d))
     assert all(e <= parity.GAMMA_TOL for _, _, e in stats)
-    run_layers_teacher_forced(w, xs, flags=pa.FLAG_CROSS_EARLIER_ONLY, what="128 tiles earlier-only T=%d" % T)
+    run_layers_teacher_forced(w, xs, flags=pa.FLAG_CROSS_EARLIER_ONLY, what="%s tiles earlier-only T=%d" % (tile, T))
     full = pa.fetch(pa.ada_select_full(xs[0].to(DEV), w.tau))
     res = pa.ada_assign_nearest(xs[0].to(DEV), torch.as_tensor(full["idx"]).to(DEV))
-    parity.check_assign(xs[0], full["idx"], res["assign"].cpu().numpy(), res["corr"].cpu().numpy(), "128 tiles assign")
+    parity.check_assign(xs[0], full["idx"], res["assign"].cpu().numpy(), res["corr"].cpu().numpy(), "%s tiles assign" % tile)
 
 
 @pytest.mark.parametrize("path", ["dma0", "dma1"])
