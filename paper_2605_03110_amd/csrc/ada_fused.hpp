@@ -53,6 +53,9 @@ struct FusedParams {
     // tile shape of the two-group direct-to-LDS form: n > 0 = choose per step for a chip of n CUs (cascade_tile_shape);
     // 0, -1, -2 = always shape 0, 1, 2
     int tile_pick;
+    // workgroups of the launch (a multiple of 8), filled in by the launcher: the built-in grid size sits in another
+    // cache line of the launch's argument block, and waiting for that line is a trip to memory at every kernel start
+    int grid;
 };
 
 // Tile shapes (representatives x tested tokens): 0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128.  A step's cost is taken as
@@ -60,18 +63,22 @@ struct FusedParams {
 // operand bytes per Gram entry fall with the tile size, but a tile count below the CU count leaves CUs idle.
 __host__ __device__ inline int tile_rows_r(int shape) { return shape == 2 ? 128 : 64; }
 __host__ __device__ inline int tile_rows_t(int shape) { return shape == 0 ? 64 : 128; }
-__host__ __device__ inline long long tile_count(int r, int T, int shape) {
+// (T <= FUSED_MAX_T: every count fits 32 bits, and 32-bit divisions are what the start of a launch can afford)
+__host__ __device__ inline int tile_count(int r, int T, int shape) {
     const int br = tile_rows_r(shape), bt = tile_rows_t(shape);
-    return (long long)((r + br - 1) / br) * ((T + bt - 1) / bt);
+    return ((r + br - 1) / br) * ((T + bt - 1) / bt);
 }
 __host__ __device__ inline int cascade_tile_shape(int r, int T, int pick) {
     if (pick <= 0) return -pick;
-    const long long slots = pick >= 8 ? pick / 8 : 1;
+    const unsigned slots = pick >= 8 ? (unsigned)pick / 8u : 1u;
+    const unsigned nr64 = (unsigned)(r + 63) >> 6, nr128 = (unsigned)(r + 127) >> 7;
+    const unsigned nt64 = (unsigned)(T + 63) >> 6, nt128 = (unsigned)(T + 127) >> 7;
+    const unsigned tiles[3] = {nr64 * nt64, nr64 * nt128, nr128 * nt128};
     int best = 0;
-    long long best_cost = 0;
+    unsigned best_cost = 0;
     for (int shape = 0; shape < 3; ++shape) {
-        const long long per = (tile_count(r, T, shape) + 7) / 8;
-        const long long cost = ((per + slots - 1) / slots) * (tile_rows_r(shape) + tile_rows_t(shape) + 40);
+        const unsigned per = (tiles[shape] + 7u) >> 3;
+        const unsigned cost = ((per + slots - 1u) / slots) * (unsigned)(tile_rows_r(shape) + tile_rows_t(shape) + 40);
         if (shape == 0 || cost < best_cost) { best = shape; best_cost = cost; }
     }
     return best;
@@ -82,8 +89,8 @@ __host__ __device__ inline int cascade_tile_shape(int r, int T, int pick) {
 // Workgroups first count per XCD (blockIdx % 8: eight counters on separate cache lines); the last of each XCD then
 // takes the device-wide ticket.  Called by one thread; true in exactly one workgroup, after all others have called.
 constexpr int TICKET_XCD0 = 64;                          // ints from the device-wide ticket to the first XCD counter
-__device__ inline bool take_ticket(int32_t* ticket) {
-    const int per = gridDim.x >> 3;                      // grids are multiples of 8
+__device__ inline bool take_ticket(int32_t* ticket, int grid) {
+    const int per = grid >> 3;                           // grids are multiples of 8
     if (atomicAdd(ticket + TICKET_XCD0 + 32 * (blockIdx.x & 7), 1) != per - 1) return false;
     return atomicAdd(ticket, 1) == 7;
 }
@@ -676,6 +683,42 @@ __device__ inline unsigned long long block_exclusive_scan64(unsigned long long v
     return wave_tot[wave] + inc - v;
 }
 
+// Ranks for stream compaction of three classes at once: thread tid owns U consecutive items, f[c][u] says whether item
+// u is in class c.  below[c] = members of class c among the items of all threads before this one, tot[c] = members in
+// the workgroup.  Inside a wave the counts come from ballots (no cross-lane data movement); across waves from one
+// exchange through LDS (scratch: THREADS / 64 x 4 ints).
+template <int THREADS, int U>
+__device__ inline void block_rank3(const bool (&f)[3][U], int (&below)[3], int (&tot)[3], int* scratch) {
+    constexpr int NW = THREADS / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int wtot[3];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) {
+        below[c] = 0;
+        wtot[c] = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned long long m = __ballot(f[c][u]);
+            below[c] += (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+            wtot[c] += __popcll(m);
+        }
+    }
+    if (lane == 0) *reinterpret_cast<int4*>(scratch + 4 * wave) = int4{wtot[0], wtot[1], wtot[2], 0};
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 3; ++c) tot[c] = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const int4 v = *reinterpret_cast<const int4*>(scratch + 4 * w);
+        const int vv[3] = {v.x, v.y, v.z};
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            tot[c] += vv[c];
+            below[c] += w < wave ? vv[c] : 0;
+        }
+    }
+}
+
 // Algorithm 1 steps 5, 9, 10 and the bookkeeping, from the hit words (run by one workgroup).
 // Per-token state lives in LDS (T <= FUSED_MAX_T bytes): bit 0 = inherited, bit 1 = kept.  The hit table is
 // word-major (hits[w * T + t]), so a thread that owns token t reads its words with loads that are coalesced across
@@ -698,7 +741,7 @@ __device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int
     u32x4 x[WMAX];
 #pragma unroll
     for (int w = 0; w < WMAX; ++w)
-        x[w] = own ? *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(w, Wa - 1) * T + 4 * tid) : u32x4{0u, 0u, 0u, 0u};
+        x[w] = (own && w < Wa) ? *reinterpret_cast<const u32x4*>(p.hits + (size_t)w * T + 4 * tid) : u32x4{0u, 0u, 0u, 0u};
     if (own) *reinterpret_cast<unsigned long long*>(pos + 4 * tid) = ~0ull;  // 0xFFFF: not inherited
     for (int w = tid; w < Wa; w += THREADS) vmask[w] = 0u;
     __syncthreads();
@@ -746,18 +789,19 @@ __device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int
         for (int u = 0; u < 4; ++u) cov[u] |= x[w][u] & vm;
     }
     int st[4];                                           // 3 kept inherited, 1 removed, 2 added, 0 covered
-    unsigned long long c = 0;                            // kept | added << 21 | removed << 42
+    bool f[3][4];                                        // in R^(l+1) | added | removed
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const bool inh = jpos[u] != 0xFFFF;
         st[u] = !own ? 0 : inh ? (any_all[u] == 0u ? 3 : 1) : (cov[u] == 0u ? 2 : 0);
-        c += (unsigned long long)((st[u] >> 1) & 1) | ((unsigned long long)(st[u] == 2) << 21) |
-             ((unsigned long long)(st[u] == 1) << 42);
+        f[0][u] = (st[u] & 2) != 0;
+        f[1][u] = st[u] == 2;
+        f[2][u] = st[u] == 1;
     }
-    unsigned long long tot;
-    const unsigned long long o = block_exclusive_scan64(c, &tot, reinterpret_cast<unsigned long long*>(scan_scratch));
-    int o_idx = (int)(o & 0x1FFFFF), o_add = (int)((o >> 21) & 0x1FFFFF), o_rem = (int)((o >> 42) & 0x1FFFFF);
-    const int n_idx = (int)(tot & 0x1FFFFF), n_add = (int)((tot >> 21) & 0x1FFFFF), n_rem = (int)((tot >> 42) & 0x1FFFFF);
+    int below[3], tot[3];
+    block_rank3<THREADS, 4>(f, below, tot, scan_scratch);
+    int o_idx = below[0], o_add = below[1], o_rem = below[2];
+    const int n_idx = tot[0], n_add = tot[1], n_rem = tot[2];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {                        // step 10
         const int t = 4 * tid + u;
@@ -946,15 +990,15 @@ template <typename In, bool ALIGNED, int KG, bool DMA>
 __device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds) {
     int shape = 0;
     if constexpr (ALIGNED && KG == 2 && DMA) shape = cascade_tile_shape(r, p.T, p.tile_pick);
-    const int br = tile_rows_r(shape), bt = tile_rows_t(shape);
-    const long long nbS = (r + br - 1) / br;
-    const long long ntiles = tile_count(r, p.T, shape);
-    const long long per = (ntiles + 7) / 8;
-    const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
-    for (long long slot = blockIdx.x >> 3; slot < per; slot += slots) {
-        const long long tile = xcd * per + slot;
+    const int sr = shape == 2 ? 7 : 6, st = shape == 0 ? 6 : 7;           // log2 of the tile's rows
+    const unsigned nbS = (unsigned)(r + (1 << sr) - 1) >> sr;
+    const unsigned ntiles = nbS * ((unsigned)(p.T + (1 << st) - 1) >> st);
+    const unsigned per = (ntiles + 7u) >> 3;
+    const unsigned xcd = blockIdx.x & 7, slots = (unsigned)p.grid >> 3;
+    for (unsigned slot = blockIdx.x >> 3; slot < per; slot += slots) {
+        const unsigned tile = xcd * per + slot;
         if (tile >= ntiles) break;
-        const int tb = (int)(tile / nbS), sb = (int)(tile % nbS);
+        const int tb = (int)(tile / nbS), sb = (int)(tile - (unsigned)tb * nbS);
         if constexpr (ALIGNED && KG == 2 && DMA) {
             if (shape == 2) fused_tile_wide<In, 4>(p, r, sb * 128, tb * 128, lds);
             else if (shape == 1) fused_tile_wide<In, 2>(p, r, sb * 64, tb * 128, lds);
@@ -987,7 +1031,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this thread's stores have left the CU
     __syncthreads();
-    if (threadIdx.x == 0) s_last = take_ticket(p.ticket) ? 1 : 0;
+    if (threadIdx.x == 0) s_last = take_ticket(p.ticket, p.grid) ? 1 : 0;
     __syncthreads();
     ADA_CLK(7);
     if (!s_last) return;
@@ -1079,7 +1123,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_pass(PassParams pp) {
         const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this thread's stores have left the CU
         __syncthreads();
-        if (threadIdx.x == 0) s_last = take_ticket(p.ticket) ? 1 : 0;
+        if (threadIdx.x == 0) s_last = take_ticket(p.ticket, p.grid) ? 1 : 0;
         __syncthreads();
         PASS_CLK(3);
         if (s_last) {                                        // uniform

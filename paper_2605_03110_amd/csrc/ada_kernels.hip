@@ -912,8 +912,10 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = A
     const long long cap = p.r_dev ? device_cus() : 2048;
     if (tiles > cap) tiles = cap;
     const unsigned grid = (unsigned)(tiles + 7) / 8 * 8;             // multiple of 8 (XCDs)
+    FusedParams q = p;
+    q.grid = (int)grid;
     ProfScope ps(prof_class, st);
-    hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG, DMA>), dim3(grid), dim3(256 * KG), lds, st, p);
+    hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG, DMA>), dim3(grid), dim3(256 * KG), lds, st, q);
     return hipGetLastError();
 }
 
@@ -996,8 +998,10 @@ hipError_t launch_pass(const PassParams& pp, hipStream_t st) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     if (attr_err != hipSuccess) return attr_err;
+    PassParams q = pp;
+    q.f.grid = device_cus();
     ProfScope ps(ADA_K_CASCADE_FUSED, st);
-    hipLaunchKernelGGL((k_cascade_pass<In, ALIGNED, KG, DMA>), dim3(device_cus()), dim3(256 * KG), lds, st, pp);
+    hipLaunchKernelGGL((k_cascade_pass<In, ALIGNED, KG, DMA>), dim3(q.f.grid), dim3(256 * KG), lds, st, q);
     return hipGetLastError();
 }
 
