@@ -307,6 +307,32 @@ def main():
                              "frac": att_bytes / (1e-6 * us_t) / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": att_bytes,
                              "mfma_tflops": att_flops / (1e-6 * us_t) / 1e12, "traffic": None}}
 
+        # ---- four independent sequences of this workload through the batched layer loop (the sequences alternate
+        # between two streams, so that one sequence's set update overlaps the other's tiles)
+        Bq = 4
+        seqs = [xs] + [[x.to(dev) for x in wl.layers(w, b)] for b in range(1, Bq)]
+        wsb = pa.workspace_batched(T, Bq, dev)
+        outb = dict(idx=torch.empty((Bq, L, T), dtype=torch.int32, device=dev),
+                    counts=torch.empty((Bq, L, 4), dtype=torch.int32, device=dev),
+                    gram_ops=torch.empty((Bq, L), dtype=torch.int64, device=dev))
+        side = [torch.cuda.Stream() for _ in range(2)]
+        use = [side[b % 2] for b in range(Bq)]
+        for _ in range(2):
+            pa.ada_cascade_layers_batched(seqs, w.tau, ws=wsb, streams=use, stream=stream, out=outb)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nb = max(1, args.steps // 4)
+        for _ in range(nb):
+            pa.ada_cascade_layers_batched(seqs, w.tau, ws=wsb, streams=use, stream=stream, out=outb)
+        torch.cuda.synchronize()
+        b_elapsed = time.perf_counter() - t0
+        assert outb["counts"][:, :, 3].cpu().flatten().tolist() == [0] * (Bq * L), "batched pass reported an error"
+        assert torch.equal(outb["counts"][0], out["counts"]), "batched sequence 0 differs from the single-sequence pass"
+        result["batched"] = {"sequences": Bq, "streams": 2, "ms_per_batch_pass": 1e3 * b_elapsed / nb,
+                             "layers_per_s": Bq * L * nb / b_elapsed,
+                             "tokens_per_s": Bq * L * nb / b_elapsed * T}
+        del seqs, wsb, outb
+
         # ---- the same selection at the long-context shape (configs[4]: T=8192, d=4096, one sequence), where the
         # triangle has enough tiles to fill the chip and the kernel is bound by the matrix pipes
         w4 = wl.config(4)

@@ -67,6 +67,7 @@ typedef enum {
                                           models of Section 6 have one) */
 
 #define ADA_MAX_T (1 << 20)
+#define ADA_MAX_BATCH 4096
 
 /* Human-readable name of a status code (static storage). */
 const char* ada_status_string(int status);
@@ -188,6 +189,25 @@ int ada_cascade_layers(const void* const* X_layers, int L, int T, int d, int64_t
                        int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all,
                        int32_t* adds_all, int32_t* removes_all,
                        void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
+ * The same layer loop for B independent sequences at once (Section 8.4 suggests keeping selection work in flight next to other
+ * work; here the selection work of several sequences is in flight together).  Sequence b runs exactly what ada_cascade_layers runs, on streams[b]; the
+ * chains are issued layer by layer across the batch, so that while one sequence's set update runs on a single CU the
+ * other sequences' tiles fill the rest of the device.
+ *   X_layers     HOST array of B*L device pointers, sequence-major: X_layers[b*L + l]
+ *   idx_all, counts_all, gram_ops_all, adds_all, removes_all   as for ada_cascade_layers, B blocks of L rows
+ *   ws           B workspaces back to back, ada_workspace_bytes(T) apart, each initialised; ws_bytes >= B times that
+ *   streams      HOST array of B HIP streams (default priority), or NULL: all chains one after the other on `stream`.
+ *                Chains on the same stream run in order; distinct streams may overlap
+ *   stream       the caller's stream: the chains start after the work enqueued on it before this call, and work
+ *                enqueued on it after this call starts after all chains (events; no host synchronisation)
+ * ADA_FLAG_RESIDENT_PASS is ignored (that form needs the whole device for one sequence).  B <= ADA_MAX_BATCH.
+ */
+int ada_cascade_layers_batched(const void* const* X_layers, int B, int L, int T, int d, int64_t ld, int dtype, float tau,
+                               int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all,
+                               int32_t* adds_all, int32_t* removes_all,
+                               void* ws, size_t ws_bytes, void* const* streams, void* stream, unsigned flags);
 
 /*
  * |A n B| and |A u B| of two representative sets given as uint8 masks [T] (device), for the

@@ -26,7 +26,7 @@ FLAG_ATTN_CAUSAL = 8
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
-           "ada_cascade_layers", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
+           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
            "ada_attention_compressed")
 
@@ -81,6 +81,9 @@ def lib():
         L.ada_cascade_layers.restype = i32
         L.ada_cascade_layers.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp,
                                          vp, sz, vp, u32]
+        L.ada_cascade_layers_batched.restype = i32
+        L.ada_cascade_layers_batched.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp,
+                                                 vp, sz, ctypes.POINTER(vp), vp, u32]
         L.ada_set_overlap.restype = i32
         L.ada_set_overlap.argtypes = [vp, vp, i32, vp, vp]
         L.ada_cascade_report.restype = i32
@@ -108,6 +111,11 @@ def status_string(status: int) -> str:
 
 def workspace_bytes(T: int) -> int:
     return int(lib().ada_workspace_bytes(int(T)))
+
+
+def workspace_batched(T: int, B: int, device="cuda") -> torch.Tensor:
+    """B zero-filled workspaces back to back, for ada_cascade_layers_batched."""
+    return torch.zeros(workspace_bytes(T) * int(B), dtype=torch.uint8, device=device)
 
 
 def workspace(T: int, device="cuda") -> torch.Tensor:
@@ -288,6 +296,49 @@ def ada_cascade_layers(Xs: Sequence[torch.Tensor], tau: float, *, want_lists: bo
     if rc != OK:
         raise AdaError(rc, "ada_cascade_layers")
     out["_keep"] = (ws, list(Xs))
+    return out
+
+
+def ada_cascade_layers_batched(seqs: Sequence[Sequence[torch.Tensor]], tau: float, *, want_lists: bool = False,
+                               ws: Optional[torch.Tensor] = None, streams=None, stream=None, flags: int = 0,
+                               out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """ada_cascade_layers for B sequences (seqs[b][l]: the T x d matrix of sequence b at layer l), sequence b on
+    streams[b] (torch streams; None = all on `stream`, one after the other).  Work enqueued on `stream` (default: the
+    current stream) after the call waits for all chains.  ws: B workspaces back to back (workspace_batched).
+    Returns device tensors idx[B,L,T], counts[B,L,4], gram_ops[B,L] and, if want_lists, adds / removes [B,L,T]."""
+    B = len(seqs)
+    if B < 1 or len(seqs[0]) < 1:
+        raise ValueError("need at least one sequence and one layer")
+    L = len(seqs[0])
+    X0 = seqs[0][0]
+    for s in seqs:
+        if len(s) != L:
+            raise ValueError("all sequences must have the same number of layers")
+        for X in s:
+            _check_x(X)
+            if X.shape != X0.shape or X.dtype != X0.dtype or X.stride(0) != X0.stride(0) or X.device != X0.device:
+                raise ValueError("all matrices must share shape, dtype, leading dimension and device")
+    if streams is not None and len(streams) != B:
+        raise ValueError("need one stream per sequence")
+    T, d = X0.shape
+    dev = X0.device
+    ws = workspace_batched(T, B, dev) if ws is None else ws
+    if out is None:
+        out = dict(idx=torch.empty((B, L, T), dtype=torch.int32, device=dev),
+                   counts=torch.empty((B, L, 4), dtype=torch.int32, device=dev),
+                   gram_ops=torch.empty((B, L), dtype=torch.int64, device=dev))
+        if want_lists:
+            out["adds"] = torch.empty((B, L, T), dtype=torch.int32, device=dev)
+            out["removes"] = torch.empty((B, L, T), dtype=torch.int32, device=dev)
+    ptrs = (ctypes.c_void_p * (B * L))(*[X.data_ptr() for s in seqs for X in s])
+    sarr = None if streams is None else (ctypes.c_void_p * B)(*[s.cuda_stream for s in streams])
+    rc = lib().ada_cascade_layers_batched(ptrs, B, L, T, d, X0.stride(0), _dtype_code(X0), float(tau), _ptr(out["idx"]),
+                                          _ptr(out["counts"]), _ptr(out["gram_ops"]), _ptr(out.get("adds")),
+                                          _ptr(out.get("removes")), _ptr(ws), ws.numel(), sarr, _stream(stream),
+                                          int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_layers_batched")
+    out["_keep"] = (ws, [list(s) for s in seqs], streams)
     return out
 
 

@@ -738,10 +738,21 @@ __device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int
     uint16_t* pos = reinterpret_cast<uint16_t*>(lds);                        // [T] list position of an inherited token
     uint32_t* vmask = reinterpret_cast<uint32_t*>(lds + FUSED_MAX_T * 2);    // [Wa] valid bits by list position
     const bool own = tid < T4;
+    // One batch of loads: a uniform row base per word plus ONE per-thread byte offset (clamped, so no lane is switched
+    // off and no address has to be kept per word), behind uniform branches only.
+    // The row stride passes through an empty asm statement: inside the resident layer loop the compiler would
+    // otherwise compute all WMAX per-thread addresses once, ahead of the loop, and keep them in (spilled) registers.
     u32x4 x[WMAX];
+    const uint32_t toff = 16u * (uint32_t)min(tid, T4 - 1);
+    int row_words = T;
+    asm volatile("" : "+s"(row_words));
 #pragma unroll
-    for (int w = 0; w < WMAX; ++w)
-        x[w] = (own && w < Wa) ? *reinterpret_cast<const u32x4*>(p.hits + (size_t)w * T + 4 * tid) : u32x4{0u, 0u, 0u, 0u};
+    for (int w = 0; w < WMAX; ++w) {
+        if (w < Wa)
+            x[w] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.hits + (size_t)w * (size_t)row_words) + toff);
+        else
+            x[w] = u32x4{0u, 0u, 0u, 0u};
+    }
     if (own) *reinterpret_cast<unsigned long long*>(pos + 4 * tid) = ~0ull;  // 0xFFFF: not inherited
     for (int w = tid; w < Wa; w += THREADS) vmask[w] = 0u;
     __syncthreads();

@@ -1198,6 +1198,64 @@ int ada_cascade_layers(const void* const* X_layers, int L, int T, int d, int64_t
     return e;
 }
 
+int ada_cascade_layers_batched(const void* const* X_layers, int B, int L, int T, int d, int64_t ld, int dtype, float tau,
+                               int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all, int32_t* adds_all,
+                               int32_t* removes_all, void* ws, size_t ws_bytes, void* const* streams, void* stream,
+                               unsigned flags) {
+    if (!X_layers || !idx_all || !counts_all || !gram_ops_all) return ADA_ERR_NULL;
+    if (B < 1 || B > ADA_MAX_BATCH || L < 1) return ADA_ERR_SHAPE;
+    for (long long i = 0; i < (long long)B * L; ++i)
+        if (!X_layers[i]) return ADA_ERR_NULL;
+    if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
+    const size_t one = ada_workspace_bytes(T);
+    if (!ws) return ADA_ERR_NULL;
+    if (ws_bytes / (size_t)B < one) return ADA_ERR_WORKSPACE;
+    for (int b = 0; b < B; ++b)
+        if (int e = check_common(X_layers[(size_t)b * L], T, d, ld, dtype, tau, (char*)ws + (size_t)b * one, one)) return e;
+    hipStream_t main = (hipStream_t)stream;
+    // fork: every chain starts after what the caller has enqueued on `stream` so far
+    hipEvent_t fork = nullptr;
+    if (streams) {
+        if (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess) return ADA_ERR_DEVICE;
+        bool ok = hipEventRecord(fork, main) == hipSuccess;
+        for (int b = 0; b < B && ok; ++b)
+            if ((hipStream_t)streams[b] != main) ok = hipStreamWaitEvent((hipStream_t)streams[b], fork, 0) == hipSuccess;
+        (void)hipEventDestroy(fork);                      // released by the runtime once it has completed
+        if (!ok) return ADA_ERR_DEVICE;
+    }
+    // layer-major issue order, so that the sequences' launches interleave from the first layer on; the resident pass
+    // needs the whole device for one sequence and is not used here
+    const unsigned fl = flags & ~ADA_FLAG_RESIDENT_PASS;
+    int rc = ADA_OK;
+    for (int l = 0; l < L && rc == ADA_OK; ++l) {
+        for (int b = 0; b < B && rc == ADA_OK; ++b) {
+            hipStream_t st = streams ? (hipStream_t)streams[b] : main;
+            const size_t row = (size_t)b * L + l, o = row * (size_t)T;
+            void* wsb = (char*)ws + (size_t)b * one;
+            if (l == 0)
+                rc = run_full(X_layers[row], T, d, ld, dtype, tau, nullptr, idx_all + o, counts_all + row * 4,
+                              gram_ops_all + row, nullptr, wsb, st);
+            else
+                rc = run_cascade(X_layers[row], T, d, ld, dtype, tau, idx_all + o - T, T, counts_all + (row - 1) * 4,
+                                 idx_all + o, adds_all ? adds_all + o : nullptr, removes_all ? removes_all + o : nullptr,
+                                 counts_all + row * 4, gram_ops_all + row, nullptr, wsb, st, fl);
+        }
+    }
+    // join: what the caller enqueues on `stream` next sees every chain's results (also after an error part-way)
+    if (streams) {
+        for (int b = 0; b < B; ++b) {
+            hipStream_t st = (hipStream_t)streams[b];
+            if (st == main) continue;
+            hipEvent_t done = nullptr;
+            if (hipEventCreateWithFlags(&done, hipEventDisableTiming) != hipSuccess) return ADA_ERR_DEVICE;
+            const bool ok = hipEventRecord(done, st) == hipSuccess && hipStreamWaitEvent(main, done, 0) == hipSuccess;
+            (void)hipEventDestroy(done);
+            if (!ok) return ADA_ERR_DEVICE;
+        }
+    }
+    return rc;
+}
+
 int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t* out, void* stream) {
     if (!mask_a || !mask_b || !out) return ADA_ERR_NULL;
     if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;

@@ -321,6 +321,54 @@ def test_layer_driver_matches_step_by_step_and_report():
     assert torch.equal(out2["counts"], out["counts"]) and torch.equal(out2["gram_ops"], out["gram_ops"])
 
 
+@pytest.mark.parametrize("T,d,K,L,dtype,B", [(600, 192, 70, 5, "bf16", 3), (333, 96, 40, 4, "f32", 2),
+                                             (2048, 512, 400, 4, "bf16", 4)])
+def test_batched_layer_loop_on_streams(T, d, K, L, dtype, B):
+    """B sequences with different seeds through ada_cascade_layers_batched, on B streams and on one stream: every
+    sequence's sets, counts and lists equal those of its own ada_cascade_layers run, and every step is checked against
+    the oracle on the set it consumed.  Work enqueued on the caller's stream afterwards sees the results (the copy
+    below is not preceded by a device synchronisation)."""
+    say("batched layer loop T=%d d=%d L=%d B=%d %s" % (T, d, L, B, dtype))
+    w = wl.small(T=T, d=d, K=K, L=L, dtype=dtype, seed=91 + T, p=0.1)
+    seqs_cpu = [wl.layer_list(w, sequence=b) for b in range(B)]
+    seqs = [[x.to(DEV) for x in s] for s in seqs_cpu]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(B)]
+    ws = pa.workspace_batched(T, B, DEV)
+    for use in (streams, None, streams):                       # the third run reuses the workspaces
+        out = pa.ada_cascade_layers_batched(seqs, w.tau, want_lists=True, ws=ws, streams=use)
+        counts = out["counts"].to("cpu", non_blocking=False)    # on the caller's stream: joined with every chain
+        idx_all, ops = out["idx"].cpu(), out["gram_ops"].cpu()
+        adds_all, rem_all = out["adds"].cpu(), out["removes"].cpu()
+        assert counts[:, :, 3].flatten().tolist() == [0] * (B * L)
+        for b in range(B):
+            single = run_driver(seqs[b], w.tau)
+            sc = single["counts"].cpu()
+            assert torch.equal(sc, counts[b]) and torch.equal(single["gram_ops"].cpu(), ops[b])
+            for l in range(L):
+                r, na, nr = (int(v) for v in sc[l, :3])
+                assert torch.equal(single["idx"][l, :r].cpu(), idx_all[b, l, :r])
+                if l > 0:
+                    assert torch.equal(single["adds"][l, :na].cpu(), adds_all[b, l, :na])
+                    assert torch.equal(single["removes"][l, :nr].cpu(), rem_all[b, l, :nr])
+    first = [idx_all[b, 0, :int(counts[b, 0, 0])].tolist() for b in range(B)]
+    assert first[0] != first[1]                                 # the sequences really differ
+    for b in range(B):                                          # against the oracle, teacher-forced
+        prev = None
+        for l in range(L):
+            r, na, nr = (int(v) for v in counts[b, l, :3])
+            idx = idx_all[b, l, :r].numpy()
+            if l == 0:
+                ref = oracle.select_full(wl.as_f64(seqs_cpu[b][0]), w.tau)
+                assert np.array_equal(idx, ref["idx"]) and int(ops[b, 0]) == T * T
+            else:
+                got = dict(idx=idx, adds=adds_all[b, l, :na].numpy(), removes=rem_all[b, l, :nr].numpy(),
+                           gram_ops=int(ops[b, l]), r=r, n_adds=na, n_removes=nr,
+                           gamma=pa.fetch(pa.ada_cascade_step(seqs[b][l], w.tau, dev_idx(prev)))["gamma"])
+                parity.check_cascade(seqs_cpu[b][l], w.tau, prev, got, what="batched seq %d layer %d" % (b, l))
+            prev = idx
+
+
 def run_driver(xs, tau, **kw):
     out = pa.ada_cascade_layers(xs, tau, **kw)
     torch.cuda.synchronize()

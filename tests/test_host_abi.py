@@ -120,6 +120,15 @@ def test_host_checkable_errors_return_before_touching_the_device(ada):
     assert lib.ada_cascade_layers(ptrs, 0, 8, 8, 8, 1, 0.1, 0x1000, 0x1000, 0x1000, None, None, 0x1000, 1 << 20,
                                   None, 0) == SHAPE
 
+    def batched(X=ptrs, B=1, L=1, T=8, ws=0x1000, nb=1 << 20):
+        return lib.ada_cascade_layers_batched(X, B, L, T, 8, 8, 1, 0.1, 0x1000, 0x1000, 0x1000, None, None, ws, nb,
+                                              None, None, 0)
+    assert batched(X=None) == NULL and batched(ws=None) == NULL and batched(B=2) == NULL      # second pointer is NULL
+    assert batched(B=0) == SHAPE and batched(L=0) == SHAPE and batched(B=4097) == SHAPE and batched(T=0) == SHAPE
+    one = lib.ada_workspace_bytes(8)
+    two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    assert batched(X=two, B=2, nb=2 * one - 1) == WS and batched(ws=0x1010) == WS
+
 
 def test_binding_rejects_host_tensors_and_wrong_dtypes(ada):
     import paper_2605_03110_amd as pa
