@@ -210,6 +210,45 @@ int ada_cascade_layers_batched(const void* const* X_layers, int B, int L, int T,
                                void* ws, size_t ws_bytes, void* const* streams, void* stream, unsigned flags);
 
 /*
+ * Several independent selection problems of one shape that live in ONE allocation, served by one launch per cascade
+ * step: the h heads of a T x (h * d_h) matrix for the per-head cascade of Section 8.5 (a representative set per head,
+ * cost h x T r_h d_h), or sequences stacked in one [G][T][ld] tensor.  Group g's matrix starts x_gstride elements
+ * after group g-1's and has the common T, d (= d_h for heads), ld and dtype.
+ */
+typedef struct {
+    int G;                  /* number of groups, 1 .. ADA_MAX_BATCH */
+    int64_t x_gstride;      /* elements between consecutive groups' X (>= d): d_h for heads side by side, T * ld for
+                               stacked sequences */
+    int64_t list_gstride;   /* int32 elements between consecutive groups in prev_idx, idx, adds, removes (>= T) */
+    int64_t counts_gstride; /* int32 elements between consecutive groups in counts, and in r_dev if given (>= 4) */
+    int64_t ops_gstride;    /* elements between consecutive groups in gram_ops (>= 1) */
+} ada_groups;
+
+/*
+ * Algorithm 1 for every group at once.  Arguments as for ada_cascade_step (the pointers are group 0's; r bounds every
+ * group's inherited count, r_dev[g * counts_gstride] is group g's actual count); every group writes its own idx,
+ * adds, removes, counts[4] and gram_ops.  There is no gamma output.
+ *   ws   G workspaces back to back, ada_workspace_bytes(T) apart, each initialised
+ * For T <= 16384 and without ADA_FLAG_TWO_PASS all groups share one launch (the chip's workgroups are divided among
+ * the groups; a group's last workgroup updates that group's set); otherwise the groups run one after the other.
+ */
+int ada_cascade_step_grouped(const ada_groups* groups, const void* X, int T, int d, int64_t ld, int dtype, float tau,
+                             const int32_t* prev_idx, int r, const int32_t* r_dev,
+                             int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts, uint64_t* gram_ops,
+                             void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
+ * The layer loop for G groups: full selection of every group at layer 0, then one grouped cascade step per layer.
+ *   X_layers   HOST array of L device pointers (group 0's matrix of each layer)
+ *   outputs    as for ada_cascade_layers_batched with B = G: idx_all [G][L][T], counts_all [G][L][4], ...
+ * Only groups->G and groups->x_gstride are read (the other strides follow from the output layout).
+ */
+int ada_cascade_layers_grouped(const ada_groups* groups, const void* const* X_layers, int L, int T, int d, int64_t ld,
+                               int dtype, float tau, int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all,
+                               int32_t* adds_all, int32_t* removes_all,
+                               void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
  * |A n B| and |A u B| of two representative sets given as uint8 masks [T] (device), for the
  * Jaccard index of eq. (3).  out: device int32 [2] = {intersection, union}.
  */

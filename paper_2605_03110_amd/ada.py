@@ -26,11 +26,18 @@ FLAG_ATTN_CAUSAL = 8
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
-           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
+           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped",
+           "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
            "ada_attention_compressed")
 
 KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused", "mfma_probe", "assign", "attn")
+
+
+class AdaGroups(ctypes.Structure):
+    """ada_groups of include/ada.h."""
+    _fields_ = [("G", ctypes.c_int), ("x_gstride", ctypes.c_int64), ("list_gstride", ctypes.c_int64),
+                ("counts_gstride", ctypes.c_int64), ("ops_gstride", ctypes.c_int64)]
 
 
 class AdaError(RuntimeError):
@@ -84,6 +91,12 @@ def lib():
         L.ada_cascade_layers_batched.restype = i32
         L.ada_cascade_layers_batched.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp,
                                                  vp, sz, ctypes.POINTER(vp), vp, u32]
+        L.ada_cascade_step_grouped.restype = i32
+        L.ada_cascade_step_grouped.argtypes = [ctypes.POINTER(AdaGroups), vp, i32, i32, i64, i32, f32, vp, i32, vp, vp, vp, vp,
+                                               vp, vp, vp, sz, vp, u32]
+        L.ada_cascade_layers_grouped.restype = i32
+        L.ada_cascade_layers_grouped.argtypes = [ctypes.POINTER(AdaGroups), ctypes.POINTER(vp), i32, i32, i32, i64, i32, f32,
+                                                 vp, vp, vp, vp, vp, vp, sz, vp, u32]
         L.ada_set_overlap.restype = i32
         L.ada_set_overlap.argtypes = [vp, vp, i32, vp, vp]
         L.ada_cascade_report.restype = i32
@@ -339,6 +352,91 @@ def ada_cascade_layers_batched(seqs: Sequence[Sequence[torch.Tensor]], tau: floa
     if rc != OK:
         raise AdaError(rc, "ada_cascade_layers_batched")
     out["_keep"] = (ws, [list(s) for s in seqs], streams)
+    return out
+
+
+def heads_view(X: torch.Tensor, H: int) -> torch.Tensor:
+    """The H column blocks of a T x (H d_h) matrix as a [H, T, d_h] view (no copy): the groups of the per-head cascade."""
+    T, d = X.shape
+    if d % H != 0:
+        raise ValueError("d must be a multiple of the head count")
+    return X.view(T, H, d // H).permute(1, 0, 2)
+
+
+def _check_xg(Xg: torch.Tensor):
+    if not Xg.is_cuda:
+        raise ValueError("X must live on the GPU")
+    if Xg.dim() != 3 or (Xg.shape[2] > 1 and Xg.stride(2) != 1):
+        raise ValueError("X must be a [G, T, d] tensor (or view) with unit stride along d")
+
+
+def ada_cascade_step_grouped(Xg: torch.Tensor, tau: float, prev_idx: torch.Tensor, r: Optional[int] = None,
+                             r_dev: Optional[torch.Tensor] = None, *, ws: Optional[torch.Tensor] = None, stream=None,
+                             flags: int = 0) -> Dict[str, torch.Tensor]:
+    """One cascade step for G problems in one allocation.  Xg: [G, T, d] view (heads_view, or stacked sequences);
+    prev_idx: [G, T] int32 (row g: group g's inherited set, ascending); r bounds every group's count (default T when
+    r_dev, a [G, 4] int32 tensor with the counts in column 0, is given).  Returns idx, adds, removes [G, T], counts
+    [G, 4], gram_ops [G]."""
+    _check_xg(Xg)
+    G, T, d = Xg.shape
+    dev = Xg.device
+    if prev_idx.dtype != torch.int32 or not prev_idx.is_cuda or prev_idx.dim() != 2 or prev_idx.shape[0] != G \
+            or prev_idx.stride(1) != 1:
+        raise ValueError("prev_idx must be a [G, n] int32 device tensor with contiguous rows")
+    if r_dev is not None and (r_dev.dtype != torch.int32 or r_dev.dim() != 2 or r_dev.shape != (G, 4) or not r_dev.is_contiguous()):
+        raise ValueError("r_dev must be a contiguous [G, 4] int32 device tensor")
+    r = int(prev_idx.shape[1]) if r is None else int(r)
+    if r > prev_idx.shape[1]:
+        raise ValueError("r exceeds the rows of prev_idx")
+    ws = workspace_batched(T, G, dev) if ws is None else ws
+    out = dict(idx=torch.empty((G, T), dtype=torch.int32, device=dev), adds=torch.empty((G, T), dtype=torch.int32, device=dev),
+               removes=torch.empty((G, T), dtype=torch.int32, device=dev),
+               counts=torch.empty((G, 4), dtype=torch.int32, device=dev),
+               gram_ops=torch.empty(G, dtype=torch.int64, device=dev))
+    if prev_idx.stride(0) != T and G > 1:
+        raise ValueError("prev_idx rows must be T entries apart (the outputs are)")
+    g = AdaGroups(G, Xg.stride(0) if G > 1 else d, T, 4, 1)
+    rc = lib().ada_cascade_step_grouped(ctypes.byref(g), _ptr(Xg), T, d, Xg.stride(1), _dtype_code(Xg), float(tau),
+                                        _ptr(prev_idx), r, _ptr(r_dev), _ptr(out["idx"]), _ptr(out["adds"]),
+                                        _ptr(out["removes"]), _ptr(out["counts"]), _ptr(out["gram_ops"]), _ptr(ws),
+                                        ws.numel(), _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_step_grouped")
+    out["_keep"] = (ws, Xg, prev_idx, r_dev)
+    return out
+
+
+def ada_cascade_layers_grouped(Xgs: Sequence[torch.Tensor], tau: float, *, want_lists: bool = False,
+                               ws: Optional[torch.Tensor] = None, stream=None, flags: int = 0,
+                               out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """The layer loop for G problems per layer (Xgs[l]: [G, T, d] view of layer l; all layers with the same strides).
+    Returns idx[G,L,T], counts[G,L,4], gram_ops[G,L] and, if want_lists, adds / removes [G,L,T]."""
+    L = len(Xgs)
+    if L < 1:
+        raise ValueError("need at least one layer")
+    for Xg in Xgs:
+        _check_xg(Xg)
+        if Xg.shape != Xgs[0].shape or Xg.dtype != Xgs[0].dtype or Xg.stride() != Xgs[0].stride():
+            raise ValueError("all layers must share shape, dtype and strides")
+    G, T, d = Xgs[0].shape
+    dev = Xgs[0].device
+    ws = workspace_batched(T, G, dev) if ws is None else ws
+    if out is None:
+        out = dict(idx=torch.empty((G, L, T), dtype=torch.int32, device=dev),
+                   counts=torch.empty((G, L, 4), dtype=torch.int32, device=dev),
+                   gram_ops=torch.empty((G, L), dtype=torch.int64, device=dev))
+        if want_lists:
+            out["adds"] = torch.empty((G, L, T), dtype=torch.int32, device=dev)
+            out["removes"] = torch.empty((G, L, T), dtype=torch.int32, device=dev)
+    g = AdaGroups(G, Xgs[0].stride(0) if G > 1 else d, 0, 0, 0)
+    ptrs = (ctypes.c_void_p * L)(*[X.data_ptr() for X in Xgs])
+    rc = lib().ada_cascade_layers_grouped(ctypes.byref(g), ptrs, L, T, d, Xgs[0].stride(1), _dtype_code(Xgs[0]), float(tau),
+                                          _ptr(out["idx"]), _ptr(out["counts"]), _ptr(out["gram_ops"]),
+                                          _ptr(out.get("adds")), _ptr(out.get("removes")), _ptr(ws), ws.numel(),
+                                          _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_layers_grouped")
+    out["_keep"] = (ws, list(Xgs))
     return out
 
 

@@ -56,11 +56,21 @@ struct FusedParams {
     // workgroups of the launch (a multiple of 8), filled in by the launcher: the built-in grid size sits in another
     // cache line of the launch's argument block, and waiting for that line is a trip to memory at every kernel start
     int grid;
+    // Several independent problems of one shape in one launch (heads of one matrix, or sequences stacked in one
+    // allocation): groups > 1.  Workgroup b serves group b % groups as its worker b / groups of wpg (grid = groups x
+    // wpg); the pointers above are group 0's, group g's lie g strides further on.
+    int groups, wpg;
+    long long x_gs;          // bytes between consecutive groups' X
+    long long list_gs;       // int32 elements between groups in prev_idx, idx, adds, removes
+    long long counts_gs;     // int32 elements between groups in counts and r_dev
+    long long ops_gs;        // elements between groups in gram_ops
+    long long ws_gs;         // bytes between groups' hit tables and tickets
 };
 
 // Tile shapes (representatives x tested tokens): 0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128.  A step's cost is taken as
-// rounds x (operand rows per tile + a fixed part worth about 40 rows), rounds = tiles per XCD over workgroups per XCD:
-// operand bytes per Gram entry fall with the tile size, but a tile count below the CU count leaves CUs idle.
+// rounds x (operand bytes per tile + a fixed part worth about 56 rows of 4096 two-byte elements: set size, list and
+// first-chunk trips before the K loop, norms and hit words after it), rounds = tiles over the workgroups that share
+// them: operand bytes per Gram entry fall with the tile size, but a tile count below the worker count leaves CUs idle.
 __host__ __device__ inline int tile_rows_r(int shape) { return shape == 2 ? 128 : 64; }
 __host__ __device__ inline int tile_rows_t(int shape) { return shape == 0 ? 64 : 128; }
 // (T <= FUSED_MAX_T: every count fits 32 bits, and 32-bit divisions are what the start of a launch can afford)
@@ -68,17 +78,20 @@ __host__ __device__ inline int tile_count(int r, int T, int shape) {
     const int br = tile_rows_r(shape), bt = tile_rows_t(shape);
     return ((r + br - 1) / br) * ((T + bt - 1) / bt);
 }
-__host__ __device__ inline int cascade_tile_shape(int r, int T, int pick) {
+// pick > 0: choose; pick = 0, -1, -2: always shape 0, 1, 2.  workers: workgroups that share the step's tiles.
+__host__ __device__ inline int cascade_tile_shape(int r, int T, int d, int pick, int workers) {
     if (pick <= 0) return -pick;
-    const unsigned slots = pick >= 8 ? (unsigned)pick / 8u : 1u;
+    const unsigned wk = workers > 0 ? (unsigned)workers : 1u;
     const unsigned nr64 = (unsigned)(r + 63) >> 6, nr128 = (unsigned)(r + 127) >> 7;
     const unsigned nt64 = (unsigned)(T + 63) >> 6, nt128 = (unsigned)(T + 127) >> 7;
     const unsigned tiles[3] = {nr64 * nt64, nr64 * nt128, nr128 * nt128};
+    const unsigned dd = (unsigned)(d < 65536 ? d : 65536);   // keeps the products below 2^32 (tiles <= 65536 / 8 per round matter)
     int best = 0;
-    unsigned best_cost = 0;
+    unsigned long long best_cost = 0;
     for (int shape = 0; shape < 3; ++shape) {
-        const unsigned per = (tiles[shape] + 7u) >> 3;
-        const unsigned cost = ((per + slots - 1u) / slots) * (unsigned)(tile_rows_r(shape) + tile_rows_t(shape) + 40);
+        const unsigned rounds = (tiles[shape] + wk - 1u) / wk;
+        const unsigned long long cost =
+            (unsigned long long)rounds * ((unsigned)(tile_rows_r(shape) + tile_rows_t(shape)) * dd + 56u * 4096u);
         if (shape == 0 || cost < best_cost) { best = shape; best_cost = cost; }
     }
     return best;
@@ -998,16 +1011,21 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
 // The tiles of one step, dealt to the workgroups in contiguous ranges per XCD (blockIdx % 8), the representative block
 // fastest, so that one XCD's L2 serves a contiguous range of tested rows.
 template <typename In, bool ALIGNED, int KG, bool DMA>
-__device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds) {
+__device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds, unsigned local, unsigned workers) {
     int shape = 0;
-    if constexpr (ALIGNED && KG == 2 && DMA) shape = cascade_tile_shape(r, p.T, p.tile_pick);
+    if constexpr (ALIGNED && KG == 2 && DMA)
+        shape = cascade_tile_shape(r, p.T, p.d, p.tile_pick, p.groups > 1 ? (int)workers : p.tile_pick);
     const int sr = shape == 2 ? 7 : 6, st = shape == 0 ? 6 : 7;           // log2 of the tile's rows
     const unsigned nbS = (unsigned)(r + (1 << sr) - 1) >> sr;
     const unsigned ntiles = nbS * ((unsigned)(p.T + (1 << st) - 1) >> st);
-    const unsigned per = (ntiles + 7u) >> 3;
-    const unsigned xcd = blockIdx.x & 7, slots = (unsigned)p.grid >> 3;
-    for (unsigned slot = blockIdx.x >> 3; slot < per; slot += slots) {
-        const unsigned tile = xcd * per + slot;
+    // one problem: contiguous tile ranges per XCD (workgroup b runs on XCD b % 8); groups: worker `local` of the
+    // group's `workers` takes every workers-th tile
+    const bool grouped = p.groups > 1;
+    const unsigned per = grouped ? ntiles : (ntiles + 7u) >> 3;
+    const unsigned base = grouped ? 0u : (local & 7u) * per;
+    const unsigned slots = grouped ? workers : workers >> 3;
+    for (unsigned slot = grouped ? local : local >> 3; slot < per; slot += slots) {
+        const unsigned tile = base + slot;
         if (tile >= ntiles) break;
         const int tb = (int)(tile / nbS), sb = (int)(tile - (unsigned)tb * nbS);
         if constexpr (ALIGNED && KG == 2 && DMA) {
@@ -1029,9 +1047,25 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     using G = FusedGeom<KG, DMA>;
     __shared__ int s_last;
     ADA_CLK(0);
+    unsigned local = blockIdx.x, workers = (unsigned)p.grid;
+    if (p.groups > 1) {                                      // uniform: this workgroup's problem
+        const unsigned g = blockIdx.x % (unsigned)p.groups;
+        local = blockIdx.x / (unsigned)p.groups;
+        workers = (unsigned)p.wpg;
+        p.X = reinterpret_cast<const char*>(p.X) + (long long)g * p.x_gs;
+        p.prev_idx += (long long)g * p.list_gs;
+        if (p.r_dev) p.r_dev += (long long)g * p.counts_gs;
+        p.hits = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(p.hits) + (long long)g * p.ws_gs);
+        p.ticket = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.ticket) + (long long)g * p.ws_gs);
+        p.idx += (long long)g * p.list_gs;
+        if (p.adds) p.adds += (long long)g * p.list_gs;
+        if (p.removes) p.removes += (long long)g * p.list_gs;
+        p.counts += (long long)g * p.counts_gs;
+        if (p.gram_ops) p.gram_ops += (long long)g * p.ops_gs;
+    }
     const int r = p.r_dev ? *p.r_dev : p.r_host;
     const bool r_ok = r >= 1 && r <= p.r_host && r <= p.T;
-    if (r_ok) fused_step_tiles<In, ALIGNED, KG, DMA>(p, r, lds);
+    if (r_ok) fused_step_tiles<In, ALIGNED, KG, DMA>(p, r, lds, local, workers);
     // The workgroup that takes the last ticket finishes the step.  Hit words and row maxima leave the CU as
     // device-scope atomics (written through the L2), so once every thread's stores are acknowledged (vmcnt(0)) and
     // the workgroup has met at the barrier, the ticket can be taken: nothing is left in the L2 to write back.
@@ -1042,7 +1076,9 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));
     __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this thread's stores have left the CU
     __syncthreads();
-    if (threadIdx.x == 0) s_last = take_ticket(p.ticket, p.grid) ? 1 : 0;
+    // (a group's few workers count on one word: the two levels are for a whole chip of workgroups)
+    if (threadIdx.x == 0)
+        s_last = (p.groups > 1 ? atomicAdd(p.ticket, 1) == (int)workers - 1 : take_ticket(p.ticket, p.grid)) ? 1 : 0;
     __syncthreads();
     ADA_CLK(7);
     if (!s_last) return;
@@ -1128,7 +1164,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_pass(PassParams pp) {
         p.counts = pp.counts_row0 + (size_t)(i + 1) * 4;
         p.gram_ops = pp.gram_ops_row0 + (i + 1);
         const bool r_ok = r >= 1 && r <= T;
-        if (r_ok) fused_step_tiles<In, ALIGNED, KG, DMA>(p, r, lds);
+        if (r_ok) fused_step_tiles<In, ALIGNED, KG, DMA>(p, r, lds, blockIdx.x, (unsigned)p.grid);
         PASS_CLK(2);
         const int jq = min((int)threadIdx.x, T - 1);         // the row has T entries whatever r is
         const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));

@@ -902,17 +902,28 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = A
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     if (attr_err != hipSuccess) return attr_err;
-    // with the set size known here the tile shape is too (the kernel makes the same choice from the same numbers)
-    int shape = 0;
-    if (ALIGNED && KG == 2 && DMA && !p.r_dev) shape = cascade_tile_shape(p.r_host, p.T, p.tile_pick);
-    long long tiles = tile_count(p.r_host, p.T, shape);
-    // Workgroups loop over tiles, so any grid is correct.  With the set size known only on the device the bound
-    // r_host = T would launch mostly idle workgroups, and dispatching those is not free: cap at one per CU (the LDS
-    // footprint admits no more at a time anyway).
-    const long long cap = p.r_dev ? device_cus() : 2048;
-    if (tiles > cap) tiles = cap;
-    const unsigned grid = (unsigned)(tiles + 7) / 8 * 8;             // multiple of 8 (XCDs)
     FusedParams q = p;
+    unsigned grid;
+    if (p.groups > 1) {
+        // the groups share the chip: about one workgroup per CU in all, and no more per group than it has tiles
+        const long long tiles = tile_count(p.r_host, p.T, 0);
+        long long wpg = device_cus() / p.groups;
+        if (wpg < 1) wpg = 1;
+        if (wpg > tiles) wpg = tiles;
+        q.wpg = (int)wpg;
+        grid = (unsigned)(p.groups * wpg);
+    } else {
+        // with the set size known here the tile shape is too (the kernel makes the same choice from the same numbers)
+        int shape = 0;
+        if (ALIGNED && KG == 2 && DMA && !p.r_dev) shape = cascade_tile_shape(p.r_host, p.T, p.d, p.tile_pick, p.tile_pick);
+        long long tiles = tile_count(p.r_host, p.T, shape);
+        // Workgroups loop over tiles, so any grid is correct.  With the set size known only on the device the bound
+        // r_host = T would launch mostly idle workgroups, and dispatching those is not free: cap at one per CU (the LDS
+        // footprint admits no more at a time anyway).
+        const long long cap = p.r_dev ? device_cus() : 2048;
+        if (tiles > cap) tiles = cap;
+        grid = (unsigned)(tiles + 7) / 8 * 8;                        // multiple of 8 (XCDs)
+    }
     q.grid = (int)grid;
     ProfScope ps(prof_class, st);
     hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG, DMA>), dim3(grid), dim3(256 * KG), lds, st, q);
@@ -944,7 +955,10 @@ int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_
     int kg = 2;
     if (int o = kgroups_override()) kg = o;
     const char* no_dma = getenv("ADA_NO_DMA");
-    hipError_t e = dispatch(dtype, p.X, p.ld, p.d, [&](auto v) {
+    // the form of the kernel must suit every group's rows: a group stride off the 16-byte grid takes the element-wise
+    // loader for all of them (dispatch looks at base, ld and d)
+    const long long ld_seen = (p.groups > 1 && p.x_gs % 16 != 0) ? 1 : p.ld;
+    hipError_t e = dispatch(dtype, p.X, ld_seen, p.d, [&](auto v) {
         using V = decltype(v);
         using In = typename V::In;
         constexpr int epc = 128 / (int)sizeof(In);
@@ -963,13 +977,22 @@ int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_
 // other token the max over ALL inherited representatives (validity is resolved after the products).
 int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, float tau, const int32_t* prev_idx, int r,
                       const int32_t* r_dev, int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
-                      uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st, unsigned flags) {
+                      uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st, unsigned flags,
+                      const ada_groups* grp = nullptr) {
     const Workspace w = carve(ws, T);
     if (gamma && fill_u32(gamma, (size_t)T, 0u, st) != hipSuccess) return ADA_ERR_DEVICE;
-    const FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
-                           (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
-                           w.meta + META_TICKET, idx, adds, removes, counts,
-                           reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
+    FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
+                     (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
+                     w.meta + META_TICKET, idx, adds, removes, counts,
+                     reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
+    if (grp && grp->G > 1) {                                     // ws: G workspaces back to back
+        p.groups = grp->G;
+        p.x_gs = grp->x_gstride * (dtype == ADA_BF16 ? 2 : 4);
+        p.list_gs = grp->list_gstride;
+        p.counts_gs = grp->counts_gstride;
+        p.ops_gs = grp->ops_gstride;
+        p.ws_gs = (long long)ws_bytes_for(T);
+    }
     return launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
 }
 
@@ -1168,6 +1191,88 @@ int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float t
     if (r < 1 || r > T) return ADA_ERR_SHAPE;
     return run_cascade(X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops, gamma, ws,
                        (hipStream_t)stream, flags);
+}
+
+namespace {
+int check_groups(const ada_groups* g, int T, int d) {
+    if (!g) return ADA_ERR_NULL;
+    if (g->G < 1 || g->G > ADA_MAX_BATCH) return ADA_ERR_SHAPE;
+    if (g->G > 1 && (g->x_gstride < d || g->list_gstride < T || g->counts_gstride < 4 || g->ops_gstride < 1)) return ADA_ERR_SHAPE;
+    return ADA_OK;
+}
+
+// one cascade step for every group: one launch when the one-launch form applies, else group by group
+int run_cascade_grouped(const ada_groups& g, const void* X, int T, int d, long long ld, int dtype, float tau,
+                        const int32_t* prev_idx, int r, const int32_t* r_dev, int32_t* idx, int32_t* adds,
+                        int32_t* removes, int32_t* counts, uint64_t* gram_ops, void* ws, hipStream_t st, unsigned flags) {
+    if (g.G == 1)
+        return run_cascade(X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops, nullptr, ws,
+                           st, flags);
+    if (!(flags & ADA_FLAG_TWO_PASS) && T <= FUSED_MAX_T)
+        return run_cascade_fused(X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops, nullptr,
+                                 ws, st, flags, &g);
+    const size_t esz = dtype == ADA_BF16 ? 2 : 4, one = ws_bytes_for(T);
+    for (int i = 0; i < g.G; ++i) {
+        const long long lo = (long long)i * g.list_gstride, co = (long long)i * g.counts_gstride;
+        const int e = run_cascade((const char*)X + (size_t)i * (size_t)g.x_gstride * esz, T, d, ld, dtype, tau, prev_idx + lo,
+                                  r, r_dev ? r_dev + co : nullptr, idx + lo, adds ? adds + lo : nullptr,
+                                  removes ? removes + lo : nullptr, counts + co,
+                                  gram_ops ? gram_ops + (long long)i * g.ops_gstride : nullptr, nullptr,
+                                  (char*)ws + (size_t)i * one, st, flags);
+        if (e != ADA_OK) return e;
+    }
+    return ADA_OK;
+}
+}  // namespace
+
+int ada_cascade_step_grouped(const ada_groups* groups, const void* X, int T, int d, int64_t ld, int dtype, float tau,
+                             const int32_t* prev_idx, int r, const int32_t* r_dev, int32_t* idx, int32_t* adds,
+                             int32_t* removes, int32_t* counts, uint64_t* gram_ops, void* ws, size_t ws_bytes, void* stream,
+                             unsigned flags) {
+    if (!prev_idx || !idx || !adds || !removes || !counts) return ADA_ERR_NULL;
+    if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
+    if (int e = check_groups(groups, T, d)) return e;
+    const size_t one = ws_bytes_for(T);
+    if (ws && ws_bytes / (size_t)groups->G < one) return ADA_ERR_WORKSPACE;
+    if (int e = check_common(X, T, d, ld, dtype, tau, ws, one)) return e;
+    if (r < 1 || r > T) return ADA_ERR_SHAPE;
+    return run_cascade_grouped(*groups, X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops,
+                               ws, (hipStream_t)stream, flags);
+}
+
+int ada_cascade_layers_grouped(const ada_groups* groups, const void* const* X_layers, int L, int T, int d, int64_t ld,
+                               int dtype, float tau, int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all,
+                               int32_t* adds_all, int32_t* removes_all, void* ws, size_t ws_bytes, void* stream,
+                               unsigned flags) {
+    if (!groups || !X_layers || !idx_all || !counts_all || !gram_ops_all) return ADA_ERR_NULL;
+    if (L < 1 || T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
+    if (groups->G < 1 || groups->G > ADA_MAX_BATCH || (groups->G > 1 && groups->x_gstride < d)) return ADA_ERR_SHAPE;
+    for (int l = 0; l < L; ++l)
+        if (!X_layers[l]) return ADA_ERR_NULL;
+    const size_t one = ws_bytes_for(T);
+    if (ws && ws_bytes / (size_t)groups->G < one) return ADA_ERR_WORKSPACE;
+    if (int e = check_common(X_layers[0], T, d, ld, dtype, tau, ws, one)) return e;
+    hipStream_t st = (hipStream_t)stream;
+    // the outputs are [G][L][...] blocks, so a group's rows are L rows apart
+    const ada_groups g = {groups->G, groups->x_gstride, (int64_t)L * T, (int64_t)L * 4, (int64_t)L};
+    const size_t esz = dtype == ADA_BF16 ? 2 : 4;
+    // layer 0: every group's full selection, one after the other
+    for (int i = 0; i < g.G; ++i) {
+        const int e = run_full((const char*)X_layers[0] + (size_t)i * (size_t)g.x_gstride * esz, T, d, ld, dtype, tau, nullptr,
+                               idx_all + (size_t)i * g.list_gstride, counts_all + (size_t)i * g.counts_gstride,
+                               gram_ops_all + (size_t)i * g.ops_gstride, nullptr, (char*)ws + (size_t)i * one, st);
+        if (e != ADA_OK) return e;
+    }
+    // layers >= 1: one launch serves all groups
+    for (int l = 1; l < L; ++l) {
+        const size_t o = (size_t)l * (size_t)T;
+        const int e = run_cascade_grouped(g, X_layers[l], T, d, ld, dtype, tau, idx_all + o - T, T,
+                                          counts_all + (size_t)(l - 1) * 4, idx_all + o, adds_all ? adds_all + o : nullptr,
+                                          removes_all ? removes_all + o : nullptr, counts_all + (size_t)l * 4,
+                                          gram_ops_all + l, ws, st, flags & ~ADA_FLAG_RESIDENT_PASS);
+        if (e != ADA_OK) return e;
+    }
+    return ADA_OK;
 }
 
 int ada_cascade_layers(const void* const* X_layers, int L, int T, int d, int64_t ld, int dtype, float tau,

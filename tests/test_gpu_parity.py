@@ -369,6 +369,133 @@ def test_batched_layer_loop_on_streams(T, d, K, L, dtype, B):
             prev = idx
 
 
+@pytest.mark.parametrize("T,d,H,K,L,dtype", [(600, 512, 4, 70, 4, "bf16"), (333, 192, 3, 40, 3, "f32"), (1100, 384, 6, 150, 3, "bf16")])
+def test_per_head_cascade_through_the_batched_call(T, d, H, K, L, dtype):
+    """One representative set per head (Section 8.5): head h selects on the columns [h d_h, (h+1) d_h) of X, passed as
+    a view (pointer offset, leading dimension d).  The H heads go through the batched layer loop as H sequences; each
+    head is checked step by step against the oracle on its own column block."""
+    say("per-head cascade T=%d d=%d H=%d %s" % (T, d, H, dtype))
+    w = wl.small(T=T, d=d, K=K, L=L, dtype=dtype, seed=57 + T, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    dh = d // H
+    heads = [[x[:, h * dh:(h + 1) * dh] for x in xs] for h in range(H)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    out = pa.ada_cascade_layers_batched(heads, w.tau, want_lists=True, streams=[streams[h % 2] for h in range(H)])
+    counts = out["counts"].cpu()
+    idx_all, ops, adds_all, rem_all = out["idx"].cpu(), out["gram_ops"].cpu(), out["adds"].cpu(), out["removes"].cpu()
+    assert counts[:, :, 3].flatten().tolist() == [0] * (H * L)
+    for h in range(H):
+        prev = None
+        for l in range(L):
+            xh = xs_cpu[l][:, h * dh:(h + 1) * dh].contiguous()
+            r, na, nr = (int(v) for v in counts[h, l, :3])
+            idx = idx_all[h, l, :r].numpy()
+            if l == 0:
+                ref = oracle.select_full(wl.as_f64(xh), w.tau)
+                assert np.array_equal(idx, ref["idx"]) and int(ops[h, 0]) == T * T
+            else:
+                got = dict(idx=idx, adds=adds_all[h, l, :na].numpy(), removes=rem_all[h, l, :nr].numpy(),
+                           gram_ops=int(ops[h, l]), r=r, n_adds=na, n_removes=nr,
+                           gamma=pa.fetch(pa.ada_cascade_step(heads[h][l], w.tau, dev_idx(prev)))["gamma"])
+                parity.check_cascade(xh, w.tau, prev, got, what="head %d layer %d" % (h, l))
+            prev = idx
+
+
+@pytest.mark.parametrize("T,d,H,K,L,dtype", [(600, 512, 4, 70, 4, "bf16"), (333, 192, 3, 40, 3, "f32"), (1100, 384, 6, 150, 3, "bf16"),
+                                             (700, 300, 6, 90, 3, "bf16"), (2048, 2048, 16, 400, 3, "bf16")])
+def test_per_head_cascade_in_one_launch_per_layer(T, d, H, K, L, dtype):
+    """ada_cascade_layers_grouped on the heads of one matrix (Section 8.5) against the same heads run one by one
+    through the batched call (bit-exact), and layer by layer against the oracle on the head's column block.
+    d_h = 50 (bf16) puts the heads off the 16-byte grid: element-wise loader."""
+    say("grouped per-head cascade T=%d d=%d H=%d %s" % (T, d, H, dtype))
+    w = wl.small(T=T, d=d, K=K, L=L, dtype=dtype, seed=61 + T, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    dh = d // H
+    ws = pa.workspace_batched(T, H, DEV)
+    grouped = pa.ada_cascade_layers_grouped([pa.heads_view(x, H) for x in xs], w.tau, want_lists=True, ws=ws)
+    again = pa.ada_cascade_layers_grouped([pa.heads_view(x, H) for x in xs], w.tau, want_lists=True, ws=ws)
+    one_by_one = pa.ada_cascade_layers_batched([[x[:, h * dh:(h + 1) * dh] for x in xs] for h in range(H)], w.tau,
+                                               want_lists=True)
+    torch.cuda.synchronize()
+    counts = grouped["counts"].cpu()
+    assert counts[:, :, 3].flatten().tolist() == [0] * (H * L)
+    for other in (again, one_by_one):
+        assert torch.equal(other["counts"].cpu(), counts) and torch.equal(other["gram_ops"], grouped["gram_ops"])
+        for h in range(H):
+            for l in range(L):
+                r, na, nr = (int(v) for v in counts[h, l, :3])
+                assert torch.equal(other["idx"][h, l, :r], grouped["idx"][h, l, :r])
+                if l > 0:
+                    assert torch.equal(other["adds"][h, l, :na], grouped["adds"][h, l, :na])
+                    assert torch.equal(other["removes"][h, l, :nr], grouped["removes"][h, l, :nr])
+    idx_all, ops = grouped["idx"].cpu(), grouped["gram_ops"].cpu()
+    adds_all, rem_all = grouped["adds"].cpu(), grouped["removes"].cpu()
+    for h in range(H if T < 2000 else 2):
+        prev = None
+        for l in range(L):
+            xh = xs_cpu[l][:, h * dh:(h + 1) * dh].contiguous()
+            r, na, nr = (int(v) for v in counts[h, l, :3])
+            idx = idx_all[h, l, :r].numpy()
+            if l == 0:
+                ref = oracle.select_full(wl.as_f64(xh), w.tau)
+                assert np.array_equal(idx, ref["idx"]) and int(ops[h, 0]) == T * T
+            else:
+                got = dict(idx=idx, adds=adds_all[h, l, :na].numpy(), removes=rem_all[h, l, :nr].numpy(),
+                           gram_ops=int(ops[h, l]), r=r, n_adds=na, n_removes=nr,
+                           gamma=pa.fetch(pa.ada_cascade_step(xs[l][:, h * dh:(h + 1) * dh], w.tau, dev_idx(prev)))["gamma"])
+                parity.check_cascade(xh, w.tau, prev, got, what="grouped head %d layer %d" % (h, l))
+            prev = idx
+
+
+@pytest.mark.parametrize("flags", [0, pa.FLAG_CROSS_EARLIER_ONLY, pa.FLAG_TWO_PASS])
+def test_grouped_step_on_stacked_sequences(flags):
+    """ada_cascade_step_grouped on G sequences stacked in one [G, T, d] tensor, with the inherited counts on the host
+    (a common bound r) and on the device, against single ada_cascade_step calls and the oracle; one group's list is
+    bad and only that group reports it."""
+    G, T, d = 5, 450, 256
+    say("grouped step, stacked sequences G=%d T=%d d=%d flags=%d" % (G, T, d, flags))
+    w = wl.small(T=T, d=d, K=60, L=2, dtype="bf16", seed=71, p=0.15)
+    seqs_cpu = [wl.layer_list(w, sequence=b) for b in range(G)]
+    x0 = torch.stack([s[0] for s in seqs_cpu]).to(DEV)
+    x1 = torch.stack([s[1] for s in seqs_cpu]).to(DEV)
+    prev = torch.zeros((G, T), dtype=torch.int32, device=DEV)
+    cnt = torch.zeros((G, 4), dtype=torch.int32, device=DEV)
+    prev_sets = []
+    for b in range(G):
+        f = pa.fetch(pa.ada_select_full(x0[b], w.tau))
+        prev_sets.append(np.asarray(f["idx"]))
+        prev[b, :len(f["idx"])] = dev_idx(f["idx"])
+        cnt[b, 0] = len(f["idx"])
+    out = pa.ada_cascade_step_grouped(x1, w.tau, prev, r=T, r_dev=cnt, flags=flags)
+    torch.cuda.synchronize()
+    c = out["counts"].cpu()
+    assert c[:, 3].tolist() == [0] * G
+    for b in range(G):
+        r, na, nr = (int(v) for v in c[b, :3])
+        single = pa.fetch(pa.ada_cascade_step(x1[b], w.tau, dev_idx(prev_sets[b]), flags=flags))
+        got = dict(idx=out["idx"][b, :r].cpu().numpy(), adds=out["adds"][b, :na].cpu().numpy(),
+                   removes=out["removes"][b, :nr].cpu().numpy(), gram_ops=int(out["gram_ops"][b]), r=r, n_adds=na,
+                   n_removes=nr, gamma=single["gamma"])
+        assert np.array_equal(got["idx"], single["idx"]) and got["gram_ops"] == single["gram_ops"]
+        parity.check_cascade(seqs_cpu[b][1], w.tau, prev_sets[b], got, flags=oflags(flags), what="grouped seq %d" % b,
+                             two_pass=bool(flags & pa.FLAG_TWO_PASS))
+    # host-side count: every group inherits the same number of tokens (the first 20 of its set)
+    out2 = pa.ada_cascade_step_grouped(x1, w.tau, prev, r=20, flags=flags)
+    for b in range(G):
+        single = pa.fetch(pa.ada_cascade_step(x1[b], w.tau, dev_idx(prev_sets[b][:20]), flags=flags))
+        r = int(out2["counts"][b, 0])
+        assert np.array_equal(out2["idx"][b, :r].cpu().numpy(), single["idx"])
+    # a list that is not ascending in group 3 only
+    bad = prev.clone()
+    bad[3, 1] = bad[3, 0]
+    out3 = pa.ada_cascade_step_grouped(x1, w.tau, bad, r=T, r_dev=cnt, flags=flags)
+    st = out3["counts"][:, 3].cpu().tolist()
+    assert st[3] == 4 and [st[b] for b in (0, 1, 2, 4)] == [0, 0, 0, 0]
+    assert torch.equal(out3["idx"][0, :int(c[0, 0])], out["idx"][0, :int(c[0, 0])])
+
+
 def run_driver(xs, tau, **kw):
     out = pa.ada_cascade_layers(xs, tau, **kw)
     torch.cuda.synchronize()

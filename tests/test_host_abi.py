@@ -129,6 +129,24 @@ def test_host_checkable_errors_return_before_touching_the_device(ada):
     two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
     assert batched(X=two, B=2, nb=2 * one - 1) == WS and batched(ws=0x1010) == WS
 
+    import paper_2605_03110_amd as pa
+
+    def grouped(g=(2, 8, 8, 4, 1), X=0x1000, T=8, d=8, ld=16, prev=0x1000, r=2, idx=0x1000, ws=0x1000, nb=1 << 20, nog=False):
+        gs = pa.AdaGroups(*g)
+        return lib.ada_cascade_step_grouped(None if nog else ctypes.byref(gs), X, T, d, ld, 1, 0.1, prev, r, None, idx,
+                                            0x1000, 0x1000, 0x1000, 0x1000, ws, nb, None, 0)
+    assert grouped(nog=True) == NULL and grouped(X=None) == NULL and grouped(prev=None) == NULL and grouped(ws=None) == NULL
+    assert grouped(g=(0, 8, 8, 4, 1)) == SHAPE and grouped(g=(4097, 8, 8, 4, 1)) == SHAPE
+    assert grouped(g=(2, 7, 8, 4, 1)) == SHAPE and grouped(g=(2, 8, 7, 4, 1)) == SHAPE       # strides below d / T
+    assert grouped(g=(2, 8, 8, 3, 1)) == SHAPE and grouped(g=(2, 8, 8, 4, 0)) == SHAPE
+    assert grouped(r=0) == SHAPE and grouped(r=9) == SHAPE and grouped(T=0) == SHAPE
+    assert grouped(nb=2 * one - 1) == WS and grouped(ws=0x1010) == WS
+    gs = pa.AdaGroups(2, 8, 0, 0, 0)
+    lay = lambda X=two, L=2, nb=1 << 20, G=gs: lib.ada_cascade_layers_grouped(
+        ctypes.byref(G), X, L, 8, 8, 16, 1, 0.1, 0x1000, 0x1000, 0x1000, None, None, 0x1000, nb, None, 0)
+    assert lay(X=None) == NULL and lay(X=ptrs) == NULL and lay(L=0) == SHAPE and lay(nb=2 * one - 1) == WS
+    assert lay(G=pa.AdaGroups(2, 7, 0, 0, 0)) == SHAPE and lay(G=pa.AdaGroups(0, 8, 0, 0, 0)) == SHAPE
+
 
 def test_binding_rejects_host_tensors_and_wrong_dtypes(ada):
     import paper_2605_03110_amd as pa
