@@ -331,7 +331,56 @@ def main():
         result["batched"] = {"sequences": Bq, "streams": 2, "ms_per_batch_pass": 1e3 * b_elapsed / nb,
                              "layers_per_s": Bq * L * nb / b_elapsed,
                              "tokens_per_s": Bq * L * nb / b_elapsed * T}
-        del seqs, wsb, outb
+        # ---- the same four sequences stacked in one [B, T, d] tensor per layer: one launch per cascade step serves
+        # all of them (ada_cascade_layers_grouped)
+        xg = [torch.stack([seqs[b][l] for b in range(Bq)]) for l in range(L)]
+        del seqs
+        for _ in range(2):
+            pa.ada_cascade_layers_grouped(xg, w.tau, ws=wsb, stream=stream, out=outb)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(nb):
+            pa.ada_cascade_layers_grouped(xg, w.tau, ws=wsb, stream=stream, out=outb)
+        torch.cuda.synchronize()
+        g_elapsed = time.perf_counter() - t0
+        assert torch.equal(outb["counts"][0], out["counts"]), "grouped sequence 0 differs from the single-sequence pass"
+        pa.ada_profile_enable(True)
+        pa.ada_cascade_layers_grouped(xg, w.tau, ws=wsb, stream=stream, out=outb)
+        torch.cuda.synchronize()
+        kg = pa.ada_profile_collect()
+        pa.ada_profile_enable(False)
+        result["batched"]["stacked_one_launch_per_step"] = {
+            "ms_per_batch_pass": 1e3 * g_elapsed / nb, "layers_per_s": Bq * L * nb / g_elapsed,
+            "tokens_per_s": Bq * L * nb / g_elapsed * T,
+            "cascade_launch_us": 1e3 * kg["cascade_fused"]["ms"] / kg["cascade_fused"]["launches"]}
+        del xg
+        # ---- a representative set per head (Section 8.5): the H column blocks of X as H problems in one launch
+        Hh = 16 if d % 16 == 0 else 1
+        hv = [pa.heads_view(x, Hh) for x in xs]
+        wsh = pa.workspace_batched(T, Hh, dev)
+        outh = dict(idx=torch.empty((Hh, L, T), dtype=torch.int32, device=dev),
+                    counts=torch.empty((Hh, L, 4), dtype=torch.int32, device=dev),
+                    gram_ops=torch.empty((Hh, L), dtype=torch.int64, device=dev))
+        for _ in range(2):
+            pa.ada_cascade_layers_grouped(hv, w.tau, ws=wsh, stream=stream, out=outh)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(nb):
+            pa.ada_cascade_layers_grouped(hv, w.tau, ws=wsh, stream=stream, out=outh)
+        torch.cuda.synchronize()
+        h_elapsed = time.perf_counter() - t0
+        pa.ada_profile_enable(True)
+        pa.ada_cascade_layers_grouped(hv, w.tau, ws=wsh, stream=stream, out=outh)
+        torch.cuda.synchronize()
+        kh = pa.ada_profile_collect()
+        pa.ada_profile_enable(False)
+        ch = outh["counts"].cpu()
+        assert ch[:, :, 3].flatten().tolist() == [0] * (Hh * L), "per-head pass reported an error"
+        result["per_head"] = {"heads": Hh, "d_h": d // Hh, "ms_per_pass": 1e3 * h_elapsed / nb,
+                              "layers_per_s": L * nb / h_elapsed,
+                              "cascade_launch_us_all_heads": 1e3 * kh["cascade_fused"]["ms"] / kh["cascade_fused"]["launches"],
+                              "mean_r_h": float(ch[:, 1:, 0].float().mean())}
+        del wsb, outb, hv, wsh, outh
 
         # ---- the same selection at the long-context shape (configs[4]: T=8192, d=4096, one sequence), where the
         # triangle has enough tiles to fill the chip and the kernel is bound by the matrix pipes
