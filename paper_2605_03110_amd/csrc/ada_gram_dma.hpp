@@ -199,6 +199,8 @@ __device__ inline int tri_row(long long v) {
 __global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* queue) {
     extern __shared__ __align__(16) char lds[];
     __shared__ long long s_next;
+    gram_group_offset(p);
+    if (p.ws_gs) queue = reinterpret_cast<int*>(reinterpret_cast<char*>(queue) + (long long)blockIdx.y * p.ws_gs);
     const DmaUnits U(p.T, big_mode);
     const int G = gridDim.x;
     long long u = (long long)(blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);     // first unit: contiguous range per XCD

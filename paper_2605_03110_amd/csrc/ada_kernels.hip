@@ -163,6 +163,16 @@ __device__ inline int block_exclusive_scan(int v, int* total, int* wave_tot /* >
 // ------------------------------------------------------------------------------------------------
 // k_norm_prep: row norms (+ optional cascade preparation in the last workgroup)
 
+// Several problems of one shape in one launch of the full-selection kernels: blockIdx.y is the problem, whose
+// pointers lie g strides after problem 0's (ws: the workspaces, back to back).  All zero: one problem.
+struct GroupOff {
+    long long x;        // bytes between consecutive problems' X
+    long long ws;       // bytes between their workspaces
+    long long list;     // int32 elements between their idx rows
+    long long counts;   // int32 elements between their counts
+    long long ops;      // elements between their gram_ops
+};
+
 struct PrepParams {
     const int32_t* prev_idx;
     const int32_t* r_dev;
@@ -173,9 +183,14 @@ struct PrepParams {
 template <typename In, bool ALIGNED>
 __global__ __launch_bounds__(256) void k_norm_prep(const In* __restrict__ X, long long ld, int T, int d,
                                                    float* __restrict__ inv_norm, float* __restrict__ gamma,
-                                                   Workspace w, PrepParams prep, int n_norm_blocks) {
+                                                   Workspace w, PrepParams prep, int n_norm_blocks, GroupOff go) {
     constexpr int EPP = 16 / (int)sizeof(In);
     __shared__ int sh[32];
+    if (go.ws) {                                             // (the cascade preparation below is not used with groups)
+        X = reinterpret_cast<const In*>(reinterpret_cast<const char*>(X) + (long long)blockIdx.y * go.x);
+        inv_norm = reinterpret_cast<float*>(reinterpret_cast<char*>(inv_norm) + (long long)blockIdx.y * go.ws);
+        gamma = reinterpret_cast<float*>(reinterpret_cast<char*>(gamma) + (long long)blockIdx.y * go.ws);
+    }
     if ((int)blockIdx.x < n_norm_blocks) {
         const int lane = threadIdx.x & 63;
         const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -246,7 +261,16 @@ struct GramParams {
     float thr;
     int mode;
     int order_mask;   // require s < t in token order (always in FULL / REP; CROSS only with the earlier-only flag)
+    long long x_gs, ws_gs;   // MODE_FULL with blockIdx.y = problem: bytes between problems' X / workspaces (0: one problem)
 };
+
+__device__ inline void gram_group_offset(GramParams& p) {
+    if (p.ws_gs) {
+        p.X = reinterpret_cast<const char*>(p.X) + (long long)blockIdx.y * p.x_gs;
+        p.inv_norm = reinterpret_cast<const float*>(reinterpret_cast<const char*>(p.inv_norm) + (long long)blockIdx.y * p.ws_gs);
+        p.gamma = reinterpret_cast<float*>(reinterpret_cast<char*>(p.gamma) + (long long)blockIdx.y * p.ws_gs);
+    }
+}
 
 template <typename In> struct Mfma;
 template <> struct Mfma<uint16_t> {
@@ -501,6 +525,7 @@ __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, cons
 template <typename In, int B, bool ALIGNED>
 __global__ __launch_bounds__(256) void k_gram(GramParams p) {
     extern __shared__ __align__(16) char lds[];
+    gram_group_offset(p);
     int nS, nT;
     const int32_t *listS = nullptr, *listT = nullptr;
     if (p.mode == MODE_FULL) {
@@ -554,11 +579,20 @@ struct UpdateParams {
     int32_t* removes;        // may be NULL
     int32_t* counts;         // [4]
     unsigned long long* gram_ops;   // may be NULL
+    GroupOff go;             // full selection of several problems: blockIdx.x is the problem
 };
 
 __global__ __launch_bounds__(1024) void k_update(UpdateParams u) {
     __shared__ int sh[3][32];
     const int tid = threadIdx.x;
+    if (u.go.ws) {
+        const long long g = blockIdx.x;
+        u.gamma = reinterpret_cast<const float*>(reinterpret_cast<const char*>(u.gamma) + g * u.go.ws);
+        if (u.mask) u.mask += g * (long long)u.T;
+        if (u.idx) u.idx += g * u.go.list;
+        u.counts += g * u.go.counts;
+        if (u.gram_ops) u.gram_ops += g * u.go.ops;
+    }
     const bool full = u.is_rep == nullptr;
     int r_prev = 0;
     if (!full) {
@@ -701,7 +735,7 @@ struct ProfScope {
 template <int B> constexpr int gram_lds_bytes() { return TileGeom<B>::LDS; }
 
 template <typename In, int B, bool ALIGNED>
-hipError_t launch_gram(const GramParams& p, long long tiles_upper, hipStream_t st) {
+hipError_t launch_gram(const GramParams& p, long long tiles_upper, hipStream_t st, int groups = 1) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     constexpr int lds = gram_lds_bytes<B>();
@@ -713,7 +747,7 @@ hipError_t launch_gram(const GramParams& p, long long tiles_upper, hipStream_t s
     if (tiles_upper < 1) return hipSuccess;
     const unsigned grid = (unsigned)((tiles_upper < 65528 ? tiles_upper : 65528) + 7) / 8 * 8;   // multiple of 8 (XCDs)
     ProfScope ps(p.mode == MODE_FULL ? ADA_K_GRAM_FULL : p.mode == MODE_REP ? ADA_K_GRAM_REP : ADA_K_GRAM_CROSS, st);
-    hipLaunchKernelGGL((k_gram<In, B, ALIGNED>), dim3(grid), dim3(256), lds, st, p);
+    hipLaunchKernelGGL((k_gram<In, B, ALIGNED>), dim3(grid, groups), dim3(256), lds, st, p);
     return hipGetLastError();
 }
 
@@ -759,7 +793,7 @@ inline double dma_makespan(int T, int big_mode, int G) {
 }
 
 // mode: 0 = 128 x 128 units everywhere, 1 = 256 x 256 off the diagonal, -1 = whichever hands out better
-hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st) {
+hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st, int groups = 1) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
@@ -767,7 +801,11 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
                                        hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom::LDS);
     });
     if (attr_err != hipSuccess) return attr_err;
-    const int G = device_cus();                                // one workgroup per CU (LDS), whole XCDs
+    int G = device_cus();                                      // one workgroup per CU (LDS), whole XCDs
+    if (groups > 1) {                                          // the problems share the chip; units beyond a problem's
+        G = G / groups / 8 * 8;                                // workgroups are handed out through its queue
+        if (G < 8) G = 8;
+    }
     if (mode < 0) {
         static std::mutex mu;
         static int last_T = 0, last_mode = 0;
@@ -779,7 +817,7 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
         mode = last_mode;
     }
     ProfScope ps(ADA_K_GRAM_FULL, st);
-    hipLaunchKernelGGL(k_gram_dma, dim3(G), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue);
+    hipLaunchKernelGGL(k_gram_dma, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue);
     return hipGetLastError();
 }
 
@@ -787,26 +825,27 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
 // 128-tiles need half the operand traffic per flop but only pay off when they still fill the chip; with sizes
 // known only on the device (exact == false) the 64-tile, which suits every skinny cascade shape, is used.
 template <typename In, bool ALIGNED>
-hipError_t launch_gram_any(const GramParams& p, int nS_upper, int nT_upper, bool exact, hipStream_t st) {
-    int B = (exact && tiles_for(p.mode, nS_upper, nT_upper, 128) >= 192) ? 128 : 64;
+hipError_t launch_gram_any(const GramParams& p, int nS_upper, int nT_upper, bool exact, hipStream_t st, int groups = 1) {
+    int B = (exact && tiles_for(p.mode, nS_upper, nT_upper, 128) * groups >= 192) ? 128 : 64;
     if (int o = tile_override()) B = o;
-    if (B == 128) return launch_gram<In, 128, ALIGNED>(p, tiles_for(p.mode, nS_upper, nT_upper, 128), st);
-    return launch_gram<In, 64, ALIGNED>(p, tiles_for(p.mode, nS_upper, nT_upper, 64), st);
+    if (B == 128) return launch_gram<In, 128, ALIGNED>(p, tiles_for(p.mode, nS_upper, nT_upper, 128), st, groups);
+    return launch_gram<In, 64, ALIGNED>(p, tiles_for(p.mode, nS_upper, nT_upper, 64), st, groups);
 }
 
 template <typename In, bool ALIGNED>
 hipError_t launch_norm_prep(const void* X, long long ld, int T, int d, float* gamma, const Workspace& w,
-                            const PrepParams& prep, hipStream_t st) {
+                            const PrepParams& prep, hipStream_t st, const GroupOff& go = GroupOff{0, 0, 0, 0, 0},
+                            int groups = 1) {
     const int nb = (T + 3) / 4;
     ProfScope ps(ADA_K_NORM_PREP, st);
-    hipLaunchKernelGGL((k_norm_prep<In, ALIGNED>), dim3(nb + (prep.enabled ? 1 : 0)), dim3(256), 0, st,
-                       reinterpret_cast<const In*>(X), ld, T, d, w.inv_norm, gamma, w, prep, nb);
+    hipLaunchKernelGGL((k_norm_prep<In, ALIGNED>), dim3(nb + (prep.enabled ? 1 : 0), groups), dim3(256), 0, st,
+                       reinterpret_cast<const In*>(X), ld, T, d, w.inv_norm, gamma, w, prep, nb, go);
     return hipGetLastError();
 }
 
-int launch_update(const UpdateParams& u, hipStream_t st) {
+int launch_update(const UpdateParams& u, hipStream_t st, int groups = 1) {
     ProfScope ps(ADA_K_UPDATE, st);
-    hipLaunchKernelGGL(k_update, dim3(1), dim3(1024), 0, st, u);
+    hipLaunchKernelGGL(k_update, dim3(groups), dim3(1024), 0, st, u);
     return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
@@ -856,33 +895,38 @@ inline float threshold_of(float tau) { return (float)(1.0 - (double)tau * (doubl
 
 // Definition "Gram threshold": norms, lower-triangular Gram tiles, threshold + compaction.  Arguments checked by the caller.
 int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, uint8_t* mask, int32_t* idx,
-             int32_t* counts, uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st) {
+             int32_t* counts, uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st,
+             int groups = 1, const GroupOff& go = GroupOff{0, 0, 0, 0, 0}) {
+    // groups > 1: that many problems in each of the three launches (go: their strides; gamma must be NULL, so that
+    // every problem's row maxima live in its own workspace)
     const Workspace w = carve(ws, T);
     float* g = gamma ? gamma : w.gamma;
     const float thr = threshold_of(tau);
     const PrepParams prep = {nullptr, nullptr, 0, 0};
-    const GramParams p = {X, ld, T, d, nullptr, nullptr, nullptr, w.inv_norm, g, thr, MODE_FULL, 1};
+    const GramParams p = {X, ld, T, d, nullptr, nullptr, nullptr, w.inv_norm, g, thr, MODE_FULL, 1, go.x, go.ws};
     const char* path_env = getenv("ADA_GRAM");               // development switch: tile, dma0, dma1
     const std::string path = path_env ? path_env : "";
-    hipError_t e = dispatch(dtype, X, ld, d, [&](auto v) {
+    const long long ld_seen = (groups > 1 && go.x % 16 != 0) ? 1 : ld;   // every problem's rows must suit the loader
+    hipError_t e = dispatch(dtype, X, ld_seen, d, [&](auto v) {
         using V = decltype(v);
         using In = typename V::In;
-        hipError_t e1 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st);
+        hipError_t e1 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st, go, groups);
         if (e1 != hipSuccess) return e1;
         if constexpr (V::aligned) {
             if constexpr (sizeof(In) == 2) {
                 // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
-                const bool can = d % DmaGeom::HC == 0;
-                if (can && (path == "dma0" || path == "dma1")) return launch_gram_dma(p, w.meta + META_QUEUE, path == "dma1", st);
-                if (can && path.empty() && T >= 1536) return launch_gram_dma(p, w.meta + META_QUEUE, -1, st);
+                const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
+                if (can && (path == "dma0" || path == "dma1"))
+                    return launch_gram_dma(p, w.meta + META_QUEUE, path == "dma1", st, groups);
+                if (can && path.empty() && T >= 1536) return launch_gram_dma(p, w.meta + META_QUEUE, -1, st, groups);
             }
         }
-        return launch_gram_any<In, V::aligned>(p, T, T, true, st);
+        return launch_gram_any<In, V::aligned>(p, T, T, true, st, groups);
     });
     if (e != hipSuccess) return ADA_ERR_DEVICE;
     const UpdateParams u = {g, nullptr, nullptr, T, thr, mask, idx, nullptr, nullptr, counts,
-                            reinterpret_cast<unsigned long long*>(gram_ops)};
-    return launch_update(u, st);
+                            reinterpret_cast<unsigned long long*>(gram_ops), go};
+    return launch_update(u, st, groups);
 }
 
 hipError_t fill_u32(void* p, size_t n_words, uint32_t v, hipStream_t st) {
@@ -1256,11 +1300,12 @@ int ada_cascade_layers_grouped(const ada_groups* groups, const void* const* X_la
     // the outputs are [G][L][...] blocks, so a group's rows are L rows apart
     const ada_groups g = {groups->G, groups->x_gstride, (int64_t)L * T, (int64_t)L * 4, (int64_t)L};
     const size_t esz = dtype == ADA_BF16 ? 2 : 4;
-    // layer 0: every group's full selection, one after the other
-    for (int i = 0; i < g.G; ++i) {
-        const int e = run_full((const char*)X_layers[0] + (size_t)i * (size_t)g.x_gstride * esz, T, d, ld, dtype, tau, nullptr,
-                               idx_all + (size_t)i * g.list_gstride, counts_all + (size_t)i * g.counts_gstride,
-                               gram_ops_all + (size_t)i * g.ops_gstride, nullptr, (char*)ws + (size_t)i * one, st);
+    // layer 0: every group's full selection in the same three launches
+    {
+        const GroupOff go = {g.G > 1 ? (long long)g.x_gstride * (long long)esz : 0, g.G > 1 ? (long long)one : 0,
+                             g.list_gstride, g.counts_gstride, g.ops_gstride};
+        const int e = run_full(X_layers[0], T, d, ld, dtype, tau, nullptr, idx_all, counts_all, gram_ops_all, nullptr, ws, st,
+                               g.G, go);
         if (e != ADA_OK) return e;
     }
     // layers >= 1: one launch serves all groups
