@@ -238,6 +238,17 @@ int ada_cascade_step_grouped(const ada_groups* groups, const void* X, int T, int
                              void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
+ * The full selection (Definition "Gram threshold") of every group, in the same three launches.
+ *   mask    [G][T] uint8, or NULL
+ *   idx     group g's representatives at idx + g * list_gstride, ascending     (required)
+ *   counts  group g's {r, r, 0, 0} at counts + g * counts_gstride               (required)
+ *   ws      G workspaces back to back (as for ada_cascade_step_grouped)
+ */
+int ada_select_full_grouped(const ada_groups* groups, const void* X, int T, int d, int64_t ld, int dtype, float tau,
+                            uint8_t* mask, int32_t* idx, int32_t* counts,
+                            void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
  * The layer loop for G groups: full selection of every group at layer 0, then one grouped cascade step per layer.
  *   X_layers   HOST array of L device pointers (group 0's matrix of each layer)
  *   outputs    as for ada_cascade_layers_batched with B = G: idx_all [G][L][T], counts_all [G][L][4], ...

@@ -26,7 +26,7 @@ FLAG_ATTN_CAUSAL = 8
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
-           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped",
+           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped",
            "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
            "ada_attention_compressed")
@@ -94,6 +94,8 @@ def lib():
         L.ada_cascade_step_grouped.restype = i32
         L.ada_cascade_step_grouped.argtypes = [ctypes.POINTER(AdaGroups), vp, i32, i32, i64, i32, f32, vp, i32, vp, vp, vp, vp,
                                                vp, vp, vp, sz, vp, u32]
+        L.ada_select_full_grouped.restype = i32
+        L.ada_select_full_grouped.argtypes = [ctypes.POINTER(AdaGroups), vp, i32, i32, i64, i32, f32, vp, vp, vp, vp, sz, vp, u32]
         L.ada_cascade_layers_grouped.restype = i32
         L.ada_cascade_layers_grouped.argtypes = [ctypes.POINTER(AdaGroups), ctypes.POINTER(vp), i32, i32, i32, i64, i32, f32,
                                                  vp, vp, vp, vp, vp, vp, sz, vp, u32]
@@ -368,6 +370,26 @@ def _check_xg(Xg: torch.Tensor):
         raise ValueError("X must live on the GPU")
     if Xg.dim() != 3 or (Xg.shape[2] > 1 and Xg.stride(2) != 1):
         raise ValueError("X must be a [G, T, d] tensor (or view) with unit stride along d")
+
+
+def ada_select_full_grouped(Xg: torch.Tensor, tau: float, *, ws: Optional[torch.Tensor] = None, stream=None,
+                            flags: int = 0) -> Dict[str, torch.Tensor]:
+    """Full selection of G problems in one allocation (Xg: [G, T, d] view).  Returns mask [G, T] u8, idx [G, T] i32,
+    counts [G, 4] i32 (usable as prev_idx / r_dev of ada_cascade_step_grouped)."""
+    _check_xg(Xg)
+    G, T, d = Xg.shape
+    dev = Xg.device
+    ws = workspace_batched(T, G, dev) if ws is None else ws
+    out = dict(mask=torch.empty((G, T), dtype=torch.uint8, device=dev), idx=torch.empty((G, T), dtype=torch.int32, device=dev),
+               counts=torch.empty((G, 4), dtype=torch.int32, device=dev))
+    g = AdaGroups(G, Xg.stride(0) if G > 1 else d, T, 4, 1)
+    rc = lib().ada_select_full_grouped(ctypes.byref(g), _ptr(Xg), T, d, Xg.stride(1), _dtype_code(Xg), float(tau),
+                                       _ptr(out["mask"]), _ptr(out["idx"]), _ptr(out["counts"]), _ptr(ws), ws.numel(),
+                                       _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_select_full_grouped")
+    out["_keep"] = (ws, Xg)
+    return out
 
 
 def ada_cascade_step_grouped(Xg: torch.Tensor, tau: float, prev_idx: torch.Tensor, r: Optional[int] = None,

@@ -1188,6 +1188,24 @@ int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float ta
     return run_full(X, T, d, ld, dtype, tau, mask, idx, count, nullptr, gamma, ws, (hipStream_t)stream);
 }
 
+int ada_select_full_grouped(const ada_groups* groups, const void* X, int T, int d, int64_t ld, int dtype, float tau,
+                            uint8_t* mask, int32_t* idx, int32_t* counts, void* ws, size_t ws_bytes, void* stream,
+                            unsigned flags) {
+    (void)flags;
+    if (!groups || !idx || !counts) return ADA_ERR_NULL;
+    if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
+    const int G = groups->G;
+    if (G < 1 || G > ADA_MAX_BATCH) return ADA_ERR_SHAPE;
+    if (G > 1 && (groups->x_gstride < d || groups->list_gstride < T || groups->counts_gstride < 4)) return ADA_ERR_SHAPE;
+    const size_t one = ws_bytes_for(T);
+    if (ws && ws_bytes / (size_t)G < one) return ADA_ERR_WORKSPACE;
+    if (int e = check_common(X, T, d, ld, dtype, tau, ws, one)) return e;
+    const long long esz = dtype == ADA_BF16 ? 2 : 4;
+    const GroupOff go = {G > 1 ? (long long)groups->x_gstride * esz : 0, G > 1 ? (long long)one : 0, groups->list_gstride,
+                         groups->counts_gstride, 0};
+    return run_full(X, T, d, ld, dtype, tau, mask, idx, counts, nullptr, nullptr, ws, (hipStream_t)stream, G, go);
+}
+
 int ada_attention_compressed(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
                              const int32_t* idx, int r, const int32_t* r_dev, const int32_t* assign, float* out,
                              int64_t ld_out, int32_t* info, void* ws, size_t ws_bytes, void* stream, unsigned flags) {

@@ -460,14 +460,16 @@ def test_grouped_step_on_stacked_sequences(flags):
     seqs_cpu = [wl.layer_list(w, sequence=b) for b in range(G)]
     x0 = torch.stack([s[0] for s in seqs_cpu]).to(DEV)
     x1 = torch.stack([s[1] for s in seqs_cpu]).to(DEV)
-    prev = torch.zeros((G, T), dtype=torch.int32, device=DEV)
-    cnt = torch.zeros((G, 4), dtype=torch.int32, device=DEV)
+    sel = pa.ada_select_full_grouped(x0, w.tau)                 # layer 0 of all sequences in the same launches
+    prev, cnt = sel["idx"], sel["counts"]
     prev_sets = []
     for b in range(G):
         f = pa.fetch(pa.ada_select_full(x0[b], w.tau))
+        parity.check_full(seqs_cpu[b][0], w.tau, f, "stacked seq %d" % b)
+        r = int(cnt[b, 0])
+        assert np.array_equal(prev[b, :r].cpu().numpy(), f["idx"]) and cnt[b].cpu().tolist() == [r, r, 0, 0]
+        assert np.array_equal(sel["mask"][b].cpu().numpy(), f["mask"])
         prev_sets.append(np.asarray(f["idx"]))
-        prev[b, :len(f["idx"])] = dev_idx(f["idx"])
-        cnt[b, 0] = len(f["idx"])
     out = pa.ada_cascade_step_grouped(x1, w.tau, prev, r=T, r_dev=cnt, flags=flags)
     torch.cuda.synchronize()
     c = out["counts"].cpu()

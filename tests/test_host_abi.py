@@ -141,6 +141,11 @@ def test_host_checkable_errors_return_before_touching_the_device(ada):
     assert grouped(g=(2, 8, 8, 3, 1)) == SHAPE and grouped(g=(2, 8, 8, 4, 0)) == SHAPE
     assert grouped(r=0) == SHAPE and grouped(r=9) == SHAPE and grouped(T=0) == SHAPE
     assert grouped(nb=2 * one - 1) == WS and grouped(ws=0x1010) == WS
+    fullg = lambda g=(2, 8, 8, 4, 1), X=0x1000, idx=0x1000, ws=0x1000, nb=1 << 20: lib.ada_select_full_grouped(
+        ctypes.byref(pa.AdaGroups(*g)), X, 8, 8, 16, 1, 0.1, None, idx, 0x1000, ws, nb, None, 0)
+    assert fullg(X=None) == NULL and fullg(idx=None) == NULL and fullg(ws=None) == NULL
+    assert fullg(g=(0, 8, 8, 4, 1)) == SHAPE and fullg(g=(2, 7, 8, 4, 1)) == SHAPE and fullg(g=(2, 8, 8, 3, 1)) == SHAPE
+    assert fullg(nb=2 * one - 1) == WS
     gs = pa.AdaGroups(2, 8, 0, 0, 0)
     lay = lambda X=two, L=2, nb=1 << 20, G=gs: lib.ada_cascade_layers_grouped(
         ctypes.byref(G), X, L, 8, 8, 16, 1, 0.1, 0x1000, 0x1000, 0x1000, None, None, 0x1000, nb, None, 0)
