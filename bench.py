@@ -280,6 +280,9 @@ def main():
 
         # ---- attention on the representative set (eq. (1)) for the last layer's set, 16 heads of d/16, with the
         # hand-over to all T tokens; synthetic Q, K, V
+        # two side streams for everything below that overlaps work (a process has few hardware queues: streams beyond
+        # them share one and serialise, so the same two are used throughout)
+        side = [torch.cuda.Stream() for _ in range(2)]
         Hh = 16
         if d % Hh == 0 and d // Hh in ((64, 128, 256) if w.dtype == "bf16" else (64, 128)):
             qd, kd, vd = (m.to(dev) for m in wl.qkv(w, Hh))
@@ -307,6 +310,31 @@ def main():
                              "frac": att_bytes / (1e-6 * us_t) / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": att_bytes,
                              "mfma_tflops": att_flops / (1e-6 * us_t) / 1e12, "traffic": None}}
 
+            # ---- every layer: selection, assignment, attention on the representative set (Section 8.4's pipeline).
+            # The same synthetic Q, K, V serve all layers; the selection runs on its own stream beside the attention.
+            wsp = pa.workspace_batched(T, 2, dev)
+            two = side
+            pipe = {}
+            for name, sa, sb in (("one_stream", None, None), ("two_streams", two[0], two[1])):
+                po = None
+                for _ in range(2):
+                    po = pa.ada_pipeline_layers(xs, [qd] * L, [kd] * L, [vd] * L, Hh, w.tau, ws=wsp, stream_sel=sa,
+                                                stream_attn=sb, stream=stream, out=po)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                npipe = max(1, args.steps // 4)
+                for _ in range(npipe):
+                    pa.ada_pipeline_layers(xs, [qd] * L, [kd] * L, [vd] * L, Hh, w.tau, ws=wsp, stream_sel=sa,
+                                           stream_attn=sb, stream=stream, out=po)
+                torch.cuda.synchronize()
+                pipe[name] = {"ms_per_pass": 1e3 * (time.perf_counter() - t0) / npipe}
+                pi = po["info"].cpu()
+                assert pi[:, 3].tolist() == [0] * L and pi[:, 7].tolist() == [0] * L, "pipeline reported an error"
+                assert torch.equal(po["counts"], out["counts"]), "pipeline sets differ from the layer loop's"
+            pipe["us_per_layer_two_streams"] = 1e3 * pipe["two_streams"]["ms_per_pass"] / L
+            result["pipeline_select_assign_attend"] = pipe
+            del wsp, po
+
         # ---- four independent sequences of this workload through the batched layer loop (the sequences alternate
         # between two streams, so that one sequence's set update overlaps the other's tiles)
         Bq = 4
@@ -315,7 +343,6 @@ def main():
         outb = dict(idx=torch.empty((Bq, L, T), dtype=torch.int32, device=dev),
                     counts=torch.empty((Bq, L, 4), dtype=torch.int32, device=dev),
                     gram_ops=torch.empty((Bq, L), dtype=torch.int64, device=dev))
-        side = [torch.cuda.Stream() for _ in range(2)]
         use = [side[b % 2] for b in range(Bq)]
         for _ in range(2):
             pa.ada_cascade_layers_batched(seqs, w.tau, ws=wsb, streams=use, stream=stream, out=outb)

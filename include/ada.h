@@ -260,6 +260,31 @@ int ada_cascade_layers_grouped(const ada_groups* groups, const void* const* X_la
                                void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
+ * Selection pipelined against attention (Section 8.4): for every layer l, the selection (full at layer 0,
+ * Algorithm 1 afterwards) runs on stream_sel; the layer's nearest-representative assignment (Section 2.3) and
+ * its attention on the representative set (eq. (1)) run on stream_attn and wait only for that layer's set.  The
+ * selection of layer l+1 needs nothing from the attention of layer l, so the two overlap.
+ *   X_layers, Q_layers, K_layers, V_layers   HOST arrays of L device pointers: T x (H * d_h) matrices, leading
+ *                dimension ld, dtype as usual; the alignment rules of ada_attention_compressed apply to Q, K, V
+ *   idx_all, counts_all, gram_ops_all        as for ada_cascade_layers
+ *   assign_all   device [L*T] int32          row l: the representative of every token at layer l
+ *   info_all     device [L*8] int32          row l: info of ada_assign_nearest, then info of ada_attention_compressed
+ *   out_layers   HOST array of L device pointers: T x (H * d_h) float outputs, leading dimension ld_out
+ *   ws           TWO workspaces back to back (ws_bytes >= 2 * ada_workspace_bytes(T)), both initialised: the two
+ *                streams work at the same time
+ *   stream_sel, stream_attn   HIP streams of default priority; NULL = `stream` (with both NULL, or both the same
+ *                stream, the layers run strictly one step after the other)
+ *   stream       the caller's stream: the pipeline starts after the work enqueued on it before the call; work
+ *                enqueued on it afterwards waits for the whole pipeline (events, no host synchronisation)
+ * flags: ADA_FLAG_CROSS_EARLIER_ONLY, ADA_FLAG_TWO_PASS (selection), ADA_FLAG_ATTN_CAUSAL (attention).
+ */
+int ada_pipeline_layers(const void* const* X_layers, const void* const* Q_layers, const void* const* K_layers,
+                        const void* const* V_layers, int L, int T, int H, int d_h, int64_t ld, int dtype, float tau,
+                        int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all, int32_t* assign_all,
+                        int32_t* info_all, float* const* out_layers, int64_t ld_out,
+                        void* ws, size_t ws_bytes, void* stream_sel, void* stream_attn, void* stream, unsigned flags);
+
+/*
  * |A n B| and |A u B| of two representative sets given as uint8 masks [T] (device), for the
  * Jaccard index of eq. (3).  out: device int32 [2] = {intersection, union}.
  */

@@ -26,7 +26,7 @@ FLAG_ATTN_CAUSAL = 8
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
-           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped",
+           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped", "ada_pipeline_layers",
            "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
            "ada_attention_compressed")
@@ -94,6 +94,9 @@ def lib():
         L.ada_cascade_step_grouped.restype = i32
         L.ada_cascade_step_grouped.argtypes = [ctypes.POINTER(AdaGroups), vp, i32, i32, i64, i32, f32, vp, i32, vp, vp, vp, vp,
                                                vp, vp, vp, sz, vp, u32]
+        L.ada_pipeline_layers.restype = i32
+        L.ada_pipeline_layers.argtypes = [ctypes.POINTER(vp)] * 4 + [i32, i32, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp,
+                                          ctypes.POINTER(vp), i64, vp, sz, vp, vp, vp, u32]
         L.ada_select_full_grouped.restype = i32
         L.ada_select_full_grouped.argtypes = [ctypes.POINTER(AdaGroups), vp, i32, i32, i64, i32, f32, vp, vp, vp, vp, sz, vp, u32]
         L.ada_cascade_layers_grouped.restype = i32
@@ -459,6 +462,45 @@ def ada_cascade_layers_grouped(Xgs: Sequence[torch.Tensor], tau: float, *, want_
     if rc != OK:
         raise AdaError(rc, "ada_cascade_layers_grouped")
     out["_keep"] = (ws, list(Xgs))
+    return out
+
+
+def ada_pipeline_layers(Xs: Sequence[torch.Tensor], Qs: Sequence[torch.Tensor], Ks: Sequence[torch.Tensor],
+                        Vs: Sequence[torch.Tensor], H: int, tau: float, *, ws: Optional[torch.Tensor] = None,
+                        stream_sel=None, stream_attn=None, stream=None, flags: int = 0,
+                        out: Optional[Dict[str, object]] = None) -> Dict[str, object]:
+    """Selection, assignment and attention on the representative set for L layers, the selection on stream_sel and
+    the rest on stream_attn (torch streams; None = `stream`).  Returns idx[L,T], counts[L,4], gram_ops[L],
+    assign[L,T], info[L,8] and out (a list of L float tensors T x d)."""
+    L = len(Xs)
+    if L < 1 or not (len(Qs) == len(Ks) == len(Vs) == L):
+        raise ValueError("need the same number (>= 1) of X, Q, K and V matrices")
+    X0 = Xs[0]
+    for M in list(Xs) + list(Qs) + list(Ks) + list(Vs):
+        _check_x(M)
+        if M.shape != X0.shape or M.dtype != X0.dtype or M.stride(0) != X0.stride(0) or M.device != X0.device:
+            raise ValueError("all matrices must share shape, dtype, leading dimension and device")
+    T, d = X0.shape
+    if d % H != 0:
+        raise ValueError("d must be a multiple of the head count")
+    dev = X0.device
+    ws = workspace_batched(T, 2, dev) if ws is None else ws
+    if out is None:
+        out = dict(idx=torch.empty((L, T), dtype=torch.int32, device=dev),
+                   counts=torch.empty((L, 4), dtype=torch.int32, device=dev),
+                   gram_ops=torch.empty(L, dtype=torch.int64, device=dev),
+                   assign=torch.empty((L, T), dtype=torch.int32, device=dev),
+                   info=torch.empty((L, 8), dtype=torch.int32, device=dev),
+                   out=[torch.empty((T, d), dtype=torch.float32, device=dev) for _ in range(L)])
+    arr = lambda ms: (ctypes.c_void_p * L)(*[m.data_ptr() for m in ms])
+    sp = lambda s_: None if s_ is None else ctypes.c_void_p(s_.cuda_stream)
+    rc = lib().ada_pipeline_layers(arr(Xs), arr(Qs), arr(Ks), arr(Vs), L, T, H, d // H, X0.stride(0), _dtype_code(X0),
+                                   float(tau), _ptr(out["idx"]), _ptr(out["counts"]), _ptr(out["gram_ops"]),
+                                   _ptr(out["assign"]), _ptr(out["info"]), arr(out["out"]), out["out"][0].stride(0),
+                                   _ptr(ws), ws.numel(), sp(stream_sel), sp(stream_attn), _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_pipeline_layers")
+    out["_keep"] = (ws, list(Xs), list(Qs), list(Ks), list(Vs), stream_sel, stream_attn)
     return out
 
 

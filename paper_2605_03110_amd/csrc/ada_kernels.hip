@@ -1424,6 +1424,67 @@ int ada_cascade_layers_batched(const void* const* X_layers, int B, int L, int T,
     return rc;
 }
 
+int ada_pipeline_layers(const void* const* X_layers, const void* const* Q_layers, const void* const* K_layers,
+                        const void* const* V_layers, int L, int T, int H, int d_h, int64_t ld, int dtype, float tau,
+                        int32_t* idx_all, int32_t* counts_all, uint64_t* gram_ops_all, int32_t* assign_all,
+                        int32_t* info_all, float* const* out_layers, int64_t ld_out, void* ws, size_t ws_bytes,
+                        void* stream_sel, void* stream_attn, void* stream, unsigned flags) {
+    if (!X_layers || !Q_layers || !K_layers || !V_layers || !out_layers) return ADA_ERR_NULL;
+    if (!idx_all || !counts_all || !gram_ops_all || !assign_all || !info_all || !ws) return ADA_ERR_NULL;
+    if (L < 1 || H < 1 || H > 65535 || d_h < 1 || d_h > (1 << 20)) return ADA_ERR_SHAPE;
+    const int64_t D64 = (int64_t)H * d_h;
+    if (D64 > (1 << 24)) return ADA_ERR_SHAPE;
+    const int d = (int)D64;
+    for (int l = 0; l < L; ++l)
+        if (!X_layers[l] || !Q_layers[l] || !K_layers[l] || !V_layers[l] || !out_layers[l]) return ADA_ERR_NULL;
+    if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
+    const size_t one = ws_bytes_for(T);
+    if (ws_bytes / 2 < one) return ADA_ERR_WORKSPACE;
+    if (int e = check_common(X_layers[0], T, d, ld, dtype, tau, ws, one)) return e;
+    void* ws_attn = (char*)ws + one;
+    hipStream_t main = (hipStream_t)stream;
+    hipStream_t ss = stream_sel ? (hipStream_t)stream_sel : main, sa = stream_attn ? (hipStream_t)stream_attn : main;
+    // the attention-side calls check their own arguments; run those checks before anything is enqueued
+    if (ld_out < D64 || ((int64_t)ld * (dtype == ADA_BF16 ? 2 : 4)) % 16 != 0) return ADA_ERR_SHAPE;
+    const bool dh_ok = dtype == ADA_BF16 ? (d_h == 64 || d_h == 128 || d_h == 256) : (d_h == 64 || d_h == 128);
+    if (!dh_ok) return ADA_ERR_SHAPE;
+    for (int l = 0; l < L; ++l)
+        if ((uintptr_t)Q_layers[l] % 16 || (uintptr_t)K_layers[l] % 16 || (uintptr_t)V_layers[l] % 16) return ADA_ERR_SHAPE;
+
+    auto fork = [&](hipStream_t from, hipStream_t to) -> bool {   // `to` continues after what `from` holds now
+        if (from == to) return true;
+        hipEvent_t ev = nullptr;
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return false;
+        const bool ok = hipEventRecord(ev, from) == hipSuccess && hipStreamWaitEvent(to, ev, 0) == hipSuccess;
+        (void)hipEventDestroy(ev);                               // released by the runtime once it has completed
+        return ok;
+    };
+    if (!fork(main, ss) || !fork(main, sa)) return ADA_ERR_DEVICE;
+    int rc = ADA_OK;
+    for (int l = 0; l < L && rc == ADA_OK; ++l) {
+        const size_t o = (size_t)l * (size_t)T;
+        // selection of layer l (Section 4.1): needs only the previous layer's set
+        if (l == 0)
+            rc = run_full(X_layers[0], T, d, ld, dtype, tau, nullptr, idx_all, counts_all, gram_ops_all, nullptr, ws, ss);
+        else
+            rc = run_cascade(X_layers[l], T, d, ld, dtype, tau, idx_all + o - T, T, counts_all + (size_t)(l - 1) * 4,
+                             idx_all + o, nullptr, nullptr, counts_all + (size_t)l * 4, gram_ops_all + l, nullptr, ws, ss,
+                             flags & (ADA_FLAG_CROSS_EARLIER_ONLY | ADA_FLAG_TWO_PASS));
+        if (rc != ADA_OK) break;
+        // layer l's assignment and attention wait for that set only; the selection stream goes on to layer l + 1
+        if (!fork(ss, sa)) { rc = ADA_ERR_DEVICE; break; }
+        rc = ada_assign_nearest(X_layers[l], T, d, ld, dtype, idx_all + o, T, counts_all + (size_t)l * 4, assign_all + o,
+                                nullptr, info_all + (size_t)l * 8, ws_attn, one, sa, 0);
+        if (rc != ADA_OK) break;
+        rc = ada_attention_compressed(Q_layers[l], K_layers[l], V_layers[l], T, H, d_h, ld, dtype, idx_all + o, T,
+                                      counts_all + (size_t)l * 4, assign_all + o, out_layers[l], ld_out,
+                                      info_all + (size_t)l * 8 + 4, ws_attn, one, sa, flags & ADA_FLAG_ATTN_CAUSAL);
+    }
+    // join: work enqueued on `stream` after the call sees everything (also after an error part-way)
+    if (!fork(ss, main) || !fork(sa, main)) return ADA_ERR_DEVICE;
+    return rc;
+}
+
 int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t* out, void* stream) {
     if (!mask_a || !mask_b || !out) return ADA_ERR_NULL;
     if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;

@@ -498,6 +498,87 @@ def test_grouped_step_on_stacked_sequences(flags):
     assert torch.equal(out3["idx"][0, :int(c[0, 0])], out["idx"][0, :int(c[0, 0])])
 
 
+def test_layer_loop_replays_from_a_hip_graph():
+    """The layer loop enqueues kernels only (flags and counters are cleared by kernels, never by memset nodes), so a
+    stream capture of it replays: three replays with eager work and synchronisation in between, each compared with
+    the eager result; then new activations are copied into the captured buffers and the replay follows them."""
+    say("HIP graph replay of ada_cascade_layers")
+    w = wl.small(T=700, d=256, K=90, L=5, dtype="bf16", seed=131, p=0.1)
+    xs = [x.to(DEV) for x in wl.layer_list(w)]
+    other = [x.to(DEV) for x in wl.layer_list(w, sequence=1)]
+    ws = pa.workspace(w.T, DEV)
+    out = dict(idx=torch.zeros((w.L, w.T), dtype=torch.int32, device=DEV),
+               counts=torch.zeros((w.L, 4), dtype=torch.int32, device=DEV),
+               gram_ops=torch.zeros(w.L, dtype=torch.int64, device=DEV))
+    eager = run_driver(xs, w.tau, want_lists=False)
+    eager_other = run_driver(other, w.tau, want_lists=False)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                # warm-up outside the capture (one-time attribute calls)
+        pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out)
+
+    def same(a):
+        c = out["counts"].cpu()
+        assert torch.equal(c, a["counts"].cpu()) and torch.equal(out["gram_ops"], a["gram_ops"])
+        for l in range(w.L):
+            assert torch.equal(out["idx"][l, :int(c[l, 0])], a["idx"][l, :int(c[l, 0])])
+
+    for rep in range(3):
+        out["counts"].zero_()
+        out["idx"].zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        same(eager)
+        run_driver(other, w.tau, want_lists=False)               # eager work of the library between replays
+    for x, y in zip(xs, other):
+        x.copy_(y)
+    graph.replay()
+    torch.cuda.synchronize()
+    same(eager_other)
+
+
+@pytest.mark.parametrize("T,H,dh,K,L,dtype", [(600, 4, 64, 70, 4, "bf16"), (333, 2, 64, 40, 3, "f32"), (1500, 3, 128, 200, 3, "bf16")])
+def test_selection_pipelined_against_attention(T, H, dh, K, L, dtype):
+    """ada_pipeline_layers on two streams and on one: sets, assignment and attention output of every layer equal
+    those of the single calls (same kernels: bit-exact), and the attention output is checked against the oracle on
+    the set and assignment the layer used."""
+    d = H * dh
+    say("pipeline T=%d H=%d d_h=%d L=%d %s" % (T, H, dh, L, dtype))
+    w = wl.small(T=T, d=d, K=K, L=L, dtype=dtype, seed=151 + T, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    qkv_cpu = [wl.qkv(w, H, layer=l) for l in range(L)]
+    xs = [x.to(DEV) for x in xs_cpu]
+    qs, ks, vs = ([t[i].to(DEV) for t in qkv_cpu] for i in range(3))
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    chain = run_driver(xs, w.tau, want_lists=False)
+    cc = chain["counts"].cpu()
+    for streams in ((s1, s2), (None, None), (s1, s1)):
+        res = pa.ada_pipeline_layers(xs, qs, ks, vs, H, w.tau, stream_sel=streams[0], stream_attn=streams[1])
+        counts = res["counts"].cpu()                              # on the caller's stream: joined with both
+        info = res["info"].cpu()
+        assert torch.equal(counts, cc) and torch.equal(res["gram_ops"], chain["gram_ops"])
+        assert info[:, 3].tolist() == [0] * L and info[:, 7].tolist() == [0] * L
+        for l in range(L):
+            r = int(counts[l, 0])
+            idx = res["idx"][l, :r]
+            assert torch.equal(idx, chain["idx"][l, :r])
+            near = pa.ada_assign_nearest(xs[l], idx.contiguous())
+            assert torch.equal(near["assign"], res["assign"][l])
+            att = pa.ada_attention_compressed(qs[l], ks[l], vs[l], H, idx.contiguous(), near["assign"])
+            assert torch.equal(att["out"], res["out"][l])
+            assert int(info[l, 0]) == T - r and int(info[l, 4]) == r
+    for l in (0, L - 1):
+        r = int(counts[l, 0])
+        parity.check_attention(qkv_cpu[l][0], qkv_cpu[l][1], qkv_cpu[l][2], H, res["idx"][l, :r].cpu().numpy(),
+                               res["assign"][l].cpu().numpy(), res["out"][l].cpu().numpy(), what="pipeline layer %d" % l)
+
+
 def run_driver(xs, tau, **kw):
     out = pa.ada_cascade_layers(xs, tau, **kw)
     torch.cuda.synchronize()

@@ -152,6 +152,20 @@ def test_host_checkable_errors_return_before_touching_the_device(ada):
     assert lay(X=None) == NULL and lay(X=ptrs) == NULL and lay(L=0) == SHAPE and lay(nb=2 * one - 1) == WS
     assert lay(G=pa.AdaGroups(2, 7, 0, 0, 0)) == SHAPE and lay(G=pa.AdaGroups(0, 8, 0, 0, 0)) == SHAPE
 
+    good = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    outs = (ctypes.c_void_p * 2)(0x3000, 0x4000)
+
+    def pipe(X=good, Q=good, outp=outs, L=2, T=8, H=2, dh=64, ld=128, dtype=1, idx=0x1000, ldo=128, ws=0x1000, nb=1 << 20):
+        return lib.ada_pipeline_layers(X, Q, good, good, L, T, H, dh, ld, dtype, 0.1, idx, 0x1000, 0x1000, 0x1000, 0x1000,
+                                       outp, ldo, ws, nb, None, None, None, 0)
+    assert pipe(X=None) == NULL and pipe(Q=ptrs) == NULL and pipe(outp=None) == NULL and pipe(idx=None) == NULL
+    assert pipe(ws=None) == NULL
+    assert pipe(L=0) == SHAPE and pipe(H=0) == SHAPE and pipe(dh=48) == SHAPE and pipe(ld=64) == SHAPE and pipe(ldo=64) == SHAPE
+    assert pipe(T=0) == SHAPE and pipe(dtype=5) == DTYPE
+    assert pipe(nb=2 * lib.ada_workspace_bytes(8) - 1) == WS and pipe(ws=0x1010) == WS
+    odd = (ctypes.c_void_p * 2)(0x1000, 0x2008)
+    assert pipe(Q=odd) == SHAPE
+
 
 def test_binding_rejects_host_tensors_and_wrong_dtypes(ada):
     import paper_2605_03110_amd as pa
