@@ -409,6 +409,22 @@ def main():
                               "mean_r_h": float(ch[:, 1:, 0].float().mean())}
         del wsb, outb, hv, wsh, outh
 
+        # ---- the greedy covering of Section 2.5 on layer 0 (pair bits from the register-staged Gram tiles, then the
+        # sequential resolution by one workgroup)
+        if T <= 16384:
+            for _ in range(2):
+                gsel = pa.ada_select_full(xs[0], w.tau, ws=ws, stream=stream, flags=pa.FLAG_GREEDY_COVER)
+            torch.cuda.synchronize()
+            pa.ada_profile_enable(True)
+            for _ in range(5):
+                gsel = pa.ada_select_full(xs[0], w.tau, ws=ws, stream=stream, flags=pa.FLAG_GREEDY_COVER)
+            torch.cuda.synchronize()
+            kgr = pa.ada_profile_collect()
+            pa.ada_profile_enable(False)
+            result["greedy_cover"] = {"r": int(gsel["counts"][0]),
+                                      "gram_us": 1e3 * kgr["gram_full"]["ms"] / kgr["gram_full"]["launches"],
+                                      "resolve_us": 1e3 * kgr["update"]["ms"] / kgr["update"]["launches"]}
+
         # ---- the same selection at the long-context shape (configs[4]: T=8192, d=4096, one sequence), where the
         # triangle has enough tiles to fill the chip and the kernel is bound by the matrix pipes
         w4 = wl.config(4)

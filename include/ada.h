@@ -66,6 +66,13 @@ typedef enum {
                                           not later than itself in the sequence (eq. (1) prints no mask; the decoder-only
                                           models of Section 6 have one) */
 
+#define ADA_FLAG_GREEDY_COVER 16u       /* ada_select_full: the greedy covering of Section 2.5 instead of the Definition: token t
+                                          is a representative iff no earlier REPRESENTATIVE s has |G_st| >= 1 - tau^2 (the
+                                          Definition compares with all earlier tokens; the two differ exactly on chains
+                                          a ~ b ~ c with a not ~ c).  The decisions are sequential in t: the Gram tiles leave one
+                                          bit per pair s < t, and one workgroup resolves them in token order.  T <= 16384.
+                                          The gamma output is still the Definition's (max over ALL earlier tokens) */
+
 #define ADA_MAX_T (1 << 20)
 #define ADA_MAX_BATCH 4096
 

@@ -23,6 +23,7 @@ FLAG_CROSS_EARLIER_ONLY = 1
 FLAG_TWO_PASS = 2
 FLAG_RESIDENT_PASS = 4
 FLAG_ATTN_CAUSAL = 8
+FLAG_GREEDY_COVER = 16
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",

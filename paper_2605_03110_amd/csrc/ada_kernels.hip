@@ -262,6 +262,8 @@ struct GramParams {
     int mode;
     int order_mask;   // require s < t in token order (always in FULL / REP; CROSS only with the earlier-only flag)
     long long x_gs, ws_gs;   // MODE_FULL with blockIdx.y = problem: bytes between problems' X / workspaces (0: one problem)
+    uint32_t* hits;          // MODE_FULL, optional: word-major bit table, bit (s mod 32) of hits[(s div 32) * T + t] =
+                             // "|G_st| >= threshold and s < t" (the greedy covering of Section 2.5 is resolved from it)
 };
 
 __device__ inline void gram_group_offset(GramParams& p) {
@@ -331,6 +333,23 @@ __device__ inline void publish_max(float m, float tscale, int ttok, int half, ui
     m = fmaxf(m, __shfl_xor(m, 32, 64));                       // the two lane halves hold different s rows
     // non-negative floats order like their bit patterns, so an integer atomicMax is an exact, order-independent max
     if (half == 0 && ttok >= 0 && m > 0.f) atomicMax(gamma_bits + ttok, __float_as_uint(m));
+}
+
+// The threshold test of one 32 x 32 block for tested token ttok, bit = "against" row within the block; the products are
+// rounded exactly as for the row maximum ((|acc| * scale_s) * scale_t), so bits and maxima never disagree.
+__device__ inline void publish_hits(const f32x16& v, const float* s_scale, const int* s_tok, int s_row0, int half,
+                                    bool need_order, int ttok, float tscale, float thr, uint32_t* hits, int T, int s_glob0) {
+    uint32_t bits = 0u;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r32 = (i & 3) + 4 * half + 8 * (i >> 2);
+        const int sl = s_row0 + r32;
+        float x = (fabsf(v[i]) * s_scale[sl]) * tscale;
+        if (need_order && !(s_tok[sl] < ttok)) x = 0.f;
+        if (x >= thr) bits |= 1u << r32;
+    }
+    bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
+    if (half == 0 && ttok >= 0) hits[(size_t)(s_glob0 >> 5) * (size_t)T + ttok] = bits;
 }
 
 template <typename In, int B, bool ALIGNED>
@@ -505,6 +524,8 @@ __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, cons
         const int ttok = t_tok[nl];
         const float m = block_max(tot, s_scale, s_tok, a * 32, half, need_order, ttok);
         publish_max(m, t_scale[nl], ttok, half, gamma_bits);
+        if (p.hits)
+            publish_hits(tot, s_scale, s_tok, a * 32, half, need_order, ttok, t_scale[nl], p.thr, p.hits, p.T, s0 + a * 32);
     } else {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
@@ -515,6 +536,12 @@ __device__ inline void gram_tile(const GramParams& p, const int32_t* listS, cons
             for (int a = 0; a < NB; ++a)
                 m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WB + a * 32, half, need_order, ttok));
             publish_max(m, t_scale[nl], ttok, half, gamma_bits);
+            if (p.hits) {
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+                    publish_hits(acc[a][b], s_scale, s_tok, ws * WB + a * 32, half, need_order, ttok, t_scale[nl], p.thr,
+                                 p.hits, p.T, s0 + ws * WB + a * 32);
+            }
         }
     }
 }
@@ -732,6 +759,113 @@ struct ProfScope {
     }
 };
 
+// ------------------------------------------------------------------------------------------------
+// k_greedy_resolve: the greedy covering of Section 2.5 from the bit table of the full Gram.
+//   token t is a representative iff no EARLIER REPRESENTATIVE s has |G_st| >= threshold.
+// The decision of token t needs the decisions of all s < t, so one workgroup walks the tokens in blocks of 64:
+//   inside a block, wave 0 decides the 64 tokens one after the other with scalar bit operations (the block's own
+//   two words of every token hold its earlier hits inside the block);
+//   then every thread pushes the block's new representatives to the later tokens it owns: token t' is covered as
+//   soon as one of its two words for this block meets the block's representative bits.
+// The words of block b + 1 are requested before block b is decided (they do not depend on it), so the trips to
+// memory overlap the serial part.  covered[] lives in LDS (T <= FUSED_MAX_T bytes).
+struct GreedyParams {
+    const uint32_t* hits;    // [words][T]
+    int T;
+    uint8_t* mask;           // [T], may be NULL
+    int32_t* idx;            // [T], may be NULL
+    int32_t* counts;         // [4] = {r, r, 0, 0}
+    unsigned long long* gram_ops;   // may be NULL
+};
+
+constexpr int GREEDY_THREADS = 1024;
+
+// TPT: tokens a thread owns (T <= TPT * 1024); AHEAD: how many blocks ahead of the decisions the words are requested
+// (registers: 2 * TPT * (AHEAD + 1) words per thread; the deeper ring of the small shapes hides a trip to memory
+// behind several blocks' decisions, which take well under a microsecond each)
+template <int TPT, int AHEAD>
+__global__ __launch_bounds__(GREEDY_THREADS) void k_greedy_resolve(GreedyParams g) {
+    __shared__ uint8_t covered[TPT * GREEDY_THREADS];
+    __shared__ uint32_t repw[TPT * GREEDY_THREADS / 32];
+    __shared__ uint32_t own_lo[64], own_hi[64];
+    __shared__ int sh[32];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int T = g.T, nblk = (T + 63) >> 6;
+    for (int t = tid; t < T; t += GREEDY_THREADS) covered[t] = 0;
+    for (int w = tid; w < 2 * nblk; w += GREEDY_THREADS) repw[w] = 0u;
+    __syncthreads();
+    // This thread owns tokens tid, tid + 1024, ...; ring[k]: their two words for block (current + k).  Addresses are
+    // clamped and the values masked where they are USED, so nothing waits at the load.
+    uint32_t lo[AHEAD + 1][TPT], hi[AHEAD + 1][TPT];
+    auto fetch = [&](int b, uint32_t (&a)[TPT], uint32_t (&c)[TPT]) {
+        const int bc = b < nblk ? b : nblk - 1;
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) {
+            const int t = tid + j * GREEDY_THREADS;
+            const int tc = t < T ? t : 0;
+            a[j] = g.hits[(size_t)(2 * bc) * T + tc];
+            c[j] = g.hits[(size_t)(2 * bc + 1) * T + tc];
+        }
+    };
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k) fetch(k, lo[k], hi[k]);
+    for (int b = 0; b < nblk; ++b) {
+        fetch(b + AHEAD, lo[AHEAD], hi[AHEAD]);              // in flight while this and the next blocks are decided
+        // hand the block's own words to wave 0 through LDS (token 64 b + l is owned by thread (64 b + l) % 1024)
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) {
+            const int t = tid + j * GREEDY_THREADS;
+            if ((t >> 6) == b && t < T) { own_lo[t & 63] = lo[0][j]; own_hi[t & 63] = hi[0][j]; }
+        }
+        __syncthreads();
+        if (tid < 64) {                                      // wave 0: the block's decisions, in token order
+            const int t = 64 * b + lane;
+            const bool exists = t < T;
+            const uint32_t mlo = exists ? own_lo[lane] : 0u, mhi = exists ? own_hi[lane] : 0u;
+            // tokens no earlier block's representative covers; only these can become representatives
+            unsigned long long cand = __ballot(exists && covered[exists ? t : 0] == 0);
+            unsigned long long rep = 0ull;
+            while (cand) {                                   // scalar loop over the candidates
+                const int i = __builtin_amdgcn_readfirstlane((int)__ffsll((long long)cand) - 1);
+                cand &= cand - 1;
+                const unsigned long long h = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)mhi, i) << 32) |
+                                             (unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)mlo, i);
+                if (!(h & rep)) rep |= 1ull << i;            // no earlier representative of this block is within tau
+            }
+            if (lane == 0) { repw[2 * b] = (uint32_t)rep; repw[2 * b + 1] = (uint32_t)(rep >> 32); }
+        }
+        __syncthreads();
+        const uint32_t rlo = repw[2 * b], rhi = repw[2 * b + 1];
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) {                      // push: later tokens hit by one of the new representatives
+            const int t = tid + j * GREEDY_THREADS;
+            if (t < T && (t >> 6) > b && ((lo[0][j] & rlo) | (hi[0][j] & rhi))) covered[t] = 1;
+        }
+#pragma unroll
+        for (int k = 0; k < AHEAD; ++k)
+#pragma unroll
+            for (int j = 0; j < TPT; ++j) { lo[k][j] = lo[k + 1][j]; hi[k][j] = hi[k + 1][j]; }
+        __syncthreads();
+    }
+    // representatives -> mask, ascending index list, count
+    const int chunk = (T + GREEDY_THREADS - 1) / GREEDY_THREADS;
+    const int t_lo = min(T, tid * chunk), t_hi = min(T, t_lo + chunk);
+    int c = 0;
+    for (int t = t_lo; t < t_hi; ++t) c += (repw[t >> 5] >> (t & 31)) & 1u;
+    int total;
+    int off = block_exclusive_scan(c, &total, sh);
+    for (int t = t_lo; t < t_hi; ++t) {
+        const int is = (repw[t >> 5] >> (t & 31)) & 1u;
+        if (g.mask) g.mask[t] = (uint8_t)is;
+        if (is && g.idx) g.idx[off] = t;
+        off += is;
+    }
+    if (tid == 0) {
+        g.counts[0] = total; g.counts[1] = total; g.counts[2] = 0; g.counts[3] = ADA_OK;
+        if (g.gram_ops) *g.gram_ops = (unsigned long long)T * (unsigned long long)T;
+    }
+}
+
 template <int B> constexpr int gram_lds_bytes() { return TileGeom<B>::LDS; }
 
 template <typename In, int B, bool ALIGNED>
@@ -896,14 +1030,17 @@ inline float threshold_of(float tau) { return (float)(1.0 - (double)tau * (doubl
 // Definition "Gram threshold": norms, lower-triangular Gram tiles, threshold + compaction.  Arguments checked by the caller.
 int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, uint8_t* mask, int32_t* idx,
              int32_t* counts, uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st,
-             int groups = 1, const GroupOff& go = GroupOff{0, 0, 0, 0, 0}) {
+             int groups = 1, const GroupOff& go = GroupOff{0, 0, 0, 0, 0}, bool greedy = false) {
     // groups > 1: that many problems in each of the three launches (go: their strides; gamma must be NULL, so that
     // every problem's row maxima live in its own workspace)
     const Workspace w = carve(ws, T);
     float* g = gamma ? gamma : w.gamma;
     const float thr = threshold_of(tau);
     const PrepParams prep = {nullptr, nullptr, 0, 0};
-    const GramParams p = {X, ld, T, d, nullptr, nullptr, nullptr, w.inv_norm, g, thr, MODE_FULL, 1, go.x, go.ws};
+    // greedy covering (Section 2.5): the tiles also leave the threshold bits of every pair s < t, and the set is
+    // resolved from them in token order (one problem, T <= FUSED_MAX_T: checked by the caller)
+    const GramParams p = {X, ld, T, d, nullptr, nullptr, nullptr, w.inv_norm, g, thr, MODE_FULL, 1, go.x, go.ws,
+                          greedy ? w.hits : nullptr};
     const char* path_env = getenv("ADA_GRAM");               // development switch: tile, dma0, dma1
     const std::string path = path_env ? path_env : "";
     const long long ld_seen = (groups > 1 && go.x % 16 != 0) ? 1 : ld;   // every problem's rows must suit the loader
@@ -914,8 +1051,8 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
         if (e1 != hipSuccess) return e1;
         if constexpr (V::aligned) {
             if constexpr (sizeof(In) == 2) {
-                // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
-                const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
+                // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel (it keeps row maxima only)
+                const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0 && !greedy;
                 if (can && (path == "dma0" || path == "dma1"))
                     return launch_gram_dma(p, w.meta + META_QUEUE, path == "dma1", st, groups);
                 if (can && path.empty() && T >= 1536) return launch_gram_dma(p, w.meta + META_QUEUE, -1, st, groups);
@@ -924,6 +1061,14 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
         return launch_gram_any<In, V::aligned>(p, T, T, true, st, groups);
     });
     if (e != hipSuccess) return ADA_ERR_DEVICE;
+    if (greedy) {
+        const GreedyParams gp = {w.hits, T, mask, idx, counts, reinterpret_cast<unsigned long long*>(gram_ops)};
+        ProfScope ps(ADA_K_UPDATE, st);
+        if (T <= 2 * GREEDY_THREADS) hipLaunchKernelGGL((k_greedy_resolve<2, 4>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
+        else if (T <= 4 * GREEDY_THREADS) hipLaunchKernelGGL((k_greedy_resolve<4, 3>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
+        else hipLaunchKernelGGL((k_greedy_resolve<FUSED_MAX_T / GREEDY_THREADS, 1>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
+        return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+    }
     const UpdateParams u = {g, nullptr, nullptr, T, thr, mask, idx, nullptr, nullptr, counts,
                             reinterpret_cast<unsigned long long*>(gram_ops), go};
     return launch_update(u, st, groups);
@@ -1182,10 +1327,12 @@ int ada_workspace_init(void* ws, size_t ws_bytes, void* stream) {
 
 int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float tau, uint8_t* mask, int32_t* idx,
                     int32_t* count, float* gamma, void* ws, size_t ws_bytes, void* stream, unsigned flags) {
-    (void)flags;
     if (!mask || !count) return ADA_ERR_NULL;
     if (int e = check_common(X, T, d, ld, dtype, tau, ws, ws_bytes)) return e;
-    return run_full(X, T, d, ld, dtype, tau, mask, idx, count, nullptr, gamma, ws, (hipStream_t)stream);
+    const bool greedy = (flags & ADA_FLAG_GREEDY_COVER) != 0;
+    if (greedy && T > FUSED_MAX_T) return ADA_ERR_SHAPE;     // the pair bits live in the workspace's hit table
+    return run_full(X, T, d, ld, dtype, tau, mask, idx, count, nullptr, gamma, ws, (hipStream_t)stream, 1,
+                    GroupOff{0, 0, 0, 0, 0}, greedy);
 }
 
 int ada_select_full_grouped(const ada_groups* groups, const void* X, int T, int d, int64_t ld, int dtype, float tau,

@@ -579,6 +579,64 @@ def test_selection_pipelined_against_attention(T, H, dh, K, L, dtype):
                                res["assign"][l].cpu().numpy(), res["out"][l].cpu().numpy(), what="pipeline layer %d" % l)
 
 
+def greedy_reference(x_cpu, tau, got_mask):
+    """The oracle's greedy covering with the decisions of band tokens (oracle gamma within the band of the threshold)
+    taken from the GPU; repeated until no new band token appears, because a forced decision changes which earlier
+    representatives later tokens are compared with."""
+    X = wl.as_f64(x_cpu)
+    T = X.shape[0]
+    force = -np.ones(T, dtype=np.int8)
+    for _ in range(8):
+        ref = oracle.select_full(X, tau, greedy=True, force=force)
+        band = (np.abs(ref["gamma"] - parity.thr_of(tau)) < parity.BAND) & (force < 0)
+        if not band.any():
+            return ref
+        force[band] = got_mask[band]
+    raise AssertionError("band tokens keep appearing")
+
+
+def chain_rows(T, d, seed):
+    """Unit vectors in a plane embedded in d dimensions, at angles that form long chains (each token within the
+    threshold of its neighbours but not of tokens further away), in shuffled order, plus exact duplicates."""
+    rng = np.random.default_rng(seed)
+    ang = rng.uniform(0, np.pi, size=T)
+    ang[rng.integers(0, T, size=T // 10)] = ang[rng.integers(0, T, size=T // 10)]
+    basis = np.linalg.qr(rng.standard_normal((d, 2)))[0]
+    X = (np.cos(ang)[:, None] * basis[:, 0] + np.sin(ang)[:, None] * basis[:, 1]) * rng.uniform(0.5, 2.0, size=(T, 1))
+    return X
+
+
+@pytest.mark.parametrize("T,d,dtype", [(1, 64, "bf16"), (64, 32, "f32"), (130, 64, "bf16"), (333, 96, "f32"), (700, 256, "bf16"),
+                                       (1290, 128, "bf16"), (2048, 64, "bf16"), (3000, 32, "bf16")])
+def test_greedy_covering_selection(T, d, dtype):
+    """ADA_FLAG_GREEDY_COVER against the oracle's greedy variant: on chain-rich inputs (where it differs from the
+    Definition in many tokens) and on the clustered workload (where the two coincide); both tile sizes."""
+    say("greedy covering T=%d d=%d %s" % (T, d, dtype))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x_chain = torch.from_numpy(chain_rows(T, d, 400 + T)).to(torch.float32).to(tdt)
+    w = wl.small(T=T, d=d, K=max(1, T // 8), L=1, dtype=dtype, seed=41 + T)
+    ws = pa.workspace(T, DEV)
+    n_differ = 0
+    for name, x_cpu, tau in (("chains", x_chain, 0.05), ("chains", x_chain, 0.3), ("clusters", wl.layer_list(w)[0], w.tau)):
+        for tile in ("64", "128"):
+            os.environ["ADA_TILE"] = tile
+            try:
+                got = pa.fetch(pa.ada_select_full(x_cpu.to(DEV), tau, ws=ws, flags=pa.FLAG_GREEDY_COVER))
+            finally:
+                del os.environ["ADA_TILE"]
+            ref = greedy_reference(x_cpu, tau, got["mask"])
+            assert np.array_equal(got["mask"], ref["mask"]), "%s tau=%g tile %s: mask differs at %s" % (
+                name, tau, tile, np.nonzero(got["mask"] != ref["mask"])[0][:8])
+            assert np.array_equal(got["idx"], ref["idx"]) and got["r"] == len(ref["idx"])
+            dfn = oracle.select_full(wl.as_f64(x_cpu), tau)
+            assert float(np.max(np.abs(got["gamma"].astype(np.float64) - dfn["gamma"]))) <= parity.GAMMA_TOL
+            n_differ += int(np.sum(ref["mask"] != dfn["mask"]))
+        # the workspace is left usable by the other calls
+        parity.check_full(x_cpu, tau, pa.fetch(pa.ada_select_full(x_cpu.to(DEV), tau, ws=ws)), "after greedy")
+    if T >= 130:
+        assert n_differ > 0                                       # the chain inputs do separate the two readings
+
+
 def run_driver(xs, tau, **kw):
     out = pa.ada_cascade_layers(xs, tau, **kw)
     torch.cuda.synchronize()

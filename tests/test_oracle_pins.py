@@ -207,6 +207,54 @@ def test_definition_and_greedy_reading_differ_exactly_on_chains():
     assert oracle.select_full(X, 0.3, greedy=True)["mask"].tolist() == [1, 0, 1]  # greedy covering: c stays
 
 
+def exact_greedy(near, T):
+    """Section 2.5 in exact arithmetic: t is kept iff no earlier KEPT token is near it."""
+    kept = []
+    for t in range(T):
+        if not any(near[s][t] for s in kept):
+            kept.append(t)
+    return kept
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("tau_q,thr_q", RATIONAL_TAUS)
+def test_greedy_covering_agrees_with_exact_integer_brute_force(seed, tau_q, thr_q):
+    rng = np.random.default_rng(300 + seed)
+    T, d = 16, 5
+    Xi = integer_tokens(rng, T, d, n_base=3)
+    near, margin = exact_near(Xi.tolist(), *thr_q)
+    if margin < 1e-9:
+        pytest.skip("a pair sits on the threshold; float64 cannot be required to decide it")
+    res = oracle.select_full(Xi.astype(np.float64), tau_q[0] / tau_q[1], greedy=True)
+    assert res["idx"].tolist() == exact_greedy(near, T)
+
+
+def test_greedy_covering_is_a_maximal_separated_set_and_contains_the_definitions_set():
+    """Section 2.5's two properties, which hold for the greedy reading: representatives are pairwise below the
+    threshold (separated), every other token is within the threshold of an earlier representative (covering).
+    And every token the Definition keeps is kept by the greedy reading too (it compares with fewer tokens)."""
+    rng = np.random.default_rng(5)
+    differ = 0
+    for trial in range(8):
+        ang = np.sort(rng.uniform(0, np.pi, size=40))            # points on a half circle: many chains
+        X = np.stack([np.cos(ang), np.sin(ang)], axis=1)[rng.permutation(40)]
+        tau = 0.3
+        thr = 1 - tau * tau
+        G = np.abs(numpy_gram(X))
+        g = oracle.select_full(X, tau, greedy=True)
+        R = g["idx"].tolist()
+        for i, a in enumerate(R):
+            for b in R[:i]:
+                assert G[a, b] < thr
+        for t in range(40):
+            if t not in R:
+                assert any(G[t, s] >= thr for s in R if s < t)
+        dfn = oracle.select_full(X, tau)["idx"].tolist()
+        assert set(dfn) <= set(R)
+        differ += set(dfn) != set(R)
+    assert differ > 0                                             # the inputs do contain chains
+
+
 def test_clustered_tokens_first_occurrence_of_each_centre_is_selected():
     w = wl.small(T=300, d=64, K=40, L=1, dtype="f32", seed=11)
     rng = np.random.default_rng(w.seed(0))
