@@ -292,6 +292,35 @@ int ada_pipeline_layers(const void* const* X_layers, const void* const* Q_layers
                         void* ws, size_t ws_bytes, void* stream_sel, void* stream_attn, void* stream, unsigned flags);
 
 /*
+ * A threshold that follows the turnover (Section 8.1: "a layer with low turnover can tolerate a tighter threshold,
+ * a layer with high turnover should use a looser one"; the paper gives no formula).  The rule used here:
+ *   eta^(l)   = (adds + removes) / |R^(l-1)|            the turnover of the step just made (eq. (8))
+ *   tau^(l+1) = clip(tau^(l) + kappa * (eta_target - eta^(l)), tau_min, tau_max)
+ * A larger tau is a tighter threshold (1 - tau^2 falls: fewer representatives).  Layers 0 and 1 use tau0.  A step the
+ * device rejects (bad list) leaves tau unchanged.  Evaluated on the device in IEEE double, one rounding per operation.
+ */
+typedef struct {
+    double kappa;       /* gain; 0 keeps tau fixed */
+    double eta_target;  /* turnover at which tau stays where it is */
+    double tau_min;     /* 0 < tau_min <= tau0 <= tau_max < 1 */
+    double tau_max;
+} ada_tau_control;
+
+/*
+ * ada_cascade_layers with the threshold adapted between layers on the device (no host synchronisation).
+ *   tau_all  device [L] double   the tau each layer used
+ *   thr_all  device [L] float    1 - tau^2 as the kernels compared with it
+ * Other arguments and outputs as for ada_cascade_layers.  T <= 16384; ADA_FLAG_TWO_PASS and
+ * ADA_FLAG_RESIDENT_PASS are not available (ADA_ERR_SHAPE / ignored).  ADA_ERR_TAU for bounds that are not
+ * 0 < tau_min <= tau0 <= tau_max < 1 or for a NaN gain / target.
+ */
+int ada_cascade_layers_adaptive(const void* const* X_layers, int L, int T, int d, int64_t ld, int dtype, float tau0,
+                                const ada_tau_control* ctl, int32_t* idx_all, int32_t* counts_all,
+                                uint64_t* gram_ops_all, int32_t* adds_all, int32_t* removes_all,
+                                double* tau_all, float* thr_all,
+                                void* ws, size_t ws_bytes, void* stream, unsigned flags);
+
+/*
  * |A n B| and |A u B| of two representative sets given as uint8 masks [T] (device), for the
  * Jaccard index of eq. (3).  out: device int32 [2] = {intersection, union}.
  */

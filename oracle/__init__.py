@@ -182,3 +182,22 @@ def attention_compressed(Q, K, V, H: int, idx, assign, flags: int = 0) -> np.nda
                                                    _p(a, ctypes.c_int32), int(flags), _p(out, ctypes.c_double)),
            "attention_compressed")
     return out
+
+
+def cascade_layers_adaptive(Xs, tau0: float, kappa: float, eta_target: float, tau_min: float, tau_max: float,
+                            flags: int = 0):
+    """The layer loop of Section 4.1 with the threshold of Section 8.1 (see metrics.adapt_tau for the reading):
+    full selection at layer 0 with tau0, Algorithm 1 afterwards; layer 1 also uses tau0 (no turnover is known yet),
+    layer l + 1 the tau adapted from the turnover (eq. (8)) of the step made at layer l.
+    Returns (taus, results): the tau each layer used, and the select_full / cascade_step result of each layer."""
+    tau = float(np.float32(tau0))                       # the library takes tau0 as a float
+    taus, results = [tau], [select_full(Xs[0], tau)]
+    prev = results[0]["idx"]
+    for X in Xs[1:]:
+        taus.append(tau)
+        step = cascade_step(X, tau, prev, flags)
+        results.append(step)
+        eta = metrics.turnover(len(step["adds"]), len(step["removes"]), len(prev))
+        tau = metrics.adapt_tau(tau, eta, kappa, eta_target, tau_min, tau_max)
+        prev = step["idx"]
+    return taus, results

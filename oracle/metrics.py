@@ -63,3 +63,10 @@ def attention_cost_compressed(L: int, r: float, d_h: int, heads: int) -> float:
     FLOPs per multiply-add: L * 4 r^2 d_h * heads.  Section 6.6 writes the formula with a factor 2 but prints
     19.3 GFLOP for GPT-J, which is this count (the factor-2 form gives 9.6); the printed value is taken."""
     return float(L) * 4.0 * float(r) ** 2 * float(d_h) * float(heads)
+
+
+def adapt_tau(tau: float, eta: float, kappa: float, eta_target: float, tau_min: float, tau_max: float) -> float:
+    """Section 8.1, which states the rule in words only (low turnover: tighter threshold; high turnover: looser):
+    tau moves by kappa * (eta_target - eta) and is clipped to [tau_min, tau_max]; a larger tau is the tighter
+    threshold (1 - tau^2 falls, fewer representatives).  Python floats: IEEE double, one rounding per operation."""
+    return min(max(tau + kappa * (eta_target - eta), tau_min), tau_max)

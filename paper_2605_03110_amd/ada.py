@@ -27,7 +27,7 @@ FLAG_GREEDY_COVER = 16
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
-           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped", "ada_pipeline_layers",
+           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped", "ada_pipeline_layers", "ada_cascade_layers_adaptive",
            "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
            "ada_attention_compressed")
@@ -39,6 +39,12 @@ class AdaGroups(ctypes.Structure):
     """ada_groups of include/ada.h."""
     _fields_ = [("G", ctypes.c_int), ("x_gstride", ctypes.c_int64), ("list_gstride", ctypes.c_int64),
                 ("counts_gstride", ctypes.c_int64), ("ops_gstride", ctypes.c_int64)]
+
+
+class AdaTauControl(ctypes.Structure):
+    """ada_tau_control of include/ada.h."""
+    _fields_ = [("kappa", ctypes.c_double), ("eta_target", ctypes.c_double), ("tau_min", ctypes.c_double),
+                ("tau_max", ctypes.c_double)]
 
 
 class AdaError(RuntimeError):
@@ -98,6 +104,9 @@ def lib():
         L.ada_pipeline_layers.restype = i32
         L.ada_pipeline_layers.argtypes = [ctypes.POINTER(vp)] * 4 + [i32, i32, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp,
                                           ctypes.POINTER(vp), i64, vp, sz, vp, vp, vp, u32]
+        L.ada_cascade_layers_adaptive.restype = i32
+        L.ada_cascade_layers_adaptive.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i64, i32, f32,
+                                                  ctypes.POINTER(AdaTauControl), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, u32]
         L.ada_select_full_grouped.restype = i32
         L.ada_select_full_grouped.argtypes = [ctypes.POINTER(AdaGroups), vp, i32, i32, i64, i32, f32, vp, vp, vp, vp, sz, vp, u32]
         L.ada_cascade_layers_grouped.restype = i32
@@ -502,6 +511,40 @@ def ada_pipeline_layers(Xs: Sequence[torch.Tensor], Qs: Sequence[torch.Tensor], 
     if rc != OK:
         raise AdaError(rc, "ada_pipeline_layers")
     out["_keep"] = (ws, list(Xs), list(Qs), list(Ks), list(Vs), stream_sel, stream_attn)
+    return out
+
+
+def ada_cascade_layers_adaptive(Xs: Sequence[torch.Tensor], tau0: float, kappa: float, eta_target: float, tau_min: float,
+                                tau_max: float, *, want_lists: bool = True, ws: Optional[torch.Tensor] = None,
+                                stream=None, flags: int = 0) -> Dict[str, torch.Tensor]:
+    """ada_cascade_layers with the threshold adapted from the turnover between layers, on the device (Section 8.1).
+    Returns the tensors of ada_cascade_layers plus tau[L] (float64) and thr[L] (float32): what each layer used."""
+    L = len(Xs)
+    if L < 1:
+        raise ValueError("need at least one layer")
+    for X in Xs:
+        _check_x(X)
+        if X.shape != Xs[0].shape or X.dtype != Xs[0].dtype or X.stride(0) != Xs[0].stride(0):
+            raise ValueError("all layers must share shape, dtype and leading dimension")
+    T, d = Xs[0].shape
+    dev = Xs[0].device
+    ws = workspace(T, dev) if ws is None else ws
+    out = dict(idx=torch.empty((L, T), dtype=torch.int32, device=dev),
+               counts=torch.empty((L, 4), dtype=torch.int32, device=dev),
+               gram_ops=torch.empty(L, dtype=torch.int64, device=dev),
+               tau=torch.empty(L, dtype=torch.float64, device=dev), thr=torch.empty(L, dtype=torch.float32, device=dev))
+    if want_lists:
+        out["adds"] = torch.empty((L, T), dtype=torch.int32, device=dev)
+        out["removes"] = torch.empty((L, T), dtype=torch.int32, device=dev)
+    ctl = AdaTauControl(float(kappa), float(eta_target), float(tau_min), float(tau_max))
+    ptrs = (ctypes.c_void_p * L)(*[X.data_ptr() for X in Xs])
+    rc = lib().ada_cascade_layers_adaptive(ptrs, L, T, d, Xs[0].stride(0), _dtype_code(Xs[0]), float(tau0), ctypes.byref(ctl),
+                                           _ptr(out["idx"]), _ptr(out["counts"]), _ptr(out["gram_ops"]),
+                                           _ptr(out.get("adds")), _ptr(out.get("removes")), _ptr(out["tau"]),
+                                           _ptr(out["thr"]), _ptr(ws), ws.numel(), _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_layers_adaptive")
+    out["_keep"] = (ws, list(Xs))
     return out
 
 

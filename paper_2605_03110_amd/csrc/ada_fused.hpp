@@ -65,7 +65,35 @@ struct FusedParams {
     long long counts_gs;     // int32 elements between groups in counts and r_dev
     long long ops_gs;        // elements between groups in gram_ops
     long long ws_gs;         // bytes between groups' hit tables and tickets
+    // Threshold adapted from layer to layer (Section 8.1): this step's tau / threshold are read from device memory
+    // (thr_in overrides thr), and the workgroup that updates the set also writes the next step's (tau_out may be NULL)
+    const double* tau_in;
+    const float* thr_in;
+    double* tau_out;
+    float* thr_out;
+    double kappa, eta_target, tau_min, tau_max;
 };
+
+// Section 8.1's rule as read here: the turnover eta = (adds + removes) / r of the step just made (eq. (8)) moves tau
+// by kappa (eta_target - eta): a stable set (low turnover) tightens the threshold (larger tau: fewer representatives),
+// an evolving one loosens it; the result is clipped to [tau_min, tau_max].  Plain IEEE double operations, one
+// rounding each (no fused multiply-add), so that a float64 CPU evaluation of the same expression gives the same bits.
+__device__ inline void adapt_tau(const FusedParams& p, int r, int n_add, int n_rem, bool step_ok) {
+#pragma clang fp contract(off)                               // a * b + c stays two roundings (device code contracts by default)
+    if (!p.tau_out) return;
+    const double tau = *p.tau_in;
+    double next = tau;
+    if (step_ok && r > 0) {
+        const double eta = (double)(n_add + n_rem) / (double)r;
+        const double gap = p.eta_target - eta;
+        const double move = p.kappa * gap;
+        next = tau + move;
+        next = fmin(fmax(next, p.tau_min), p.tau_max);
+    }
+    const double sq = next * next;
+    *p.tau_out = next;
+    *p.thr_out = (float)(1.0 - sq);
+}
 
 // Tile shapes (representatives x tested tokens): 0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128.  A step's cost is taken as
 // rounds x (operand bytes per tile + a fixed part worth about 56 rows of 4096 two-byte elements: set size, list and
@@ -781,6 +809,7 @@ __device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int
         if (tid == 0) {
             p.counts[0] = 0; p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = ADA_ERR_INDEX;
             if (p.gram_ops) *p.gram_ops = 0ull;
+            adapt_tau(p, r, 0, 0, false);
             reset_tickets(p.ticket);
         }
         return 0;
@@ -835,6 +864,7 @@ __device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int
     }
     if (tid == 0) {
         p.counts[0] = n_idx; p.counts[1] = n_add; p.counts[2] = n_rem; p.counts[3] = ADA_OK;
+        adapt_tau(p, r, n_add, n_rem, true);
         if (p.gram_ops) {
             const unsigned long long TT = (unsigned long long)T, rr = (unsigned long long)r;
             *p.gram_ops = rr * rr + (TT - rr) * (unsigned long long)(r - n_rem);   // entries Algorithm 1 needs
@@ -899,6 +929,7 @@ __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q
         if (tid == 0) {
             p.counts[0] = 0; p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = status;
             if (p.gram_ops) *p.gram_ops = 0ull;
+            adapt_tau(p, r, 0, 0, false);
             reset_tickets(p.ticket);
         }
         return 0;
@@ -966,6 +997,7 @@ __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q
     }
     if (tid == 0) {
         p.counts[0] = n_idx; p.counts[1] = n_add; p.counts[2] = n_rem; p.counts[3] = ADA_OK;
+        adapt_tau(p, r, n_add, n_rem, true);
         if (p.gram_ops) {
             const unsigned long long TT = (unsigned long long)T, rr = (unsigned long long)r;
             *p.gram_ops = rr * rr + (TT - rr) * (unsigned long long)(r - n_rem);   // entries Algorithm 1 needs
@@ -1063,6 +1095,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
         p.counts += (long long)g * p.counts_gs;
         if (p.gram_ops) p.gram_ops += (long long)g * p.ops_gs;
     }
+    if (p.thr_in) p.thr = *p.thr_in;                         // adaptive threshold: travels with the set size
     const int r = p.r_dev ? *p.r_dev : p.r_host;
     const bool r_ok = r >= 1 && r <= p.r_host && r <= p.T;
     if (r_ok) fused_step_tiles<In, ALIGNED, KG, DMA>(p, r, lds, local, workers);

@@ -1167,13 +1167,18 @@ int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_
 int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, float tau, const int32_t* prev_idx, int r,
                       const int32_t* r_dev, int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
                       uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st, unsigned flags,
-                      const ada_groups* grp = nullptr) {
+                      const ada_groups* grp = nullptr, const ada_tau_control* ctl = nullptr, const double* tau_in = nullptr,
+                      const float* thr_in = nullptr, double* tau_out = nullptr, float* thr_out = nullptr) {
     const Workspace w = carve(ws, T);
     if (gamma && fill_u32(gamma, (size_t)T, 0u, st) != hipSuccess) return ADA_ERR_DEVICE;
     FusedParams p = {X, ld, T, d, prev_idx, r_dev, r, threshold_of(tau),
                      (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
                      w.meta + META_TICKET, idx, adds, removes, counts,
                      reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
+    if (ctl) {                                                   // Section 8.1: threshold carried on the device
+        p.tau_in = tau_in; p.thr_in = thr_in; p.tau_out = tau_out; p.thr_out = thr_out;
+        p.kappa = ctl->kappa; p.eta_target = ctl->eta_target; p.tau_min = ctl->tau_min; p.tau_max = ctl->tau_max;
+    }
     if (grp && grp->G > 1) {                                     // ws: G workspaces back to back
         p.groups = grp->G;
         p.x_gs = grp->x_gstride * (dtype == ADA_BF16 ? 2 : 4);
@@ -1630,6 +1635,44 @@ int ada_pipeline_layers(const void* const* X_layers, const void* const* Q_layers
     // join: work enqueued on `stream` after the call sees everything (also after an error part-way)
     if (!fork(ss, main) || !fork(sa, main)) return ADA_ERR_DEVICE;
     return rc;
+}
+
+namespace {
+__global__ void k_tau_init(double* tau_all, float* thr_all, double tau0, float thr0, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { tau_all[i] = tau0; thr_all[i] = thr0; }
+}
+}  // namespace
+
+int ada_cascade_layers_adaptive(const void* const* X_layers, int L, int T, int d, int64_t ld, int dtype, float tau0,
+                                const ada_tau_control* ctl, int32_t* idx_all, int32_t* counts_all,
+                                uint64_t* gram_ops_all, int32_t* adds_all, int32_t* removes_all, double* tau_all,
+                                float* thr_all, void* ws, size_t ws_bytes, void* stream, unsigned flags) {
+    if (!X_layers || !ctl || !idx_all || !counts_all || !gram_ops_all || !tau_all || !thr_all) return ADA_ERR_NULL;
+    if (L < 1) return ADA_ERR_SHAPE;
+    for (int l = 0; l < L; ++l)
+        if (!X_layers[l]) return ADA_ERR_NULL;
+    if (int e = check_common(X_layers[0], T, d, ld, dtype, tau0, ws, ws_bytes)) return e;
+    if (!(ctl->tau_min > 0.0 && ctl->tau_min <= ctl->tau_max && ctl->tau_max < 1.0)) return ADA_ERR_TAU;
+    if (!((double)tau0 >= ctl->tau_min && (double)tau0 <= ctl->tau_max)) return ADA_ERR_TAU;
+    if (!(ctl->kappa == ctl->kappa) || !(ctl->eta_target == ctl->eta_target)) return ADA_ERR_TAU;     // NaN
+    if (T > FUSED_MAX_T || (flags & ADA_FLAG_TWO_PASS)) return ADA_ERR_SHAPE;   // the one-launch step carries the threshold
+    hipStream_t st = (hipStream_t)stream;
+    // every layer's tau starts as tau0 (layers 0 and 1 use it as it is: no turnover is known before the first step)
+    hipLaunchKernelGGL(k_tau_init, dim3((L + 255) / 256), dim3(256), 0, st, tau_all, thr_all, (double)tau0,
+                       threshold_of(tau0), L);
+    if (hipGetLastError() != hipSuccess) return ADA_ERR_DEVICE;
+    int e = run_full(X_layers[0], T, d, ld, dtype, tau0, nullptr, idx_all, counts_all, gram_ops_all, nullptr, ws, st);
+    for (int l = 1; l < L && e == ADA_OK; ++l) {
+        const size_t o = (size_t)l * (size_t)T;
+        const bool last = l + 1 == L;
+        e = run_cascade_fused(X_layers[l], T, d, ld, dtype, tau0, idx_all + o - T, T, counts_all + (size_t)(l - 1) * 4,
+                              idx_all + o, adds_all ? adds_all + o : nullptr, removes_all ? removes_all + o : nullptr,
+                              counts_all + (size_t)l * 4, gram_ops_all + l, nullptr, ws, st,
+                              flags & ADA_FLAG_CROSS_EARLIER_ONLY, nullptr, ctl, tau_all + l, thr_all + l,
+                              last ? nullptr : tau_all + l + 1, last ? nullptr : thr_all + l + 1);
+    }
+    return e;
 }
 
 int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t* out, void* stream) {

@@ -637,6 +637,76 @@ def test_greedy_covering_selection(T, d, dtype):
         assert n_differ > 0                                       # the chain inputs do separate the two readings
 
 
+def drifting_chain_layers(T, d, L, seed):
+    """Layers whose rows are unit vectors spread over a plane (so that the threshold decides how many neighbours a
+    token has) and drift a little from layer to layer."""
+    rng = np.random.default_rng(seed)
+    ang = rng.uniform(0, np.pi, size=T)
+    basis = np.linalg.qr(rng.standard_normal((d, 2)))[0]
+    out = []
+    for _ in range(L):
+        out.append(np.cos(ang)[:, None] * basis[:, 0] + np.sin(ang)[:, None] * basis[:, 1])
+        ang = ang + rng.normal(0, 0.02, size=T)
+    return out
+
+
+@pytest.mark.parametrize("kind,T,d,dtype,ctl", [("clusters", 600, 192, "bf16", (0.05, 0.8, 0.02, 0.6)),
+                                                ("chains", 500, 64, "f32", (0.1, 1.5, 0.05, 0.4)),
+                                                ("chains", 1100, 128, "bf16", (0.1, 1.5, 0.05, 0.4)),
+                                                ("chains", 700, 96, "bf16", (0.0, 0.3, 0.02, 0.6))])
+def test_threshold_adapted_on_the_device(kind, T, d, dtype, ctl):
+    """ada_cascade_layers_adaptive: the tau of every layer equals, bit for bit, the rule applied in float64 to the
+    previous step's own counts; every step is checked against the oracle at that tau on the set it consumed; and
+    the whole trajectory equals the oracle's own adaptive loop when no decision falls into the band."""
+    L = 7
+    say("adaptive tau %s T=%d d=%d %s ctl=%s" % (kind, T, d, dtype, ctl))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    if kind == "clusters":
+        w = wl.small(T=T, d=d, K=70, L=L, dtype=dtype, seed=171, p=0.15)
+        xs_cpu, tau0 = wl.layer_list(w), w.tau
+    else:
+        xs_cpu = [torch.from_numpy(x).to(torch.float32).to(tdt) for x in drifting_chain_layers(T, d, L, 181 + T)]
+        tau0 = 0.2
+    xs = [x.to(DEV) for x in xs_cpu]
+    kappa, eta_t, tmin, tmax = ctl
+    out = pa.ada_cascade_layers_adaptive(xs, tau0, kappa, eta_t, tmin, tmax)
+    torch.cuda.synchronize()
+    counts, taus, thrs = out["counts"].cpu(), out["tau"].cpu().numpy(), out["thr"].cpu().numpy()
+    assert counts[:, 3].tolist() == [0] * L
+    t32 = float(np.float32(tau0))
+    assert taus[0] == t32 and taus[1] == t32
+    prev = None
+    for l in range(L):
+        r, na, nr = (int(v) for v in counts[l, :3])
+        idx = out["idx"][l, :r].cpu().numpy()
+        assert thrs[l] == np.float32(1.0 - taus[l] * taus[l])
+        if l == 0:
+            parity.check_full(xs_cpu[0], taus[0], pa.fetch(pa.ada_select_full(xs[0], tau0)), "adaptive layer 0")
+            assert np.array_equal(idx, pa.fetch(pa.ada_select_full(xs[0], tau0))["idx"])
+        else:
+            if l + 1 < L:
+                eta = oracle.metrics.turnover(na, nr, len(prev))
+                assert taus[l + 1] == oracle.metrics.adapt_tau(float(taus[l]), eta, kappa, eta_t, tmin, tmax)
+            got = dict(idx=idx, adds=out["adds"][l, :na].cpu().numpy(), removes=out["removes"][l, :nr].cpu().numpy(),
+                       gram_ops=int(out["gram_ops"][l]), r=r, n_adds=na, n_removes=nr,
+                       gamma=pa.fetch(pa.ada_cascade_step(xs[l], float(taus[l]), dev_idx(prev)))["gamma"])
+            parity.check_cascade(xs_cpu[l], float(taus[l]), prev, got, what="adaptive layer %d tau %.4f" % (l, taus[l]))
+        prev = idx
+    if kappa != 0.0:
+        assert len(set(taus.tolist())) > 2                       # the threshold moved
+    if kind == "chains":
+        sizes = [int(c) for c in counts[:, 0]]
+        fixed = run_driver(xs, tau0, want_lists=False)["counts"][:, 0].cpu().tolist()
+        assert (sizes != fixed) == (kappa != 0.0)                # ... and moving it changes the sets on these inputs
+    ref_taus, ref = oracle.cascade_layers_adaptive([wl.as_f64(x) for x in xs_cpu], tau0, kappa, eta_t, tmin, tmax)
+    if all(np.array_equal(ref[l]["idx"], out["idx"][l, :int(counts[l, 0])].cpu().numpy()) for l in range(L)):
+        assert ref_taus == taus.tolist()
+    else:                                                          # only a band decision may separate the two loops
+        l = next(l for l in range(L) if not np.array_equal(ref[l]["idx"], out["idx"][l, :int(counts[l, 0])].cpu().numpy()))
+        g = ref[l]["gamma"]
+        assert np.any(np.abs(g - parity.thr_of(ref_taus[l])) < parity.BAND), "loops differ at layer %d without a band token" % l
+
+
 def run_driver(xs, tau, **kw):
     out = pa.ada_cascade_layers(xs, tau, **kw)
     torch.cuda.synchronize()

@@ -166,6 +166,18 @@ def test_host_checkable_errors_return_before_touching_the_device(ada):
     odd = (ctypes.c_void_p * 2)(0x1000, 0x2008)
     assert pipe(Q=odd) == SHAPE
 
+    TAU = 3
+
+    def adaptive(X=good, ctl=(0.1, 0.2, 0.05, 0.5), tau0=0.1, L=2, T=8, tau_all=0x1000, ws=0x1000, nb=1 << 20, flags=0, noctl=False):
+        c = pa.AdaTauControl(*ctl)
+        return lib.ada_cascade_layers_adaptive(X, L, T, 8, 8, 1, tau0, None if noctl else ctypes.byref(c), 0x1000, 0x1000,
+                                               0x1000, None, None, tau_all, 0x1000, ws, nb, None, flags)
+    assert adaptive(X=None) == NULL and adaptive(noctl=True) == NULL and adaptive(tau_all=None) == NULL and adaptive(X=ptrs) == NULL
+    assert adaptive(L=0) == SHAPE and adaptive(T=0) == SHAPE and adaptive(flags=2) == SHAPE
+    assert adaptive(ctl=(0.1, 0.2, 0.0, 0.5)) == TAU and adaptive(ctl=(0.1, 0.2, 0.05, 1.0)) == TAU
+    assert adaptive(ctl=(0.1, 0.2, 0.3, 0.2)) == TAU and adaptive(tau0=0.6) == TAU and adaptive(tau0=0.01) == TAU
+    assert adaptive(ctl=(float("nan"), 0.2, 0.05, 0.5)) == TAU and adaptive(nb=64) == WS
+
 
 def test_binding_rejects_host_tensors_and_wrong_dtypes(ada):
     import paper_2605_03110_amd as pa

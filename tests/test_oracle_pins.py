@@ -606,3 +606,44 @@ def test_attention_rejects_bad_input():
             oracle.attention_compressed(Q, Q, Q, 2, R, a)
     with pytest.raises(ValueError):
         oracle.attention_compressed(Q, Q, Q, 3, [0, 2], good)       # 4 columns do not split into 3 heads
+
+
+# ----------------------------------------------------------------------------- Section 8.1 (adaptive threshold)
+def test_adapt_tau_closed_forms():
+    m = oracle.metrics
+    assert m.adapt_tau(0.2, 0.25, 0.0, 0.1, 0.05, 0.5) == 0.2                    # no gain: fixed
+    assert m.adapt_tau(0.2, 0.1, 0.5, 0.1, 0.05, 0.5) == 0.2                     # on target: fixed
+    assert m.adapt_tau(0.25, 0.0, 0.5, 0.5, 0.05, 0.9) == 0.5                    # stable set: tighter (tau up by 0.25)
+    assert m.adapt_tau(0.5, 1.0, 0.25, 0.0, 0.05, 0.9) == 0.25                   # evolving set: looser (tau down)
+    assert m.adapt_tau(0.25, 0.0, 4.0, 0.5, 0.05, 0.75) == 0.75                  # clipped above
+    assert m.adapt_tau(0.25, 2.0, 4.0, 0.5, 0.125, 0.75) == 0.125                # clipped below
+    # low turnover gives the larger tau, i.e. the lower threshold 1 - tau^2: fewer representatives
+    lo, hi = m.adapt_tau(0.2, 0.0, 0.3, 0.2, 0.01, 0.9), m.adapt_tau(0.2, 0.6, 0.3, 0.2, 0.01, 0.9)
+    assert lo > 0.2 > hi and 1 - lo * lo < 1 - hi * hi
+
+
+def test_adaptive_layer_loop_with_zero_gain_is_the_fixed_loop_and_follows_the_turnover_otherwise():
+    w = wl.small(T=300, d=64, K=40, L=6, dtype="f32", seed=19, p=0.15)
+    Xs = [wl.as_f64(x) for x in wl.layer_list(w)]
+    taus, res = oracle.cascade_layers_adaptive(Xs, w.tau, 0.0, 0.1, 0.01, 0.9)
+    t32 = float(np.float32(w.tau))
+    assert taus == [t32] * w.L
+    prev = oracle.select_full(Xs[0], t32)["idx"]
+    assert res[0]["idx"].tolist() == prev.tolist()
+    for l in range(1, w.L):
+        step = oracle.cascade_step(Xs[l], t32, prev)
+        assert res[l]["idx"].tolist() == step["idx"].tolist()
+        prev = step["idx"]
+    # with a gain: layers 0 and 1 use tau0, every later tau is the rule applied to the previous step's own counts
+    taus, res = oracle.cascade_layers_adaptive(Xs, w.tau, 0.05, 0.8, 0.02, 0.6)
+    assert taus[0] == taus[1] == t32
+    prev_r = len(res[0]["idx"])
+    for l in range(1, w.L - 1):
+        eta = (len(res[l]["adds"]) + len(res[l]["removes"])) / prev_r
+        assert taus[l + 1] == min(max(taus[l] + 0.05 * (0.8 - eta), 0.02), 0.6)
+        prev_r = len(res[l]["idx"])
+    assert len(set(taus)) > 2                                                    # the threshold really moved
+    # identical layers: no turnover at all, so tau climbs by kappa * eta_target per layer until it is clipped
+    taus, res = oracle.cascade_layers_adaptive([Xs[0]] * 5, 0.25, 0.5, 0.25, 0.05, 0.5)
+    assert taus == [0.25, 0.25, 0.375, 0.5, 0.5]
+    assert all(len(r["removes"]) == 0 for r in res[1:3])
