@@ -409,6 +409,31 @@ def main():
                               "mean_r_h": float(ch[:, 1:, 0].float().mean())}
         del wsb, outb, hv, wsh, outh
 
+        # ---- the cascade step at the two other d=4096 shapes (first six layers of configs[3] and configs[4]), where
+        # the wider tiles take over: 64 x 128 at r ~ 920, 128 x 128 at T = 8192
+        other = {}
+        for ci in (3, 4):
+            if ci == args.config:
+                continue
+            wo = wl.config(ci)
+            xo = [x.to(dev) for x in wl.layers(wo, 0, 6)]
+            wso = pa.workspace(wo.T, dev)
+            for _ in range(2):
+                oo = pa.ada_cascade_layers(xo, wo.tau, ws=wso, stream=stream, want_lists=False)
+            torch.cuda.synchronize()
+            pa.ada_profile_enable(True)
+            for _ in range(5):
+                oo = pa.ada_cascade_layers(xo, wo.tau, ws=wso, stream=stream, want_lists=False)
+            torch.cuda.synchronize()
+            ko = pa.ada_profile_collect()
+            pa.ada_profile_enable(False)
+            us_o = 1e3 * ko["cascade_fused"]["ms"] / ko["cascade_fused"]["launches"]
+            by = wo.T * wo.d * (2 if wo.dtype == "bf16" else 4)
+            other[wo.name] = {"T": wo.T, "d": wo.d, "mean_r": float(oo["counts"][1:, 0].float().mean()),
+                              "cascade_launch_us": us_o, "hbm_frac": by / (1e-6 * us_o) / 1e9 / HBM_PEAK_GBS}
+            del xo, wso, oo
+        result["cascade_other_shapes"] = other
+
         # ---- the greedy covering of Section 2.5 on layer 0 (pair bits from the register-staged Gram tiles, then the
         # sequential resolution by one workgroup)
         if T <= 16384:
