@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the full-selection timing and the profiled pass")
     ap.add_argument("--probe", action="store_true", help="short run for rocprofv3 --pmc (no timing, no JSON result)")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="the timed passes and the event-timed pass of the roofline only (for a kernel trace in which "
+                         "k_cascade_fused runs this workload's cascade steps and nothing else)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
@@ -190,6 +193,10 @@ def main():
                               "mfma_frac": casc_flops / casc_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
         result["kernel_avg_us"] = avg_us
         result["ms_per_step_with_events"] = 1e3 * prof_elapsed / args.steps
+    if args.roofline_only:
+        print(json.dumps(result))
+        return
+    if not args.no_extras:
 
         # ---- the full T x T selection at every layer (the comparison path), same buffers
         fo = [pa.ada_select_full(xs[0], w.tau, ws=ws) for _ in range(2)]
