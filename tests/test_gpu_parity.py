@@ -849,6 +849,54 @@ def test_config4_one_sequence_sampled():
         step_and_check(xs[1], xs_cpu[1], w.tau, full["idx"], flags, w.name + " layer 1")
 
 
+@pytest.mark.parametrize("ci,B,n_layers,checked", [(2, 4, 4, (0, 3)), (4, 4, 3, (1,))])
+def test_stacked_batch_at_full_size(ci, B, n_layers, checked):
+    """The batch of the long-context configuration (four sequences with different seeds) and of the benchmark's
+    configuration, stacked in one tensor per layer as bench.py runs them: one launch per step for all sequences.
+    Every sequence equals its own single-sequence run bit for bit; the sequences in `checked` are also checked
+    step by step against the oracle (their full selection on sampled gamma_t at T = 8192)."""
+    w = wl.config(ci)
+    say("%s: %d stacked sequences, %d layers" % (w.name, B, n_layers))
+    seqs_cpu = [wl.layer_list(w, b, n_layers) for b in range(B)]
+    xg = [torch.stack([seqs_cpu[b][l] for b in range(B)]).to(DEV) for l in range(n_layers)]
+    out = pa.ada_cascade_layers_grouped(xg, w.tau, want_lists=True)
+    torch.cuda.synchronize()
+    counts = out["counts"].cpu()
+    assert counts[:, :, 3].flatten().tolist() == [0] * (B * n_layers)
+    for b in range(B):
+        single = run_driver([xg[l][b] for l in range(n_layers)], w.tau)
+        assert torch.equal(single["counts"].cpu(), counts[b]) and torch.equal(single["gram_ops"], out["gram_ops"][b])
+        for l in range(n_layers):
+            r, na, nr = (int(v) for v in counts[b, l, :3])
+            assert torch.equal(single["idx"][l, :r], out["idx"][b, l, :r])
+            if l > 0:
+                assert torch.equal(single["adds"][l, :na], out["adds"][b, l, :na])
+                assert torch.equal(single["removes"][l, :nr], out["removes"][b, l, :nr])
+    assert len({tuple(counts[b, :, 0].tolist()) for b in range(B)}) > 1          # the sequences differ
+    rng = np.random.default_rng(ci)
+    for b in checked:
+        prev = None
+        for l in range(n_layers):
+            r, na, nr = (int(v) for v in counts[b, l, :3])
+            idx = out["idx"][b, l, :r].cpu().numpy()
+            if l == 0:
+                X0 = wl.as_f64(seqs_cpu[b][0])
+                if w.T <= 2048:
+                    assert np.array_equal(idx, oracle.select_full(X0, w.tau)["idx"])
+                else:
+                    rows = np.unique(np.concatenate([[0, 1, w.T - 1], rng.integers(0, w.T, 40)]))
+                    ref = oracle.gamma_full_rows(X0, rows)
+                    assert np.all(np.abs(ref - parity.thr_of(w.tau)) > parity.BAND)
+                    member = np.isin(rows, idx)
+                    assert np.array_equal(member, ref < parity.thr_of(w.tau))
+            else:
+                got = dict(idx=idx, adds=out["adds"][b, l, :na].cpu().numpy(), removes=out["removes"][b, l, :nr].cpu().numpy(),
+                           gram_ops=int(out["gram_ops"][b, l]), r=r, n_adds=na, n_removes=nr,
+                           gamma=pa.fetch(pa.ada_cascade_step(xg[l][b], w.tau, dev_idx(prev)))["gamma"])
+                parity.check_cascade(seqs_cpu[b][l], w.tau, prev, got, what="%s seq %d layer %d" % (w.name, b, l))
+            prev = idx
+
+
 # ------------------------------------------------------------------------------------------ Section 2.3: assignment
 def assign_and_check(x_cpu, idx, what, **kw):
     res = pa.ada_assign_nearest(x_cpu.to(DEV), torch.as_tensor(np.asarray(idx, dtype=np.int32)).to(DEV), **kw)
