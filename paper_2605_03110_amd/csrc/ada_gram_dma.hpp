@@ -172,6 +172,12 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         for (int a = 0; a < NB; ++a)
             m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WM + a * 32, half, need_order, ttok));
         publish_max(m, t_scale[nl], ttok, half, gamma_bits);
+        if (p.hits) {                                              // greedy covering: one bit per pair s < t as well
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+                publish_hits(acc[a][b], s_scale, s_tok, ws * WM + a * 32, half, need_order, ttok, t_scale[nl], p.thr,
+                             p.hits, T, s0 + ws * WM + a * 32);
+        }
     }
     DMA_CLK(3);
 #ifdef ADA_PHASE_CLOCKS

@@ -349,7 +349,8 @@ __device__ inline void publish_hits(const f32x16& v, const float* s_scale, const
         if (x >= thr) bits |= 1u << r32;
     }
     bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
-    if (half == 0 && ttok >= 0) hits[(size_t)(s_glob0 >> 5) * (size_t)T + ttok] = bits;
+    // (a block of "against" rows past the end has no word in the table: tiles are padded further than the table is)
+    if (half == 0 && ttok >= 0 && s_glob0 < T) hits[(size_t)(s_glob0 >> 5) * (size_t)T + ttok] = bits;
 }
 
 template <typename In, int B, bool ALIGNED>
@@ -815,7 +816,8 @@ __global__ __launch_bounds__(GREEDY_THREADS) void k_greedy_resolve(GreedyParams 
 #pragma unroll
         for (int j = 0; j < TPT; ++j) {
             const int t = tid + j * GREEDY_THREADS;
-            if ((t >> 6) == b && t < T) { own_lo[t & 63] = lo[0][j]; own_hi[t & 63] = hi[0][j]; }
+            // (the block's second word may lie wholly past the end of the sequence: nobody wrote it)
+            if ((t >> 6) == b && t < T) { own_lo[t & 63] = lo[0][j]; own_hi[t & 63] = 64 * b + 32 < T ? hi[0][j] : 0u; }
         }
         __syncthreads();
         if (tid < 64) {                                      // wave 0: the block's decisions, in token order
@@ -835,7 +837,7 @@ __global__ __launch_bounds__(GREEDY_THREADS) void k_greedy_resolve(GreedyParams 
             if (lane == 0) { repw[2 * b] = (uint32_t)rep; repw[2 * b + 1] = (uint32_t)(rep >> 32); }
         }
         __syncthreads();
-        const uint32_t rlo = repw[2 * b], rhi = repw[2 * b + 1];
+        const uint32_t rlo = repw[2 * b], rhi = 64 * b + 32 < T ? repw[2 * b + 1] : 0u;
 #pragma unroll
         for (int j = 0; j < TPT; ++j) {                      // push: later tokens hit by one of the new representatives
             const int t = tid + j * GREEDY_THREADS;
@@ -1051,8 +1053,8 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
         if (e1 != hipSuccess) return e1;
         if constexpr (V::aligned) {
             if constexpr (sizeof(In) == 2) {
-                // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel (it keeps row maxima only)
-                const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0 && !greedy;
+                // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
+                const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
                 if (can && (path == "dma0" || path == "dma1"))
                     return launch_gram_dma(p, w.meta + META_QUEUE, path == "dma1", st, groups);
                 if (can && path.empty() && T >= 1536) return launch_gram_dma(p, w.meta + META_QUEUE, -1, st, groups);

@@ -607,7 +607,8 @@ def chain_rows(T, d, seed):
 
 
 @pytest.mark.parametrize("T,d,dtype", [(1, 64, "bf16"), (64, 32, "f32"), (130, 64, "bf16"), (333, 96, "f32"), (700, 256, "bf16"),
-                                       (1290, 128, "bf16"), (2048, 64, "bf16"), (3000, 32, "bf16")])
+                                       (1290, 128, "bf16"), (2048, 64, "bf16"), (3000, 32, "bf16"), (2060, 64, "bf16"),
+                                       (2100, 96, "bf16")])
 def test_greedy_covering_selection(T, d, dtype):
     """ADA_FLAG_GREEDY_COVER against the oracle's greedy variant: on chain-rich inputs (where it differs from the
     Definition in many tokens) and on the clustered workload (where the two coincide); both tile sizes."""
@@ -618,15 +619,17 @@ def test_greedy_covering_selection(T, d, dtype):
     ws = pa.workspace(T, DEV)
     n_differ = 0
     for name, x_cpu, tau in (("chains", x_chain, 0.05), ("chains", x_chain, 0.3), ("clusters", wl.layer_list(w)[0], w.tau)):
-        for tile in ("64", "128"):
-            os.environ["ADA_TILE"] = tile
+        # the register-staged tiles of both sizes, and the direct-to-LDS kernel with both ways of cutting the triangle
+        # (where the shape allows it; otherwise these switches change nothing)
+        for var, tile in (("ADA_TILE", "64"), ("ADA_TILE", "128"), ("ADA_GRAM", "tile"), ("ADA_GRAM", "dma0"), ("ADA_GRAM", "dma1")):
+            os.environ[var] = tile
             try:
                 got = pa.fetch(pa.ada_select_full(x_cpu.to(DEV), tau, ws=ws, flags=pa.FLAG_GREEDY_COVER))
             finally:
-                del os.environ["ADA_TILE"]
+                del os.environ[var]
             ref = greedy_reference(x_cpu, tau, got["mask"])
-            assert np.array_equal(got["mask"], ref["mask"]), "%s tau=%g tile %s: mask differs at %s" % (
-                name, tau, tile, np.nonzero(got["mask"] != ref["mask"])[0][:8])
+            assert np.array_equal(got["mask"], ref["mask"]), "%s tau=%g %s=%s: mask differs at %s" % (
+                name, tau, var, tile, np.nonzero(got["mask"] != ref["mask"])[0][:8])
             assert np.array_equal(got["idx"], ref["idx"]) and got["r"] == len(ref["idx"])
             dfn = oracle.select_full(wl.as_f64(x_cpu), tau)
             assert float(np.max(np.abs(got["gamma"].astype(np.float64) - dfn["gamma"]))) <= parity.GAMMA_TOL
