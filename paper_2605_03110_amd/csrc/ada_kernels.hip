@@ -1068,6 +1068,7 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
         ProfScope ps(ADA_K_UPDATE, st);
         if (T <= 2 * GREEDY_THREADS) hipLaunchKernelGGL((k_greedy_resolve<2, 4>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
         else if (T <= 4 * GREEDY_THREADS) hipLaunchKernelGGL((k_greedy_resolve<4, 3>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
+        else if (T <= 8 * GREEDY_THREADS) hipLaunchKernelGGL((k_greedy_resolve<8, 3>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
         else hipLaunchKernelGGL((k_greedy_resolve<FUSED_MAX_T / GREEDY_THREADS, 1>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
         return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
     }

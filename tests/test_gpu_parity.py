@@ -608,7 +608,7 @@ def chain_rows(T, d, seed):
 
 @pytest.mark.parametrize("T,d,dtype", [(1, 64, "bf16"), (64, 32, "f32"), (130, 64, "bf16"), (333, 96, "f32"), (700, 256, "bf16"),
                                        (1290, 128, "bf16"), (2048, 64, "bf16"), (3000, 32, "bf16"), (2060, 64, "bf16"),
-                                       (2100, 96, "bf16")])
+                                       (2100, 96, "bf16"), (5000, 32, "bf16")])
 def test_greedy_covering_selection(T, d, dtype):
     """ADA_FLAG_GREEDY_COVER against the oracle's greedy variant: on chain-rich inputs (where it differs from the
     Definition in many tokens) and on the clustered workload (where the two coincide); both tile sizes."""
