@@ -710,6 +710,56 @@ def test_threshold_adapted_on_the_device(kind, T, d, dtype, ctl):
         assert np.any(np.abs(g - parity.thr_of(ref_taus[l])) < parity.BAND), "loops differ at layer %d without a band token" % l
 
 
+@pytest.mark.parametrize("T,d,K,dtype", [(4100, 64, 300, "bf16"), (5001, 96, 500, "bf16"), (6000, 32, 900, "f32"), (8192, 128, 400, "bf16"),
+                                         (12000, 64, 2500, "bf16")])
+def test_cascade_step_on_long_sequences(T, d, K, dtype):
+    """Sequences longer than 4096 tokens (odd T: scalar loads in the set update; r above 1024: more than one pass over
+    the list): against the oracle, twice on one workspace, with the set size on the host and on the device, for a
+    bad list, and with three stacked sequences in one launch."""
+    say("long sequence T=%d d=%d K=%d %s" % (T, d, K, dtype))
+    w = wl.small(T=T, d=d, K=K, L=3, dtype=dtype, seed=211 + T, p=0.1)
+    xs_cpu = wl.layer_list(w)
+    xs = [x.to(DEV) for x in xs_cpu]
+    ws = pa.workspace(T, DEV)
+    full = pa.fetch(pa.ada_select_full(xs[0], w.tau, ws=ws))
+    prev = full["idx"]
+    for l in (1, 2):
+        for flags in (0, pa.FLAG_CROSS_EARLIER_ONLY):
+            got = pa.fetch(pa.ada_cascade_step(xs[l], w.tau, dev_idx(prev), ws=ws, flags=flags))
+            parity.check_cascade(xs_cpu[l], w.tau, prev, got, flags=oflags(flags), what="long sequence layer %d" % l)
+        again = pa.fetch(pa.ada_cascade_step(xs[l], w.tau, dev_idx(prev), ws=ws, flags=flags))
+        for k in ("idx", "adds", "removes"):
+            assert np.array_equal(again[k], got[k])
+        # the count on the device, the list padded to T entries
+        padded = torch.zeros(T, dtype=torch.int32, device=DEV)
+        padded[:len(prev)] = dev_idx(prev)
+        cnt = torch.tensor([len(prev), 0, 0, 0], dtype=torch.int32, device=DEV)
+        dv = pa.fetch(pa.ada_cascade_step(xs[l], w.tau, padded, r=T, r_dev=cnt, ws=ws, flags=flags))
+        for k in ("idx", "adds", "removes"):
+            assert np.array_equal(dv[k], got[k])
+        prev = pa.fetch(pa.ada_cascade_step(xs[l], w.tau, dev_idx(prev), ws=ws))["idx"]
+    bad = np.array(full["idx"], copy=True)
+    bad[3] = bad[2]
+    res = pa.ada_cascade_step(xs[1], w.tau, dev_idx(bad), ws=ws)
+    assert res["counts"].cpu().tolist() == [0, 0, 0, 4]
+    parity.check_cascade(xs_cpu[1], w.tau, full["idx"], pa.fetch(pa.ada_cascade_step(xs[1], w.tau, dev_idx(full["idx"]), ws=ws)),
+                         what="after a rejected list")
+    if T <= 6000:
+        G = 3
+        seqs_cpu = [wl.layer_list(w, sequence=b, n_layers=2) for b in range(G)]
+        xg = [torch.stack([seqs_cpu[b][l] for b in range(G)]).to(DEV) for l in range(2)]
+        out = pa.ada_cascade_layers_grouped(xg, w.tau, want_lists=True)
+        c = out["counts"].cpu()
+        assert c[:, :, 3].flatten().tolist() == [0] * (2 * G)
+        for b in range(G):
+            single = run_driver([xg[l][b] for l in range(2)], w.tau)
+            assert torch.equal(single["counts"].cpu(), c[b])
+            r, na, nr = (int(v) for v in c[b, 1, :3])
+            assert torch.equal(single["idx"][1, :r], out["idx"][b, 1, :r])
+            assert torch.equal(single["adds"][1, :na], out["adds"][b, 1, :na])
+            assert torch.equal(single["removes"][1, :nr], out["removes"][b, 1, :nr])
+
+
 def run_driver(xs, tau, **kw):
     out = pa.ada_cascade_layers(xs, tau, **kw)
     torch.cuda.synchronize()
