@@ -877,7 +877,7 @@ __device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int
 // Returns |R^(l+1)| to every thread (0 if the step is rejected).
 template <int THREADS>
 __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q0, int qp0, char* lds, int* scan_scratch) {
-    constexpr int WU = 15;                              // hit words fetched per batch by one thread
+    constexpr int WU = 11;                              // hit words fetched per batch by one thread (22, 33, ... words: whole batches)
     const int tid = threadIdx.x, lane = tid & 63;
     const int T = p.T;
     if (r_ok && (T & 3) == 0 && (T >> 2) <= THREADS) {  // uniform
@@ -890,11 +890,12 @@ __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q
     for (int t = tid; t < T; t += THREADS) flag[t] = 2;                      // not inherited, kept unless covered
     // the token pass's first batch of hit words does not depend on the validity mask: fetch it now, use it later
     const bool vec = (T & 3) == 0;
-    const bool have_pre = vec && r_ok && tid < (T >> 2);
     u32x4 pre[WU];
+    if (vec && r_ok) {                                  // uniform; clamped address, used only by threads that own tokens
+        const int t4c = min(tid, (T >> 2) - 1);
 #pragma unroll
-    for (int v = 0; v < WU; ++v)
-        pre[v] = have_pre ? *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(v, Wa - 1) * T + 4 * tid) : u32x4{0u, 0u, 0u, 0u};
+        for (int v = 0; v < WU; ++v) pre[v] = *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(v, Wa - 1) * T + 4 * t4c);
+    }
     __syncthreads();
     ADA_CLK_LAST(10);
     // step 5: an inherited representative with a hit from an earlier inherited one is removed.  The list is checked
@@ -902,24 +903,41 @@ __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q
     // Lanes of a wave hold 64 consecutive list positions, so a ballot is two words of the validity mask.
     int ok = 1;
     if (r_ok) {
-        for (int j = tid; j < r; j += THREADS) {
-            const int q = j < THREADS ? q0 : list_at(p, j);
-            const int qp = j < THREADS ? qp0 : list_at(p, j - 1);
-            if (q < 0 || q >= T || (j > 0 && !(qp < q))) ok = 0;
-            const int tok = min(max(q, 0), T - 1);
-            uint32_t any = 0u;
-            for (int w0 = 0; w0 < Wa; w0 += WU) {
-                uint32_t x[WU];
+        // two list entries per thread and round (j and j + THREADS), with the words of both requested before either is
+        // used: the scattered loads are trips to memory, and this halves their number
+        for (int j0 = 0; j0 < r; j0 += 2 * THREADS) {
+            int tok[2];
+            bool have[2];
 #pragma unroll
-                for (int v = 0; v < WU; ++v) x[v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + tok];
-#pragma unroll
-                for (int v = 0; v < WU; ++v) any |= (w0 + v < Wa) ? x[v] : 0u;
+            for (int e = 0; e < 2; ++e) {
+                const int j = j0 + e * THREADS + tid;
+                have[e] = j < r;
+                const int q = !have[e] ? 0 : (j < THREADS ? q0 : list_at(p, j));
+                const int qp = !have[e] || j == 0 ? -1 : (j < THREADS ? qp0 : list_at(p, j - 1));
+                if (have[e] && (q < 0 || q >= T || !(qp < q))) ok = 0;
+                tok[e] = min(max(q, 0), T - 1);
             }
-            flag[tok] = any ? 1 : 3;
-            const unsigned long long valid = __ballot(any == 0u);            // lanes past the list are inactive: 0
-            if (lane == 0) {
-                vmask[j >> 5] = (uint32_t)valid;
-                if ((j >> 5) + 1 < Wa) vmask[(j >> 5) + 1] = (uint32_t)(valid >> 32);
+            uint32_t any[2] = {0u, 0u};
+            for (int w0 = 0; w0 < Wa; w0 += WU) {
+                uint32_t x[2][WU];
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int v = 0; v < WU; ++v) x[e][v] = p.hits[(size_t)min(w0 + v, Wa - 1) * T + tok[e]];
+#pragma unroll
+                for (int e = 0; e < 2; ++e)
+#pragma unroll
+                    for (int v = 0; v < WU; ++v) any[e] |= (w0 + v < Wa) ? x[e][v] : 0u;
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int j = j0 + e * THREADS + tid;
+                if (have[e]) flag[tok[e]] = any[e] ? 1 : 3;
+                const unsigned long long valid = __ballot(have[e] && any[e] == 0u);   // 64 consecutive list positions
+                if (lane == 0 && j < r) {
+                    vmask[j >> 5] = (uint32_t)valid;
+                    if ((j >> 5) + 1 < Wa) vmask[(j >> 5) + 1] = (uint32_t)(valid >> 32);
+                }
             }
         }
     }
@@ -937,29 +955,41 @@ __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q
     ADA_CLK_LAST(12);
     // step 9: any other token with a hit on a VALID representative is covered
     if (vec) {
-        for (int t4 = tid; t4 < (T >> 2); t4 += THREADS) {                  // tokens 4 t4 .. 4 t4 + 3
-            u32x4 any = {0u, 0u, 0u, 0u};
-            for (int w0 = 0; w0 < Wa; w0 += WU) {
-                u32x4 x[WU];
-                if (t4 == tid && w0 == 0) {                                  // uniform: the batch fetched up front
+        // Work items (four tokens, one batch of WU words), one after the other per thread; item k + 1 is requested
+        // before item k is used, so that the phase runs at the CU's load rate and not at one trip to memory per batch.
+        // Addresses are clamped and the values masked where they are used (nothing waits at a load).
+        const int T4 = T >> 2, nb = (Wa + WU - 1) / WU, n_it = (T4 + THREADS - 1) / THREADS, items = nb * n_it;
+        auto request = [&](u32x4 (&x)[WU], int k) {
+            const int it = k / nb, w0 = (k - it * nb) * WU;
+            const int t4 = min(tid + it * THREADS, T4 - 1);
 #pragma unroll
-                    for (int v = 0; v < WU; ++v) x[v] = pre[v];
-                } else {
+            for (int v = 0; v < WU; ++v) x[v] = *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(w0 + v, Wa - 1) * T + 4 * t4);
+        };
+        u32x4 any = {0u, 0u, 0u, 0u};
+        auto use = [&](const u32x4 (&x)[WU], int k) {
+            const int it = k / nb, b = k - it * nb, w0 = b * WU;
+            if (b == 0) any = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-                    for (int v = 0; v < WU; ++v)
-                        x[v] = *reinterpret_cast<const u32x4*>(p.hits + (size_t)min(w0 + v, Wa - 1) * T + 4 * t4);
-                }
+            for (int v = 0; v < WU; ++v) any |= x[v] & ((w0 + v < Wa) ? vmask[w0 + v] : 0u);
+            const int t4 = tid + it * THREADS;
+            if (b == nb - 1 && t4 < T4) {
+                uint32_t f4 = *reinterpret_cast<const uint32_t*>(flag + 4 * t4);
 #pragma unroll
-                for (int v = 0; v < WU; ++v) {
-                    const uint32_t vm = (w0 + v < Wa) ? vmask[w0 + v] : 0u;
-                    any |= x[v] & vm;
-                }
+                for (int u = 0; u < 4; ++u)
+                    if (((f4 >> (8 * u)) & 0xFFu) == 2u && any[u]) f4 &= ~(0xFFu << (8 * u));
+                *reinterpret_cast<uint32_t*>(flag + 4 * t4) = f4;
             }
-            uint32_t f4 = *reinterpret_cast<const uint32_t*>(flag + 4 * t4);
+        };
+        u32x4 xa[WU], xb[WU];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (((f4 >> (8 * u)) & 0xFFu) == 2u && any[u]) f4 &= ~(0xFFu << (8 * u));
-            *reinterpret_cast<uint32_t*>(flag + 4 * t4) = f4;
+        for (int v = 0; v < WU; ++v) xa[v] = pre[v];          // item 0 was requested before the validity pass
+        for (int k = 0; k < items; k += 2) {
+            if (k + 1 < items) request(xb, k + 1);
+            use(xa, k);
+            if (k + 1 < items) {
+                if (k + 2 < items) request(xa, k + 2);
+                use(xb, k + 1);
+            }
         }
     } else {
         for (int t = tid; t < T; t += THREADS) {
