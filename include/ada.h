@@ -321,6 +321,14 @@ int ada_cascade_layers_adaptive(const void* const* X_layers, int L, int T, int d
                                 void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
+ * Which tile shape a one-launch cascade step takes when `workgroups` workgroups share its tiles (the CU count for a
+ * single problem; that divided by the number of groups for a grouped call) and the rows come in whole aligned
+ * 128-byte chunks: 0 = 64 x 64, 1 = 64 representatives x 128 tokens, 2 = 128 x 128; -1 for arguments out of range.
+ * Host only (no device is touched): the same function the kernel evaluates with the set size it finds.
+ */
+int ada_plan_tile_shape(int r, int T, int d, int workgroups);
+
+/*
  * |A n B| and |A u B| of two representative sets given as uint8 masks [T] (device), for the
  * Jaccard index of eq. (3).  out: device int32 [2] = {intersection, union}.
  */

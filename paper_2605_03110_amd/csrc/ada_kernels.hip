@@ -1678,6 +1678,11 @@ int ada_cascade_layers_adaptive(const void* const* X_layers, int L, int T, int d
     return e;
 }
 
+int ada_plan_tile_shape(int r, int T, int d, int workgroups) {
+    if (r < 1 || T < 1 || r > T || d < 1 || workgroups < 1) return -1;
+    return cascade_tile_shape(r, T, d, workgroups, workgroups);
+}
+
 int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t* out, void* stream) {
     if (!mask_a || !mask_b || !out) return ADA_ERR_NULL;
     if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;
