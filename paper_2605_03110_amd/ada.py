@@ -263,9 +263,11 @@ def ada_assign_nearest(X: torch.Tensor, idx: torch.Tensor, r: Optional[int] = No
 
 def ada_attention_compressed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, H: int, idx: torch.Tensor,
                              assign: torch.Tensor, r: Optional[int] = None, r_dev: Optional[torch.Tensor] = None, *,
-                             ws: Optional[torch.Tensor] = None, stream=None, flags: int = 0) -> Dict[str, torch.Tensor]:
+                             ws: Optional[torch.Tensor] = None, stream=None, flags: int = 0,
+                             out: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
     """Attention on the representative set (eq. (1)) with every token taking its representative's output row.
-    Q, K, V: device T x (H * d_h), same dtype and strides.  Returns device tensors out[T, H * d_h] (float32) and
+    Q, K, V: device T x (H * d_h), same dtype and strides.  Returns device tensors out[T, H * d_h] (float32; the
+    caller's `out`, a float32 T x (H * d_h) view with unit column stride, if one is given) and
     info[4] = {|R|, 0, 0, status}."""
     for M in (Q, K, V):
         _check_x(M)
@@ -286,10 +288,15 @@ def ada_attention_compressed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, 
         raise ValueError("r exceeds the capacity of idx")
     dev = Q.device
     ws = workspace(T, dev) if ws is None else ws
-    out = dict(out=torch.empty((T, D), dtype=torch.float32, device=dev),
-               info=torch.empty(4, dtype=torch.int32, device=dev))
+    if out is None:
+        out = torch.empty((T, D), dtype=torch.float32, device=dev)
+    elif (out.dtype != torch.float32 or out.device != dev or tuple(out.shape) != (T, D) or out.stride(1) != 1
+          or out.stride(0) < D):
+        raise ValueError("out must be a float32 T x (H * d_h) device view with unit column stride")
+    out = dict(out=out, info=torch.empty(4, dtype=torch.int32, device=dev))
     rc = lib().ada_attention_compressed(_ptr(Q), _ptr(K), _ptr(V), T, int(H), D // int(H), Q.stride(0), _dtype_code(Q),
-                                        _ptr(idx), r, _ptr(r_dev), _ptr(assign), _ptr(out["out"]), D, _ptr(out["info"]),
+                                        _ptr(idx), r, _ptr(r_dev), _ptr(assign), _ptr(out["out"]), out["out"].stride(0),
+                                        _ptr(out["info"]),
                                         _ptr(ws), ws.numel(), _stream(stream), int(flags))
     if rc != OK:
         raise AdaError(rc, "ada_attention_compressed")

@@ -997,8 +997,38 @@ hipError_t dispatch(int dtype, const void* X, long long ld, int d, F&& f) {
     return al ? f(Variant<float, true>{}) : f(Variant<float, false>{});
 }
 
+// bf16: the kernel that keeps scores and weights in registers
+template <int DH>
+hipError_t launch_attn_regs(const AttnParams& p, hipStream_t st) {
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    constexpr int lds = AttnGeom2<DH>::LDS;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_rep2<DH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    ProfScope ps(ADA_K_ATTN, st);
+    int gx = (p.r_host + 63) / 64;
+    if (p.r_dev) {
+        const int fit = (device_cus() + p.H - 1) / p.H;
+        gx = gx < fit ? gx : fit;
+    }
+    hipLaunchKernelGGL((k_attn_rep2<DH>), dim3(gx, p.H), dim3(256), lds, st, p);
+    return hipGetLastError();
+}
+
 template <typename In, int DH>
 hipError_t launch_attn(const AttnParams& p, hipStream_t st) {
+    if constexpr (sizeof(In) == 2) {
+        static const bool first_kernel = [] {             // development switch: ADA_ATTN=lds keeps the first kernel
+            const char* e = getenv("ADA_ATTN");
+            return e && std::string(e) == "lds";
+        }();
+        // its hand-over stores 16 bytes per lane
+        const bool out16 = (uintptr_t)p.out % 16 == 0 && p.ld_out % 4 == 0;
+        if (!first_kernel && out16) return launch_attn_regs<DH>(p, st);
+    }
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     constexpr int lds = AttnGeom<In, DH>::LDS;

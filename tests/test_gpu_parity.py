@@ -1097,6 +1097,68 @@ def test_attention_with_device_side_set_size_loops_over_query_blocks():
                            "looping grid")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_long_sequence_hands_over_in_chunks(causal):
+    """T = 4500: the hand-over reads the tokens' positions 2048 at a time (three rounds), five key blocks."""
+    say("attention T=4500 causal=%s" % causal)
+    attention_case(4500, 256, 2, 300, "bf16", 91, causal, "attention T=4500")
+
+
+@pytest.mark.parametrize("gain", [16.0, 64.0])
+def test_attention_with_steep_scores_moves_the_reference(gain):
+    """Queries scaled by a power of two (exact in bf16): scores spread over tens to hundreds of units, so later key
+    blocks pass the reference of the running weights by more than its slack and the accumulated rows are rescaled;
+    the softmax is close to a hard maximum.  A score of size |s| summed over d_h fp32 terms carries up to
+    d_h 2^-24 |s| of rounding, which the exponential turns into that much relative error of a weight: the bar grows
+    by that amount (a lost or doubled rescale would be off by the size of V itself)."""
+    say("attention steep scores x%g" % gain)
+    w = wl.small(T=900, d=512, K=400, L=1, dtype="bf16", seed=23, p=0.1)
+    x = wl.layer_list(w)[0]
+    q, k, v = wl.qkv(w, 2)
+    q = (q.float() * gain).to(q.dtype)
+    full = pa.fetch(pa.ada_select_full(x.to(DEV), w.tau))
+    assert full["r"] > 256                                         # more than four key blocks
+    idx = torch.as_tensor(full["idx"]).to(DEV)
+    near = pa.ada_assign_nearest(x.to(DEV), idx)
+    rows = np.asarray(full["idx"][:full["r"]])
+    d_h = 256
+    smax = max(float(np.abs(wl.as_f64(q)[rows, h * d_h:(h + 1) * d_h] @ wl.as_f64(k)[rows, h * d_h:(h + 1) * d_h].T).max())
+               for h in range(2)) / np.sqrt(d_h)
+    assert smax > 60.0
+    vmax = float(np.abs(wl.as_f64(v)).max())
+    tol = (parity.ATTN_TOL + smax * d_h * 2.0 ** -24) * max(1.0, vmax)
+    for causal in (False, True):
+        res = pa.ada_attention_compressed(q.to(DEV), k.to(DEV), v.to(DEV), 2, idx, near["assign"],
+                                          flags=pa.FLAG_ATTN_CAUSAL if causal else 0)
+        assert res["info"].cpu().tolist() == [full["r"], 0, 0, 0]
+        ref = oracle.attention_compressed(wl.as_f64(q), wl.as_f64(k), wl.as_f64(v), 2, full["idx"],
+                                          near["assign"].cpu().numpy(), flags=oracle.ATTN_CAUSAL if causal else 0)
+        err = float(np.abs(res["out"].cpu().numpy().astype(np.float64) - ref).max())
+        assert err <= tol, "steep scores x%g causal=%s: error %.3g, bar %.3g" % (gain, causal, err, tol)
+
+
+def test_attention_into_a_strided_unaligned_output():
+    """An output view whose rows start at odd float offsets (the vector stores of the bf16 kernel do not apply: the
+    general kernel runs) gives the same rows as the contiguous output, and leaves the padding alone."""
+    say("attention strided output")
+    w = wl.small(T=400, d=256, K=60, L=1, dtype="bf16", seed=12, p=0.1)
+    x = wl.layer_list(w)[0]
+    q, k, v = (m.to(DEV) for m in wl.qkv(w, 2))
+    sel = pa.ada_select_full(x.to(DEV), w.tau)
+    r = int(sel["counts"][0].item())
+    idx = sel["idx"][:r].clone()
+    near = pa.ada_assign_nearest(x.to(DEV), idx)
+    ref = pa.ada_attention_compressed(q, k, v, 2, idx, near["assign"])
+    big = torch.full((w.T, 256 + 3), -7.0, dtype=torch.float32, device=DEV)
+    view = big[:, 1:257]
+    got = pa.ada_attention_compressed(q, k, v, 2, idx, near["assign"], out=view)
+    assert got["info"].cpu().tolist() == ref["info"].cpu().tolist()
+    assert np.abs(view.cpu().numpy() - ref["out"].cpu().numpy()).max() <= parity.ATTN_TOL * max(1.0, float(v.float().abs().max()))
+    assert bool((big[:, 0] == -7.0).all()) and bool((big[:, 257:] == -7.0).all())
+    parity.check_attention(q.cpu(), k.cpu(), v.cpu(), 2, idx.cpu().numpy(), near["assign"].cpu().numpy(),
+                           view.cpu().numpy(), False, "strided output")
+
+
 def test_attention_rejects_bad_sets_and_assignments():
     say("attention bad input")
     w = wl.small(T=200, d=128, K=20, L=1, dtype="bf16", seed=3)
