@@ -312,7 +312,7 @@ def main():
             att_flops = 4.0 * r_last * r_last * d              # two r x r x d_h products per head
             result["attention_compressed"] = {
                 "avg_launch_us": us_t, "r": r_last, "heads": Hh, "d_h": d // Hh,
-                "roofline": {"bound": "hbm", "kernel": "k_attn_rep (eq. (1) + hand-over)",
+                "roofline": {"bound": "hbm", "kernel": "k_attn_rep2 (eq. (1) + hand-over)",
                              "achieved": att_bytes / (1e-6 * us_t) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": att_bytes / (1e-6 * us_t) / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": att_bytes,
                              "mfma_tflops": att_flops / (1e-6 * us_t) / 1e12, "traffic": None}}
