@@ -59,7 +59,7 @@ def recorded_traffic(name):
 
 def probe(pa, xs, w, ws, out, stream):
     """Short run for hardware counters: one cascade pass, full selection on four layers and twice at the long-context
-    shape, and the 256 MiB copy probe."""
+    shape, two assignments and two attention launches on the last layer's set, and the 256 MiB copy probe."""
     import torch
     pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out, stream=stream)
     for l in range(4):
@@ -70,6 +70,16 @@ def probe(pa, xs, w, ws, out, stream):
     ws4 = pa.workspace(w4.T, xs[0].device)
     for _ in range(2):
         pa.ada_select_full(x4, w4.tau, ws=ws4, stream=stream)
+    # the last layer's set: two assignment launches (the last two k_cascade_fused of the run) and two attention launches
+    L = len(xs)
+    if w.d % 16 == 0 and w.d // 16 in (64, 128, 256) and w.dtype == "bf16":
+        last = out["idx"][L - 1]
+        qd, kd, vd = (m.to(xs[0].device) for m in wl.qkv(w, 16))
+        for _ in range(2):
+            near = pa.ada_assign_nearest(xs[L - 1], last, r=w.T, r_dev=out["counts"][L - 1], ws=ws, stream=stream)
+        for _ in range(2):
+            pa.ada_attention_compressed(qd, kd, vd, 16, last, near["assign"], r=w.T, r_dev=out["counts"][L - 1], ws=ws,
+                                        stream=stream)
     src = torch.empty(256 << 20, dtype=torch.uint8, device=xs[0].device).fill_(1)
     dst = torch.empty_like(src)
     for _ in range(2):
@@ -283,7 +293,8 @@ def main():
                                     "roofline": {"bound": "hbm", "kernel": "k_cascade_fused (arg-max epilogue)",
                                                  "achieved": layer_bytes / (1e-6 * us_a) / 1e9, "peak": HBM_PEAK_GBS,
                                                  "unit": "GB/s", "frac": layer_bytes / (1e-6 * us_a) / 1e9 / HBM_PEAK_GBS,
-                                                 "bytes_per_launch": layer_bytes, "traffic": None}}
+                                                 "bytes_per_launch": layer_bytes,
+                                                 "traffic": recorded_traffic("assign_c%d_pmc.txt" % args.config)}}
 
         # ---- attention on the representative set (eq. (1)) for the last layer's set, 16 heads of d/16, with the
         # hand-over to all T tokens; synthetic Q, K, V
@@ -315,7 +326,8 @@ def main():
                 "roofline": {"bound": "hbm", "kernel": "k_attn_rep2 (eq. (1) + hand-over)",
                              "achieved": att_bytes / (1e-6 * us_t) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": att_bytes / (1e-6 * us_t) / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": att_bytes,
-                             "mfma_tflops": att_flops / (1e-6 * us_t) / 1e12, "traffic": None}}
+                             "mfma_tflops": att_flops / (1e-6 * us_t) / 1e12,
+                             "traffic": recorded_traffic("attention_c%d_pmc.txt" % args.config)}}
 
             # ---- every layer: selection, assignment, attention on the representative set (Section 8.4's pipeline).
             # The same synthetic Q, K, V serve all layers; the selection runs on its own stream beside the attention.
