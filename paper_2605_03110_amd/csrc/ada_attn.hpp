@@ -386,7 +386,7 @@ template <int DH> struct AttnGeom2 {
     static constexpr int ROWB = DH * 2, PPR = ROWB / 16, PPRV = 8;
     static constexpr int KSTAGE = 64 * ROWB;                                           // K: two stages (even and odd key blocks)
     static constexpr int OFF_Q = 0, OFF_K = 64 * ROWB, OFF_VT = 3 * 64 * ROWB;        // V^T: DH rows of 128 bytes
-    static constexpr int OS = DH + 1;                                                  // padded row of the output block
+    static constexpr int OS = DH + 4;      // row of the output block: 16-byte accesses, consecutive rows one slot apart
     static constexpr int OFF_TAKERS = (64 * OS * 4 + 15) / 16 * 16;                    // behind the output block
     static constexpr int MAIN = (4 * 64 * ROWB > OFF_TAKERS + 2048 * 4) ? 4 * 64 * ROWB : OFF_TAKERS + 2048 * 4;
     static constexpr int OFF_ROW = MAIN;                                               // qtok[64], ktok[64], m[2][64], l[2][64]
@@ -581,6 +581,15 @@ __global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
         }
     }
     ATTN_CLK(6);
+    int rel[8];                                            // hand-over: positions of 2048 tokens, relative to this block
+    auto load_rel = [&](int tb) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int t = tb + u * 256 + tid;
+            rel[u] = t < p.T ? p.pos[t] - q0 : -1;
+        }
+    };
+    load_rel(0);                                           // in flight behind the merge
     // ---- the two waves of a query block hold sums over different keys: exchange (m, l), bring both to the common
     // maximum and the common denominator, and add the second wave's rows onto the first's in the output block
     if (half == 0) { mrow[kh * 64 + my_q] = m_run; lrow[kh * 64 + my_q] = l_run; }
@@ -601,8 +610,10 @@ __global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
             for (int i = 0; i < NB / 2; ++i) {
                 const int blk = (1 - KH) * (NB / 2) + i;   // given away
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    obuf[my_q * G::OS + 32 * blk + (e & 3) + 4 * half + 8 * (e >> 2)] = acc_o[blk][e] * f;
+                for (int q = 0; q < 4; ++q)                // registers 4 q .. 4 q + 3 are four consecutive columns
+                    *reinterpret_cast<float4*>(obuf + my_q * G::OS + 32 * blk + 8 * q + 4 * half) =
+                        float4{acc_o[blk][4 * q] * f, acc_o[blk][4 * q + 1] * f, acc_o[blk][4 * q + 2] * f,
+                               acc_o[blk][4 * q + 3] * f};
             }
         };
         auto finish = [&](auto khc) {
@@ -611,8 +622,12 @@ __global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
             for (int i = 0; i < NB / 2; ++i) {
                 const int blk = KH * (NB / 2) + i;         // finished here
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    obuf[my_q * G::OS + 32 * blk + (e & 3) + 4 * half + 8 * (e >> 2)] += acc_o[blk][e] * f;
+                for (int q = 0; q < 4; ++q) {
+                    float4* at = reinterpret_cast<float4*>(obuf + my_q * G::OS + 32 * blk + 8 * q + 4 * half);
+                    const float4 o = *at;
+                    *at = float4{o.x + acc_o[blk][4 * q] * f, o.y + acc_o[blk][4 * q + 1] * f,
+                                 o.z + acc_o[blk][4 * q + 2] * f, o.w + acc_o[blk][4 * q + 3] * f};
+                }
             }
         };
         if (kh == 0) give(std::integral_constant<int, 0>{}); else give(std::integral_constant<int, 1>{});
@@ -626,35 +641,37 @@ __global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
     // (d_h floats) per store instruction.
     float* outh = p.out + (size_t)h * DH;
     for (int tb = 0; tb < p.T; tb += 8 * 256) {
-        int rel[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int t = tb + u * 256 + tid;
-            rel[u] = t < p.T ? p.pos[t] - q0 : -1;
-        }
+        if (tb > 0) load_rel(tb);                          // (the first 2048 were asked for before the merge)
         if (tid == 0) list[0] = 0;
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < 8; ++u)
             if ((unsigned)rel[u] < 64u) takers[atomicAdd(&list[0], 1)] = ((tb + u * 256 + tid) << 6) | rel[u];
         __syncthreads();
+        ATTN_CLK(5);
         const int n = list[0];
         constexpr int LPR = DH / 4, RPI = 64 / LPR;        // lanes per row (a float4 each), rows per instruction
         const int sub = lane / LPR, c4 = (lane % LPR) * 4;
-        for (int j0 = wave * RPI + sub; j0 < n; j0 += 4 * 4 * RPI) {          // four rows in flight per lane group
-            int ent[4];
+        // a wave's share of the list (entries wave * RPI + sub + 4 RPI k) is read 64 entries at a time, one per lane,
+        // and handed to the lane groups by lane reads; eight rows are in flight per lane group
+        constexpr int KPB = 64 / RPI;                      // steps k per batch
+        const int steps = (n - wave * RPI + 4 * RPI - 1) / (4 * RPI);             // k with a first entry below n
+        for (int k0 = 0; k0 < steps; k0 += KPB) {
+            const int mine = takers[min(wave * RPI + (lane % RPI) + 4 * RPI * (k0 + lane / RPI), n - 1)];
+            const int kend = min(KPB, steps - k0);
+            for (int kk = 0; kk < kend; kk += 8) {
+                int ent[8];
+                float4 v4[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) ent[u] = takers[min(j0 + u * 4 * RPI, n - 1)];
-            float4 v4[4];
+                for (int u = 0; u < 8; ++u) ent[u] = __shfl(mine, min(kk + u, KPB - 1) * RPI + sub, 64);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float* src = obuf + (ent[u] & 63) * G::OS + c4;
-                v4[u] = float4{src[0], src[1], src[2], src[3]};
+                for (int u = 0; u < 8; ++u)
+                    v4[u] = *reinterpret_cast<const float4*>(obuf + (ent[u] & 63) * G::OS + c4);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (kk + u < kend && wave * RPI + sub + 4 * RPI * (k0 + kk + u) < n)
+                        *reinterpret_cast<float4*>(outh + (size_t)(ent[u] >> 6) * (size_t)p.ld_out + c4) = v4[u];
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (j0 + u * 4 * RPI < n)
-                    *reinterpret_cast<float4*>(outh + (size_t)(ent[u] >> 6) * (size_t)p.ld_out + c4) = v4[u];
         }
         __syncthreads();
     }
