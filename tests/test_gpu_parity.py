@@ -1104,6 +1104,28 @@ def test_attention_long_sequence_hands_over_in_chunks(causal):
     attention_case(4500, 256, 2, 300, "bf16", 91, causal, "attention T=4500")
 
 
+def test_attention_one_representative_owns_every_token():
+    """One cluster, T = 3000: |R| = 1, so one workgroup per head hands its single row to all 3000 tokens (full lists of
+    2048 takers, then 952), and the wave that owns the upper key half never sees a valid key."""
+    say("attention, one representative for 3000 tokens")
+    w = wl.small(T=3000, d=256, K=1, L=1, dtype="bf16", seed=8, p=0.0)
+    x = wl.layer_list(w)[0]
+    q, k, v = wl.qkv(w, 2)
+    full = pa.fetch(pa.ada_select_full(x.to(DEV), w.tau))
+    assert full["r"] == 1
+    idx = torch.as_tensor(full["idx"]).to(DEV)
+    near = pa.ada_assign_nearest(x.to(DEV), idx)
+    for causal in (False, True):
+        res = pa.ada_attention_compressed(q.to(DEV), k.to(DEV), v.to(DEV), 2, idx, near["assign"],
+                                          flags=pa.FLAG_ATTN_CAUSAL if causal else 0)
+        assert res["info"].cpu().tolist() == [1, 0, 0, 0]
+        out = res["out"].cpu().numpy()
+        parity.check_attention(q, k, v, 2, full["idx"], near["assign"].cpu().numpy(), out, causal, "one representative")
+        assert np.array_equal(out, np.broadcast_to(out[0], out.shape))      # every token holds the same row, bit for bit
+        # softmax over one key: the row is that key's value row exactly
+        assert np.array_equal(out[0], wl.as_f64(v)[int(full["idx"][0])].astype(np.float32))
+
+
 @pytest.mark.parametrize("gain", [16.0, 64.0])
 def test_attention_with_steep_scores_moves_the_reference(gain):
     """Queries scaled by a power of two (exact in bf16): scores spread over tens to hundreds of units, so later key
