@@ -171,11 +171,13 @@ int ada_assign_nearest(const void* X, int T, int d, int64_t ld, int dtype,
  *   idx, r, r_dev   the set R as for ada_assign_nearest
  *   assign   [T] int32, the representative of every token (the output of ada_assign_nearest for the same R)
  * Outputs
- *   out   [T x (H * d_h)] float, leading dimension ld_out (elements)
+ *   out   [T x (H * d_h)] float, leading dimension ld_out (elements), any alignment (a 16-byte aligned base with
+ *         ld_out a multiple of 4 lets the bf16 kernel store whole rows per instruction)
  *   info  [4] int32  {|R|, 0, 0, status}; status is ADA_OK, or ADA_ERR_INDEX (idx not strictly ascending / out of
  *                    range, or an assign entry that is not a member of R) / ADA_ERR_SHAPE (bad r_dev), and then out
  *                    is not written
- * Scores and weights are fp32 (row maxima subtracted); bf16 weights enter the second product as hi + lo pairs.
+ * Scores and weights are fp32 (a per-row reference close to the running maximum subtracted, so no weight exceeds
+ * 2^10); bf16 weights enter the second product as hi + lo pairs.
  * ADA_FLAG_ATTN_CAUSAL masks later members of R.  Three small launches (status clear, positions, attention).
  */
 int ada_attention_compressed(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
