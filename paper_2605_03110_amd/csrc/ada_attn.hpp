@@ -491,6 +491,10 @@ __global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
     fetch(0);
     ids(1);
     ATTN_CLK(1);
+    // The query operands of the first eight k-steps stay in registers (this lane's query row); the rest is read from
+    // LDS in every block: the score product is bound by LDS reads, and the register file has no room for more.
+    constexpr int QREG = KS < 8 ? KS : 8;
+    u32x4 qf[QREG];
     for (int kb = 0; kb < nkb; ++kb) {
         // the previous block's products are done with V^T and with the K stage the next fetch writes; this block's K
         // has landed in LDS and its V in registers (the barrier's fence waits for both)
@@ -501,15 +505,21 @@ __global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
         __syncthreads();
         if (kb == 1) ATTN_CLK(3);
         if (kb + 1 < nkb) { fetch((kb + 1) & 1); ids(kb + 2); }                   // in flight behind this block's products
+        if (kb == 0) {                                     // (Q was staged before the first pair of barriers)
+#pragma unroll
+            for (int ks = 0; ks < QREG; ++ks)
+                qf[ks] = *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
+        }
         const char* kcur = kbuf + (kb & 1) * G::KSTAGE;
         // ---- S^T = K Q^T: this wave's 32 keys (half kh of the block) against its 32 queries
         f32x16 acc_s;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc_s[e] = 0.f;
-#pragma unroll 4
+#pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const u32x4 fq = *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
             const u32x4 fk = *reinterpret_cast<const u32x4*>(kcur + attn_off(kh * 32 + l32, 2 * ks + half, PPR));
+            const u32x4 fq = ks < QREG ? qf[ks < QREG ? ks : 0]
+                                       : *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
             Mfma<In>::run(acc_s, fk, fq);
         }
         // ---- weights of this lane's query (register e is key 32 kh + (e & 3) + 4 half + 8 (e >> 2)), in base 2:
