@@ -178,7 +178,7 @@ int ada_assign_nearest(const void* X, int T, int d, int64_t ld, int dtype,
  *                    is not written
  * Scores and weights are fp32 (a per-row reference close to the running maximum subtracted, so no weight exceeds
  * 2^10); bf16 weights enter the second product as hi + lo pairs.
- * ADA_FLAG_ATTN_CAUSAL masks later members of R.  Three small launches (status clear, positions, attention).
+ * ADA_FLAG_ATTN_CAUSAL masks later members of R.  Two launches (positions and validation, attention).
  */
 int ada_attention_compressed(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
                              const int32_t* idx, int r, const int32_t* r_dev, const int32_t* assign,

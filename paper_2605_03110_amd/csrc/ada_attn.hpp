@@ -27,37 +27,57 @@ struct AttnParams {
     long long ld_out;
     float scale;               // 1 / sqrt(d_h)
     int causal;
-    int32_t* info;             // [4]; info[3] holds the status (k_attn_pos)
+    int32_t* info;             // [4]: written by workgroup (0, 0) of the attention kernel
+    const int32_t* err;        // [nerr] one status word per workgroup of k_attn_pos
+    int nerr;
 };
 
 // position of every token's representative in R, by binary search; validates R (strictly ascending, in range) and
-// assign (a member of R).  info[3] was zeroed by the launcher; any thread that sees a fault raises it.
+// assign (a member of R).  Every workgroup leaves ONE status word (its own, written whatever it found: nothing has
+// to be cleared beforehand); the attention kernel reads them all.
 __global__ __launch_bounds__(256) void k_attn_pos(const int32_t* __restrict__ idx, const int32_t* r_dev, int r_host,
                                                   const int32_t* __restrict__ assign, int T, int32_t* __restrict__ pos,
-                                                  int32_t* info) {
+                                                  int32_t* __restrict__ err) {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    int r = r_dev ? *r_dev : r_host;
-    const bool r_ok = r >= 1 && r <= r_host && r <= T;
+    const int r = r_dev ? *r_dev : r_host;
+    const bool r_ok = r >= 1 && r <= r_host && r <= T;         // the same for every thread of the launch
+    int bad = 0;
     if (!r_ok) {
-        if (i == 0) { info[0] = 0; atomicMax(info + 3, (int)ADA_ERR_SHAPE); }
         if (i < T) pos[i] = 0;
-        return;
-    }
-    if (i == 0) info[0] = r;
-    if (i < r) {
-        const int q = idx[i];
-        if (q < 0 || q >= T || (i > 0 && !(idx[i - 1] < q))) atomicMax(info + 3, (int)ADA_ERR_INDEX);
-    }
-    if (i < T) {
-        const int a = assign[i];
-        int lo = 0, hi = r - 1;
-        while (lo < hi) {                                  // first position with idx[pos] >= a
-            const int mid = (lo + hi) >> 1;
-            if (idx[mid] < a) lo = mid + 1; else hi = mid;
+    } else {
+        if (i < r) {
+            const int q = idx[i];
+            if (q < 0 || q >= T || (i > 0 && !(idx[i - 1] < q))) bad = 1;
         }
-        if (idx[lo] != a) atomicMax(info + 3, (int)ADA_ERR_INDEX);
-        pos[i] = lo;
+        if (i < T) {
+            const int a = assign[i];
+            int lo = 0, hi = r - 1;
+            while (lo < hi) {                              // first position with idx[pos] >= a
+                const int mid = (lo + hi) >> 1;
+                if (idx[mid] < a) lo = mid + 1; else hi = mid;
+            }
+            if (idx[lo] != a) bad = 1;
+            pos[i] = lo;
+        }
     }
+    bad = __syncthreads_or(bad);
+    if (threadIdx.x == 0) err[blockIdx.x] = !r_ok ? (int)ADA_ERR_SHAPE : bad ? (int)ADA_ERR_INDEX : (int)ADA_OK;
+}
+
+// The status of the call (the worst word k_attn_pos left), the same in every thread; workgroup (0, 0) reports it.
+__device__ inline int attn_status(const AttnParams& p, int r) {
+    const int lane = threadIdx.x & 63;
+    int e = 0;
+    for (int i = lane; i < p.nerr; i += 64) e = max(e, p.err[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) e = max(e, __shfl_xor(e, o, 64));
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        p.info[0] = e == (int)ADA_ERR_SHAPE ? 0 : r;
+        p.info[1] = 0;
+        p.info[2] = 0;
+        p.info[3] = e;
+    }
+    return e;
 }
 
 // Workgroup -> (head, first query block).  Workgroups go to the eight XCDs in turn by their linear index, and every
@@ -123,8 +143,8 @@ __global__ __launch_bounds__(256) void k_attn_rep(AttnParams p) {
     int* list = reinterpret_cast<int*>(lds + G::OFF_LIST);
 
     ATTN_CLK(0);
-    if (p.info[3] != ADA_OK) return;                       // k_attn_pos rejected the set or the assignment
     const int r = p.r_dev ? *p.r_dev : p.r_host;
+    if (attn_status(p, r) != ADA_OK) return;               // k_attn_pos rejected the set or the assignment
     const AttnWho who = attn_who(p.H);
     const int h = who.h;
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
@@ -410,8 +430,8 @@ __global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
     int* list = reinterpret_cast<int*>(lds + G::OFF_LIST);                 // the takers' counter
     int* takers = reinterpret_cast<int*>(lds + G::OFF_TAKERS);            // up to 2048 (token, row) pairs
 
-    if (p.info[3] != ADA_OK) return;                       // k_attn_pos rejected the set or the assignment
     const int r = p.r_dev ? *p.r_dev : p.r_host;
+    if (attn_status(p, r) != ADA_OK) return;               // k_attn_pos rejected the set or the assignment
     const AttnWho who = attn_who(p.H);
     const int h = who.h;
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;

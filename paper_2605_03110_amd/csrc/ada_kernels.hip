@@ -1405,12 +1405,13 @@ int ada_attention_compressed(const void* Q, const void* K, const void* V, int T,
     if (ws_bytes < ws_bytes_for(T) || ((uintptr_t)ws % 256) != 0) return ADA_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const Workspace w = carve(ws, T);
-    if (fill_u32(info, 4, 0u, st) != hipSuccess) return ADA_ERR_DEVICE;
-    const int n = T > r ? T : r;
-    hipLaunchKernelGGL(k_attn_pos, dim3((n + 255) / 256), dim3(256), 0, st, idx, r_dev, r, assign, T, w.nonrep_idx, info);
+    // positions and validation; its workgroups' status words go to the (otherwise unused) row-maximum array
+    const int nerr = (T + 255) / 256;                      // (r <= T)
+    int32_t* err = reinterpret_cast<int32_t*>(w.gamma);
+    hipLaunchKernelGGL(k_attn_pos, dim3(nerr), dim3(256), 0, st, idx, r_dev, r, assign, T, w.nonrep_idx, err);
     if (hipGetLastError() != hipSuccess) return ADA_ERR_DEVICE;
     const AttnParams p = {Q, K, V, ld, T, H, idx, r_dev, r, w.nonrep_idx, out, ld_out,
-                          (float)(1.0 / sqrt((double)d_h)), (flags & ADA_FLAG_ATTN_CAUSAL) ? 1 : 0, info};
+                          (float)(1.0 / sqrt((double)d_h)), (flags & ADA_FLAG_ATTN_CAUSAL) ? 1 : 0, info, err, nerr};
     hipError_t e;
     if (dtype == ADA_BF16)
         e = d_h == 64 ? launch_attn<uint16_t, 64>(p, st) : d_h == 128 ? launch_attn<uint16_t, 128>(p, st)
