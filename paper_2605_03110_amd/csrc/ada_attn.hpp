@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void k_attn_pos(const int32_t* __restrict__ id
 // The status of the call (the worst word k_attn_pos left), the same in every thread; workgroup (0, 0) reports it.
 __device__ inline int attn_status(const AttnParams& p, int r) {
     const int lane = threadIdx.x & 63;
-    int e = 0;
+    int e = (r >= 1 && r <= p.r_host && r <= p.T) ? 0 : (int)ADA_ERR_SHAPE;   // (positions from elsewhere: nerr = 0)
     for (int i = lane; i < p.nerr; i += 64) e = max(e, p.err[i]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) e = max(e, __shfl_xor(e, o, 64));

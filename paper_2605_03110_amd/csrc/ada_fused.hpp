@@ -72,6 +72,10 @@ struct FusedParams {
     double* tau_out;
     float* thr_out;
     double kappa, eta_target, tau_min, tau_max;
+    // assignment: optional [T], the POSITION in R of every token's representative (what the attention's hand-over
+    // needs).  The arg-max keys then carry positions instead of token ids: R is ascending, so the order among equal
+    // cosines is the same.
+    int32_t* pos_out;
 };
 
 // Section 8.1's rule as read here: the turnover eta = (adds + removes) / r of the step just made (eq. (8)) moves tau
@@ -214,8 +218,9 @@ __device__ inline void finish_block(const FusedParams& p, const f32x16& tot, con
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float c = (fabsf(tot[4 * q + e]) * sc4[q][e]) * tsc;
+                const int who = p.pos_out ? word * 32 + 8 * q + 4 * half + e : tk4[q][e];   // (rows past r: c = 0)
                 const unsigned long long k = ((unsigned long long)__float_as_uint(c) << 32) |
-                                             (unsigned long long)(uint32_t)(INT_MAX - tk4[q][e]);
+                                             (unsigned long long)(uint32_t)(INT_MAX - who);
                 key = k > key ? k : key;
             }
         const unsigned long long other = ((unsigned long long)(uint32_t)__shfl_xor((int)(key >> 32), 32, 64) << 32) |
@@ -1047,7 +1052,14 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
     for (int t = tid; t < T; t += THREADS) {
         const unsigned long long key = p.best[t];
         p.best[t] = 0ull;
-        p.assign[t] = INT_MAX - (int)(uint32_t)key;
+        const int who = INT_MAX - (int)(uint32_t)key;
+        if (p.pos_out) {                                 // keys carry positions: the token id comes from the list
+            const int pos = r_ok ? min(max(who, 0), r - 1) : 0;
+            p.pos_out[t] = pos;
+            p.assign[t] = r_ok ? list_at(p, pos) : 0;
+        } else {
+            p.assign[t] = who;
+        }
         if (p.corr) p.corr[t] = __uint_as_float((uint32_t)(key >> 32));
     }
     int ok = 1;
@@ -1058,6 +1070,7 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
             const int qp = j < THREADS ? qp0 : list_at(p, j - 1);
             if (q < 0 || q >= T || (j > 0 && !(qp < q))) { ok = 0; continue; }
             p.assign[q] = q;
+            if (p.pos_out) p.pos_out[q] = j;
             if (p.corr) p.corr[q] = 1.0f;
         }
     }

@@ -1224,11 +1224,13 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
 }
 
 // Section 2.3 on the same tile engine: T x r products against the set R, per-token arg max.
+// pos: optional [T], the position in R of every token's representative (for the attention that follows)
 int run_assign(const void* X, int T, int d, long long ld, int dtype, const int32_t* idx, int r, const int32_t* r_dev,
-               int32_t* assign, float* corr, int32_t* info, void* ws, hipStream_t st) {
+               int32_t* assign, float* corr, int32_t* info, void* ws, hipStream_t st, int32_t* pos = nullptr) {
     const Workspace w = carve(ws, T);
-    const FusedParams p = {X, ld, T, d, idx, r_dev, r, 2.0f, 0, nullptr, 0, nullptr, w.meta + META_TICKET,
-                           nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr, 0, cascade_tile_pick()};
+    FusedParams p = {X, ld, T, d, idx, r_dev, r, 2.0f, 0, nullptr, 0, nullptr, w.meta + META_TICKET,
+                     nullptr, nullptr, nullptr, info, nullptr, 1, w.best, assign, corr, 0, cascade_tile_pick()};
+    p.pos_out = pos;
     return launch_fused_any(p, dtype, ADA_K_ASSIGN, st);
 }
 
@@ -1391,9 +1393,12 @@ int ada_select_full_grouped(const ada_groups* groups, const void* X, int T, int 
     return run_full(X, T, d, ld, dtype, tau, mask, idx, counts, nullptr, nullptr, ws, (hipStream_t)stream, G, go);
 }
 
-int ada_attention_compressed(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
-                             const int32_t* idx, int r, const int32_t* r_dev, const int32_t* assign, float* out,
-                             int64_t ld_out, int32_t* info, void* ws, size_t ws_bytes, void* stream, unsigned flags) {
+// pos_given: the positions of the tokens' representatives are already in the workspace's position array (left there
+// by the assignment of the same workspace): the position pass and its validation are skipped.
+static int attention_run(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
+                         const int32_t* idx, int r, const int32_t* r_dev, const int32_t* assign, float* out,
+                         int64_t ld_out, int32_t* info, void* ws, size_t ws_bytes, void* stream, unsigned flags,
+                         bool pos_given) {
     if (!Q || !K || !V || !idx || !assign || !out || !info || !ws) return ADA_ERR_NULL;
     if (dtype != ADA_F32 && dtype != ADA_BF16) return ADA_ERR_DTYPE;
     if (T < 1 || T > ADA_MAX_T || H < 1 || H > 65535 || r < 1 || r > T) return ADA_ERR_SHAPE;
@@ -1406,10 +1411,12 @@ int ada_attention_compressed(const void* Q, const void* K, const void* V, int T,
     hipStream_t st = (hipStream_t)stream;
     const Workspace w = carve(ws, T);
     // positions and validation; its workgroups' status words go to the (otherwise unused) row-maximum array
-    const int nerr = (T + 255) / 256;                      // (r <= T)
+    const int nerr = pos_given ? 0 : (T + 255) / 256;      // (r <= T)
     int32_t* err = reinterpret_cast<int32_t*>(w.gamma);
-    hipLaunchKernelGGL(k_attn_pos, dim3(nerr), dim3(256), 0, st, idx, r_dev, r, assign, T, w.nonrep_idx, err);
-    if (hipGetLastError() != hipSuccess) return ADA_ERR_DEVICE;
+    if (!pos_given) {
+        hipLaunchKernelGGL(k_attn_pos, dim3(nerr), dim3(256), 0, st, idx, r_dev, r, assign, T, w.nonrep_idx, err);
+        if (hipGetLastError() != hipSuccess) return ADA_ERR_DEVICE;
+    }
     const AttnParams p = {Q, K, V, ld, T, H, idx, r_dev, r, w.nonrep_idx, out, ld_out,
                           (float)(1.0 / sqrt((double)d_h)), (flags & ADA_FLAG_ATTN_CAUSAL) ? 1 : 0, info, err, nerr};
     hipError_t e;
@@ -1419,6 +1426,13 @@ int ada_attention_compressed(const void* Q, const void* K, const void* V, int T,
     else
         e = d_h == 64 ? launch_attn<float, 64>(p, st) : launch_attn<float, 128>(p, st);
     return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
+}
+
+int ada_attention_compressed(const void* Q, const void* K, const void* V, int T, int H, int d_h, int64_t ld, int dtype,
+                             const int32_t* idx, int r, const int32_t* r_dev, const int32_t* assign, float* out,
+                             int64_t ld_out, int32_t* info, void* ws, size_t ws_bytes, void* stream, unsigned flags) {
+    return attention_run(Q, K, V, T, H, d_h, ld, dtype, idx, r, r_dev, assign, out, ld_out, info, ws, ws_bytes, stream,
+                         flags, false);
 }
 
 int ada_assign_nearest(const void* X, int T, int d, int64_t ld, int dtype, const int32_t* idx, int r,
@@ -1659,12 +1673,13 @@ int ada_pipeline_layers(const void* const* X_layers, const void* const* Q_layers
         if (rc != ADA_OK) break;
         // layer l's assignment and attention wait for that set only; the selection stream goes on to layer l + 1
         if (!fork(ss, sa)) { rc = ADA_ERR_DEVICE; break; }
-        rc = ada_assign_nearest(X_layers[l], T, d, ld, dtype, idx_all + o, T, counts_all + (size_t)l * 4, assign_all + o,
-                                nullptr, info_all + (size_t)l * 8, ws_attn, one, sa, 0);
+        // the assignment also leaves every token's position in R where the attention looks for it: no position pass
+        rc = run_assign(X_layers[l], T, d, ld, dtype, idx_all + o, T, counts_all + (size_t)l * 4, assign_all + o, nullptr,
+                        info_all + (size_t)l * 8, ws_attn, sa, carve(ws_attn, T).nonrep_idx);
         if (rc != ADA_OK) break;
-        rc = ada_attention_compressed(Q_layers[l], K_layers[l], V_layers[l], T, H, d_h, ld, dtype, idx_all + o, T,
-                                      counts_all + (size_t)l * 4, assign_all + o, out_layers[l], ld_out,
-                                      info_all + (size_t)l * 8 + 4, ws_attn, one, sa, flags & ADA_FLAG_ATTN_CAUSAL);
+        rc = attention_run(Q_layers[l], K_layers[l], V_layers[l], T, H, d_h, ld, dtype, idx_all + o, T,
+                           counts_all + (size_t)l * 4, assign_all + o, out_layers[l], ld_out,
+                           info_all + (size_t)l * 8 + 4, ws_attn, one, sa, flags & ADA_FLAG_ATTN_CAUSAL, true);
     }
     // join: work enqueued on `stream` after the call sees everything (also after an error part-way)
     if (!fork(ss, main) || !fork(sa, main)) return ADA_ERR_DEVICE;
