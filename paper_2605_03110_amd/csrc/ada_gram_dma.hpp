@@ -202,9 +202,32 @@ __device__ inline int tri_row(long long v) {
     return n;
 }
 
-__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* queue) {
+// Definition "Gram threshold", last step, run by the workgroup that leaves the launch last (u.counts != NULL): the
+// row maxima are complete then, so the threshold test and the compaction need no launch of their own.
+__device__ inline void full_selection_finish(UpdateParams u, const float* gamma, int* sh /* 3 x 32 ints */) {
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int T = u.T;
+    const int chunk = (T + nthr - 1) / nthr;
+    const int lo = min(T, tid * chunk), hi = min(T, lo + chunk);
+    int c_idx = 0;
+    for (int t = lo; t < hi; ++t) c_idx += gamma[t] < u.thr;          // strict "<" of the Definition
+    int n_idx;
+    int o_idx = block_exclusive_scan(c_idx, &n_idx, sh);
+    for (int t = lo; t < hi; ++t) {
+        const bool keep = gamma[t] < u.thr;
+        if (u.mask) u.mask[t] = keep ? 1 : 0;
+        if (keep) { if (u.idx) u.idx[o_idx] = t; ++o_idx; }
+    }
+    if (tid == 0) {
+        u.counts[0] = n_idx; u.counts[1] = n_idx; u.counts[2] = 0; u.counts[3] = ADA_OK;
+        if (u.gram_ops) *u.gram_ops = (unsigned long long)T * (unsigned long long)T;   // Table 6 / eq. (6)
+    }
+}
+
+__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* queue, UpdateParams upd) {
     extern __shared__ __align__(16) char lds[];
     __shared__ long long s_next;
+    __shared__ int s_last, s_scan[32];
     gram_group_offset(p);
     if (p.ws_gs) queue = reinterpret_cast<int*>(reinterpret_cast<char*>(queue) + (long long)blockIdx.y * p.ws_gs);
     const DmaUnits U(p.T, big_mode);
@@ -232,8 +255,26 @@ __global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, in
         u = s_next;
         __syncthreads();
     }
+    // This workgroup's row maxima left the CU as device-scope atomics; once they are acknowledged (vmcnt(0)) and the
+    // workgroup has met, it signs off.  Every workgroup's last fetch precedes its sign-off, so whoever signs off last
+    // may clear both counters, and sees every row maximum after one invalidate.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
     if (threadIdx.x == 0) {
-        // every workgroup's last fetch precedes its sign-off, so whoever signs off last may clear both counters
-        if (atomicAdd(queue + 1, 1) == G - 1) { atomicExch(queue, 0); atomicExch(queue + 1, 0); }
+        const bool last = atomicAdd(queue + 1, 1) == G - 1;
+        if (last) { atomicExch(queue, 0); atomicExch(queue + 1, 0); }
+        s_last = last ? 1 : 0;
     }
+    __syncthreads();
+    if (!upd.counts || !s_last) return;
+    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    __syncthreads();
+    if (upd.go.ws) {                                         // several problems: blockIdx.y is the problem
+        const long long g = blockIdx.y;
+        if (upd.mask) upd.mask += g * (long long)upd.T;
+        if (upd.idx) upd.idx += g * upd.go.list;
+        upd.counts += g * upd.go.counts;
+        if (upd.gram_ops) upd.gram_ops += g * upd.go.ops;
+    }
+    full_selection_finish(upd, p.gamma, s_scan);             // (p.gamma is this problem's: gram_group_offset)
 }

@@ -929,7 +929,9 @@ inline double dma_makespan(int T, int big_mode, int G) {
 }
 
 // mode: 0 = 128 x 128 units everywhere, 1 = 256 x 256 off the diagonal, -1 = whichever hands out better
-hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st, int groups = 1) {
+// u.counts != NULL: the workgroup that leaves last also applies the threshold and compacts the set (no update launch)
+hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st, int groups,
+                           const UpdateParams& u) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
@@ -953,7 +955,7 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
         mode = last_mode;
     }
     ProfScope ps(ADA_K_GRAM_FULL, st);
-    hipLaunchKernelGGL(k_gram_dma, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue);
+    hipLaunchKernelGGL(k_gram_dma, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue, u);
     return hipGetLastError();
 }
 
@@ -1073,6 +1075,14 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
     // resolved from them in token order (one problem, T <= FUSED_MAX_T: checked by the caller)
     const GramParams p = {X, ld, T, d, nullptr, nullptr, nullptr, w.inv_norm, g, thr, MODE_FULL, 1, go.x, go.ws,
                           greedy ? w.hits : nullptr};
+    const UpdateParams u = {g, nullptr, nullptr, T, thr, mask, idx, nullptr, nullptr, counts,
+                            reinterpret_cast<unsigned long long*>(gram_ops), go};
+    // Up to T = 4096 a launch is mostly latency, and the direct-to-LDS kernel finishes the selection itself (its last
+    // workgroup applies the threshold and compacts): one launch and one gap less.  Beyond that the tiles keep the
+    // chip busy for hundreds of microseconds and the update stays a launch of its own.
+    const bool finish_in_kernel = !greedy && T <= 4096;
+    const UpdateParams in_kernel = finish_in_kernel ? u : UpdateParams{};
+    bool finished = false;
     const char* path_env = getenv("ADA_GRAM");               // development switch: tile, dma0, dma1
     const std::string path = path_env ? path_env : "";
     const long long ld_seen = (groups > 1 && go.x % 16 != 0) ? 1 : ld;   // every problem's rows must suit the loader
@@ -1085,9 +1095,10 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
             if constexpr (sizeof(In) == 2) {
                 // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
                 const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
-                if (can && (path == "dma0" || path == "dma1"))
-                    return launch_gram_dma(p, w.meta + META_QUEUE, path == "dma1", st, groups);
-                if (can && path.empty() && T >= 1536) return launch_gram_dma(p, w.meta + META_QUEUE, -1, st, groups);
+                if (can && (path == "dma0" || path == "dma1" || (path.empty() && T >= 1536))) {
+                    finished = finish_in_kernel;
+                    return launch_gram_dma(p, w.meta + META_QUEUE, path.empty() ? -1 : path == "dma1", st, groups, in_kernel);
+                }
             }
         }
         return launch_gram_any<In, V::aligned>(p, T, T, true, st, groups);
@@ -1102,8 +1113,7 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
         else hipLaunchKernelGGL((k_greedy_resolve<FUSED_MAX_T / GREEDY_THREADS, 1>), dim3(1), dim3(GREEDY_THREADS), 0, st, gp);
         return hipGetLastError() == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
     }
-    const UpdateParams u = {g, nullptr, nullptr, T, thr, mask, idx, nullptr, nullptr, counts,
-                            reinterpret_cast<unsigned long long*>(gram_ops), go};
+    if (finished) return ADA_OK;
     return launch_update(u, st, groups);
 }
 
