@@ -108,11 +108,14 @@ def test_small_shapes_one_launch_cascade_on_wide_tiles(T, d, K, dtype, tile, mon
 
 @pytest.mark.parametrize("path", ["dma0", "dma1"])
 @pytest.mark.parametrize("T,d,K", [(257, 128, 30), (700, 4096, 120), (1000, 64, 90), (1, 64, 1), (129, 32, 8),
-                                   (1290, 96, 140), (512, 160, 60), (3000, 64, 300), (5500, 32, 400)])
+                                   (1290, 96, 140), (512, 160, 60), (3000, 64, 300), (5500, 32, 400),
+                                   (4096, 64, 350), (4097, 64, 350)])
 def test_direct_to_lds_full_selection(T, d, K, path, monkeypatch):
     """The direct-to-LDS Gram kernel of the full selection, both ways of cutting the triangle into units, forced onto
-    small and ragged shapes (T off the 128 and 256 grids, one to three half chunks, a single token) and onto two
-    shapes with more units than workgroups, where the rest is handed out through the counter in the workspace."""
+    small and ragged shapes (T off the 128 and 256 grids, one to three half chunks, a single token) and onto
+    shapes with more units than workgroups, where the rest is handed out through the counter in the workspace.
+    Up to T = 4096 the kernel's last workgroup applies the threshold and compacts the set; beyond (4097, 5500) the
+    update is a launch of its own."""
     monkeypatch.setenv("ADA_GRAM", path)
     say("direct-to-LDS %s T=%d d=%d" % (path, T, d))
     w = wl.small(T=T, d=d, K=K, L=2, dtype="bf16", seed=29 + T, p=0.1)
