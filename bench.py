@@ -451,6 +451,32 @@ def main():
             other[wo.name] = {"T": wo.T, "d": wo.d, "mean_r": float(oo["counts"][1:, 0].float().mean()),
                               "cascade_launch_us": us_o, "hbm_frac": by / (1e-6 * us_o) / 1e9 / HBM_PEAK_GBS}
             del xo, wso, oo
+        # configs[4] as the configuration states it: a batch of four sequences, here stacked in one tensor with one
+        # launch per step for all four (three layers of each)
+        if args.config != 4:
+            w4b = wl.config(4)
+            B4, L4 = 4, 3
+            per4 = [list(wl.layers(w4b, b, L4)) for b in range(B4)]
+            x4g = [torch.stack([per4[b][l] for b in range(B4)]).to(dev) for l in range(L4)]
+            del per4
+            ws4g = pa.workspace_batched(w4b.T, B4, dev)
+            o4 = None
+            for _ in range(2):
+                o4 = pa.ada_cascade_layers_grouped(x4g, w4b.tau, ws=ws4g, stream=stream, want_lists=False, out=o4)
+            torch.cuda.synchronize()
+            pa.ada_profile_enable(True)
+            for _ in range(4):
+                pa.ada_cascade_layers_grouped(x4g, w4b.tau, ws=ws4g, stream=stream, want_lists=False, out=o4)
+            torch.cuda.synchronize()
+            k4g = pa.ada_profile_collect()
+            pa.ada_profile_enable(False)
+            us_g = 1e3 * k4g["cascade_fused"]["ms"] / k4g["cascade_fused"]["launches"]
+            by4 = B4 * w4b.T * w4b.d * 2
+            other[w4b.name + "_batch4_stacked"] = {"T": w4b.T, "d": w4b.d, "sequences": B4,
+                                                   "mean_r": float(o4["counts"][:, 1:, 0].float().mean()),
+                                                   "cascade_launch_us": us_g, "us_per_layer_and_sequence": us_g / B4,
+                                                   "hbm_frac": by4 / (1e-6 * us_g) / 1e9 / HBM_PEAK_GBS}
+            del x4g, ws4g, o4
         result["cascade_other_shapes"] = other
 
         # ---- the greedy covering of Section 2.5 on layer 0 (pair bits from the register-staged Gram tiles, then the
