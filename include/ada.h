@@ -247,7 +247,8 @@ int ada_cascade_step_grouped(const ada_groups* groups, const void* X, int T, int
                              void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
- * The full selection (Definition "Gram threshold") of every group, in the same three launches.
+ * The full selection (Definition "Gram threshold") of every group, in the launches one problem takes (norms and
+ * Gram tiles; the set update is the tiles' last workgroup up to T = 4096 and a third launch beyond).
  *   mask    [G][T] uint8, or NULL
  *   idx     group g's representatives at idx + g * list_gstride, ascending     (required)
  *   counts  group g's {r, r, 0, 0} at counts + g * counts_gstride               (required)
