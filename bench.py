@@ -3,12 +3,13 @@
 
 One "step" = one pass of the whole path over one synthetic sequence: full Gram-threshold selection at
 layer 0 and a cascade step at each of the layers 1..L-1 (Section 4.1), all chained on the device through
-ada_cascade_layers with inputs already resident in HBM.  The workload is the benchmark's configs[2]
-(GPT-J-shaped: T=2048, d=4096, 28 layers, bf16, tau=0.1, 400 centres), the configuration the metric is
-quoted on.  The 28 layer buffers (448 MiB) exceed the 256 MB Infinity Cache, so each layer's X comes from
+ada_cascade_layers with inputs already resident in HBM.  The workload is the configuration the metric is quoted on
+(GPT-J-shaped: T=2048, d=4096, 28 layers, bf16, tau=0.1, 400 centres).  The 28 layer buffers (448 MiB) exceed the 256 MB Infinity Cache, so each layer's X comes from
 HBM when the step reaches it.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit and the run's settings, `roofline` (the dominant kernel against the HBM
+peak, with the hardware-counter traffic), `cpu_baseline` (the float64 oracle on the host cores), and one block per
+further measurement (full selection, assignment, attention, pipeline, batches, per-head groups, other shapes).
 """
 import argparse
 import json
@@ -93,7 +94,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="index into BASELINE.json configs (default 2)")
+    ap.add_argument("--config", type=int, default=2, help="which of the five workload configurations, 0..4 (default 2: T=2048, d=4096, 28 layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the full-selection timing and the profiled pass")
     ap.add_argument("--probe", action="store_true", help="short run for rocprofv3 --pmc (no timing, no JSON result)")
@@ -103,7 +104,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
-              "in this library: see DESIGN.md, 'How the path would shard')" % args.gpus, file=sys.stderr)
+              "in this library)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
