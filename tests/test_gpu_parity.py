@@ -18,6 +18,12 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.fixture(autouse=True)
+def dev_switches(monkeypatch):
+    """the library reads its path-forcing variables only under this master switch"""
+    monkeypatch.setenv("ADA_DEV_SWITCHES", "1")
+
+
 def say(msg):
     print("[case] " + msg, flush=True)
 
@@ -869,43 +875,133 @@ def test_config1_all_layers_with_full_selection_at_every_layer():
     say(w.name)
     xs_cpu = wl.layer_list(w)
     run_layers_teacher_forced(w, xs_cpu, what=w.name)
-    for l in (3, 7, 11):
+    for l in range(w.L):                      # the configuration's comparison path: the full selection at every layer
         parity.check_full(xs_cpu[l], w.tau, pa.fetch(pa.ada_select_full(xs_cpu[l].to(DEV), w.tau)),
                           "%s full layer %d" % (w.name, l))
 
 
-@pytest.mark.parametrize("ci,n_layers", [(2, 8), (3, 6)])
-def test_config2_and_3_first_layers(ci, n_layers):
+CUS = 256     # workgroups that share a single problem's tiles on this device (what ada_plan_tile_shape is asked with)
+
+
+@pytest.mark.parametrize("ci,full_every", [(2, 1), (3, 4)])
+def test_config2_and_3_all_layers(ci, full_every):
+    """Every layer of the configuration, teacher-forced: the cascade set grows and shrinks with depth, so the later
+    layers reach representative-block counts (and with them tile plans and set-update forms) that the first few do
+    not.  The full selection (the configuration's comparison path) is checked at every `full_every`-th layer."""
     w = wl.config(ci)
-    say("%s, first %d layers" % (w.name, n_layers))
-    stats = run_layers_teacher_forced(w, wl.layer_list(w, 0, n_layers), what=w.name)
-    assert sum(a + r for a, r, _ in stats) > 0
-
-
-def test_config4_one_sequence_sampled():
-    """T = 8192 in the launch configuration the benchmark uses: the cascade step is checked completely (the
-    oracle needs seconds for it); the full selection is checked on sampled gamma_t plus what holds for any input:
-    the mask is the threshold of gamma, token 0 is representative, r counts the mask."""
-    w = wl.config(4)
-    say("%s, sequence 1, layers 0-1" % w.name)
-    xs_cpu = wl.layer_list(w, 1, 2)
+    say("%s, all %d layers" % (w.name, w.L))
+    xs_cpu = wl.layer_list(w)
     xs = [x.to(DEV) for x in xs_cpu]
     full = pa.fetch(pa.ada_select_full(xs[0], w.tau))
-    rng = np.random.default_rng(0)
-    rows = np.unique(np.concatenate([[0, 1, 127, 128, 129, 4095, 4096, 8190, 8191], rng.integers(0, w.T, 48)]))
-    ref = oracle.gamma_full_rows(wl.as_f64(xs_cpu[0]), rows)
-    assert np.max(np.abs(full["gamma"][rows] - ref)) <= parity.GAMMA_TOL
-    thr32 = np.float32(1.0 - np.float64(np.float32(w.tau)) ** 2)
-    assert np.array_equal(full["mask"], (full["gamma"] < thr32).astype(np.uint8))
-    assert full["mask"][0] == 1 and full["r"] == int(full["mask"].sum())
-    assert np.array_equal(full["idx"], np.flatnonzero(full["mask"]))
-    assert np.all(np.abs(ref - parity.thr_of(w.tau)) > parity.BAND)       # sampled decisions are unambiguous
-    assert np.array_equal(full["mask"][rows], (ref < parity.thr_of(w.tau)).astype(np.uint8))
+    parity.check_full(xs_cpu[0], w.tau, full, w.name + " layer 0")
+    prev = full["idx"]
+    inherited, moved = [], 0
+    for l in range(1, w.L):
+        say("%s layer %d, r=%d" % (w.name, l, len(prev)))
+        inherited.append(len(prev))
+        got, _ = step_and_check(xs[l], xs_cpu[l], w.tau, prev, 0, "%s layer %d" % (w.name, l))
+        moved += got["n_adds"] + got["n_removes"]
+        prev = got["idx"]
+        if l % full_every == 0:
+            parity.check_full(xs_cpu[l], w.tau, pa.fetch(pa.ada_select_full(xs[l], w.tau)), "%s full layer %d" % (w.name, l))
+    assert moved > 0
+    shapes = {pa.ada_plan_tile_shape(r, w.T, w.d, CUS) for r in inherited}
+    say("%s: inherited sizes %d..%d, tile plans %s" % (w.name, min(inherited), max(inherited), sorted(shapes)))
+    assert shapes == {EXPECTED_PLANS[ci]}, shapes
+    blocks64 = {(r + 63) // 64 for r in inherited}
+    if ci == 2:
+        assert len(blocks64) > 1, "the set never crossed a 64-representative block boundary"
+        assert max(inherited) <= 512 and min(inherited) > 384     # one update form, both sides of 448
+    else:
+        assert min(inherited) > 512 and max(inherited) <= 1024    # the 32-word update form
+
+
+# the tile plan (ada_plan_tile_shape) each configuration's single-sequence cascade step is meant to take
+EXPECTED_PLANS = {2: 0, 3: 1, 4: 2}
+
+
+@pytest.fixture(scope="module")
+def config4_batch():
+    """The long-sequence configuration as it is stated: four sequences with their own seeds, stacked in one tensor per
+    layer, layers 0..8 (the full selection at layer 0, eight cascade steps; layer 8 is where the configuration asks for
+    the next full selection).  One stacked GPU pass; the tests below check every sequence against the oracle."""
+    w = wl.config(4)
+    n_layers = 9
+    say("%s: generating %d sequences x %d layers" % (w.name, w.batch, n_layers))
+    seqs_cpu = [wl.layer_list(w, b, n_layers) for b in range(w.batch)]
+    xg = [torch.stack([seqs_cpu[b][l] for b in range(w.batch)]).to(DEV) for l in range(n_layers)]
+    out = pa.ada_cascade_layers_grouped(xg, w.tau, want_lists=True)
+    torch.cuda.synchronize()
+    host = {k: v.cpu() for k, v in out.items() if isinstance(v, torch.Tensor)}
+    return w, n_layers, seqs_cpu, xg, host
+
+
+def full_selection_sampled(X64, tau, idx, rows, what):
+    ref = oracle.gamma_full_rows(X64, rows)
+    assert np.all(np.abs(ref - parity.thr_of(tau)) > parity.BAND), what
+    assert np.array_equal(np.isin(rows, idx), ref < parity.thr_of(tau)), what
+
+
+@pytest.mark.parametrize("b", [0, 1, 2, 3])
+def test_config4_every_sequence_of_the_stacked_batch(config4_batch, b):
+    """Sequence b of the stacked pass: every cascade step against the oracle (teacher-forced), the layer-0 selection
+    completely for sequence 0 and on sampled tokens for the others."""
+    w, n_layers, seqs_cpu, xg, out = config4_batch
+    counts = out["counts"]
+    assert counts[:, :, 3].flatten().tolist() == [0] * (w.batch * n_layers)
+    assert len({tuple(counts[s, :, 0].tolist()) for s in range(w.batch)}) == w.batch          # the sequences differ
+    rng = np.random.default_rng(40 + b)
+    prev = None
+    single_plans, stacked_plans = set(), set()
+    for l in range(n_layers):
+        r, na, nr = (int(v) for v in counts[b, l, :3])
+        idx = out["idx"][b, l, :r].numpy()
+        say("%s sequence %d layer %d, r=%d" % (w.name, b, l, r))
+        if l == 0:
+            X0 = wl.as_f64(seqs_cpu[b][0])
+            if b == 0:
+                ref = oracle.select_full(X0, w.tau)
+                assert np.all(np.abs(ref["gamma"] - parity.thr_of(w.tau)) > parity.BAND)
+                assert np.array_equal(idx, ref["idx"])
+            else:
+                rows = np.unique(np.concatenate([[0, 1, 255, 256, w.T - 1], rng.integers(0, w.T, 40)]))
+                full_selection_sampled(X0, w.tau, idx, rows, "%s sequence %d layer 0" % (w.name, b))
+        else:
+            single_plans.add(pa.ada_plan_tile_shape(len(prev), w.T, w.d, CUS))
+            stacked_plans.add(pa.ada_plan_tile_shape(len(prev), w.T, w.d, CUS // w.batch))
+            got = dict(idx=idx, adds=out["adds"][b, l, :na].numpy(), removes=out["removes"][b, l, :nr].numpy(),
+                       gram_ops=int(out["gram_ops"][b, l]), r=r, n_adds=na, n_removes=nr,
+                       gamma=pa.fetch(pa.ada_cascade_step(xg[l][b], w.tau, dev_idx(prev)))["gamma"])
+            parity.check_cascade(seqs_cpu[b][l], w.tau, prev, got, what="%s seq %d layer %d" % (w.name, b, l))
+        prev = idx
+    say("%s sequence %d: tile plans single %s, stacked %s" % (w.name, b, sorted(single_plans), sorted(stacked_plans)))
+    assert single_plans == {EXPECTED_PLANS[4]}, single_plans
+
+
+@pytest.mark.parametrize("layer", [0, 8])
+def test_config4_full_selection_compared_completely(config4_batch, layer):
+    """T = 8192, d = 4096 in the launch configuration the benchmark times: mask, index list and every gamma_t against
+    the oracle, at layer 0 and at layer 8 (the layers at which the configuration runs the full selection)."""
+    w, n_layers, seqs_cpu, xg, _ = config4_batch
+    say("%s sequence 0 layer %d: complete full selection" % (w.name, layer))
+    got = pa.fetch(pa.ada_select_full(xg[layer][0], w.tau))
+    info = parity.check_full(seqs_cpu[0][layer], w.tau, got, "%s full layer %d" % (w.name, layer))
+    say("gamma error %.3g, %d tokens in the band" % (info["gamma_err"], info["n_band"]))
+    assert got["mask"][0] == 1 and got["r"] == int(got["mask"].sum())
+
+
+def test_config4_single_sequence_step_in_both_forms(config4_batch):
+    """One sequence on its own (the single-problem launch configuration): a deep cascade step in the one-launch and
+    the two-launch form, the latter returning Algorithm 1's gamma^cross itself."""
+    w, n_layers, seqs_cpu, xg, out = config4_batch
+    b, l = 1, 6
+    r = int(out["counts"][b, l - 1, 0])
+    prev = out["idx"][b, l - 1, :r].numpy()
     for flags in (0, pa.FLAG_TWO_PASS):
-        step_and_check(xs[1], xs_cpu[1], w.tau, full["idx"], flags, w.name + " layer 1")
+        step_and_check(xg[l][b], seqs_cpu[b][l], w.tau, prev, flags, "%s seq %d layer %d flags %d" % (w.name, b, l, flags))
 
 
-@pytest.mark.parametrize("ci,B,n_layers,checked", [(2, 4, 4, (0, 3)), (4, 4, 3, (1,))])
+@pytest.mark.parametrize("ci,B,n_layers,checked", [(2, 4, 4, (0, 1, 2, 3))])
 def test_stacked_batch_at_full_size(ci, B, n_layers, checked):
     """The batch of the long-context configuration (four sequences with different seeds) and of the benchmark's
     configuration, stacked in one tensor per layer as bench.py runs them: one launch per step for all sequences.
