@@ -295,8 +295,8 @@ int ada_pipeline_layers(const void* const* X_layers, const void* const* Q_layers
                         void* ws, size_t ws_bytes, void* stream_sel, void* stream_attn, void* stream, unsigned flags);
 
 /*
- * A threshold that follows the turnover (Section 8.1: "a layer with low turnover can tolerate a tighter threshold,
- * a layer with high turnover should use a looser one"; the paper gives no formula).  The rule used here:
+ * A threshold that follows the turnover (Section 8.1 gives only the direction of the adjustment -- tighten where the
+ * set is stable, loosen where it changes -- and no formula).  The rule used here:
  *   eta^(l)   = (adds + removes) / |R^(l-1)|            the turnover of the step just made (eq. (8))
  *   tau^(l+1) = clip(tau^(l) + kappa * (eta_target - eta^(l)), tau_min, tau_max)
  * A larger tau is a tighter threshold (1 - tau^2 falls: fewer representatives).  Layers 0 and 1 use tau0.  A step the
@@ -369,6 +369,18 @@ int ada_profile_copy_probe(void* dst, const void* src, size_t bytes, void* strea
  * (written only in a case that does not occur; keeps the arithmetic alive).  Returns ADA_ERR_SHAPE for
  * workgroups < 1, iters < 1 or more than 2^20 of either. */
 int ada_profile_mfma_probe(int workgroups, int iters, float* sink, void* stream);
+
+/*
+ * Development switches (environment variables; not part of the interface).  They force code paths that the library
+ * otherwise chooses by shape, for tests and measurements, and are read only when ADA_DEV_SWITCHES=1 is set as well:
+ *   ADA_GRAM=tile|dma0|dma1       full selection: register-staged tiles / direct-to-LDS kernel with 128- or 256-row units
+ *   ADA_TILE=64|128               register-staged Gram tile size
+ *   ADA_KGROUPS=1|2               K-groups of the 64 x 64 one-launch cascade tile
+ *   ADA_CASCADE_TILE=64|64x128|128   tile shape of the one-launch cascade step
+ *   ADA_NO_DMA=1                  operands through registers instead of straight into LDS
+ *   ADA_ATTN=lds                  the first attention kernel
+ *   ADA_SPIN_LIMIT=n              bound of the resident pass's wait between layers (polls)
+ */
 
 #ifdef __cplusplus
 }

@@ -68,6 +68,16 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def library_is_stale() -> bool:
+    """True if libada.so is missing or older than a source it is built from."""
+    if not os.path.exists(LIB_PATH):
+        return True
+    built = os.path.getmtime(LIB_PATH)
+    inc = os.path.join(os.path.dirname(_HERE), "include")
+    deps = [os.path.join(SRC_DIR, f) for f in os.listdir(SRC_DIR)] + [os.path.join(inc, f) for f in os.listdir(inc)]
+    return any(os.path.getmtime(f) > built for f in deps)
+
+
 _lib = None
 
 

@@ -1150,7 +1150,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
     // (entries below r_host are the caller's memory whatever r turns out to be)
     const int jq = min((int)threadIdx.x, max(p.r_host, 1) - 1);
     const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));
-    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0): this thread's stores have left the CU
+    drain_stores();                                          // this thread's stores have left the CU
     __syncthreads();
     // (a group's few workers count on one word: the two levels are for a whole chip of workgroups)
     if (threadIdx.x == 0)
@@ -1244,7 +1244,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_pass(PassParams pp) {
         PASS_CLK(2);
         const int jq = min((int)threadIdx.x, T - 1);         // the row has T entries whatever r is
         const int q0 = list_at(p, jq), qp0 = list_at(p, max(jq - 1, 0));
-        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this thread's stores have left the CU
+        drain_stores();                                      // this thread's stores have left the CU
         __syncthreads();
         if (threadIdx.x == 0) s_last = take_ticket(p.ticket, p.grid) ? 1 : 0;
         __syncthreads();

@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, in
     // This workgroup's row maxima left the CU as device-scope atomics; once they are acknowledged (vmcnt(0)) and the
     // workgroup has met, it signs off.  Every workgroup's last fetch precedes its sign-off, so whoever signs off last
     // may clear both counters, and sees every row maximum after one invalidate.
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    drain_stores();
     __syncthreads();
     if (threadIdx.x == 0) {
         const bool last = atomicAdd(queue + 1, 1) == G - 1;

@@ -56,16 +56,14 @@ struct Workspace {
     unsigned long long* best;   // [T] arg-max keys of the assignment; zero between calls
 };
 
-__host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-inline int hit_words(int r_cap) {                            // whole 64- or 128-row tiles, whichever needs more words
-    const int w64 = 2 * ((r_cap + 63) / 64), w128 = 4 * ((r_cap + 127) / 128);
-    return w64 > w128 ? w64 : w128;
+__host__ __device__ constexpr size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+constexpr int hit_words(int r_cap) {                         // whole 64- or 128-row tiles, whichever needs more words
+    return 2 * ((r_cap + 63) / 64) > 4 * ((r_cap + 127) / 128) ? 2 * ((r_cap + 63) / 64) : 4 * ((r_cap + 127) / 128);
 }
 
-inline size_t ws_bytes_for(int T) {
-    size_t t4 = align_up((size_t)T * 4, 256), t1 = align_up((size_t)T, 256);
-    size_t hits = T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0;
-    return t4 * 3 + t1 + META_BYTES + hits + align_up((size_t)T * 8, 256);
+constexpr size_t ws_bytes_for(int T) {
+    return align_up((size_t)T * 4, 256) * 3 + align_up((size_t)T, 256) + META_BYTES +
+           (T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0) + align_up((size_t)T * 8, 256);
 }
 
 inline Workspace carve(void* ws, int T) {
@@ -130,6 +128,17 @@ __device__ inline float piece_sumsq(u32x4 v) {
 #pragma unroll
     for (int i = 0; i < EPP; ++i) { float f = to_f32<In>(u.e[i]); s = fmaf(f, f, s); }
     return s;
+}
+
+// Hand-over of results to the workgroup that finishes a launch.  Results leave the CU as device-scope atomic stores
+// (written through the L2, where every XCD sees them); on this chip such a store is acknowledged in the vector-memory
+// counter, so once vmcnt is zero the data is visible device-wide and a relaxed ticket may follow.  The empty asm
+// statements keep the compiler from moving memory operations across the wait in either direction; the reader
+// invalidates its CU's caches once (acquire fence by one thread, then a barrier) before it loads.
+__device__ inline void drain_stores() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0); the other counters are left alone
+    asm volatile("" ::: "memory");
 }
 
 __device__ inline float wave_sum(float v) {
@@ -892,8 +901,16 @@ inline long long tiles_for(int mode, int nS, int nT, int B) {
     return mode == MODE_CROSS ? nbS * nbT : nbT * (nbT + 1) / 2;
 }
 
+// Development switches (listed in include/ada.h) force code paths for tests and measurements.  They are honoured only
+// when ADA_DEV_SWITCHES=1 is set as well, so that a stray variable in a user's environment changes nothing.
+const char* dev_switch(const char* name) {
+    const char* on = getenv("ADA_DEV_SWITCHES");
+    if (!on || on[0] != '1' || on[1] != '\0') return nullptr;
+    return getenv(name);
+}
+
 int tile_override() {
-    const char* e = getenv("ADA_TILE");
+    const char* e = dev_switch("ADA_TILE");
     if (!e) return 0;
     const int v = atoi(e);
     return (v == 64 || v == 128) ? v : 0;
@@ -946,11 +963,12 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
     }
     if (mode < 0) {
         static std::mutex mu;
-        static int last_T = 0, last_mode = 0;
+        static int last_T = 0, last_G = 0, last_mode = 0;     // the choice depends on both the size and the workgroups
         std::lock_guard<std::mutex> lock(mu);
-        if (last_T != p.T) {
+        if (last_T != p.T || last_G != G) {
             last_mode = dma_makespan(p.T, 1, G) < dma_makespan(p.T, 0, G) ? 1 : 0;
             last_T = p.T;
+            last_G = G;
         }
         mode = last_mode;
     }
@@ -1024,7 +1042,7 @@ template <typename In, int DH>
 hipError_t launch_attn(const AttnParams& p, hipStream_t st) {
     if constexpr (sizeof(In) == 2) {
         static const bool first_kernel = [] {             // development switch: ADA_ATTN=lds keeps the first kernel
-            const char* e = getenv("ADA_ATTN");
+            const char* e = dev_switch("ADA_ATTN");
             return e && std::string(e) == "lds";
         }();
         // its hand-over stores 16 bytes per lane
@@ -1083,7 +1101,7 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
     const bool finish_in_kernel = !greedy && T <= 4096;
     const UpdateParams in_kernel = finish_in_kernel ? u : UpdateParams{};
     bool finished = false;
-    const char* path_env = getenv("ADA_GRAM");               // development switch: tile, dma0, dma1
+    const char* path_env = dev_switch("ADA_GRAM");               // development switch: tile, dma0, dma1
     const std::string path = path_env ? path_env : "";
     const long long ld_seen = (groups > 1 && go.x % 16 != 0) ? 1 : ld;   // every problem's rows must suit the loader
     hipError_t e = dispatch(dtype, X, ld_seen, d, [&](auto v) {
@@ -1163,7 +1181,7 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = A
 }
 
 int kgroups_override() {
-    const char* e = getenv("ADA_KGROUPS");
+    const char* e = dev_switch("ADA_KGROUPS");
     if (!e) return 0;
     const int v = atoi(e);
     return (v == 1 || v == 2) ? v : 0;
@@ -1171,7 +1189,7 @@ int kgroups_override() {
 
 // FusedParams::tile_pick: the CU count (automatic choice per step) unless the development switch fixes the shape.
 int cascade_tile_pick() {
-    const char* e = getenv("ADA_CASCADE_TILE");              // 64 = 64 x 64, 64x128 = 64 x 128, 128 = 128 x 128
+    const char* e = dev_switch("ADA_CASCADE_TILE");              // 64 = 64 x 64, 64x128 = 64 x 128, 128 = 128 x 128
     if (e) {
         const std::string v(e);
         if (v == "64") return 0;
@@ -1186,7 +1204,7 @@ int cascade_tile_pick() {
 int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_t st) {
     int kg = 2;
     if (int o = kgroups_override()) kg = o;
-    const char* no_dma = getenv("ADA_NO_DMA");
+    const char* no_dma = dev_switch("ADA_NO_DMA");
     // the form of the kernel must suit every group's rows: a group stride off the 16-byte grid takes the element-wise
     // loader for all of them (dispatch looks at base, ld and d)
     const long long ld_seen = (p.groups > 1 && p.x_gs % 16 != 0) ? 1 : p.ld;
@@ -1272,7 +1290,7 @@ hipError_t launch_pass(const PassParams& pp, hipStream_t st) {
 // to one workgroup per CU); the caller falls back to one launch per layer otherwise.
 bool pass_eligible(const void* const* X_layers, int L, int T, int d, long long ld, int dtype, unsigned flags) {
     if (!(flags & ADA_FLAG_RESIDENT_PASS) || (flags & ADA_FLAG_TWO_PASS) || T > FUSED_MAX_T || L < 2) return false;
-    if (getenv("ADA_NO_DMA") || kgroups_override() == 1) return false;
+    if (dev_switch("ADA_NO_DMA") || kgroups_override() == 1) return false;
     const int epc = dtype == ADA_BF16 ? 64 : 32;
     if (d % epc != 0 || ld % (epc / 8) != 0) return false;
     for (int l = 0; l < L; ++l)
@@ -1301,7 +1319,7 @@ int run_cascade_pass(const void* const* X_layers, int first, int n, int T, int d
     pp.removes_row0 = removes_all ? removes_all + row0 * (size_t)T : nullptr;
     pp.epoch = w.meta + META_EPOCH;
     pp.spin_limit = 1 << 20;                                 // about a second of polling
-    if (const char* e = getenv("ADA_SPIN_LIMIT")) { const int v = atoi(e); if (v >= 1) pp.spin_limit = v; }
+    if (const char* e = dev_switch("ADA_SPIN_LIMIT")) { const int v = atoi(e); if (v >= 1) pp.spin_limit = v; }
     // a layer that is never finished (a workgroup gave up waiting) keeps this status
     hipLaunchKernelGGL(k_fill_status, dim3((n * 4 + 255) / 256), dim3(256), 0, st, pp.counts_row0 + 4, n, (int)ADA_ERR_DEVICE);
     if (hipGetLastError() != hipSuccess) return ADA_ERR_DEVICE;
