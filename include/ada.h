@@ -140,6 +140,22 @@ int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float t
                      void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
+ * ada_cascade_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation.  Same arguments, outputs, flags and results as ada_cascade_step, without a
+ * workspace: the step's scratch memory (row maxima, hit table, counters; about 2.2 MB) is an array in the library's
+ * own image, one copy per GPU for the life of the process.  The call allocates nothing and frees nothing.
+ *   T <= ADA_STATIC_MAX_T, else ADA_ERR_SHAPE (nothing is enqueued).
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different streams, or threads)
+ * race and must be ordered by the caller.  What must start at zero is cleared at the start of each call (by a small
+ * kernel, so the call can be captured), whatever an earlier call left behind.
+ */
+#define ADA_STATIC_MAX_T 4096
+int ada_cascade_step_static(const void* X, int T, int d, int64_t ld, int dtype, float tau,
+                            const int32_t* prev_idx, int r, const int32_t* r_dev,
+                            int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
+                            uint64_t* gram_ops, float* gamma, void* stream, unsigned flags);
+
+/*
  * Nearest-representative assignment -- Section 2.3 ("Attention on the representative set"): a token outside R
  * takes the attention output of the member s* of R that maximises |G_{t s*}|.  The maximum runs over the whole
  * set handed in (earlier and later tokens alike); a member of R is its own representative.  One launch: the

@@ -30,7 +30,7 @@ SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ad
            "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped", "ada_pipeline_layers", "ada_cascade_layers_adaptive", "ada_plan_tile_shape",
            "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
-           "ada_attention_compressed")
+           "ada_attention_compressed", "ada_cascade_step_static")
 
 KERNEL_CLASSES = ("norm_prep", "gram_full", "gram_rep", "gram_cross", "update", "cascade_fused", "mfma_probe", "assign", "attn")
 
@@ -102,6 +102,8 @@ def lib():
         L.ada_cascade_step.restype = i32
         L.ada_cascade_step.argtypes = [vp, i32, i32, i64, i32, f32, vp, i32, vp, vp, vp, vp, vp, vp, vp,
                                        vp, sz, vp, u32]
+        L.ada_cascade_step_static.restype = i32
+        L.ada_cascade_step_static.argtypes = [vp, i32, i32, i64, i32, f32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32]
         L.ada_cascade_layers.restype = i32
         L.ada_cascade_layers.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i64, i32, f32, vp, vp, vp, vp, vp,
                                          vp, sz, vp, u32]
@@ -241,6 +243,31 @@ def ada_cascade_step(X: torch.Tensor, tau: float, prev_idx: torch.Tensor, r: Opt
     if rc != OK:
         raise AdaError(rc, "ada_cascade_step")
     out["_keep"] = (ws, prev_idx, r_dev)
+    return out
+
+
+STATIC_MAX_T = 4096
+
+
+def ada_cascade_step_static(X: torch.Tensor, tau: float, prev_idx: torch.Tensor, out: Dict[str, torch.Tensor],
+                            r: Optional[int] = None, r_dev: Optional[torch.Tensor] = None, *, stream=None,
+                            flags: int = 0) -> Dict[str, torch.Tensor]:
+    """ada_cascade_step on the library's own scratch array: no workspace, and nothing is allocated here either --
+    the caller brings the output tensors (`out`: idx[T], adds[T], removes[>= r], counts[4], gram_ops[1] int64,
+    gamma[T]), e.g. those of an earlier ada_cascade_step."""
+    _check_x(X)
+    T, d = X.shape
+    if prev_idx.dtype != torch.int32 or not prev_idx.is_cuda or not prev_idx.is_contiguous():
+        raise ValueError("prev_idx must be a contiguous int32 device tensor")
+    r = int(prev_idx.numel()) if r is None else int(r)
+    if r > prev_idx.numel() or out["removes"].numel() < r or out["idx"].numel() < T or out["adds"].numel() < T:
+        raise ValueError("r exceeds the capacity of prev_idx, or an output tensor is too small")
+    rc = lib().ada_cascade_step_static(_ptr(X), T, d, X.stride(0), _dtype_code(X), float(tau), _ptr(prev_idx), r,
+                                       _ptr(r_dev), _ptr(out["idx"]), _ptr(out["adds"]), _ptr(out["removes"]),
+                                       _ptr(out["counts"]), _ptr(out["gram_ops"]), _ptr(out.get("gamma")),
+                                       _stream(stream), int(flags))
+    if rc != OK:
+        raise AdaError(rc, "ada_cascade_step_static")
     return out
 
 

@@ -1483,6 +1483,48 @@ int ada_cascade_step(const void* X, int T, int d, int64_t ld, int dtype, float t
                        (hipStream_t)stream, flags);
 }
 
+// ------------------------------------------------------------------------------------------------
+// ada_cascade_step_static: the same step on a workspace that lives in this library's image, for callers that cannot
+// allocate.  `scratch` is a host-side stand-in for the array; its device address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[ws_bytes_for(ADA_STATIC_MAX_T)];
+
+namespace {
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[STATIC_MAX_DEVICES];          // per device: every GPU holds its own copy of the array
+
+// The array's address on the current device (looked up on the first call there), or NULL.
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int ada_cascade_step_static(const void* X, int T, int d, int64_t ld, int dtype, float tau, const int32_t* prev_idx, int r,
+                            const int32_t* r_dev, int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
+                            uint64_t* gram_ops, float* gamma, void* stream, unsigned flags) {
+    if (!prev_idx || !idx || !adds || !removes || !counts) return ADA_ERR_NULL;
+    if (T > ADA_STATIC_MAX_T) return ADA_ERR_SHAPE;            // beyond what the array holds
+    void* ws = static_scratch();
+    if (!ws) return ADA_ERR_DEVICE;
+    const size_t ws_bytes = ws_bytes_for(ADA_STATIC_MAX_T);
+    if (int e = check_common(X, T, d, ld, dtype, tau, ws, ws_bytes)) return e;
+    if (r < 1 || r > T) return ADA_ERR_SHAPE;
+    // The counters a step relies on being zero (tickets, queue, hand-over word) are cleared by a fill kernel, so the
+    // array is good whatever an earlier call left behind; everything else a step reads it writes first.
+    const Workspace w = carve(ws, T);
+    if (fill_u32(w.meta, META_BYTES / 4, 0u, (hipStream_t)stream) != hipSuccess) return ADA_ERR_DEVICE;
+    return run_cascade(X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops, gamma, ws,
+                       (hipStream_t)stream, flags);
+}
+
 namespace {
 int check_groups(const ada_groups* g, int T, int d) {
     if (!g) return ADA_ERR_NULL;
