@@ -342,7 +342,8 @@ int ada_cascade_layers_adaptive(const void* const* X_layers, int L, int T, int d
 /*
  * Which tile shape a one-launch cascade step takes when `workgroups` workgroups share its tiles (the CU count for a
  * single problem; that divided by the number of groups for a grouped call) and the rows come in whole aligned
- * 128-byte chunks: 0 = 64 x 64, 1 = 64 representatives x 128 tokens, 2 = 128 x 128; -1 for arguments out of range.
+ * 128-byte chunks of bf16: 0 = 64 x 64, 1 = 64 representatives x 128 tokens, 2 = 128 x 128, 3 = 128 representatives x
+ * 256 tokens; -1 for arguments out of range.
  * Host only (no device is touched): the same function the kernel evaluates with the set size it finds.
  */
 int ada_plan_tile_shape(int r, int T, int d, int workgroups);
@@ -392,7 +393,7 @@ int ada_profile_mfma_probe(int workgroups, int iters, float* sink, void* stream)
  *   ADA_GRAM=tile|dma0|dma1       full selection: register-staged tiles / direct-to-LDS kernel with 128- or 256-row units
  *   ADA_TILE=64|128               register-staged Gram tile size
  *   ADA_KGROUPS=1|2               K-groups of the 64 x 64 one-launch cascade tile
- *   ADA_CASCADE_TILE=64|64x128|128   tile shape of the one-launch cascade step
+ *   ADA_CASCADE_TILE=64|64x128|128|256x128   tile shape of the one-launch cascade step
  *   ADA_NO_DMA=1                  operands through registers instead of straight into LDS
  *   ADA_ATTN=lds                  the first attention kernel
  *   ADA_SPIN_LIMIT=n              bound of the resident pass's wait between layers (polls)

@@ -76,6 +76,10 @@ struct FusedParams {
     // needs).  The arg-max keys then carry positions instead of token ids: R is ascending, so the order among equal
     // cosines is the same.
     int32_t* pos_out;
+    // cascade step: [T], zero on entry and on exit (it shares the arg-max table's memory: the two modes never run on one
+    // workspace at once).  first[t] = 0xFFFFFFFF - (smallest list position of a representative that hits token t), 0 if
+    // none does: what the set update needs of a token's hit words in all but rare cases (see fused_update_rec).
+    uint32_t* first;
 };
 
 // Section 8.1's rule as read here: the turnover eta = (adds + removes) / r of the step just made (eq. (8)) moves tau
@@ -103,27 +107,29 @@ __device__ inline void adapt_tau(const FusedParams& p, int r, int n_add, int n_r
 // rounds x (operand bytes per tile + a fixed part worth about 56 rows of 4096 two-byte elements: set size, list and
 // first-chunk trips before the K loop, norms and hit words after it), rounds = tiles over the workgroups that share
 // them: operand bytes per Gram entry fall with the tile size, but a tile count below the worker count leaves CUs idle.
-__host__ __device__ inline int tile_rows_r(int shape) { return shape == 2 ? 128 : 64; }
-__host__ __device__ inline int tile_rows_t(int shape) { return shape == 0 ? 64 : 128; }
+__host__ __device__ inline int tile_rows_r(int shape) { return shape >= 2 ? 128 : 64; }
+__host__ __device__ inline int tile_rows_t(int shape) { return shape == 0 ? 64 : shape == 3 ? 256 : 128; }
 // (T <= FUSED_MAX_T: every count fits 32 bits, and 32-bit divisions are what the start of a launch can afford)
 __host__ __device__ inline int tile_count(int r, int T, int shape) {
     const int br = tile_rows_r(shape), bt = tile_rows_t(shape);
     return ((r + br - 1) / br) * ((T + bt - 1) / bt);
 }
-// pick > 0: choose; pick = 0, -1, -2: always shape 0, 1, 2.  workers: workgroups that share the step's tiles.
-__host__ __device__ inline int cascade_tile_shape(int r, int T, int d, int pick, int workers) {
-    if (pick <= 0) return -pick;
+// pick > 0: choose; pick = 0, -1, -2, -3: always shape 0, 1, 2, 3.  workers: workgroups that share the step's tiles.
+// nshapes: 4 when the ring tiles apply (bf16 rows in whole 64-byte pieces), else 3.  The operand bytes are weighted by
+// how far from the CU's fill rate each engine was measured (quarters): the 64 x 64 tile and the ring tiles run at it,
+// the register-free 64 x 128 tile at 5/4 and the 128 x 128 tile of the same engine (fp32 only now) at twice that time.
+__host__ __device__ inline int cascade_tile_shape(int r, int T, int d, int pick, int workers, int nshapes = 4) {
+    if (pick <= 0) return -pick < nshapes ? -pick : nshapes - 1;
     const unsigned wk = workers > 0 ? (unsigned)workers : 1u;
-    const unsigned nr64 = (unsigned)(r + 63) >> 6, nr128 = (unsigned)(r + 127) >> 7;
-    const unsigned nt64 = (unsigned)(T + 63) >> 6, nt128 = (unsigned)(T + 127) >> 7;
-    const unsigned tiles[3] = {nr64 * nt64, nr64 * nt128, nr128 * nt128};
     const unsigned dd = (unsigned)(d < 65536 ? d : 65536);   // keeps the products below 2^32 (tiles <= 65536 / 8 per round matter)
     int best = 0;
     unsigned long long best_cost = 0;
-    for (int shape = 0; shape < 3; ++shape) {
-        const unsigned rounds = (tiles[shape] + wk - 1u) / wk;
-        const unsigned long long cost =
-            (unsigned long long)rounds * ((unsigned)(tile_rows_r(shape) + tile_rows_t(shape)) * dd + 56u * 4096u);
+    for (int shape = 0; shape < nshapes; ++shape) {
+        const unsigned tiles = (unsigned)tile_count(r, T, shape);
+        const unsigned rounds = (tiles + wk - 1u) / wk;
+        const unsigned weight = shape == 1 ? 5u : (shape == 2 && nshapes == 3) ? 8u : 4u;
+        const unsigned long long cost = (unsigned long long)rounds *
+            ((unsigned long long)(unsigned)(tile_rows_r(shape) + tile_rows_t(shape)) * dd * weight + 4ull * 56u * 4096u);
         if (shape == 0 || cost < best_cost) { best = shape; best_cost = cost; }
     }
     return best;
@@ -166,9 +172,11 @@ template <int KG, bool DMA> struct FusedGeom {
     static constexpr int OFF_SCAN = OFF_SCALE + 512;      // scan scratch of the update phase
     static constexpr int META = OFF_SCAN + 512;
     static constexpr int RING = DMA ? KG * NS * STAGE : KG * 2 * STAGE;
-    static constexpr int BODY = RING > 65536 ? RING : 65536;   // stages / reduction scratch (64 KB) / update state
-    static constexpr int OFF_BIG = META + BODY;           // metadata of the 128 x 128 tile (two-group direct-to-LDS form)
+    static constexpr int RINGMAX = 3 * 384 * 128;         // the widest ring tile: three stages of 384 rows (144 KB)
+    static constexpr int BODY = (KG == 2 && DMA) ? RINGMAX : (RING > 65536 ? RING : 65536);   // stages / reduction scratch (64 KB) / update state
+    static constexpr int OFF_BIG = META + BODY;           // metadata of the wide tiles (two-group direct-to-LDS form)
     static constexpr int LDS = META + BODY + ((KG == 2 && DMA) ? 8192 : 0);
+    static_assert(LDS <= 160 * 1024, "one workgroup's LDS");
 };
 
 constexpr int waitcnt_vm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }   // s_waitcnt vmcnt(n) only (gfx9 encoding)
@@ -247,6 +255,9 @@ __device__ inline void finish_block(const FusedParams& p, const f32x16& tot, con
         // the L2 to where every XCD sees it), so that handing the words over needs no L2 write-back: a write-back
         // per workgroup serialises on the L2 and was the longest single wait of the step.
         __hip_atomic_store(p.hits + (size_t)word * p.T + t, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // the earliest representative that hits t, over all tiles: an integer max of the inverted position (exact and
+        // order-independent); few tokens have hits in more than one or two blocks of 32
+        if (bits != 0u && p.first) atomicMax(p.first + t, 0xFFFFFFFFu - (uint32_t)(word * 32 + __builtin_ctz(bits)));
         if (p.gamma && m > 0.f) atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
     }
 }
@@ -707,6 +718,220 @@ __device__ inline void fused_tile_wide(const FusedParams& p, int r, int s0, int 
     }
 }
 
+// s_waitcnt vmcnt(n) lgkmcnt(0): the direct-to-LDS loads are counted, every LDS read of this wave has returned
+constexpr int waitcnt_vm_lgkm0(int n) { return 0x0070 | (n & 15) | ((n >> 4) << 14); }
+
+// The same step with the hand-ordered ring of the direct-to-LDS full-Gram kernel (k_gram_dma), for bf16 rows in whole
+// aligned 128-byte chunks: 128 NT tested tokens (MFMA N side) against 64 NR inherited representatives (M side); eight
+// waves as 4 (tokens) x 2 (representatives), each holding a 32 NT x 32 NR block of accumulators over ALL of K, two
+// waves per SIMD.  Operands go global -> LDS in whole 128-byte chunks (one cache line per row and stage: what the
+// memory side serves at its best rate is requests, not bytes, so a line is asked for once and whole), a ring of NS
+// stages; the order of fragment reads, barrier, loads and MFMAs is pinned by hand, the waits are counted, and there
+// is one barrier per chunk (four k-steps).  Operand requests per Gram entry fall as 1 / tokens + 1 / representatives,
+// which is why the tile is as large as the step's tile count allows.  Sums of squares (Section 2.1) come from the
+// fragments in hand, every 32-row block summed by exactly one of the waves that hold it.
+template <int NT, int NR>
+__device__ inline void fused_tile_ring(const FusedParams& p, int r, int s0, int t0, char* lds) {
+    using G = FusedGeom<2, true>;
+    constexpr int BR = 64 * NR, BT = 128 * NT, ROWS = BR + BT, EPC = 64, STAGE = ROWS * 128;
+    constexpr int NS = 4 * STAGE <= G::BODY ? 4 : 3;
+    static_assert(ROWS % 64 == 0, "every wave issues the same number of 8-row loads per stage");
+    constexpr int LPT = ROWS / 64;
+    static_assert(NS * STAGE <= G::RINGMAX, "ring does not fit");
+    static_assert(BR <= 256 && BT <= 256, "metadata area");
+    int* s_tok = reinterpret_cast<int*>(lds + G::OFF_BIG);        // [BR] token id of each representative row (INT_MAX: none)
+    int* repf = s_tok + 256;                                      // [BT] tested token is inherited
+    float* ssq = reinterpret_cast<float*>(repf + 256);            // [ROWS] sums of squares
+    float* scale = ssq + 512;                                     // [ROWS] 1 / norm (0 for rows that do not exist)
+    char* ring = lds + G::META;
+
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wt = wave & 3, wr = wave >> 2;
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
+    const int T = p.T;
+
+    // One load instruction fills 1 KB = 8 rows of a stage: lane l serves row l / 8, slot l % 8, and fetches piece
+    // (l % 8) ^ lds_swz(row), which reproduces the XOR-swizzled layout the fragment reads expect (see fused_tile).
+    // Instruction j of wave w covers rows 8 (8 j + w) ...; rows below BR are representatives (through the list), the
+    // rest tested tokens.
+    const int r8 = lane >> 3;
+    int ptok[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int row = (j * 8 + wave) * 8 + r8;
+        const int li = s0 + min(row, BR - 1);
+        ptok[j] = list_at(p, li < r ? li : r - 1);               // every list entry is requested before anything waits
+    }
+    for (int i = tid; i < BR; i += G::THREADS) {
+        const int li = s0 + i;
+        const bool ok = li < r;
+        int tok = list_at(p, ok ? li : r - 1);
+        tok = min(max(tok, 0), T - 1);
+        s_tok[i] = ok ? tok : INT_MAX;
+    }
+    for (int i = tid; i < BT; i += G::THREADS) repf[i] = 0;
+    const int pcd = (lane & 7) ^ lds_swz(wave * 8 + r8);          // 64 j leaves bits 0..3 of the row alone
+    const uint16_t* rowp[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int row = (j * 8 + wave) * 8 + r8;
+        const int tok = row < BR ? min(max(ptok[j], 0), T - 1) : min(t0 + row - BR, T - 1);
+        rowp[j] = X + (size_t)tok * (size_t)p.ld + pcd * 8;
+    }
+    const int nk = p.d / EPC;
+    auto issue = [&](int stage_off, int k) {
+        const int chunk = min(k, nk - 1);                        // surplus issues repeat the last chunk into a dead stage
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            char* dst = ring + stage_off + (j * 8 + wave) * 1024;                // wave-uniform
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + chunk * EPC),
+                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(s * STAGE, s);
+    __syncthreads();                                              // (drains the loads above as well: the prologue waits anyway)
+    if (!p.assign_mode) {                                         // which tested tokens are inherited (read in the epilogue)
+        for (int j = tid; j < r; j += G::THREADS) {
+            const unsigned q = (unsigned)(list_at(p, j) - t0);
+            if (q < (unsigned)BT) repf[q] = 1;
+        }
+    }
+
+    f32x16 acc[NR][NT];
+#pragma unroll
+    for (int a = 0; a < NR; ++a)
+#pragma unroll
+        for (int b = 0; b < NT; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    // Which 32-row blocks a wave holds, in which order.  A token block is held by the two waves wr = 0, 1 and a
+    // representative block by the four waves wt = 0 .. 3; each block's sum of squares is needed once.  So that the K loop
+    // stays straight-line code (a branch per block would cut it into pieces and undo the pinned order), every wave sums
+    // the blocks at FIXED local positions -- its representative block 0 and its even token blocks -- and the local order
+    // is permuted per wave so that those positions cover every block: local representative block a is block
+    // a ^ (wt % NR) of the wave's NR, local token block b is block b ^ wr of its NT (NT >= 2).  Where more waves hold a
+    // block than are needed (wt >= NR; wr = 1 with NT = 1) the surplus sums are simply not written.
+    constexpr int PR = NR >= 4 ? 3 : NR - 1, PT = NT >= 2 ? 1 : 0;
+    static_assert(NR <= 4, "a representative block is summed by one of four waves");
+    int ablk[NR], bblk[NT];                                       // block index within the tile's representative / token rows
+#pragma unroll
+    for (int a = 0; a < NR; ++a) ablk[a] = wr * NR + (a ^ (wt & PR));
+#pragma unroll
+    for (int b = 0; b < NT; ++b) bblk[b] = wt * NT + (b ^ (wr & PT));
+    // fragment addresses: row l32 of a 32-row block, piece 2 ks + half of the chunk (k-step ks of four)
+    const char* aptr[4][NR];
+    const char* bptr[4][NT];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+        for (int a = 0; a < NR; ++a) aptr[ks][a] = ring + lds_off(ablk[a] * 32 + l32, 2 * ks + half);
+#pragma unroll
+        for (int b = 0; b < NT; ++b) bptr[ks][b] = ring + lds_off(BR + bblk[b] * 32 + l32, 2 * ks + half);
+    }
+    u32x4 fa[2][NR], fb[2][NT];
+    auto read_frags = [&](int set, int stage_off, int ks) {
+#pragma unroll
+        for (int a = 0; a < NR; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(aptr[ks][a] + stage_off);
+#pragma unroll
+        for (int b = 0; b < NT; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bptr[ks][b] + stage_off);
+    };
+    float ssa = 0.f, ssb[(NT + 1) / 2];
+#pragma unroll
+    for (int b = 0; b < (NT + 1) / 2; ++b) ssb[b] = 0.f;
+    auto mma = [&](int set) {
+#pragma unroll
+        for (int a = 0; a < NR; ++a)
+#pragma unroll
+            for (int b = 0; b < NT; ++b) Mfma<uint16_t>::run(acc[a][b], fa[set][a], fb[set][b]);
+        ssa += piece_sumsq_fast<uint16_t>(fa[set][0]);            // Section 2.1: ||x||^2 from the fragments in hand
+#pragma unroll
+        for (int b = 0; b < NT; b += 2) ssb[b >> 1] += piece_sumsq_fast<uint16_t>(fb[set][b]);
+    };
+    // Chunk k (four k-steps) with the fragments of its k-step 0 already in set 0.  The fragments of k-step i + 1 are
+    // read while k-step i multiplies; before the last k-step comes the barrier that opens chunk k + 1 (everybody's part
+    // of it has landed, and everybody has read the last fragments of chunk k), then the fragment reads of its k-step 0
+    // and the loads of chunk k + NS into the stage just left, issued in the shadow of the last k-step's MFMAs.
+    auto step = [&](int cur_off, int nxt_off, int k) {
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, cur_off, 1);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(0, cur_off, 2);
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, cur_off, 3);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * LPT));   // chunk k + 1 has landed (this wave's part)
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, nxt_off, 0);
+        issue(cur_off, k + NS);
+        mma(1);
+        __builtin_amdgcn_sched_group_barrier(0x100, NR + NT, 0);  // the LDS reads first
+        constexpr int PAIRS = NR * NT < LPT ? NR * NT : LPT;
+#pragma unroll
+        for (int j = 0; j < PAIRS; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // then one MFMA ...
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);    // ... per global load
+        }
+        if constexpr (LPT > PAIRS) __builtin_amdgcn_sched_group_barrier(0x020, LPT - PAIRS, 0);
+        if constexpr (NR * NT > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, NR * NT - PAIRS, 0);
+    };
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));              // chunks 0 .. NS - 2 and the list have landed (this wave's part)
+    __builtin_amdgcn_s_barrier();
+    issue((NS - 1) * STAGE, NS - 1);
+    read_frags(0, 0, 0);
+    int k = 0;
+    for (; k + NS < nk; k += NS) {                               // every step here has a successor: no branches inside
+#pragma unroll
+        for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, k + s);
+    }
+    for (; k + 1 < nk; ++k) step((k % NS) * STAGE, ((k + 1) % NS) * STAGE, k);
+    {                                                            // last chunk
+        const int off = (k % NS) * STAGE;
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, off, 1);
+        mma(0);
+        read_frags(0, off, 2);
+        mma(1);
+        read_frags(1, off, 3);
+        mma(0);
+        mma(1);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));             // surplus loads land before the ring is reused
+    ssa += __shfl_xor(ssa, 32, 64);                               // the two lane halves hold different k pieces
+#pragma unroll
+    for (int b = 0; b < (NT + 1) / 2; ++b) ssb[b] += __shfl_xor(ssb[b], 32, 64);
+    if (half == 0) {
+        if (wt < NR) ssq[ablk[0] * 32 + l32] = ssa;
+        if (NT >= 2 || wr == 0) {
+#pragma unroll
+            for (int b = 0; b < NT; b += 2) ssq[BR + bblk[b] * 32 + l32] = ssb[b >> 1];
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < ROWS; i += G::THREADS) {
+        const float sum = ssq[i];
+        float sc = sum > 0.f ? 1.0f / sqrtf(sum) : 0.f;          // a zero row normalises to zero: all its cosines are 0
+        if (i < BR ? (s_tok[i] == INT_MAX) : (t0 + i - BR >= T)) sc = 0.f;
+        scale[i] = sc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < NT; ++b) {
+        const int nl = bblk[b] * 32 + l32;
+        const bool ordered = repf[nl] != 0 || p.earlier_only;
+        const float tsc = scale[BR + nl];
+#pragma unroll
+        for (int a = 0; a < NR; ++a)
+            finish_block(p, acc[a][b], s_tok + ablk[a] * 32, scale + ablk[a] * 32, tsc, ordered, t0 + nl,
+                         (s0 >> 5) + ablk[a], half);
+    }
+}
+
 // exclusive prefix sum of one 64-bit value per thread over the workgroup (three 21-bit counters ride in one scan)
 __device__ inline unsigned long long block_exclusive_scan64(unsigned long long v, unsigned long long* total,
                                                             unsigned long long* wave_tot /* >= 17 words of LDS */) {
@@ -765,41 +990,47 @@ __device__ inline void block_rank3(const bool (&f)[3][U], int (&below)[3], int (
     }
 }
 
-// Algorithm 1 steps 5, 9, 10 and the bookkeeping, from the hit words (run by one workgroup).
-// Per-token state lives in LDS (T <= FUSED_MAX_T bytes): bit 0 = inherited, bit 1 = kept.  The hit table is
-// word-major (hits[w * T + t]), so a thread that owns token t reads its words with loads that are coalesced across
-// the workgroup, independent of each other and branch-free (indices are clamped, results masked): a whole batch is
-// in flight before the first use.  One CU's load path is what this phase costs, so nothing is fetched twice:
-// the first THREADS list entries arrive in registers (q0 / qp0, loaded before the ticket), representatives take one
-// batch each, and the token pass reads four tokens per 16-byte load when T allows.
-// The same steps when one thread can own four consecutive tokens with all their hit words in registers
-// (T % 4 == 0, T <= 4 THREADS, at most WMAX words per token).  The hit words of an inherited token are among the
-// words its owner holds, so validity (step 5) needs no second trip to memory: one batch of 16-byte loads, the list
-// (to learn which tokens are inherited and at which position), then bit operations and one scan.
-template <int THREADS, int WMAX>
-__device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int qp0, char* lds, int* scan_scratch) {
+// Algorithm 1 steps 5, 9, 10 and the bookkeeping (run by one workgroup).  Two forms: from the first-hit records
+// (fused_update_rec, whenever T is a multiple of 4) and from the hit words alone (fused_update's general path).
+// In the general path per-token state lives in LDS (T <= FUSED_MAX_T bytes): bit 0 = inherited, bit 1 = kept.  The hit
+// table is word-major (hits[w * T + t]), so a thread that owns token t reads its words with loads that are coalesced
+// across the workgroup, independent of each other and branch-free (indices are clamped, results masked): a whole batch
+// is in flight before the first use.
+
+// Algorithm 1 steps 5, 9, 10 from the first-hit records.  For every token the tiles left, next to its hit words, the
+// smallest list position of a representative that hits it (p.first).  That decides almost everything:
+//   * an inherited representative is valid (step 5) iff it has no hit at all (its words hold earlier ones only);
+//   * any other token is new (step 9) if it has no hit, and covered if its earliest hit is a valid representative.
+// Only a token whose earliest hit turns out invalid needs its hit words (is one of the later hits valid?): a chain
+// t ~ s1 ~ s0 with t not ~ s0, which clustered activations produce rarely.  So the workgroup reads 4 T bytes instead of
+// the whole hit table (T x ceil(r / 32) words: 114 KB at T = 2048, r = 435; 720 KB at T = 8192, r = 700), which was most
+// of this phase.  Thread tid owns the 4 NV consecutive tokens from 4 NV tid on (T a multiple of 4, T <= 4 NV THREADS);
+// the records are cleared as they are read, so the table is zero again for the next call.
+template <int THREADS, int NV>
+__device__ inline int fused_update_rec(const FusedParams& p, int r, int q0, int qp0, char* lds, int* scan_scratch) {
+    constexpr int U = 4 * NV;
     const int tid = threadIdx.x;
     const int T = p.T, T4 = T >> 2;
     const int Wa = (r + 31) >> 5;
     uint16_t* pos = reinterpret_cast<uint16_t*>(lds);                        // [T] list position of an inherited token
     uint32_t* vmask = reinterpret_cast<uint32_t*>(lds + FUSED_MAX_T * 2);    // [Wa] valid bits by list position
-    const bool own = tid < T4;
-    // One batch of loads: a uniform row base per word plus ONE per-thread byte offset (clamped, so no lane is switched
-    // off and no address has to be kept per word), behind uniform branches only.
-    // The row stride passes through an empty asm statement: inside the resident layer loop the compiler would
-    // otherwise compute all WMAX per-thread addresses once, ahead of the loop, and keep them in (spilled) registers.
-    u32x4 x[WMAX];
-    const uint32_t toff = 16u * (uint32_t)min(tid, T4 - 1);
-    int row_words = T;
-    asm volatile("" : "+s"(row_words));
+    u32x4 key[NV];
 #pragma unroll
-    for (int w = 0; w < WMAX; ++w) {
-        if (w < Wa)
-            x[w] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.hits + (size_t)w * (size_t)row_words) + toff);
-        else
-            x[w] = u32x4{0u, 0u, 0u, 0u};
+    for (int v = 0; v < NV; ++v) {
+        const int t4 = tid * NV + v;
+        u32x4* src = reinterpret_cast<u32x4*>(p.first) + min(t4, T4 - 1);   // clamped: no lane is switched off at the load
+        key[v] = *src;
+        if (t4 < T4) {
+            *reinterpret_cast<unsigned long long*>(pos + 4 * t4) = ~0ull;    // 0xFFFF: not inherited
+        } else {
+            key[v] = u32x4{0u, 0u, 0u, 0u};
+        }
     }
-    if (own) *reinterpret_cast<unsigned long long*>(pos + 4 * tid) = ~0ull;  // 0xFFFF: not inherited
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {                                           // (after every load of this thread: a store
+        const int t4 = tid * NV + v;                                         //  in between would make the loads wait)
+        if (t4 < T4) reinterpret_cast<u32x4*>(p.first)[t4] = u32x4{0u, 0u, 0u, 0u};
+    }
     for (int w = tid; w < Wa; w += THREADS) vmask[w] = 0u;
     __syncthreads();
     int ok = 1;
@@ -819,53 +1050,59 @@ __device__ inline int fused_update_fast(const FusedParams& p, int r, int q0, int
         }
         return 0;
     }
-    // step 5: an inherited representative with a hit from an earlier inherited one is removed (the tile epilogue
-    // already kept only earlier representatives in an inherited token's words)
-    uint32_t any_all[4] = {0u, 0u, 0u, 0u};
+    // step 5: an inherited representative with a hit from an earlier inherited one is removed (the tile epilogue kept
+    // only earlier representatives in an inherited token's words, so any hit at all removes it)
+    int jpos[U];
 #pragma unroll
-    for (int w = 0; w < WMAX; ++w) {
-        const bool in = w < Wa;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) any_all[u] |= in ? x[w][u] : 0u;
-    }
-    int jpos[4];
-    {
-        const unsigned long long pk = own ? *reinterpret_cast<const unsigned long long*>(pos + 4 * tid) : ~0ull;
+    for (int v = 0; v < NV; ++v) {
+        const int t4 = tid * NV + v;
+        const unsigned long long pk = t4 < T4 ? *reinterpret_cast<const unsigned long long*>(pos + 4 * t4) : ~0ull;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            jpos[u] = (int)((pk >> (16 * u)) & 0xFFFFu);
-            if (jpos[u] != 0xFFFF && any_all[u] == 0u) atomicOr(&vmask[jpos[u] >> 5], 1u << (jpos[u] & 31));
+            const int j = (int)((pk >> (16 * u)) & 0xFFFFu);
+            jpos[4 * v + u] = j;
+            if (j != 0xFFFF && key[v][u] == 0u) atomicOr(&vmask[j >> 5], 1u << (j & 31));
         }
     }
     __syncthreads();
     // step 9: any other token with a hit on a VALID representative is covered
-    uint32_t cov[4] = {0u, 0u, 0u, 0u};
+    bool f[3][U];                                        // in R^(l+1) | added | removed
 #pragma unroll
-    for (int w = 0; w < WMAX; ++w) {
-        const uint32_t vm = w < Wa ? vmask[w] : 0u;
+    for (int v = 0; v < NV; ++v) {
+        const int t4 = tid * NV + v;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) cov[u] |= x[w][u] & vm;
-    }
-    int st[4];                                           // 3 kept inherited, 1 removed, 2 added, 0 covered
-    bool f[3][4];                                        // in R^(l+1) | added | removed
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const bool inh = jpos[u] != 0xFFFF;
-        st[u] = !own ? 0 : inh ? (any_all[u] == 0u ? 3 : 1) : (cov[u] == 0u ? 2 : 0);
-        f[0][u] = (st[u] & 2) != 0;
-        f[1][u] = st[u] == 2;
-        f[2][u] = st[u] == 1;
+        for (int u = 0; u < 4; ++u) {
+            const int i = 4 * v + u;
+            const bool own = t4 < T4, inh = jpos[i] != 0xFFFF;
+            const uint32_t k = key[v][u];
+            bool covered = false;
+            if (own && !inh && k != 0u) {
+                const uint32_t fp = 0xFFFFFFFFu - k;     // earliest hit; a position below r by construction (clamped anyway)
+                const uint32_t fw = min(fp >> 5, (uint32_t)(Wa - 1));
+                covered = (vmask[fw] >> (fp & 31)) & 1u;
+                if (!covered) {                          // rare: is one of the later hits valid?
+                    const int t = 4 * t4 + u;
+                    uint32_t any = 0u;
+                    for (int w = (int)fw; w < Wa; ++w) any |= p.hits[(size_t)w * T + t] & vmask[w];
+                    covered = any != 0u;
+                }
+            }
+            const int st = !own ? 0 : inh ? (k == 0u ? 3 : 1) : (k == 0u ? 2 : (covered ? 0 : 2));
+            f[0][i] = (st & 2) != 0;
+            f[1][i] = st == 2;
+            f[2][i] = st == 1;
+        }
     }
     int below[3], tot[3];
-    block_rank3<THREADS, 4>(f, below, tot, scan_scratch);
+    block_rank3<THREADS, U>(f, below, tot, scan_scratch);
     int o_idx = below[0], o_add = below[1], o_rem = below[2];
     const int n_idx = tot[0], n_add = tot[1], n_rem = tot[2];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {                        // step 10
-        const int t = 4 * tid + u;
-        if (st[u] & 2) p.idx[o_idx++] = t;
-        if (st[u] == 2) { if (p.adds) p.adds[o_add] = t; ++o_add; }
-        if (st[u] == 1) { if (p.removes) p.removes[o_rem] = t; ++o_rem; }
+    for (int i = 0; i < U; ++i) {                        // step 10
+        const int t = U * tid + i;
+        if (f[0][i]) p.idx[o_idx++] = t;
+        if (f[1][i]) { if (p.adds) p.adds[o_add] = t; ++o_add; }
+        if (f[2][i]) { if (p.removes) p.removes[o_rem] = t; ++o_rem; }
     }
     if (tid == 0) {
         p.counts[0] = n_idx; p.counts[1] = n_add; p.counts[2] = n_rem; p.counts[3] = ADA_OK;
@@ -885,9 +1122,12 @@ __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q
     constexpr int WU = 11;                              // hit words fetched per batch by one thread (22, 33, ... words: whole batches)
     const int tid = threadIdx.x, lane = tid & 63;
     const int T = p.T;
-    if (r_ok && (T & 3) == 0 && (T >> 2) <= THREADS) {  // uniform
-        if (r <= 16 * 32) return fused_update_fast<THREADS, 16>(p, r, q0, qp0, lds, scan_scratch);
-        if (r <= 32 * 32) return fused_update_fast<THREADS, 32>(p, r, q0, qp0, lds, scan_scratch);
+    if (r_ok && p.first && (T & 3) == 0 && T <= 32 * THREADS) {             // uniform
+        const int t4 = T >> 2;
+        if (t4 <= THREADS) return fused_update_rec<THREADS, 1>(p, r, q0, qp0, lds, scan_scratch);
+        if (t4 <= 2 * THREADS) return fused_update_rec<THREADS, 2>(p, r, q0, qp0, lds, scan_scratch);
+        if (t4 <= 4 * THREADS) return fused_update_rec<THREADS, 4>(p, r, q0, qp0, lds, scan_scratch);
+        return fused_update_rec<THREADS, 8>(p, r, q0, qp0, lds, scan_scratch);
     }
     uint8_t* flag = reinterpret_cast<uint8_t*>(lds);                         // [T]
     uint32_t* vmask = reinterpret_cast<uint32_t*>(lds + FUSED_MAX_T);        // one bit per inherited representative: valid
@@ -1088,25 +1328,39 @@ __device__ inline void assign_finish(const FusedParams& p, int r, bool r_ok, int
 template <typename In, bool ALIGNED, int KG, bool DMA>
 __device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds, unsigned local, unsigned workers) {
     int shape = 0;
+    constexpr int NSHAPES = sizeof(In) == 2 ? 4 : 3;                      // the ring tiles are bf16 only
     if constexpr (ALIGNED && KG == 2 && DMA)
-        shape = cascade_tile_shape(r, p.T, p.d, p.tile_pick, p.groups > 1 ? (int)workers : p.tile_pick);
-    const int sr = shape == 2 ? 7 : 6, st = shape == 0 ? 6 : 7;           // log2 of the tile's rows
+        shape = cascade_tile_shape(r, p.T, p.d, p.tile_pick, p.groups > 1 ? (int)workers : p.tile_pick, NSHAPES);
+    const int sr = shape >= 2 ? 7 : 6, st = shape == 0 ? 6 : shape == 3 ? 8 : 7;   // log2 of the tile's rows
     const unsigned nbS = (unsigned)(r + (1 << sr) - 1) >> sr;
     const unsigned ntiles = nbS * ((unsigned)(p.T + (1 << st) - 1) >> st);
-    // one problem: contiguous tile ranges per XCD (workgroup b runs on XCD b % 8); groups: worker `local` of the
-    // group's `workers` takes every workers-th tile
-    const bool grouped = p.groups > 1;
-    const unsigned per = grouped ? ntiles : (ntiles + 7u) >> 3;
-    const unsigned base = grouped ? 0u : (local & 7u) * per;
-    const unsigned slots = grouped ? workers : workers >> 3;
-    for (unsigned slot = grouped ? local : local >> 3; slot < per; slot += slots) {
+    // Contiguous tile ranges per XCD (workgroup b of the launch runs on XCD b % 8), so that the tiles an L2 serves at
+    // one time share their rows.  One problem: worker b is on XCD b % 8.  Groups: worker `local` of group g is
+    // workgroup local * groups + g, so a group's workers live on nx = 8 / gcd(8, groups) XCDs, worker `local` on the
+    // (local % nx)-th of them.
+    const unsigned G = p.groups > 1 ? (unsigned)p.groups : 1u;
+    const unsigned low = G & (0u - G);                                    // lowest set bit of the group count
+    const unsigned nx0 = 8u / (low < 8u ? low : 8u);
+    const unsigned nx = nx0 < workers ? nx0 : workers;                    // (fewer workers than XCDs: one range each)
+    const unsigned xi = local % nx, li = local / nx;
+    const unsigned per = (ntiles + nx - 1u) / nx;
+    const unsigned base = xi * per;
+    const unsigned slots = (workers - xi + nx - 1u) / nx;                 // workers of this problem on this XCD
+    for (unsigned slot = li; slot < per; slot += slots) {
         const unsigned tile = base + slot;
         if (tile >= ntiles) break;
         const int tb = (int)(tile / nbS), sb = (int)(tile - (unsigned)tb * nbS);
         if constexpr (ALIGNED && KG == 2 && DMA) {
-            if (shape == 2) fused_tile_wide<In, 4>(p, r, sb * 128, tb * 128, lds);
-            else if (shape == 1) fused_tile_wide<In, 2>(p, r, sb * 64, tb * 128, lds);
-            else fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
+            if constexpr (sizeof(In) == 2) {
+                if (shape == 3) fused_tile_ring<2, 2>(p, r, sb * 128, tb * 256, lds);
+                else if (shape == 2) fused_tile_ring<1, 2>(p, r, sb * 128, tb * 128, lds);
+                else if (shape == 1) fused_tile_wide<In, 2>(p, r, sb * 64, tb * 128, lds);
+                else fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
+            } else {
+                if (shape == 2) fused_tile_wide<In, 4>(p, r, sb * 128, tb * 128, lds);
+                else if (shape == 1) fused_tile_wide<In, 2>(p, r, sb * 64, tb * 128, lds);
+                else fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
+            }
         } else {
             fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
         }
@@ -1132,6 +1386,7 @@ __global__ __launch_bounds__(256 * KG) void k_cascade_fused(FusedParams p) {
         if (p.r_dev) p.r_dev += (long long)g * p.counts_gs;
         p.hits = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(p.hits) + (long long)g * p.ws_gs);
         p.ticket = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(p.ticket) + (long long)g * p.ws_gs);
+        if (p.first) p.first = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(p.first) + (long long)g * p.ws_gs);
         p.idx += (long long)g * p.list_gs;
         if (p.adds) p.adds += (long long)g * p.list_gs;
         if (p.removes) p.removes += (long long)g * p.list_gs;

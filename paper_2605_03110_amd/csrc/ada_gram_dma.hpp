@@ -27,9 +27,6 @@ struct DmaGeom {
     static constexpr int LDS = META + NS * STAGE;              // 132 KB: one workgroup per CU
 };
 
-// s_waitcnt vmcnt(n) lgkmcnt(0): the direct-to-LDS loads are counted, every LDS read of this wave has returned
-constexpr int waitcnt_vm_lgkm0(int n) { return 0x0070 | (n & 15) | ((n >> 4) << 14); }
-
 #ifdef ADA_PHASE_CLOCKS
 #define DMA_CLK(i) do { if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) { const unsigned long long t_ = clock64(); g_phase_clk[(i) + (WM == 128 ? 32 : 48)] += t_ - last_clk; last_clk = t_; } } while (0)
 #else

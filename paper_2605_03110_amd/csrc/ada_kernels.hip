@@ -1165,7 +1165,8 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = A
     } else {
         // with the set size known here the tile shape is too (the kernel makes the same choice from the same numbers)
         int shape = 0;
-        if (ALIGNED && KG == 2 && DMA && !p.r_dev) shape = cascade_tile_shape(p.r_host, p.T, p.d, p.tile_pick, p.tile_pick);
+        if (ALIGNED && KG == 2 && DMA && !p.r_dev)
+            shape = cascade_tile_shape(p.r_host, p.T, p.d, p.tile_pick, p.tile_pick, sizeof(In) == 2 ? 4 : 3);
         long long tiles = tile_count(p.r_host, p.T, shape);
         // Workgroups loop over tiles, so any grid is correct.  With the set size known only on the device the bound
         // r_host = T would launch mostly idle workgroups, and dispatching those is not free: cap at one per CU (the LDS
@@ -1175,6 +1176,8 @@ hipError_t launch_fused(const FusedParams& p, hipStream_t st, int prof_class = A
         grid = (unsigned)(tiles + 7) / 8 * 8;                        // multiple of 8 (XCDs)
     }
     q.grid = (int)grid;
+    // first-hit records are kept only where the update can take them (four tokens per 16-byte load, 32 per thread)
+    if (p.T % 4 != 0 || p.T > 32 * 256 * KG) q.first = nullptr;
     ProfScope ps(prof_class, st);
     hipLaunchKernelGGL((k_cascade_fused<In, ALIGNED, KG, DMA>), dim3(grid), dim3(256 * KG), lds, st, q);
     return hipGetLastError();
@@ -1189,12 +1192,13 @@ int kgroups_override() {
 
 // FusedParams::tile_pick: the CU count (automatic choice per step) unless the development switch fixes the shape.
 int cascade_tile_pick() {
-    const char* e = dev_switch("ADA_CASCADE_TILE");              // 64 = 64 x 64, 64x128 = 64 x 128, 128 = 128 x 128
+    const char* e = dev_switch("ADA_CASCADE_TILE");          // representatives x tokens: 64, 64x128, 128, 256x128 (tokens x reps)
     if (e) {
         const std::string v(e);
         if (v == "64") return 0;
         if (v == "64x128") return -1;
         if (v == "128") return -2;
+        if (v == "256x128") return -3;
     }
     return device_cus();
 }
@@ -1236,6 +1240,7 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
                      (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
                      w.meta + META_TICKET, idx, adds, removes, counts,
                      reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
+    p.first = reinterpret_cast<uint32_t*>(w.best);               // first-hit records live where the arg-max keys do
     if (ctl) {                                                   // Section 8.1: threshold carried on the device
         p.tau_in = tau_in; p.thr_in = thr_in; p.tau_out = tau_out; p.thr_out = thr_out;
         p.kappa = ctl->kappa; p.eta_target = ctl->eta_target; p.tau_min = ctl->tau_min; p.tau_max = ctl->tau_max;
@@ -1306,6 +1311,7 @@ int run_cascade_pass(const void* const* X_layers, int first, int n, int T, int d
     pp.f = {nullptr, ld, T, d, nullptr, nullptr, T, threshold_of(tau), (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0,
             w.hits, hit_words(T), nullptr, w.meta + META_TICKET, nullptr, nullptr, nullptr, nullptr, nullptr,
             0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
+    pp.f.first = T % 4 == 0 ? reinterpret_cast<uint32_t*>(w.best) : nullptr;   // (two K-groups: T <= 16384 fits)
     // rows of idx_all that share a 128-byte line with their neighbour could be cached half-written
     pp.f.coherent_list = ((uintptr_t)idx_all % 128 != 0 || T % 32 != 0) ? 1 : 0;
     for (int i = 0; i < n; ++i) pp.X[i] = X_layers[first + i];
@@ -1521,6 +1527,7 @@ int ada_cascade_step_static(const void* X, int T, int d, int64_t ld, int dtype, 
     // array is good whatever an earlier call left behind; everything else a step reads it writes first.
     const Workspace w = carve(ws, T);
     if (fill_u32(w.meta, META_BYTES / 4, 0u, (hipStream_t)stream) != hipSuccess) return ADA_ERR_DEVICE;
+    if (fill_u32(w.best, (size_t)T, 0u, (hipStream_t)stream) != hipSuccess) return ADA_ERR_DEVICE;   // first-hit records
     return run_cascade(X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops, gamma, ws,
                        (hipStream_t)stream, flags);
 }

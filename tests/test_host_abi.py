@@ -205,16 +205,16 @@ def test_cascade_report_is_the_papers_bookkeeping(ada):
 
 def test_tile_shape_plan_follows_tiles_per_workgroup(ada):
     """The cost model of the cascade tiles (host-side evaluation of the function the kernel uses): rounds of tiles
-    per workgroup x (bytes per tile + a fixed part).  The three d = 4096 configurations take the three shapes on a
-    256-CU device; sharing the device among groups pushes towards the larger tiles; short rows too."""
+    per workgroup x (weighted bytes per tile + a fixed part).  The three d = 4096 configurations take three different
+    shapes on a 256-CU device; sharing the device among groups pushes towards the larger tiles; short rows too."""
     lib = ada.lib()
     plan = lib.ada_plan_tile_shape
     assert plan(435, 2048, 4096, 256) == 0          # 224 tiles of 64 x 64: one round, least bytes per workgroup
     assert plan(920, 2048, 4096, 256) == 1          # 480 / 240 / 128 tiles: 64 x 128 is one round of 1.5 MB
-    assert plan(690, 8192, 4096, 256) == 2          # 1408 / 704 / 384 tiles: two rounds of 128 x 128
+    assert plan(690, 8192, 4096, 256) == 3          # 1408 / 704 / 384 / 192 tiles: one round of 128 representatives x 256 tokens
     assert plan(435, 2048, 4096, 64) == 2           # a quarter of the device per sequence
-    assert plan(435, 2048, 256, 16) == 2            # 16 heads of 256 columns
+    assert plan(435, 2048, 256, 16) == 3            # 16 heads of 256 columns: short rows, the fixed part per round decides
     assert plan(20, 64, 4096, 256) == 0 and plan(1, 1, 1, 1) == 0
     assert plan(0, 8, 8, 8) == -1 and plan(9, 8, 8, 8) == -1 and plan(4, 8, 0, 8) == -1 and plan(4, 8, 8, 0) == -1
     for r, T, d, wg in [(300, 4096, 1024, 256), (2000, 4096, 4096, 256), (5000, 16384, 512, 128)]:
-        assert plan(r, T, d, wg) in (0, 1, 2)
+        assert plan(r, T, d, wg) in (0, 1, 2, 3)
