@@ -51,8 +51,7 @@ typedef enum {
                                           proposition uses) instead of all of them (Algorithm 1, step 8) */
 
 #define ADA_FLAG_TWO_PASS 2u           /* cascade: run the r x r Gram and the cross-Gram as separate launches instead of
-                                          the one-launch form.  Sets, counts and gram_ops are identical; only the optional
-                                          gamma output differs (see ada_cascade_step) */
+                                          the one-launch form.  Same results (sets, counts, gram_ops, gamma) */
 
 #define ADA_FLAG_RESIDENT_PASS 4u      /* ada_cascade_layers: run the cascade layers (up to 64 per launch) in ONE launch whose
                                           workgroups stay resident and hand the set from layer to layer through device memory,
@@ -125,11 +124,12 @@ int ada_select_full(const void* X, int T, int d, int64_t ld, int dtype, float ta
  *                       ADA_ERR_SHAPE for a bad prev_idx / r_dev, in which case the sizes are 0
  *   gram_ops [1] uint64 r^2 + (T-r) * r_valid Gram entries (eq. (6) counts T*r, which is the same
  *                       when nothing is removed; one operation = one Gram entry as in Table 6)  (may be NULL)
- *   gamma    [T] float  (may be NULL) for an inherited token gamma^rep; for any other token the largest |cosine|
- *                       against ALL inherited representatives (>= gamma^cross, equal to it unless the nearest one was
- *                       removed) -- the one-launch form decides validity after the products.  With ADA_FLAG_TWO_PASS
- *                       it is the exact gamma^cross of step 8.  (With ADA_FLAG_CROSS_EARLIER_ONLY only earlier
- *                       representatives enter either maximum.)
+ *   gamma    [T] float  (may be NULL) Algorithm 1's maxima: gamma^rep (step 4) for an inherited token, gamma^cross (step 8,
+ *                       over the VALID representatives) for any other, 0 where the maximum is empty.  (With
+ *                       ADA_FLAG_CROSS_EARLIER_ONLY only earlier representatives enter either maximum.)  In the one-launch
+ *                       form validity is known only after the products, so asking for gamma adds a small second launch
+ *                       that recomputes the tokens whose nearest inherited representative was removed; sets and counts
+ *                       never depend on it.
  * The one-launch form is used for T <= 16384; larger T always takes the two-launch form.
  * Output buffers must not overlap the inputs (prev_idx in particular: idx is written while prev_idx is still read).
  */

@@ -17,8 +17,9 @@
 
 #ifdef ADA_PHASE_CLOCKS
 __device__ unsigned long long g_phase_clk[64];
-#define ADA_CLK(i) do { if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) g_phase_clk[i] = clock64(); } while (0)
-#define ADA_CLK_LAST(i) do { if (threadIdx.x == 0) g_phase_clk[i] = clock64(); } while (0)
+// (the constant-rate 100 MHz counter, comparable across workgroups and XCDs)
+#define ADA_CLK(i) do { if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) g_phase_clk[i] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#define ADA_CLK_LAST(i) do { if (threadIdx.x == 0) g_phase_clk[i] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define ADA_CLK(i) do { } while (0)
 #define ADA_CLK_LAST(i) do { } while (0)
@@ -80,6 +81,14 @@ struct FusedParams {
     // workspace at once).  first[t] = 0xFFFFFFFF - (smallest list position of a representative that hits token t), 0 if
     // none does: what the set update needs of a token's hit words in all but rare cases (see fused_update_rec).
     uint32_t* first;
+    // cascade step with a gamma output: Algorithm 1's gamma^cross is the maximum over the VALID representatives, which are
+    // known only after all products.  The tiles therefore also keep, per non-inherited token, the arg max over all
+    // inherited representatives (p.best, keyed by list position); the workgroup that updates the set lists the tokens
+    // whose nearest representative was removed (fix_list, fix_count[0]) and leaves every representative's validity
+    // (valid_out, by list position) for the pass that recomputes those few tokens' maxima (k_gamma_cross_fix).
+    int32_t* fix_list;
+    int32_t* fix_count;
+    uint8_t* valid_out;
 };
 
 // Section 8.1's rule as read here: the turnover eta = (adds + removes) / r of the step just made (eq. (8)) moves tau
@@ -206,7 +215,9 @@ template <> __device__ inline float piece_sumsq_fast<uint16_t>(u32x4 v) {
 // s_tok32 / scale32: token ids and 1/norm of the block's 32 representative rows; tsc: 1/norm of this lane's token t;
 // word: index of the hit word these 32 representatives fill.
 __device__ inline void finish_block(const FusedParams& p, const f32x16& tot, const int* s_tok32, const float* scale32,
-                                    float tsc, bool ordered, int t, int word, int half) {
+                                    float tsc, int mode, int t, int word, int half) {
+    const bool ordered = (mode & 1) != 0;             // only earlier representatives count for this token
+    const bool inherited = (mode & 2) != 0;           // the token is itself an inherited representative
     // accumulator register 4q+e of a 32x32 MFMA block is row 8q + 4*half + e: four consecutive rows per q
     f32x4 sc4[4];
     i32x4 tk4[4];
@@ -239,6 +250,7 @@ __device__ inline void finish_block(const FusedParams& p, const f32x16& tot, con
     }
     uint32_t bits = 0u;
     float m = 0.f;
+    int who = 0;                                      // row (within the block's 32) that holds this lane's maximum
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -246,10 +258,14 @@ __device__ inline void finish_block(const FusedParams& p, const f32x16& tot, con
             float c = (fabsf(tot[4 * q + e]) * sc4[q][e]) * tsc;
             if (ordered && !(tk4[q][e] < t)) c = 0.f;     // only earlier representatives count
             if (c >= p.thr) bits |= 1u << (8 * q + 4 * half + e);
-            m = fmaxf(m, c);
+            if (c > m) { m = c; who = 8 * q + 4 * half + e; }   // strict: the smaller position among equals
         }
     bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
-    m = fmaxf(m, __shfl_xor(m, 32, 64));
+    {
+        const float mo = __shfl_xor(m, 32, 64);
+        const int wo = __shfl_xor(who, 32, 64);
+        if (mo > m || (mo == m && wo < who)) { m = mo; who = wo; }
+    }
     if (half == 0 && t < p.T) {
         // word-major: 32 lanes store 32 consecutive words.  The store is a device-scope atomic (written through
         // the L2 to where every XCD sees it), so that handing the words over needs no L2 write-back: a write-back
@@ -258,7 +274,14 @@ __device__ inline void finish_block(const FusedParams& p, const f32x16& tot, con
         // the earliest representative that hits t, over all tiles: an integer max of the inverted position (exact and
         // order-independent); few tokens have hits in more than one or two blocks of 32
         if (bits != 0u && p.first) atomicMax(p.first + t, 0xFFFFFFFFu - (uint32_t)(word * 32 + __builtin_ctz(bits)));
-        if (p.gamma && m > 0.f) atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
+        if (p.gamma && m > 0.f) {
+            atomicMax(reinterpret_cast<uint32_t*>(p.gamma) + t, __float_as_uint(m));
+            // step 8 needs to know WHO holds a non-inherited token's maximum: the assignment's packed key (value bits,
+            // then the smaller list position), exact and order-independent
+            if (!inherited && p.fix_list)
+                atomicMax(p.best + t, ((unsigned long long)__float_as_uint(m) << 32) |
+                                      (unsigned long long)(uint32_t)(INT_MAX - (word * 32 + who)));
+        }
     }
 }
 
@@ -534,7 +557,7 @@ __device__ inline void fused_tile(const FusedParams& p, int r, int s0, int t0, i
         const int a = wa, b = wb;
         const int nl = b * 32 + l32;
         const int t = t0 + nl;
-        finish_block(p, tot, s_tok + a * 32, scale + a * 32, scale[B + nl], repf[nl] != 0 || p.earlier_only, t,
+        finish_block(p, tot, s_tok + a * 32, scale + a * 32, scale[B + nl], (repf[nl] != 0 ? 3 : 0) | (p.earlier_only ? 1 : 0), t,
                      sb * 2 + a, half);
     }
     ADA_CLK(5);
@@ -713,7 +736,7 @@ __device__ inline void fused_tile_wide(const FusedParams& p, int r, int s0, int 
 #pragma unroll
     for (int c = 0; c < NBW; ++c) {
         const int nl = (b0 + c) * 32 + l32;
-        finish_block(p, acc[c], s_tok + wa * 32, scale + wa * 32, scale[BR + nl], repf[nl] != 0 || p.earlier_only,
+        finish_block(p, acc[c], s_tok + wa * 32, scale + wa * 32, scale[BR + nl], (repf[nl] != 0 ? 3 : 0) | (p.earlier_only ? 1 : 0),
                      t0 + nl, (s0 >> 5) + wa, half);
     }
 }
@@ -923,7 +946,7 @@ __device__ inline void fused_tile_ring(const FusedParams& p, int r, int s0, int 
 #pragma unroll
     for (int b = 0; b < NT; ++b) {
         const int nl = bblk[b] * 32 + l32;
-        const bool ordered = repf[nl] != 0 || p.earlier_only;
+        const int ordered = (repf[nl] != 0 ? 3 : 0) | (p.earlier_only ? 1 : 0);
         const float tsc = scale[BR + nl];
 #pragma unroll
         for (int a = 0; a < NR; ++a)
@@ -997,6 +1020,31 @@ __device__ inline void block_rank3(const bool (&f)[3][U], int (&below)[3], int (
 // across the workgroup, independent of each other and branch-free (indices are clamped, results masked): a whole batch
 // is in flight before the first use.
 
+// Algorithm 1 step 8 for callers that ask for gamma: once validity is known (vmask: one bit per list position), leave it
+// for the recomputation pass and list the non-inherited tokens whose nearest inherited representative was removed --
+// their maximum over the VALID representatives is not the one the tiles accumulated.  The arg-max keys are cleared
+// on the way (the table is zero between calls).  ok == false: a rejected step, only the clearing is done.
+template <int THREADS>
+__device__ inline void gamma_fix_collect(const FusedParams& p, int r, const uint32_t* vmask, bool ok) {
+    if (!p.fix_list) return;                             // uniform
+    __shared__ int s_fix;
+    const int tid = threadIdx.x;
+    if (tid == 0) s_fix = 0;
+    __syncthreads();
+    if (ok)
+        for (int j = tid; j < r; j += THREADS) p.valid_out[j] = (uint8_t)((vmask[j >> 5] >> (j & 31)) & 1u);
+    for (int t = tid; t < p.T; t += THREADS) {
+        const unsigned long long key = p.best[t];
+        if (key == 0ull) continue;
+        p.best[t] = 0ull;
+        if (!ok) continue;
+        const int pos = min(max(INT_MAX - (int)(uint32_t)key, 0), r - 1);
+        if (!((vmask[pos >> 5] >> (pos & 31)) & 1u)) p.fix_list[atomicAdd(&s_fix, 1)] = t;
+    }
+    __syncthreads();
+    if (tid == 0) *p.fix_count = s_fix;
+}
+
 // Algorithm 1 steps 5, 9, 10 from the first-hit records.  For every token the tiles left, next to its hit words, the
 // smallest list position of a representative that hits it (p.first).  That decides almost everything:
 //   * an inherited representative is valid (step 5) iff it has no hit at all (its words hold earlier ones only);
@@ -1042,6 +1090,7 @@ __device__ inline int fused_update_rec(const FusedParams& p, int r, int q0, int 
     }
     ok = __syncthreads_and(ok);
     if (!ok) {
+        gamma_fix_collect<THREADS>(p, r, vmask, false);
         if (tid == 0) {
             p.counts[0] = 0; p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = ADA_ERR_INDEX;
             if (p.gram_ops) *p.gram_ops = 0ull;
@@ -1065,6 +1114,7 @@ __device__ inline int fused_update_rec(const FusedParams& p, int r, int q0, int 
         }
     }
     __syncthreads();
+    gamma_fix_collect<THREADS>(p, r, vmask, true);       // (gamma output only)
     // step 9: any other token with a hit on a VALID representative is covered
     bool f[3][U];                                        // in R^(l+1) | added | removed
 #pragma unroll
@@ -1188,6 +1238,7 @@ __device__ inline int fused_update(const FusedParams& p, int r, bool r_ok, int q
     }
     ok = __syncthreads_and(ok);
     const int status = !r_ok ? ADA_ERR_SHAPE : (!ok ? ADA_ERR_INDEX : ADA_OK);
+    gamma_fix_collect<THREADS>(p, r, vmask, status == ADA_OK);               // (gamma output only)
     if (status != ADA_OK) {
         if (tid == 0) {
             p.counts[0] = 0; p.counts[1] = 0; p.counts[2] = 0; p.counts[3] = status;

@@ -40,7 +40,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 enum { MODE_FULL = 0, MODE_REP = 1, MODE_CROSS = 2 };
 // meta: 8 words of scalars, then (from word META_TICKET + 64 on, one per 128-byte line) the per-XCD ticket counters
 constexpr size_t META_BYTES = 2048;
-enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_TICKET = 4, META_QUEUE = 5 /* and 6 */, META_EPOCH = 7, META_WORDS = 8 };
+enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_FIX = 3, META_TICKET = 4, META_QUEUE = 5 /* and 6 */, META_EPOCH = 7, META_WORDS = 8 };
 
 // The one-launch cascade step keeps one hit word per token and per 32 inherited representatives; beyond this T
 // the table would dominate the workspace and the two-launch path is used instead.
@@ -53,7 +53,8 @@ struct Workspace {
     uint8_t* is_rep;     // [T]
     int32_t* meta;       // [META_WORDS]; meta[META_TICKET], the META_QUEUE pair and meta[META_EPOCH] are zero between calls
     uint32_t* hits;      // [T][hit_words(T)] (only for T <= FUSED_MAX_T)
-    unsigned long long* best;   // [T] arg-max keys of the assignment; zero between calls
+    unsigned long long* best;   // [T] arg-max keys (assignment; cascade step with a gamma output); zero between calls
+    uint32_t* first;            // [T] first-hit records of the one-launch cascade step; zero between calls
 };
 
 __host__ __device__ constexpr size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -63,7 +64,8 @@ constexpr int hit_words(int r_cap) {                         // whole 64- or 128
 
 constexpr size_t ws_bytes_for(int T) {
     return align_up((size_t)T * 4, 256) * 3 + align_up((size_t)T, 256) + META_BYTES +
-           (T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0) + align_up((size_t)T * 8, 256);
+           (T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0) + align_up((size_t)T * 8, 256) +
+           align_up((size_t)T * 4, 256);
 }
 
 inline Workspace carve(void* ws, int T) {
@@ -76,7 +78,8 @@ inline Workspace carve(void* ws, int T) {
     w.is_rep = (uint8_t*)p; p += t1;
     w.meta = (int32_t*)p; p += META_BYTES;
     w.hits = (uint32_t*)p; p += T <= FUSED_MAX_T ? align_up((size_t)T * hit_words(T) * 4, 256) : 0;
-    w.best = (unsigned long long*)p;
+    w.best = (unsigned long long*)p; p += align_up((size_t)T * 8, 256);
+    w.first = (uint32_t*)p;
     return w;
 }
 
@@ -1227,8 +1230,75 @@ int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_
     return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
+// Algorithm 1 step 8 after the one-launch step, for callers that ask for gamma: the tiles accumulated every token's
+// maximum over ALL inherited representatives, because validity (step 5) is known only after the products.  For the
+// tokens whose nearest representative turned out removed (listed by the set update) the maximum over the VALID
+// representatives is recomputed here, one workgroup per token: every wave takes every fourth representative, the lanes
+// share a row's elements, products and sums in fp32 as in the tiles.  A few dozen tokens per step at most.
+struct GammaFixParams {
+    const void* X;
+    long long ld;
+    int T, d;
+    const int32_t* prev_idx;
+    const int32_t* r_dev;
+    int r_host;
+    const uint8_t* valid;        // by list position
+    const int32_t* fix_list;
+    const int32_t* fix_count;
+    const int32_t* counts;       // the step's counts: nothing is done for a rejected step
+    int earlier_only;
+    float* gamma;
+};
+
+template <typename In, bool ALIGNED>
+__global__ __launch_bounds__(256) void k_gamma_cross_fix(GammaFixParams p) {
+    constexpr int EPP = 16 / (int)sizeof(In);
+    __shared__ float s_red[4];
+    if (p.counts[3] != ADA_OK) return;
+    const int r = p.r_dev ? *p.r_dev : p.r_host;
+    const int n = *p.fix_count;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const In* X = reinterpret_cast<const In*>(p.X);
+    const int np = (p.d + EPP - 1) / EPP;
+    for (int i = blockIdx.x; i < n; i += gridDim.x) {
+        const int t = p.fix_list[i];
+        const In* xt = X + (size_t)t * (size_t)p.ld;
+        float tt = 0.f;                                          // ||x_t||^2: every wave sums all of it
+        for (int pi = lane; pi < np; pi += 64) tt += piece_sumsq<In>(load_piece<In, ALIGNED>(xt, pi * EPP, p.d));
+        tt = wave_sum(tt);
+        const float tsc = tt > 0.f ? 1.0f / sqrtf(tt) : 0.f;
+        float m = 0.f;
+        for (int j = wave; j < r; j += 4) {
+            if (!p.valid[j]) continue;                           // wave-uniform
+            const int s = min(max(p.prev_idx[j], 0), p.T - 1);
+            if (p.earlier_only && !(s < t)) continue;
+            const In* xs = X + (size_t)s * (size_t)p.ld;
+            float dot = 0.f, ss = 0.f;
+            for (int pi = lane; pi < np; pi += 64) {
+                union { u32x4 v; In e[EPP]; } a, b;
+                a.v = load_piece<In, ALIGNED>(xs, pi * EPP, p.d);
+                b.v = load_piece<In, ALIGNED>(xt, pi * EPP, p.d);
+#pragma unroll
+                for (int e = 0; e < EPP; ++e) {
+                    const float fs = to_f32<In>(a.e[e]);
+                    dot = fmaf(fs, to_f32<In>(b.e[e]), dot);
+                    ss = fmaf(fs, fs, ss);
+                }
+            }
+            dot = wave_sum(dot);
+            ss = wave_sum(ss);
+            const float ssc = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+            m = fmaxf(m, (fabsf(dot) * ssc) * tsc);
+        }
+        if (lane == 0) s_red[wave] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) p.gamma[t] = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+        __syncthreads();
+    }
+}
+
 // Algorithm 1 in one launch (ada_fused.hpp).  gamma, if given, receives for an inherited token gamma^rep and for any
-// other token the max over ALL inherited representatives (validity is resolved after the products).
+// other token gamma^cross; the latter costs a second, small launch for the tokens whose nearest representative was removed.
 int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, float tau, const int32_t* prev_idx, int r,
                       const int32_t* r_dev, int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
                       uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st, unsigned flags,
@@ -1240,7 +1310,10 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
                      (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, w.hits, hit_words(r), gamma,
                      w.meta + META_TICKET, idx, adds, removes, counts,
                      reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
-    p.first = reinterpret_cast<uint32_t*>(w.best);               // first-hit records live where the arg-max keys do
+    p.first = w.first;
+    if (gamma && !(grp && grp->G > 1)) {                          // Algorithm 1's gamma^cross: see k_gamma_cross_fix
+        p.best = w.best; p.fix_list = w.nonrep_idx; p.fix_count = w.meta + META_FIX; p.valid_out = w.is_rep;
+    }
     if (ctl) {                                                   // Section 8.1: threshold carried on the device
         p.tau_in = tau_in; p.thr_in = thr_in; p.tau_out = tau_out; p.thr_out = thr_out;
         p.kappa = ctl->kappa; p.eta_target = ctl->eta_target; p.tau_min = ctl->tau_min; p.tau_max = ctl->tau_max;
@@ -1253,7 +1326,17 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
         p.ops_gs = grp->ops_gstride;
         p.ws_gs = (long long)ws_bytes_for(T);
     }
-    return launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
+    const int rc = launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
+    if (rc != ADA_OK || !p.fix_list) return rc;
+    const GammaFixParams gp = {X, ld, T, d, prev_idx, r_dev, r, w.is_rep, w.nonrep_idx, w.meta + META_FIX, counts,
+                               (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, gamma};
+    const hipError_t e = dispatch(dtype, X, ld, d, [&](auto v) {
+        using V = decltype(v);
+        ProfScope ps(ADA_K_UPDATE, st);
+        hipLaunchKernelGGL((k_gamma_cross_fix<typename V::In, V::aligned>), dim3(128), dim3(256), 0, st, gp);
+        return hipGetLastError();
+    });
+    return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
 // Section 2.3 on the same tile engine: T x r products against the set R, per-token arg max.
@@ -1311,7 +1394,7 @@ int run_cascade_pass(const void* const* X_layers, int first, int n, int T, int d
     pp.f = {nullptr, ld, T, d, nullptr, nullptr, T, threshold_of(tau), (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0,
             w.hits, hit_words(T), nullptr, w.meta + META_TICKET, nullptr, nullptr, nullptr, nullptr, nullptr,
             0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
-    pp.f.first = T % 4 == 0 ? reinterpret_cast<uint32_t*>(w.best) : nullptr;   // (two K-groups: T <= 16384 fits)
+    pp.f.first = T % 4 == 0 ? w.first : nullptr;              // (two K-groups: T <= 16384 fits)
     // rows of idx_all that share a 128-byte line with their neighbour could be cached half-written
     pp.f.coherent_list = ((uintptr_t)idx_all % 128 != 0 || T % 32 != 0) ? 1 : 0;
     for (int i = 0; i < n; ++i) pp.X[i] = X_layers[first + i];
@@ -1527,7 +1610,8 @@ int ada_cascade_step_static(const void* X, int T, int d, int64_t ld, int dtype, 
     // array is good whatever an earlier call left behind; everything else a step reads it writes first.
     const Workspace w = carve(ws, T);
     if (fill_u32(w.meta, META_BYTES / 4, 0u, (hipStream_t)stream) != hipSuccess) return ADA_ERR_DEVICE;
-    if (fill_u32(w.best, (size_t)T, 0u, (hipStream_t)stream) != hipSuccess) return ADA_ERR_DEVICE;   // first-hit records
+    if (fill_u32(w.best, (size_t)T * 2, 0u, (hipStream_t)stream) != hipSuccess ||                       // arg-max keys
+        fill_u32(w.first, (size_t)T, 0u, (hipStream_t)stream) != hipSuccess) return ADA_ERR_DEVICE;         // first-hit records
     return run_cascade(X, T, d, ld, dtype, tau, prev_idx, r, r_dev, idx, adds, removes, counts, gram_ops, gamma, ws,
                        (hipStream_t)stream, flags);
 }

@@ -41,9 +41,9 @@ def check_full(x_cpu, tau, got, what=""):
 
 
 def check_cascade(x_cpu, tau, prev_idx, got, flags=0, what="", two_pass=False):
-    """got: ada.fetch() of ada_cascade_step on the same prev_idx.  two_pass says which gamma the call reports for
-    non-inherited tokens: the exact gamma^cross (two-launch form) or the row maximum over all inherited
-    representatives (one-launch form); decisions are checked the same way for both."""
+    """got: ada.fetch() of ada_cascade_step on the same prev_idx.  Both launch forms report Algorithm 1's own maxima
+    (gamma^rep for an inherited token, gamma^cross over the valid representatives for any other), so `two_pass` only
+    names the form in messages."""
     X = wl.as_f64(x_cpu)
     T = X.shape[0]
     prev_idx = np.asarray(prev_idx, dtype=np.int32)
@@ -58,8 +58,7 @@ def check_cascade(x_cpu, tau, prev_idx, got, flags=0, what="", two_pass=False):
             break
         force[band] = in_gpu[band]
         ref = oracle.cascade_step(X, tau, prev_idx, flags=flags, force=force)
-    ref_gamma = ref["gamma"] if two_pass else ref["gamma_all"]
-    err = float(np.max(np.abs(got["gamma"].astype(np.float64) - ref_gamma)))
+    err = float(np.max(np.abs(got["gamma"].astype(np.float64) - ref["gamma"])))
     assert err <= GAMMA_TOL, "%s gamma error %.3g" % (what, err)
     for k in ("idx", "adds", "removes"):
         assert np.array_equal(got[k], ref[k]), "%s %s differs: gpu %s... oracle %s..." % (

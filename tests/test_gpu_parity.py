@@ -897,6 +897,40 @@ def test_deterministic_reruns():
     assert torch.equal(c["gamma"], d["gamma"]) and torch.equal(c["counts"], d["counts"])
 
 
+@pytest.mark.parametrize("ci,groups", [(2, 1), (3, 1), (2, 4)])
+def test_repeated_passes_are_bit_identical(ci, groups):
+    """300 passes of the layer loop at the benchmark's shapes (one sequence of configurations 2 and 3; four stacked
+    sequences of configuration 2 in one launch per step): every pass must reproduce pass 0 bit for bit (index sets,
+    counts, Gram-operation counts).  The hand-over between workgroups inside a launch (hit words and first-hit records
+    written through the L2, tickets, one cache invalidate) and the workspace's zero-between-calls state are what this
+    exercises; pass 0 itself is the one the configuration tests check against the oracle."""
+    w = wl.config(ci)
+    n_layers = 10
+    say("%s: 300 passes, %d layers, %d group(s)" % (w.name, n_layers, groups))
+    if groups == 1:
+        xs = [x.to(DEV) for x in wl.layers(w, 0, n_layers)]
+        ws = pa.workspace(w.T, DEV)
+        run = lambda out: pa.ada_cascade_layers(xs, w.tau, ws=ws, out=out, want_lists=True)
+    else:
+        per = [wl.layer_list(w, b, n_layers) for b in range(groups)]
+        xg = [torch.stack([per[b][l] for b in range(groups)]).to(DEV) for l in range(n_layers)]
+        ws = pa.workspace_batched(w.T, groups, DEV)
+        run = lambda out: pa.ada_cascade_layers_grouped(xg, w.tau, ws=ws, out=out, want_lists=True)
+    out = run(None)
+    torch.cuda.synchronize()
+    keys = ("idx", "counts", "gram_ops", "adds", "removes")
+    for k in keys:                                   # unwritten tails must compare equal too: start them from zero
+        out[k].zero_()
+    out = run(out)
+    torch.cuda.synchronize()
+    first = {k: out[k].clone() for k in keys}
+    assert first["counts"].reshape(-1, 4)[:, 3].abs().sum().item() == 0
+    for i in range(1, 300):
+        out = run(out)
+        for k in keys:
+            assert torch.equal(out[k], first[k]), "pass %d differs from pass 0 in %s" % (i, k)
+
+
 # ------------------------------------------------------------------------------------------ the five configurations
 def test_config0_all_layers():
     w = wl.config(0)
