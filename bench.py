@@ -41,10 +41,46 @@ def cpu_baseline(w, xs_cpu, n_cascade=3):
         t_c.append(time.perf_counter() - t0)
         prev = res["idx"]
     mean_c = sum(t_c) / len(t_c)
-    return dict(value=w.L / (t_full + (w.L - 1) * mean_c), unit="layers/s", cores=oracle.threads(), kind="oracle",
+    extra = cpu_baseline_extras()
+    return dict(value=w.L / (t_full + (w.L - 1) * mean_c), unit="layers/s", cores=oracle.threads(), kind="oracle", **extra,
                 sample="float64 C oracle (OpenMP) on layer 0 (full, %.2f s) and layers 1-%d (cascade, mean %.2f s) of the "
                        "same sequence; extrapolated to the %d-layer pass" % (t_full, n_cascade, mean_c, w.L),
                 t_full_s=t_full, t_cascade_s=mean_c)
+
+
+def cpu_baseline_extras():
+    """Two more samples of the oracle as it stands: the small fp32 configuration on ONE thread, and one full selection
+    at the long-context shape on all cores."""
+    import oracle
+    from paper_2605_03110_amd import workloads as wl
+    out = {}
+    w0 = wl.config(0)
+    xs0 = [wl.as_f64(x) for x in wl.layer_list(w0, 0, 3)]
+    before = oracle.set_threads(1)
+    try:
+        t0 = time.perf_counter()
+        f0 = oracle.select_full(xs0[0], w0.tau)
+        tf = time.perf_counter() - t0
+        prev, tc = f0["idx"], []
+        for X in xs0[1:]:
+            t0 = time.perf_counter()
+            res = oracle.cascade_step(X, w0.tau, prev)
+            tc.append(time.perf_counter() - t0)
+            prev = res["idx"]
+        th = oracle.threads()
+    finally:
+        oracle.set_threads(before)
+    tcm = sum(tc) / len(tc)
+    out["single_thread_c0"] = {"threads": th, "t_full_s": tf, "t_cascade_s": tcm,
+                               "layers_per_s": w0.L / (tf + (w0.L - 1) * tcm),
+                               "sample": "%s: layer 0 full + 2 cascade layers, extrapolated to %d layers" % (w0.name, w0.L)}
+    w4 = wl.config(4)
+    x4 = wl.as_f64(next(iter(wl.layers(w4, 0, 1))))
+    t0 = time.perf_counter()
+    oracle.select_full(x4, w4.tau)
+    out["full_selection_c4"] = {"threads": oracle.threads(), "t_full_s": time.perf_counter() - t0,
+                                "sample": "%s layer 0 of one sequence (T=%d, d=%d)" % (w4.name, w4.T, w4.d)}
+    return out
 
 
 def recorded_traffic(name):
@@ -92,7 +128,7 @@ def probe(pa, xs, w, ws, out, stream):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="which of the five workload configurations, 0..4 (default 2: T=2048, d=4096, 28 layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -135,14 +171,18 @@ def main():
         probe(pa, xs, w, ws, out, stream)
         return
 
-    for _ in range(args.warmup):
+    out["idx"].zero_()                                   # (entries past a layer's set size are never written)
+    for _ in range(max(args.warmup, 1)):
         step()
     torch.cuda.synchronize()
+    first_pass = {k: out[k].clone() for k in ("idx", "counts", "gram_ops")}
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    for k, v in first_pass.items():                      # every timed pass writes the same buffers: the last equals the first
+        assert torch.equal(out[k], v), "the last timed pass differs from the first in %s" % k
     ms_per_step = 1e3 * elapsed / args.steps
     layers_per_s = L * args.steps / elapsed
 
@@ -401,6 +441,33 @@ def main():
             "tokens_per_s": Bq * L * nb / g_elapsed * T,
             "cascade_launch_us": 1e3 * kg["cascade_fused"]["ms"] / kg["cascade_fused"]["launches"]}
         del xg
+        # ---- sixteen stacked sequences (four layers each): the regime in which a launch's fixed chain of memory round
+        # trips is shared by enough tiles to matter little, i.e. what the tile engine itself sustains
+        B16, L16 = 16, 4
+        per16 = [list(wl.layers(w, b, L16)) for b in range(B16)]
+        x16 = [torch.stack([per16[b][l] for b in range(B16)]).to(dev) for l in range(L16)]
+        del per16
+        ws16 = pa.workspace_batched(T, B16, dev)
+        o16 = None
+        for _ in range(2):
+            o16 = pa.ada_cascade_layers_grouped(x16, w.tau, ws=ws16, stream=stream, out=o16)
+        torch.cuda.synchronize()
+        pa.ada_profile_enable(True)
+        for _ in range(5):
+            pa.ada_cascade_layers_grouped(x16, w.tau, ws=ws16, stream=stream, out=o16)
+        torch.cuda.synchronize()
+        k16 = pa.ada_profile_collect()
+        pa.ada_profile_enable(False)
+        us16 = 1e3 * k16["cascade_fused"]["ms"] / k16["cascade_fused"]["launches"]
+        r16 = float(o16["counts"][:, :-1, 0].float().mean())
+        result["batched"]["stacked_16_sequences"] = {
+            "sequences": B16, "layers": L16, "cascade_launch_us": us16, "us_per_layer_and_sequence": us16 / B16,
+            "roofline": {"bound": "hbm", "kernel": "k_cascade_fused (16 problems per launch)",
+                         "achieved": B16 * layer_bytes / (1e-6 * us16) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": B16 * layer_bytes / (1e-6 * us16) / 1e9 / HBM_PEAK_GBS,
+                         "bytes_per_launch": B16 * layer_bytes,
+                         "mfma_frac": B16 * 2.0 * d * T * r16 / (1e-6 * us16) / 1e12 / MFMA_BF16_PEAK_TFLOPS}}
+        del x16, ws16, o16
         # ---- a representative set per head (Section 8.5): the H column blocks of X as H problems in one launch
         Hh = 16 if d % 16 == 0 else 1
         hv = [pa.heads_view(x, Hh) for x in xs]
@@ -449,14 +516,21 @@ def main():
             pa.ada_profile_enable(False)
             us_o = 1e3 * ko["cascade_fused"]["ms"] / ko["cascade_fused"]["launches"]
             by = wo.T * wo.d * (2 if wo.dtype == "bf16" else 4)
+            r_in = float(oo["counts"][:-1, 0].float().mean())         # the sets the timed steps inherited
+            fl = 2.0 * wo.d * wo.T * r_in                             # T x r Gram entries of eq. (6), 2 d flops each
             other[wo.name] = {"T": wo.T, "d": wo.d, "mean_r": float(oo["counts"][1:, 0].float().mean()),
-                              "cascade_launch_us": us_o, "hbm_frac": by / (1e-6 * us_o) / 1e9 / HBM_PEAK_GBS}
+                              "mean_r_inherited": r_in, "cascade_launch_us": us_o,
+                              "hbm_frac": by / (1e-6 * us_o) / 1e9 / HBM_PEAK_GBS,
+                              "mfma_tflops": fl / (1e-6 * us_o) / 1e12,
+                              "mfma_frac": fl / (1e-6 * us_o) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                              "bound": "mfma" if fl / (MFMA_BF16_PEAK_TFLOPS * 1e12) > by / (HBM_PEAK_GBS * 1e9) else "hbm",
+                              "traffic": recorded_traffic("cascade_fused_c%d_pmc.txt" % ci)}
             del xo, wso, oo
         # configs[4] as the configuration states it: a batch of four sequences, here stacked in one tensor with one
         # launch per step for all four (three layers of each)
         if args.config != 4:
             w4b = wl.config(4)
-            B4, L4 = 4, 3
+            B4, L4 = 4, 5
             per4 = [list(wl.layers(w4b, b, L4)) for b in range(B4)]
             x4g = [torch.stack([per4[b][l] for b in range(B4)]).to(dev) for l in range(L4)]
             del per4
@@ -473,10 +547,35 @@ def main():
             pa.ada_profile_enable(False)
             us_g = 1e3 * k4g["cascade_fused"]["ms"] / k4g["cascade_fused"]["launches"]
             by4 = B4 * w4b.T * w4b.d * 2
+            r4 = float(o4["counts"][:, :-1, 0].float().mean())
+            fl4 = 2.0 * w4b.d * w4b.T * r4 * B4
             other[w4b.name + "_batch4_stacked"] = {"T": w4b.T, "d": w4b.d, "sequences": B4,
                                                    "mean_r": float(o4["counts"][:, 1:, 0].float().mean()),
                                                    "cascade_launch_us": us_g, "us_per_layer_and_sequence": us_g / B4,
-                                                   "hbm_frac": by4 / (1e-6 * us_g) / 1e9 / HBM_PEAK_GBS}
+                                                   "hbm_frac": by4 / (1e-6 * us_g) / 1e9 / HBM_PEAK_GBS,
+                                                   "mfma_frac": fl4 / (1e-6 * us_g) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+            # the configuration's own schedule on these layers: the cascade at every layer, and the full T x T selection
+            # of all four sequences at layer 0 and at every 8th layer (here: layers 0 and L4 - 1 stand for 0 and 8)
+            m4 = torch.empty((B4, w4b.T), dtype=torch.uint8, device=dev)
+            i4 = torch.empty((B4, w4b.T), dtype=torch.int32, device=dev)
+            c4 = torch.empty((B4, 4), dtype=torch.int32, device=dev)
+
+            def schedule_pass():
+                pa.ada_cascade_layers_grouped(x4g, w4b.tau, ws=ws4g, stream=stream, want_lists=False, out=o4)
+                pa.ada_select_full_grouped(x4g[L4 - 1], w4b.tau, ws=ws4g, stream=stream,
+                                           out=dict(mask=m4, idx=i4, counts=c4))
+            schedule_pass()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                schedule_pass()
+            torch.cuda.synchronize()
+            sched_ms = 1e3 * (time.perf_counter() - t0) / 3
+            other[w4b.name + "_schedule"] = {
+                "what": "four stacked sequences: full selection at layer 0, cascade at layers 1..%d, full selection "
+                        "again at the last of them (the configuration repeats this every 8 layers)" % (L4 - 1),
+                "layers": L4, "sequences": B4, "ms_per_pass": sched_ms,
+                "layers_per_s": B4 * L4 / (1e-3 * sched_ms), "tokens_per_s": B4 * L4 * w4b.T / (1e-3 * sched_ms)}
             del x4g, ws4g, o4
         result["cascade_other_shapes"] = other
 

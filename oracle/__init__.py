@@ -49,6 +49,8 @@ def _load():
         c_i8p = ctypes.POINTER(ctypes.c_int8)
         c_u64p = ctypes.POINTER(ctypes.c_uint64)
         lib.ada_oracle_threads.restype = ctypes.c_int
+        lib.ada_oracle_set_threads.restype = ctypes.c_int
+        lib.ada_oracle_set_threads.argtypes = [ctypes.c_int]
         lib.ada_oracle_normalize.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_dp, c_dp]
         lib.ada_oracle_gram.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, c_dp]
         lib.ada_oracle_select_full.argtypes = [c_dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int,
@@ -82,6 +84,11 @@ def _check(rc: int, what: str):
 
 def threads() -> int:
     return int(_load().ada_oracle_threads())
+
+
+def set_threads(n: int) -> int:
+    """Number of OpenMP threads for later calls (timing only: results do not depend on it); returns the previous one."""
+    return int(_load().ada_oracle_set_threads(int(n)))
 
 
 def normalize(X):

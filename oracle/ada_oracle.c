@@ -68,6 +68,19 @@ int ada_oracle_threads(void) {
 #endif
 }
 
+/* Sets the number of OpenMP threads later calls use (n >= 1); returns the previous maximum.  No arithmetic depends
+ * on it: every Gram entry is one thread's left-to-right dot product. */
+int ada_oracle_set_threads(int n) {
+#ifdef _OPENMP
+    const int before = omp_get_max_threads();
+    if (n >= 1) omp_set_num_threads(n);
+    return before;
+#else
+    (void)n;
+    return 1;
+#endif
+}
+
 /* Section 2.1: Xhat = D^{-1} X with D = diag(||x_t||).  Reading R5 for a zero row. */
 int ada_oracle_normalize(const double* X, int T, int d, double* Xhat, double* norms) {
     if (!X || !Xhat || T < 1 || d < 1) return ADA_ORACLE_ERR_ARG;

@@ -432,15 +432,17 @@ def _check_xg(Xg: torch.Tensor):
 
 
 def ada_select_full_grouped(Xg: torch.Tensor, tau: float, *, ws: Optional[torch.Tensor] = None, stream=None,
-                            flags: int = 0) -> Dict[str, torch.Tensor]:
+                            flags: int = 0, out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
     """Full selection of G problems in one allocation (Xg: [G, T, d] view).  Returns mask [G, T] u8, idx [G, T] i32,
     counts [G, 4] i32 (usable as prev_idx / r_dev of ada_cascade_step_grouped)."""
     _check_xg(Xg)
     G, T, d = Xg.shape
     dev = Xg.device
     ws = workspace_batched(T, G, dev) if ws is None else ws
-    out = dict(mask=torch.empty((G, T), dtype=torch.uint8, device=dev), idx=torch.empty((G, T), dtype=torch.int32, device=dev),
-               counts=torch.empty((G, 4), dtype=torch.int32, device=dev))
+    if out is None:
+        out = dict(mask=torch.empty((G, T), dtype=torch.uint8, device=dev),
+                   idx=torch.empty((G, T), dtype=torch.int32, device=dev),
+                   counts=torch.empty((G, 4), dtype=torch.int32, device=dev))
     g = AdaGroups(G, Xg.stride(0) if G > 1 else d, T, 4, 1)
     rc = lib().ada_select_full_grouped(ctypes.byref(g), _ptr(Xg), T, d, Xg.stride(1), _dtype_code(Xg), float(tau),
                                        _ptr(out["mask"]), _ptr(out["idx"]), _ptr(out["counts"]), _ptr(ws), ws.numel(),
