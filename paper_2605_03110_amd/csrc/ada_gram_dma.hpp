@@ -34,7 +34,11 @@ struct DmaGeom {
 #endif
 
 // One WM*2 x WM*2 tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side.
-template <int WM>
+// NORMS: the rows' sums of squares (Section 2.1) come from the fragments in hand instead of a pass of their own: a
+// 32-row block is held by two waves, each wave sums the blocks at its even local positions, and the local order of a
+// wave's blocks is permuted (block a ^ parity) so that those positions cover every block and the K loop stays
+// straight-line code.
+template <int WM, bool NORMS>
 __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool need_order, char* lds) {
     using G = DmaGeom;
     constexpr int BT = 2 * WM, ROWS = 2 * BT, NB = WM / 32, LPT = ROWS / 64, NS = G::NS, HC = G::HC;
@@ -59,7 +63,8 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         const bool isS = i < BT;
         const int tok = isS ? s0 + i : t0 + (i - BT);
         const bool ok = tok < T;
-        const float sc = ok ? p.inv_norm[ok ? tok : 0] : 0.f;
+        float sc = 0.f;
+        if constexpr (!NORMS) sc = ok ? p.inv_norm[ok ? tok : 0] : 0.f;
         if (isS) { s_tok[i] = ok ? tok : INT_MAX; s_scale[i] = sc; }
         else { t_tok[i - BT] = ok ? tok : -1; t_scale[i - BT] = sc; }
     }
@@ -97,21 +102,48 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
     // lane part of a fragment address for k-step ks of a half chunk: row l32 of a 32-row block, piece 2 ks + half
     const int lo0 = l32 * 64 + (((0 + half) ^ ((l32 >> 2) & 3)) << 4);
     const int lo1 = l32 * 64 + (((2 + half) ^ ((l32 >> 2) & 3)) << 4);
+    // local block a of this wave is block ablk(a) of its NB "against" blocks, likewise bblk for the tested blocks
+    // (identity without NORMS)
+    const int pa = NORMS ? wt : 0, pb = NORMS ? ws : 0;
     const char* abase = ring + (ws * WM) * 64;
     const char* bbase = ring + (BT + wt * WM) * 64;
+    const char* aptr[2][NB];
+    const char* bptr[2][NB];
+#pragma unroll
+    for (int a = 0; a < NB; ++a) {
+        aptr[0][a] = abase + (a ^ pa) * 2048 + lo0; aptr[1][a] = abase + (a ^ pa) * 2048 + lo1;
+        bptr[0][a] = bbase + (a ^ pb) * 2048 + lo0; bptr[1][a] = bbase + (a ^ pb) * 2048 + lo1;
+    }
     u32x4 fa[2][NB], fb[2][NB];
     auto read_frags = [&](int set, int stage_off, int ks) {
-        const int lo = ks ? lo1 : lo0;
+        if constexpr (NORMS) {
 #pragma unroll
-        for (int a = 0; a < NB; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(abase + stage_off + a * 2048 + lo);
+            for (int a = 0; a < NB; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(aptr[ks][a] + stage_off);
 #pragma unroll
-        for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bbase + stage_off + b * 2048 + lo);
+            for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bptr[ks][b] + stage_off);
+        } else {
+            const int lo = ks ? lo1 : lo0;
+#pragma unroll
+            for (int a = 0; a < NB; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(abase + stage_off + a * 2048 + lo);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bbase + stage_off + b * 2048 + lo);
+        }
     };
+    float ssa[NB / 2], ssb[NB / 2];
+#pragma unroll
+    for (int i = 0; i < NB / 2; ++i) { ssa[i] = 0.f; ssb[i] = 0.f; }
     auto mma = [&](int set) {
 #pragma unroll
         for (int a = 0; a < NB; ++a)
 #pragma unroll
             for (int b = 0; b < NB; ++b) Mfma<uint16_t>::run(acc[a][b], fa[set][a], fb[set][b]);
+        if constexpr (NORMS) {
+#pragma unroll
+            for (int i = 0; i < NB; i += 2) {
+                ssa[i >> 1] += piece_sumsq_fast<uint16_t>(fa[set][i]);
+                ssb[i >> 1] += piece_sumsq_fast<uint16_t>(fb[set][i]);
+            }
+        }
     };
 
     // Half step h multiplies half chunk h (two k-steps of 16).  With one wave per SIMD nothing else hides latency, so
@@ -158,22 +190,35 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
     __syncthreads();
     DMA_CLK(2);
+    if constexpr (NORMS) {
+        // the two lane halves hold different k pieces; rows that do not exist keep scale 0
+#pragma unroll
+        for (int i = 0; i < NB / 2; ++i) {
+            const float va = ssa[i] + __shfl_xor(ssa[i], 32, 64), vb = ssb[i] + __shfl_xor(ssb[i], 32, 64);
+            if (half == 0) {
+                const int ra = ws * WM + ((2 * i) ^ pa) * 32 + l32, rb = wt * WM + ((2 * i) ^ pb) * 32 + l32;
+                s_scale[ra] = (s_tok[ra] != INT_MAX && va > 0.f) ? 1.0f / sqrtf(va) : 0.f;   // a zero row normalises to zero
+                t_scale[rb] = (t_tok[rb] >= 0 && vb > 0.f) ? 1.0f / sqrtf(vb) : 0.f;
+            }
+        }
+        __syncthreads();
+    }
 
     uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        const int nl = wt * WM + b * 32 + l32;
+        const int nl = wt * WM + (b ^ pb) * 32 + l32;
         const int ttok = t_tok[nl];
         float m = 0.f;
 #pragma unroll
         for (int a = 0; a < NB; ++a)
-            m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WM + a * 32, half, need_order, ttok));
+            m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WM + (a ^ pa) * 32, half, need_order, ttok));
         publish_max(m, t_scale[nl], ttok, half, gamma_bits);
         if (p.hits) {                                              // greedy covering: one bit per pair s < t as well
 #pragma unroll
             for (int a = 0; a < NB; ++a)
-                publish_hits(acc[a][b], s_scale, s_tok, ws * WM + a * 32, half, need_order, ttok, t_scale[nl], p.thr,
-                             p.hits, T, s0 + ws * WM + a * 32);
+                publish_hits(acc[a][b], s_scale, s_tok, ws * WM + (a ^ pa) * 32, half, need_order, ttok, t_scale[nl], p.thr,
+                             p.hits, T, s0 + ws * WM + (a ^ pa) * 32);
         }
     }
     DMA_CLK(3);
@@ -201,7 +246,10 @@ __device__ inline int tri_row(long long v) {
 
 // Definition "Gram threshold", last step, run by the workgroup that leaves the launch last (u.counts != NULL): the
 // row maxima are complete then, so the threshold test and the compaction need no launch of their own.
-__device__ inline void full_selection_finish(UpdateParams u, const float* gamma, int* sh /* 3 x 32 ints */) {
+// acc_reset: the maxima were accumulated in a workspace array that is zero between calls (no launch cleared it):
+// hand them to the caller's array (gamma_out, may be NULL) and zero the accumulator again.
+__device__ inline void full_selection_finish(UpdateParams u, float* gamma, int* sh /* 3 x 32 ints */, bool acc_reset,
+                                             float* gamma_out) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int T = u.T;
     const int chunk = (T + nthr - 1) / nthr;
@@ -211,9 +259,14 @@ __device__ inline void full_selection_finish(UpdateParams u, const float* gamma,
     int n_idx;
     int o_idx = block_exclusive_scan(c_idx, &n_idx, sh);
     for (int t = lo; t < hi; ++t) {
-        const bool keep = gamma[t] < u.thr;
+        const float g = gamma[t];
+        const bool keep = g < u.thr;
         if (u.mask) u.mask[t] = keep ? 1 : 0;
         if (keep) { if (u.idx) u.idx[o_idx] = t; ++o_idx; }
+        if (acc_reset) {
+            if (gamma_out) gamma_out[t] = g;
+            gamma[t] = 0.f;
+        }
     }
     if (tid == 0) {
         u.counts[0] = n_idx; u.counts[1] = n_idx; u.counts[2] = 0; u.counts[3] = ADA_OK;
@@ -221,7 +274,8 @@ __device__ inline void full_selection_finish(UpdateParams u, const float* gamma,
     }
 }
 
-__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* queue, UpdateParams upd) {
+template <bool NORMS>
+__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* queue, UpdateParams upd, float* gamma_out) {
     extern __shared__ __align__(16) char lds[];
     __shared__ long long s_next;
     __shared__ int s_last, s_scan[32];
@@ -233,19 +287,23 @@ __global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, in
     while (u < U.n_units) {
         long long nxt = 0;
         if (threadIdx.x == 0) nxt = (long long)G + atomicAdd(queue, 1);           // next unit: the reply arrives behind the tile
-        if (u < U.n_big) {
+        if constexpr (NORMS) {                                 // (launched with 128-row units only: big_mode == 0)
+            const int tb = tri_row(u);                         // 128-blocks: 0 <= sb <= tb
+            const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
+            gram_tile_dma<64, true>(p, sb * 128, tb * 128, sb == tb, lds);
+        } else if (u < U.n_big) {
             const int tb = tri_row(u) + 1;                     // off-diagonal 256-blocks: 0 <= sb < tb
             const int sb = (int)(u - (long long)tb * (tb - 1) / 2);
-            gram_tile_dma<128>(p, sb * 256, tb * 256, false, lds);
+            gram_tile_dma<128, false>(p, sb * 256, tb * 256, false, lds);
         } else if (big_mode) {
             const long long v = u - U.n_big;                   // diagonal 256-block i in three 128 x 128 units
             const int i = (int)(v / 3), k = (int)(v % 3);
             const int t0 = (2 * i + (k >= 1)) * 128, s0 = (2 * i + (k == 2)) * 128;
-            if (t0 < p.T) gram_tile_dma<64>(p, s0, t0, k != 1, lds);
+            if (t0 < p.T) gram_tile_dma<64, false>(p, s0, t0, k != 1, lds);
         } else {
             const int tb = tri_row(u);                         // 128-blocks: 0 <= sb <= tb
             const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
-            gram_tile_dma<64>(p, sb * 128, tb * 128, sb == tb, lds);
+            gram_tile_dma<64, false>(p, sb * 128, tb * 128, sb == tb, lds);
         }
         if (threadIdx.x == 0) s_next = nxt;
         __syncthreads();
@@ -273,5 +331,6 @@ __global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, in
         upd.counts += g * upd.go.counts;
         if (upd.gram_ops) upd.gram_ops += g * upd.go.ops;
     }
-    full_selection_finish(upd, p.gamma, s_scan);             // (p.gamma is this problem's: gram_group_offset)
+    if (NORMS && gamma_out && upd.go.ws) gamma_out = nullptr; // (several problems: no gamma output)
+    full_selection_finish(upd, p.gamma, s_scan, NORMS, gamma_out);   // (p.gamma is this problem's: gram_group_offset)
 }

@@ -950,12 +950,13 @@ inline double dma_makespan(int T, int big_mode, int G) {
 
 // mode: 0 = 128 x 128 units everywhere, 1 = 256 x 256 off the diagonal, -1 = whichever hands out better
 // u.counts != NULL: the workgroup that leaves last also applies the threshold and compacts the set (no update launch)
+template <bool NORMS>
 hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st, int groups,
-                           const UpdateParams& u) {
+                           const UpdateParams& u, float* gamma_out = nullptr) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gram_dma),
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gram_dma<NORMS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom::LDS);
     });
     if (attr_err != hipSuccess) return attr_err;
@@ -964,6 +965,7 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
         G = G / groups / 8 * 8;                                // workgroups are handed out through its queue
         if (G < 8) G = 8;
     }
+    if (NORMS) mode = 0;                                       // the one-launch form runs on 128-row units
     if (mode < 0) {
         static std::mutex mu;
         static int last_T = 0, last_G = 0, last_mode = 0;     // the choice depends on both the size and the workgroups
@@ -976,7 +978,8 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
         mode = last_mode;
     }
     ProfScope ps(ADA_K_GRAM_FULL, st);
-    hipLaunchKernelGGL(k_gram_dma, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue, u);
+    hipLaunchKernelGGL(k_gram_dma<NORMS>, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue, u,
+                       gamma_out);
     return hipGetLastError();
 }
 
@@ -1110,18 +1113,28 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
     hipError_t e = dispatch(dtype, X, ld_seen, d, [&](auto v) {
         using V = decltype(v);
         using In = typename V::In;
-        hipError_t e1 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st, go, groups);
-        if (e1 != hipSuccess) return e1;
-        if constexpr (V::aligned) {
-            if constexpr (sizeof(In) == 2) {
-                // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
-                const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
-                if (can && (path == "dma0" || path == "dma1" || (path.empty() && T >= 1536))) {
-                    finished = finish_in_kernel;
-                    return launch_gram_dma(p, w.meta + META_QUEUE, path.empty() ? -1 : path == "dma1", st, groups, in_kernel);
+        if constexpr (V::aligned && sizeof(In) == 2) {
+            // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
+            const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
+            if (can && (path == "dma0" || path == "dma1" || (path.empty() && T >= 1536))) {
+                const int mode = path.empty() ? -1 : path == "dma1";
+                if (finish_in_kernel) {
+                    // ONE launch: the norms come from the tiles' own fragments, and the row maxima are accumulated in a
+                    // workspace array that is zero between calls (the workgroup that finishes hands them over and
+                    // clears it again), so nothing has to be computed or cleared ahead of the tiles.
+                    GramParams q = p;
+                    q.inv_norm = nullptr;
+                    q.gamma = reinterpret_cast<float*>(w.first);
+                    finished = true;
+                    return launch_gram_dma<true>(q, w.meta + META_QUEUE, mode, st, groups, in_kernel, gamma);
                 }
+                hipError_t e0 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st, go, groups);
+                if (e0 != hipSuccess) return e0;
+                return launch_gram_dma<false>(p, w.meta + META_QUEUE, mode, st, groups, in_kernel);
             }
         }
+        hipError_t e1 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st, go, groups);
+        if (e1 != hipSuccess) return e1;
         return launch_gram_any<In, V::aligned>(p, T, T, true, st, groups);
     });
     if (e != hipSuccess) return ADA_ERR_DEVICE;
