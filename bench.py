@@ -134,6 +134,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the full-selection timing and the profiled pass")
     ap.add_argument("--probe", action="store_true", help="short run for rocprofv3 --pmc (no timing, no JSON result)")
+    ap.add_argument("--layers", type=int, default=0, help="use only the first N layers of the configuration (0 = all); "
+                    "for counter runs at the large shapes, where generating every layer on the host takes longest")
     ap.add_argument("--roofline-only", action="store_true",
                     help="the timed passes and the event-timed pass of the roofline only (for a kernel trace in which "
                          "k_cascade_fused runs this workload's cascade steps and nothing else)")
@@ -153,6 +155,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = wl.config(args.config)
+    if args.layers > 0:
+        w = wl.config(args.config, L=min(args.layers, w.L))
     T, d, L = w.T, w.d, w.L
     esz = 2 if w.dtype == "bf16" else 4
 
