@@ -390,7 +390,8 @@ int ada_profile_mfma_probe(int workgroups, int iters, float* sink, void* stream)
 /*
  * Development switches (environment variables; not part of the interface).  They force code paths that the library
  * otherwise chooses by shape, for tests and measurements, and are read only when ADA_DEV_SWITCHES=1 is set as well:
- *   ADA_GRAM=tile|dma0|dma1       full selection: register-staged tiles / direct-to-LDS kernel with 128- or 256-row units
+ *   ADA_GRAM=tile|dma0|dma1|dma2  full selection: register-staged tiles / direct-to-LDS kernel with 128-row, 256-row or
+ *                                 64 x 128 units
  *   ADA_TILE=64|128               register-staged Gram tile size
  *   ADA_KGROUPS=1|2               K-groups of the 64 x 64 one-launch cascade tile
  *   ADA_CASCADE_TILE=64|64x128|128|256x128   tile shape of the one-launch cascade step

@@ -15,8 +15,9 @@
 // block is cut into three 128 x 128 "small" units (the same code with 64 x 64 per wave).  For mid-sized T, where
 // 256-blocks cannot fill the chip, the whole triangle is cut into small units.  Units are handed out big first: the
 // first one by workgroup id (a contiguous range per XCD, so neighbours share rows in that XCD's L2), the rest from an
-// atomic counter, which packs the short units into the tail.  The counter pair lives in the workspace and is zero
-// between launches: the last workgroup to leave resets it.
+// atomic counter, which packs the short units into the tail.  The counter and the sign-off tickets (counted per XCD
+// first, as in the cascade step) live in the workspace and are zero between launches: the last workgroup to leave
+// resets them.
 #pragma once
 
 struct DmaGeom {
@@ -28,45 +29,50 @@ struct DmaGeom {
 };
 
 #ifdef ADA_PHASE_CLOCKS
-#define DMA_CLK(i) do { if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) { const unsigned long long t_ = clock64(); g_phase_clk[(i) + (WM == 128 ? 32 : 48)] += t_ - last_clk; last_clk = t_; } } while (0)
+// (constant-rate 100 MHz counter; the stamps of the last unit a workgroup ran stay)
+#define DMA_CLK(i) do { if (threadIdx.x == 0) { const unsigned long long t_ = __builtin_amdgcn_s_memrealtime(); \
+    if (blockIdx.x == (ADA_PHASE_CLOCKS)) g_phase_clk[(i) + 48] = t_; if ((i) < 8) g_pass_clk[(blockIdx.x & 511) * 8 + (i)] = t_; } } while (0)
+#define DMA_CLK_ANY(i) do { if (threadIdx.x == 0) g_phase_clk[(i) + 48] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #else
 #define DMA_CLK(i) do { } while (0)
+#define DMA_CLK_ANY(i) do { } while (0)
 #endif
 
-// One WM*2 x WM*2 tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side.
+// One (2 WA) x (2 WB) tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side; the four waves
+// are a 2 x 2 grid of WA x WB blocks.
 // NORMS: the rows' sums of squares (Section 2.1) come from the fragments in hand instead of a pass of their own: a
 // 32-row block is held by two waves, each wave sums the blocks at its even local positions, and the local order of a
 // wave's blocks is permuted (block a ^ parity) so that those positions cover every block and the K loop stays
-// straight-line code.
-template <int WM, bool NORMS>
+// straight-line code (a side with one block per wave is summed by both of its waves).
+template <int WA, int WB, bool NORMS>
 __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool need_order, char* lds) {
     using G = DmaGeom;
-    constexpr int BT = 2 * WM, ROWS = 2 * BT, NB = WM / 32, LPT = ROWS / 64, NS = G::NS, HC = G::HC;
+    constexpr int BS = 2 * WA, BT = 2 * WB, ROWS = BS + BT;
+    constexpr int NA = WA / 32, NB = WB / 32, LPT = ROWS / 64, NS = G::NS, HC = G::HC;
     constexpr int STAGE = ROWS * 64;
+    static_assert(ROWS % 64 == 0 && STAGE <= G::STAGE && 2 * (BS + BT) * 4 <= G::META, "ring and tables fit");
     int* s_tok = reinterpret_cast<int*>(lds);
-    int* t_tok = s_tok + BT;
+    int* t_tok = s_tok + BS;
     float* s_scale = reinterpret_cast<float*>(t_tok + BT);
-    float* t_scale = s_scale + BT;
+    float* t_scale = s_scale + BS;
     char* ring = lds + G::META;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int ws = wave >> 1, wt = wave & 1;
-#ifdef ADA_PHASE_CLOCKS
-    unsigned long long last_clk = clock64();
-#endif
+    DMA_CLK(4);
     const int T = p.T;
     const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
 
-    for (int i = tid; i < ROWS; i += G::THREADS) {
-        const bool isS = i < BT;
-        const int tok = isS ? s0 + i : t0 + (i - BT);
+    for (int i = tid; i < BS + BT; i += G::THREADS) {
+        const bool isS = i < BS;
+        const int tok = isS ? s0 + i : t0 + (i - BS);
         const bool ok = tok < T;
         float sc = 0.f;
         if constexpr (!NORMS) sc = ok ? p.inv_norm[ok ? tok : 0] : 0.f;
         if (isS) { s_tok[i] = ok ? tok : INT_MAX; s_scale[i] = sc; }
-        else { t_tok[i - BT] = ok ? tok : -1; t_scale[i - BT] = sc; }
+        else { t_tok[i - BS] = ok ? tok : -1; t_scale[i - BS] = sc; }
     }
 
     // Stage layout: rows of 64 bytes = 4 pieces; piece c of row r sits at slot c ^ ((r >> 2) & 3).  Sixteen lanes that
@@ -77,7 +83,7 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
         const int row = (j * 4 + wave) * 16 + (lane >> 2);
-        const int tok = min(row < BT ? s0 + row : t0 + (row - BT), T - 1);
+        const int tok = min(row < BS ? s0 + row : t0 + (row - BS), T - 1);
         rowp[j] = X + (size_t)tok * (size_t)p.ld + (((lane & 3) ^ ((lane >> 4) & 3)) << 3);
     }
     const int nh = p.d / HC;
@@ -91,9 +97,9 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         }
     };
 
-    f32x16 acc[NB][NB];
+    f32x16 acc[NA][NB];
 #pragma unroll
-    for (int a = 0; a < NB; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -104,45 +110,46 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
     const int lo1 = l32 * 64 + (((2 + half) ^ ((l32 >> 2) & 3)) << 4);
     // local block a of this wave is block ablk(a) of its NB "against" blocks, likewise bblk for the tested blocks
     // (identity without NORMS)
-    const int pa = NORMS ? wt : 0, pb = NORMS ? ws : 0;
-    const char* abase = ring + (ws * WM) * 64;
-    const char* bbase = ring + (BT + wt * WM) * 64;
-    const char* aptr[2][NB];
+    const int pa = (NORMS && NA > 1) ? wt : 0, pb = (NORMS && NB > 1) ? ws : 0;
+    const char* abase = ring + (ws * WA) * 64;
+    const char* bbase = ring + (BS + wt * WB) * 64;
+    const char* aptr[2][NA];
     const char* bptr[2][NB];
 #pragma unroll
-    for (int a = 0; a < NB; ++a) {
-        aptr[0][a] = abase + (a ^ pa) * 2048 + lo0; aptr[1][a] = abase + (a ^ pa) * 2048 + lo1;
-        bptr[0][a] = bbase + (a ^ pb) * 2048 + lo0; bptr[1][a] = bbase + (a ^ pb) * 2048 + lo1;
-    }
-    u32x4 fa[2][NB], fb[2][NB];
+    for (int a = 0; a < NA; ++a) { aptr[0][a] = abase + (a ^ pa) * 2048 + lo0; aptr[1][a] = abase + (a ^ pa) * 2048 + lo1; }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) { bptr[0][b] = bbase + (b ^ pb) * 2048 + lo0; bptr[1][b] = bbase + (b ^ pb) * 2048 + lo1; }
+    u32x4 fa[2][NA], fb[2][NB];
     auto read_frags = [&](int set, int stage_off, int ks) {
         if constexpr (NORMS) {
 #pragma unroll
-            for (int a = 0; a < NB; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(aptr[ks][a] + stage_off);
+            for (int a = 0; a < NA; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(aptr[ks][a] + stage_off);
 #pragma unroll
             for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bptr[ks][b] + stage_off);
         } else {
             const int lo = ks ? lo1 : lo0;
 #pragma unroll
-            for (int a = 0; a < NB; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(abase + stage_off + a * 2048 + lo);
+            for (int a = 0; a < NA; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(abase + stage_off + a * 2048 + lo);
 #pragma unroll
             for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bbase + stage_off + b * 2048 + lo);
         }
     };
-    float ssa[NB / 2], ssb[NB / 2];
+    constexpr int DA = (NA + 1) / 2, DB = (NB + 1) / 2;       // blocks a wave sums on each side
+    float ssa[DA], ssb[DB];
 #pragma unroll
-    for (int i = 0; i < NB / 2; ++i) { ssa[i] = 0.f; ssb[i] = 0.f; }
+    for (int i = 0; i < DA; ++i) ssa[i] = 0.f;
+#pragma unroll
+    for (int i = 0; i < DB; ++i) ssb[i] = 0.f;
     auto mma = [&](int set) {
 #pragma unroll
-        for (int a = 0; a < NB; ++a)
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
             for (int b = 0; b < NB; ++b) Mfma<uint16_t>::run(acc[a][b], fa[set][a], fb[set][b]);
         if constexpr (NORMS) {
 #pragma unroll
-            for (int i = 0; i < NB; i += 2) {
-                ssa[i >> 1] += piece_sumsq_fast<uint16_t>(fa[set][i]);
-                ssb[i >> 1] += piece_sumsq_fast<uint16_t>(fb[set][i]);
-            }
+            for (int i = 0; i < NA; i += 2) ssa[i >> 1] += piece_sumsq_fast<uint16_t>(fa[set][i]);
+#pragma unroll
+            for (int i = 0; i < NB; i += 2) ssb[i >> 1] += piece_sumsq_fast<uint16_t>(fb[set][i]);
         }
     };
 
@@ -160,13 +167,13 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         read_frags(0, nxt_off, 0);
         issue(cur_off, h + 4);
         mma(1);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * NB, 0);  // the LDS reads first
+        __builtin_amdgcn_sched_group_barrier(0x100, NA + NB, 0); // the LDS reads first
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // then one MFMA ...
+            if (j < NA * NB) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // then one MFMA ...
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // ... per global load
         }
-        if constexpr (NB * NB > LPT) __builtin_amdgcn_sched_group_barrier(0x008, NB * NB - LPT, 0);
+        if constexpr (NA * NB > LPT) __builtin_amdgcn_sched_group_barrier(0x008, NA * NB - LPT, 0);
     };
     issue(0 * STAGE, 0);
     issue(1 * STAGE, 1);
@@ -193,13 +200,16 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
     if constexpr (NORMS) {
         // the two lane halves hold different k pieces; rows that do not exist keep scale 0
 #pragma unroll
-        for (int i = 0; i < NB / 2; ++i) {
-            const float va = ssa[i] + __shfl_xor(ssa[i], 32, 64), vb = ssb[i] + __shfl_xor(ssb[i], 32, 64);
-            if (half == 0) {
-                const int ra = ws * WM + ((2 * i) ^ pa) * 32 + l32, rb = wt * WM + ((2 * i) ^ pb) * 32 + l32;
-                s_scale[ra] = (s_tok[ra] != INT_MAX && va > 0.f) ? 1.0f / sqrtf(va) : 0.f;   // a zero row normalises to zero
-                t_scale[rb] = (t_tok[rb] >= 0 && vb > 0.f) ? 1.0f / sqrtf(vb) : 0.f;
-            }
+        for (int i = 0; i < DA; ++i) {
+            const float va = ssa[i] + __shfl_xor(ssa[i], 32, 64);
+            const int ra = ws * WA + ((2 * i) ^ pa) * 32 + l32;
+            if (half == 0) s_scale[ra] = (s_tok[ra] != INT_MAX && va > 0.f) ? 1.0f / sqrtf(va) : 0.f;   // a zero row normalises to zero
+        }
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+            const float vb = ssb[i] + __shfl_xor(ssb[i], 32, 64);
+            const int rb = wt * WB + ((2 * i) ^ pb) * 32 + l32;
+            if (half == 0) t_scale[rb] = (t_tok[rb] >= 0 && vb > 0.f) ? 1.0f / sqrtf(vb) : 0.f;
         }
         __syncthreads();
     }
@@ -207,32 +217,162 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
     uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        const int nl = wt * WM + (b ^ pb) * 32 + l32;
+        const int nl = wt * WB + (b ^ pb) * 32 + l32;
         const int ttok = t_tok[nl];
         float m = 0.f;
 #pragma unroll
-        for (int a = 0; a < NB; ++a)
-            m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WM + (a ^ pa) * 32, half, need_order, ttok));
+        for (int a = 0; a < NA; ++a)
+            m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WA + (a ^ pa) * 32, half, need_order, ttok));
         publish_max(m, t_scale[nl], ttok, half, gamma_bits);
         if (p.hits) {                                              // greedy covering: one bit per pair s < t as well
 #pragma unroll
-            for (int a = 0; a < NB; ++a)
-                publish_hits(acc[a][b], s_scale, s_tok, ws * WM + (a ^ pa) * 32, half, need_order, ttok, t_scale[nl], p.thr,
-                             p.hits, T, s0 + ws * WM + (a ^ pa) * 32);
+            for (int a = 0; a < NA; ++a)
+                publish_hits(acc[a][b], s_scale, s_tok, ws * WA + (a ^ pa) * 32, half, need_order, ttok, t_scale[nl], p.thr,
+                             p.hits, T, s0 + ws * WA + (a ^ pa) * 32);
         }
     }
     DMA_CLK(3);
-#ifdef ADA_PHASE_CLOCKS
-    if (threadIdx.x == 0 && blockIdx.x == (ADA_PHASE_CLOCKS)) g_phase_clk[(WM == 128 ? 32 : 48) + 8] += 1;
-#endif
 }
 
+// A 128-token block ON the diagonal, for the one-launch form (sums of squares from the fragments): its rows are staged
+// once, and of its sixteen 32 x 32 blocks only the ten with "against" block <= tested block are multiplied, three per
+// wave and k-step instead of four: wave 0 holds (0,0), (0,1), (1,1), wave 1 holds (2,2), (2,3), (3,3), wave 2 holds
+// (0,2), (0,3) and wave 3 holds (1,2), (1,3).  Written as one code path: four fragments P, Q, R, S per wave and the
+// products P x Q, P x R, S x R (the third is idle work in waves 2 and 3).  Same ring, waits and barrier as gram_tile_dma.
+__device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
+    using G = DmaGeom;
+    constexpr int ROWS = 128, LPT = ROWS / 64, NS = G::NS, HC = G::HC, STAGE = ROWS * 64;
+    int* s_tok = reinterpret_cast<int*>(lds);                  // INT_MAX past the end (never "earlier")
+    int* t_tok = s_tok + ROWS;                                 // -1 past the end (never published)
+    float* scale = reinterpret_cast<float*>(t_tok + ROWS);
+    char* ring = lds + G::META;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const bool tri = wave < 2;
+    const int bP = tri ? 2 * wave : wave - 2, bQ = tri ? bP : 2, bR = tri ? bP + 1 : 3, bS = tri ? bP + 1 : bP;
+    DMA_CLK(4);
+    const int T = p.T;
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
+    for (int i = tid; i < ROWS; i += G::THREADS) {
+        const bool ok = t0 + i < T;
+        s_tok[i] = ok ? t0 + i : INT_MAX;
+        t_tok[i] = ok ? t0 + i : -1;
+        scale[i] = 0.f;
+    }
+    const uint16_t* rowp[LPT];                                 // (stage layout and lane roles: see gram_tile_dma)
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int tok = min(t0 + (j * 4 + wave) * 16 + (lane >> 2), T - 1);
+        rowp[j] = X + (size_t)tok * (size_t)p.ld + (((lane & 3) ^ ((lane >> 4) & 3)) << 3);
+    }
+    const int nh = p.d / HC;
+    auto issue = [&](int stage_off, int h) {
+        const int hc = min(h, nh - 1);
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            char* dst = ring + stage_off + (j * 4 + wave) * 1024;
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + hc * HC),
+                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+        }
+    };
+    f32x16 acc[3];
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+    const int lo0 = l32 * 64 + (((0 + half) ^ ((l32 >> 2) & 3)) << 4);
+    const int lo1 = l32 * 64 + (((2 + half) ^ ((l32 >> 2) & 3)) << 4);
+    const int blk[4] = {bP, bQ, bR, bS};
+    const char* fptr[2][4];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) { fptr[0][f] = ring + blk[f] * 2048 + lo0; fptr[1][f] = ring + blk[f] * 2048 + lo1; }
+    u32x4 fr[2][4];
+    auto read_frags = [&](int set, int stage_off, int ks) {
+#pragma unroll
+        for (int f = 0; f < 4; ++f) fr[set][f] = *reinterpret_cast<const u32x4*>(fptr[ks][f] + stage_off);
+    };
+    float ssP = 0.f, ssR = 0.f;                                // waves 0 and 1 cover the four blocks; 2 and 3 repeat two
+    auto mma = [&](int set) {
+        Mfma<uint16_t>::run(acc[0], fr[set][0], fr[set][1]);
+        Mfma<uint16_t>::run(acc[1], fr[set][0], fr[set][2]);
+        Mfma<uint16_t>::run(acc[2], fr[set][3], fr[set][2]);
+        ssP += piece_sumsq_fast<uint16_t>(fr[set][0]);
+        ssR += piece_sumsq_fast<uint16_t>(fr[set][2]);
+    };
+    auto step = [&](int cur_off, int nxt_off, int h) {
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, cur_off, 1);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));   // h + 1 has landed; my reads of this stage have returned
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, nxt_off, 0);
+        issue(cur_off, h + NS);
+        mma(1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);       // the LDS reads first
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // then one MFMA ...
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // ... per global load
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 3 - LPT, 0);
+    };
+    issue(0 * STAGE, 0);
+    issue(1 * STAGE, 1);
+    issue(2 * STAGE, 2);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));     // half chunk 0 has landed (this wave's part)
+    __builtin_amdgcn_s_barrier();
+    issue(3 * STAGE, 3);
+    read_frags(0, 0, 0);
+    DMA_CLK(0);
+    int h = 0;
+    for (; h + NS < nh; h += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, h + s);
+    }
+    for (; h + 1 < nh; ++h) step((h % NS) * STAGE, ((h + 1) % NS) * STAGE, h);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(1, (h % NS) * STAGE, 1);
+    mma(0);
+    mma(1);
+    DMA_CLK(1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
+    __syncthreads();
+    DMA_CLK(2);
+    {
+        const float vP = ssP + __shfl_xor(ssP, 32, 64), vR = ssR + __shfl_xor(ssR, 32, 64);
+        // (waves that sum the same block write the same bits: same pieces, same order)
+        if (half == 0) {
+            const int rP = bP * 32 + l32, rR = bR * 32 + l32;
+            scale[rP] = (t_tok[rP] >= 0 && vP > 0.f) ? 1.0f / sqrtf(vP) : 0.f;    // a zero row normalises to zero
+            scale[rR] = (t_tok[rR] >= 0 && vR > 0.f) ? 1.0f / sqrtf(vR) : 0.f;
+        }
+        __syncthreads();
+    }
+    uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
+    const int sblk[3] = {bP, bP, bS}, tblk[3] = {bQ, bR, bR};
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        if (a == 2 && !tri) break;                             // (wave-uniform)
+        const int nl = tblk[a] * 32 + l32;
+        const int ttok = t_tok[nl];
+        const float m = block_max(acc[a], scale, s_tok, sblk[a] * 32, half, sblk[a] == tblk[a], ttok);
+        publish_max(m, scale[nl], ttok, half, gamma_bits);
+    }
+    DMA_CLK(3);
+}
+
+// mode 0: 128 x 128 units over the whole triangle; 1: 256 x 256 off the diagonal ("big"), the diagonal 256-blocks in
+// three 128 x 128 units; 2: 64 x 128 units off the diagonal of 128-blocks ("big": two per pair of blocks, 192 rows
+// staged instead of 256, for sizes where 128 x 128 units leave CUs idle), the diagonal blocks as gram_tile_diag units.
 struct DmaUnits {
     long long n_big, n_units;
-    __host__ __device__ DmaUnits(int T, int big_mode) {
+    __host__ __device__ DmaUnits(int T, int mode) {
         const long long nb256 = (T + 255) / 256, nb128 = (T + 127) / 128;
-        n_big = big_mode ? nb256 * (nb256 - 1) / 2 : 0;
-        n_units = big_mode ? n_big + 3 * nb256 : nb128 * (nb128 + 1) / 2;
+        n_big = mode == 1 ? nb256 * (nb256 - 1) / 2 : mode == 2 ? nb128 * (nb128 - 1) : 0;
+        n_units = mode == 1 ? n_big + 3 * nb256 : mode == 2 ? n_big + nb128 : nb128 * (nb128 + 1) / 2;
     }
 };
 
@@ -252,6 +392,47 @@ __device__ inline void full_selection_finish(UpdateParams u, float* gamma, int* 
                                              float* gamma_out) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int T = u.T;
+    constexpr int MG = 4;                                      // groups of four tokens per thread on the fast path
+    const bool vec = T % 4 == 0 && T <= nthr * 4 * MG && ((uintptr_t)gamma & 15) == 0 &&
+                     (!gamma_out || ((uintptr_t)gamma_out & 15) == 0) && (!u.mask || ((uintptr_t)u.mask & 3) == 0);
+    if (vec) {
+        // one trip to memory: a thread's (up to) sixteen consecutive maxima in four 16-byte reads, kept in registers
+        // across the scan; mask, maxima and the cleared accumulator leave in whole words
+        const int ng = T >> 2;
+        float4 v[MG];
+        int c_idx = 0;
+#pragma unroll
+        for (int j = 0; j < MG; ++j) {
+            const int g = tid * MG + j;
+            v[j] = g < ng ? reinterpret_cast<const float4*>(gamma)[g] : float4{INFINITY, INFINITY, INFINITY, INFINITY};
+            c_idx += (v[j].x < u.thr) + (v[j].y < u.thr) + (v[j].z < u.thr) + (v[j].w < u.thr);   // strict "<" of the Definition
+        }
+        int n_idx;
+        int o_idx = block_exclusive_scan(c_idx, &n_idx, sh);
+#pragma unroll
+        for (int j = 0; j < MG; ++j) {
+            const int g = tid * MG + j;
+            if (g >= ng) continue;
+            const float e[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+            uint32_t m4 = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool keep = e[k] < u.thr;
+                m4 |= (keep ? 1u : 0u) << (8 * k);
+                if (keep) { if (u.idx) u.idx[o_idx] = 4 * g + k; ++o_idx; }
+            }
+            if (u.mask) reinterpret_cast<uint32_t*>(u.mask)[g] = m4;
+            if (acc_reset) {
+                if (gamma_out) reinterpret_cast<float4*>(gamma_out)[g] = v[j];
+                reinterpret_cast<float4*>(gamma)[g] = float4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+        if (tid == 0) {
+            u.counts[0] = n_idx; u.counts[1] = n_idx; u.counts[2] = 0; u.counts[3] = ADA_OK;
+            if (u.gram_ops) *u.gram_ops = (unsigned long long)T * (unsigned long long)T;   // Table 6 / eq. (6)
+        }
+        return;
+    }
     const int chunk = (T + nthr - 1) / nthr;
     const int lo = min(T, tid * chunk), hi = min(T, lo + chunk);
     int c_idx = 0;
@@ -275,35 +456,50 @@ __device__ inline void full_selection_finish(UpdateParams u, float* gamma, int* 
 }
 
 template <bool NORMS>
-__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* queue, UpdateParams upd, float* gamma_out) {
+__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* meta, UpdateParams upd, float* gamma_out) {
     extern __shared__ __align__(16) char lds[];
     __shared__ long long s_next;
     __shared__ int s_last, s_scan[32];
     gram_group_offset(p);
-    if (p.ws_gs) queue = reinterpret_cast<int*>(reinterpret_cast<char*>(queue) + (long long)blockIdx.y * p.ws_gs);
+    if (p.ws_gs) meta = reinterpret_cast<int*>(reinterpret_cast<char*>(meta) + (long long)blockIdx.y * p.ws_gs);
+    int* queue = meta + META_QUEUE;                            // the workspace's unit counter and its sign-off tickets
+    int* ticket = meta + META_TICKET;
     const DmaUnits U(p.T, big_mode);
     const int G = gridDim.x;
+    DMA_CLK(5);
     long long u = (long long)(blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);     // first unit: contiguous range per XCD
     while (u < U.n_units) {
         long long nxt = 0;
-        if (threadIdx.x == 0) nxt = (long long)G + atomicAdd(queue, 1);           // next unit: the reply arrives behind the tile
-        if constexpr (NORMS) {                                 // (launched with 128-row units only: big_mode == 0)
-            const int tb = tri_row(u);                         // 128-blocks: 0 <= sb <= tb
-            const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
-            gram_tile_dma<64, true>(p, sb * 128, tb * 128, sb == tb, lds);
+        // next unit: the reply arrives behind the tile (no unit is left when each workgroup starts with one)
+        if (threadIdx.x == 0) nxt = U.n_units > G ? (long long)G + atomicAdd(queue, 1) : U.n_units;
+        if constexpr (NORMS) {                                 // (launched with mode 0 or 2)
+            if (big_mode == 2) {
+                if (u < U.n_big) {                             // tested 128-block tb >= 1 against the 64-blocks 0 .. 2 tb - 1
+                    const int tb = tri_row(u >> 1) + 1;
+                    const int sb = (int)(u - (long long)tb * (tb - 1));
+                    gram_tile_dma<32, 64, true>(p, sb * 64, tb * 128, false, lds);
+                } else {
+                    const int i = (int)(u - U.n_big);
+                    gram_tile_diag(p, i * 128, lds);
+                }
+            } else {
+                const int tb = tri_row(u);                     // 128-blocks: 0 <= sb <= tb
+                const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
+                gram_tile_dma<64, 64, true>(p, sb * 128, tb * 128, sb == tb, lds);
+            }
         } else if (u < U.n_big) {
             const int tb = tri_row(u) + 1;                     // off-diagonal 256-blocks: 0 <= sb < tb
             const int sb = (int)(u - (long long)tb * (tb - 1) / 2);
-            gram_tile_dma<128, false>(p, sb * 256, tb * 256, false, lds);
+            gram_tile_dma<128, 128, false>(p, sb * 256, tb * 256, false, lds);
         } else if (big_mode) {
             const long long v = u - U.n_big;                   // diagonal 256-block i in three 128 x 128 units
             const int i = (int)(v / 3), k = (int)(v % 3);
             const int t0 = (2 * i + (k >= 1)) * 128, s0 = (2 * i + (k == 2)) * 128;
-            if (t0 < p.T) gram_tile_dma<64, false>(p, s0, t0, k != 1, lds);
+            if (t0 < p.T) gram_tile_dma<64, 64, false>(p, s0, t0, k != 1, lds);
         } else {
             const int tb = tri_row(u);                         // 128-blocks: 0 <= sb <= tb
             const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
-            gram_tile_dma<64, false>(p, sb * 128, tb * 128, sb == tb, lds);
+            gram_tile_dma<64, 64, false>(p, sb * 128, tb * 128, sb == tb, lds);
         }
         if (threadIdx.x == 0) s_next = nxt;
         __syncthreads();
@@ -313,17 +509,22 @@ __global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, in
     // This workgroup's row maxima left the CU as device-scope atomics; once they are acknowledged (vmcnt(0)) and the
     // workgroup has met, it signs off.  Every workgroup's last fetch precedes its sign-off, so whoever signs off last
     // may clear both counters, and sees every row maximum after one invalidate.
+    DMA_CLK(6);
     drain_stores();
     __syncthreads();
+    DMA_CLK(7);
     if (threadIdx.x == 0) {
-        const bool last = atomicAdd(queue + 1, 1) == G - 1;
-        if (last) { atomicExch(queue, 0); atomicExch(queue + 1, 0); }
+        const bool last = take_ticket(ticket, G);              // (per XCD first: one counter would serve 256 in turn)
+        if (last) { atomicExch(queue, 0); reset_tickets(ticket); }
         s_last = last ? 1 : 0;
     }
     __syncthreads();
+    DMA_CLK(8);
     if (!upd.counts || !s_last) return;
+    DMA_CLK_ANY(9);
     if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     __syncthreads();
+    DMA_CLK_ANY(10);
     if (upd.go.ws) {                                         // several problems: blockIdx.y is the problem
         const long long g = blockIdx.y;
         if (upd.mask) upd.mask += g * (long long)upd.T;
@@ -333,4 +534,5 @@ __global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, in
     }
     if (NORMS && gamma_out && upd.go.ws) gamma_out = nullptr; // (several problems: no gamma output)
     full_selection_finish(upd, p.gamma, s_scan, NORMS, gamma_out);   // (p.gamma is this problem's: gram_group_offset)
+    DMA_CLK_ANY(11);
 }

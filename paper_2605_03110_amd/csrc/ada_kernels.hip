@@ -22,7 +22,9 @@
 #include <limits.h>
 #include <math.h>
 #include <stdlib.h>
+#include <functional>
 #include <mutex>
+#include <queue>
 #include <string>
 #include <type_traits>
 #include <vector>
@@ -948,10 +950,30 @@ inline double dma_makespan(int T, int big_mode, int G) {
     return m;
 }
 
-// mode: 0 = 128 x 128 units everywhere, 1 = 256 x 256 off the diagonal, -1 = whichever hands out better
+// Makespan, in staged rows, of the one-launch form's units (big first, then the shared-row diagonal blocks of 128
+// rows) handed to G workgroups: what a CU can pull out of the L2 bounds these sizes, so rows are the cost.
+inline long long dma_makespan_norms(int T, int mode, int G) {
+    const DmaUnits U(T, mode);
+    std::priority_queue<long long, std::vector<long long>, std::greater<long long>> fin;
+    for (int g = 0; g < G; ++g) fin.push(0);
+    long long m = 0;
+    for (long long u = 0; u < U.n_units; ++u) {
+        long long rows;
+        if (mode == 2) rows = u < U.n_big ? 192 : 128;
+        else rows = 256;
+        const long long f = fin.top() + rows + 64;            // (+ a unit's fixed part, in the same currency)
+        fin.pop();
+        fin.push(f);
+        m = f > m ? f : m;
+    }
+    return m;
+}
+
+// mode: 0 = 128 x 128 units everywhere, 1 = 256 x 256 off the diagonal, 2 = 64 x 128 off the diagonal (one-launch form
+// only), -1 = whichever hands out better
 // u.counts != NULL: the workgroup that leaves last also applies the threshold and compacts the set (no update launch)
 template <bool NORMS>
-hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStream_t st, int groups,
+hipError_t launch_gram_dma(const GramParams& p, int32_t* meta, int mode, hipStream_t st, int groups,
                            const UpdateParams& u, float* gamma_out = nullptr) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
@@ -965,8 +987,22 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
         G = G / groups / 8 * 8;                                // workgroups are handed out through its queue
         if (G < 8) G = 8;
     }
-    if (NORMS) mode = 0;                                       // the one-launch form runs on 128-row units
-    if (mode < 0) {
+    if (NORMS) {                                               // the one-launch form runs on 128-row units: whole or halved
+        if (mode == 1) mode = 0;                               // (256-row units are not built for this form)
+        if (mode < 0) {
+            static std::mutex mu;
+            static int last_T = 0, last_G = 0, last_mode = 0;
+            std::lock_guard<std::mutex> lock(mu);
+            if (last_T != p.T || last_G != G) {
+                last_mode = dma_makespan_norms(p.T, 2, G) < dma_makespan_norms(p.T, 0, G) ? 2 : 0;
+                last_T = p.T;
+                last_G = G;
+            }
+            mode = last_mode;
+        }
+    } else if (mode == 2) {
+        mode = 0;                                              // (64 x 128 units exist in the one-launch form only)
+    } else if (mode < 0) {
         static std::mutex mu;
         static int last_T = 0, last_G = 0, last_mode = 0;     // the choice depends on both the size and the workgroups
         std::lock_guard<std::mutex> lock(mu);
@@ -978,7 +1014,7 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* queue, int mode, hipStr
         mode = last_mode;
     }
     ProfScope ps(ADA_K_GRAM_FULL, st);
-    hipLaunchKernelGGL(k_gram_dma<NORMS>, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, queue, u,
+    hipLaunchKernelGGL(k_gram_dma<NORMS>, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, meta, u,
                        gamma_out);
     return hipGetLastError();
 }
@@ -1107,7 +1143,7 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
     const bool finish_in_kernel = !greedy && T <= 4096;
     const UpdateParams in_kernel = finish_in_kernel ? u : UpdateParams{};
     bool finished = false;
-    const char* path_env = dev_switch("ADA_GRAM");               // development switch: tile, dma0, dma1
+    const char* path_env = dev_switch("ADA_GRAM");               // development switch: tile, dma0, dma1, dma2
     const std::string path = path_env ? path_env : "";
     const long long ld_seen = (groups > 1 && go.x % 16 != 0) ? 1 : ld;   // every problem's rows must suit the loader
     hipError_t e = dispatch(dtype, X, ld_seen, d, [&](auto v) {
@@ -1116,8 +1152,8 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
         if constexpr (V::aligned && sizeof(In) == 2) {
             // whole 64-byte pieces of bf16 rows: the direct-to-LDS kernel
             const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
-            if (can && (path == "dma0" || path == "dma1" || (path.empty() && T >= 1536))) {
-                const int mode = path.empty() ? -1 : path == "dma1";
+            if (can && (path == "dma0" || path == "dma1" || path == "dma2" || (path.empty() && T >= 1536))) {
+                const int mode = path.empty() ? -1 : path == "dma1" ? 1 : path == "dma2" ? 2 : 0;
                 if (finish_in_kernel) {
                     // ONE launch: the norms come from the tiles' own fragments, and the row maxima are accumulated in a
                     // workspace array that is zero between calls (the workgroup that finishes hands them over and
@@ -1126,11 +1162,11 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
                     q.inv_norm = nullptr;
                     q.gamma = reinterpret_cast<float*>(w.first);
                     finished = true;
-                    return launch_gram_dma<true>(q, w.meta + META_QUEUE, mode, st, groups, in_kernel, gamma);
+                    return launch_gram_dma<true>(q, w.meta, mode, st, groups, in_kernel, gamma);
                 }
                 hipError_t e0 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st, go, groups);
                 if (e0 != hipSuccess) return e0;
-                return launch_gram_dma<false>(p, w.meta + META_QUEUE, mode, st, groups, in_kernel);
+                return launch_gram_dma<false>(p, w.meta, mode, st, groups, in_kernel);
             }
         }
         hipError_t e1 = launch_norm_prep<In, V::aligned>(X, ld, T, d, g, w, prep, st, go, groups);

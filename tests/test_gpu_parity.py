@@ -113,13 +113,14 @@ def test_small_shapes_one_launch_cascade_on_wide_tiles(T, d, K, dtype, tile, mon
     parity.check_assign(xs[0], full["idx"], res["assign"].cpu().numpy(), res["corr"].cpu().numpy(), "%s tiles assign" % tile)
 
 
-@pytest.mark.parametrize("path", ["dma0", "dma1"])
+@pytest.mark.parametrize("path", ["dma0", "dma1", "dma2"])
 @pytest.mark.parametrize("T,d,K", [(257, 128, 30), (700, 4096, 120), (1000, 64, 90), (1, 64, 1), (129, 32, 8),
                                    (1290, 96, 140), (512, 160, 60), (3000, 64, 300), (5500, 32, 400),
                                    (4096, 64, 350), (4097, 64, 350)])
 def test_direct_to_lds_full_selection(T, d, K, path, monkeypatch):
-    """The direct-to-LDS Gram kernel of the full selection, both ways of cutting the triangle into units, forced onto
-    small and ragged shapes (T off the 128 and 256 grids, one to three half chunks, a single token) and onto
+    """The direct-to-LDS Gram kernel of the full selection, every way of cutting the triangle into units (128 x 128
+    everywhere; 256 x 256 off the diagonal, which the one-launch form up to T = 4096 does not have; 64 x 128 off the
+    diagonal with the diagonal blocks' rows staged once, which only that form has), forced onto small and ragged shapes (T off the 128 and 256 grids, one to three half chunks, a single token) and onto
     shapes with more units than workgroups, where the rest is handed out through the counter in the workspace.
     Up to T = 4096 the kernel's last workgroup applies the threshold and compacts the set; beyond (4097, 5500) the
     update is a launch of its own."""
@@ -132,8 +133,9 @@ def test_direct_to_lds_full_selection(T, d, K, path, monkeypatch):
     # the counters in the workspace (behind three T-word arrays and one T-byte array, each padded to 256 bytes) must
     # be back at zero for the next launch
     up = lambda n: (n + 255) // 256 * 256
-    meta = ws[3 * up(4 * T) + up(T):][:32].view(torch.int32).cpu().tolist()
+    meta = ws[3 * up(4 * T) + up(T):][:2048].view(torch.int32).cpu().tolist()
     assert meta[4:7] == [0, 0, 0]
+    assert [meta[4 + 64 + 32 * x] for x in range(8)] == [0] * 8          # the sign-off counters of the eight XCDs
 
 
 @pytest.mark.parametrize("T,d,K,dtype", [(1600, 64, 200, "bf16"), (1600, 72, 200, "bf16"), (1600, 64, 200, "f32")])
@@ -665,7 +667,7 @@ def test_greedy_covering_selection(T, d, dtype):
     for name, x_cpu, tau in (("chains", x_chain, 0.05), ("chains", x_chain, 0.3), ("clusters", wl.layer_list(w)[0], w.tau)):
         # the register-staged tiles of both sizes, and the direct-to-LDS kernel with both ways of cutting the triangle
         # (where the shape allows it; otherwise these switches change nothing)
-        for var, tile in (("ADA_TILE", "64"), ("ADA_TILE", "128"), ("ADA_GRAM", "tile"), ("ADA_GRAM", "dma0"), ("ADA_GRAM", "dma1")):
+        for var, tile in (("ADA_TILE", "64"), ("ADA_TILE", "128"), ("ADA_GRAM", "tile"), ("ADA_GRAM", "dma0"), ("ADA_GRAM", "dma1"), ("ADA_GRAM", "dma2")):
             os.environ[var] = tile
             try:
                 got = pa.fetch(pa.ada_select_full(x_cpu.to(DEV), tau, ws=ws, flags=pa.FLAG_GREEDY_COVER))
