@@ -44,6 +44,10 @@ struct DmaGeom {
 // 32-row block is held by two waves, each wave sums the blocks at its even local positions, and the local order of a
 // wave's blocks is permuted (block a ^ parity) so that those positions cover every block and the K loop stays
 // straight-line code (a side with one block per wave is summed by both of its waves).
+// The NORMS tiles (few MFMAs per load) run with eight waves: a wave that issues a load waits for room in the memory
+// pipeline, and with one wave per SIMD those waits add to the MFMA time instead of hiding behind it.  Waves 4 .. 7 do
+// nothing but issue the loads (and count them in); waves 0 .. 3 multiply and never touch memory inside the K loop.
+// Both kinds meet at the same barriers: one when half chunk 0 has landed, one per step, one after the loop.
 template <int WA, int WB, bool NORMS>
 __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool need_order, char* lds) {
     using G = DmaGeom;
@@ -57,15 +61,18 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
     float* t_scale = s_scale + BS;
     char* ring = lds + G::META;
 
+    constexpr bool SPLIT = NORMS;                               // loader waves beside the multiplying ones
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = SPLIT && wave8 >= 4;
+    const int wave = wave8 & 3;                                // place among the waves of its kind
     const int l32 = lane & 31, half = lane >> 5;
     const int ws = wave >> 1, wt = wave & 1;
     DMA_CLK(4);
     const int T = p.T;
     const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
 
-    for (int i = tid; i < BS + BT; i += G::THREADS) {
+    for (int i = tid; i < BS + BT; i += (SPLIT ? 2 : 1) * G::THREADS) {
         const bool isS = i < BS;
         const int tok = isS ? s0 + i : t0 + (i - BS);
         const bool ok = tok < T;
@@ -175,46 +182,88 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         }
         if constexpr (NA * NB > LPT) __builtin_amdgcn_sched_group_barrier(0x008, NA * NB - LPT, 0);
     };
-    issue(0 * STAGE, 0);
-    issue(1 * STAGE, 1);
-    issue(2 * STAGE, 2);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));     // half chunk 0 has landed (this wave's part)
-    __builtin_amdgcn_s_barrier();
-    issue(3 * STAGE, 3);
-    read_frags(0, 0, 0);
-    DMA_CLK(0);
-    int h = 0;
-    for (; h + NS < nh; h += NS) {                             // every step here has a successor: no branches inside
+    if (loader) {
+        issue(0 * STAGE, 0);
+        issue(1 * STAGE, 1);
+        issue(2 * STAGE, 2);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT)); // half chunk 0 has landed (this wave's part)
+        __builtin_amdgcn_s_barrier();
+        issue(3 * STAGE, 3);
+        for (int h = 0; h + 1 < nh; ++h) {                     // the barrier of step h: h + 1 has landed, h is free
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));
+            __builtin_amdgcn_s_barrier();
+            issue((h % NS) * STAGE, h + NS);
+        }
+    } else if constexpr (SPLIT) {
+        auto mstep = [&](int cur_off, int nxt_off) {
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(1, cur_off, 1);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of this stage have returned
+            __builtin_amdgcn_s_barrier();
+            read_frags(0, nxt_off, 0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        __builtin_amdgcn_s_barrier();                          // half chunk 0 has landed
+        read_frags(0, 0, 0);
+        DMA_CLK(0);
+        int h = 0;
+        for (; h + NS < nh; h += NS) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, h + s);
+            for (int s = 0; s < NS; ++s) mstep(s * STAGE, ((s + 1) % NS) * STAGE);
+        }
+        for (; h + 1 < nh; ++h) mstep((h % NS) * STAGE, ((h + 1) % NS) * STAGE);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, (h % NS) * STAGE, 1);                    // last half chunk
+        mma(0);
+        mma(1);
+    } else {
+        issue(0 * STAGE, 0);
+        issue(1 * STAGE, 1);
+        issue(2 * STAGE, 2);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT)); // half chunk 0 has landed (this wave's part)
+        __builtin_amdgcn_s_barrier();
+        issue(3 * STAGE, 3);
+        read_frags(0, 0, 0);
+        DMA_CLK(0);
+        int h = 0;
+        for (; h + NS < nh; h += NS) {                         // every step here has a successor: no branches inside
+#pragma unroll
+            for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, h + s);
+        }
+        for (; h + 1 < nh; ++h) step((h % NS) * STAGE, ((h + 1) % NS) * STAGE, h);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, (h % NS) * STAGE, 1);                    // last half chunk
+        mma(0);
+        mma(1);
     }
-    for (; h + 1 < nh; ++h) step((h % NS) * STAGE, ((h + 1) % NS) * STAGE, h);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(1, (h % NS) * STAGE, 1);                        // last half chunk
-    mma(0);
-    mma(1);
     DMA_CLK(1);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
     __syncthreads();
     DMA_CLK(2);
     if constexpr (NORMS) {
         // the two lane halves hold different k pieces; rows that do not exist keep scale 0
+        if (!loader) {
 #pragma unroll
-        for (int i = 0; i < DA; ++i) {
-            const float va = ssa[i] + __shfl_xor(ssa[i], 32, 64);
-            const int ra = ws * WA + ((2 * i) ^ pa) * 32 + l32;
-            if (half == 0) s_scale[ra] = (s_tok[ra] != INT_MAX && va > 0.f) ? 1.0f / sqrtf(va) : 0.f;   // a zero row normalises to zero
-        }
+            for (int i = 0; i < DA; ++i) {
+                const float va = ssa[i] + __shfl_xor(ssa[i], 32, 64);
+                const int ra = ws * WA + ((2 * i) ^ pa) * 32 + l32;
+                if (half == 0) s_scale[ra] = (s_tok[ra] != INT_MAX && va > 0.f) ? 1.0f / sqrtf(va) : 0.f;   // a zero row normalises to zero
+            }
 #pragma unroll
-        for (int i = 0; i < DB; ++i) {
-            const float vb = ssb[i] + __shfl_xor(ssb[i], 32, 64);
-            const int rb = wt * WB + ((2 * i) ^ pb) * 32 + l32;
-            if (half == 0) t_scale[rb] = (t_tok[rb] >= 0 && vb > 0.f) ? 1.0f / sqrtf(vb) : 0.f;
+            for (int i = 0; i < DB; ++i) {
+                const float vb = ssb[i] + __shfl_xor(ssb[i], 32, 64);
+                const int rb = wt * WB + ((2 * i) ^ pb) * 32 + l32;
+                if (half == 0) t_scale[rb] = (t_tok[rb] >= 0 && vb > 0.f) ? 1.0f / sqrtf(vb) : 0.f;
+            }
         }
         __syncthreads();
     }
 
     uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
+    if (loader) return;                                        // (no barrier follows inside the tile)
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int nl = wt * WB + (b ^ pb) * 32 + l32;
@@ -238,7 +287,8 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
 // once, and of its sixteen 32 x 32 blocks only the ten with "against" block <= tested block are multiplied, three per
 // wave and k-step instead of four: wave 0 holds (0,0), (0,1), (1,1), wave 1 holds (2,2), (2,3), (3,3), wave 2 holds
 // (0,2), (0,3) and wave 3 holds (1,2), (1,3).  Written as one code path: four fragments P, Q, R, S per wave and the
-// products P x Q, P x R, S x R (the third is idle work in waves 2 and 3).  Same ring, waits and barrier as gram_tile_dma.
+// products P x Q, P x R, S x R (the third is idle work in waves 2 and 3).  Same ring, waits, barriers and split into
+// multiplying waves (0 .. 3) and loader waves (4 .. 7) as gram_tile_dma's.
 __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
     using G = DmaGeom;
     constexpr int ROWS = 128, LPT = ROWS / 64, NS = G::NS, HC = G::HC, STAGE = ROWS * 64;
@@ -248,14 +298,16 @@ __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
     char* ring = lds + G::META;
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave8 >= 4;
+    const int wave = wave8 & 3;
     const int l32 = lane & 31, half = lane >> 5;
     const bool tri = wave < 2;
     const int bP = tri ? 2 * wave : wave - 2, bQ = tri ? bP : 2, bR = tri ? bP + 1 : 3, bS = tri ? bP + 1 : bP;
     DMA_CLK(4);
     const int T = p.T;
     const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
-    for (int i = tid; i < ROWS; i += G::THREADS) {
+    for (int i = tid; i < ROWS; i += 2 * G::THREADS) {
         const bool ok = t0 + i < T;
         s_tok[i] = ok ? t0 + i : INT_MAX;
         t_tok[i] = ok ? t0 + i : -1;
@@ -301,42 +353,44 @@ __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
         ssP += piece_sumsq_fast<uint16_t>(fr[set][0]);
         ssR += piece_sumsq_fast<uint16_t>(fr[set][2]);
     };
-    auto step = [&](int cur_off, int nxt_off, int h) {
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, cur_off, 1);
-        mma(0);
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));   // h + 1 has landed; my reads of this stage have returned
+    if (loader) {
+        issue(0 * STAGE, 0);
+        issue(1 * STAGE, 1);
+        issue(2 * STAGE, 2);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT)); // half chunk 0 has landed (this wave's part)
         __builtin_amdgcn_s_barrier();
-        read_frags(0, nxt_off, 0);
-        issue(cur_off, h + NS);
-        mma(1);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);       // the LDS reads first
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // then one MFMA ...
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // ... per global load
+        issue(3 * STAGE, 3);
+        for (int h = 0; h + 1 < nh; ++h) {                     // the barrier of step h: h + 1 has landed, h is free
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));
+            __builtin_amdgcn_s_barrier();
+            issue((h % NS) * STAGE, h + NS);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 3 - LPT, 0);
-    };
-    issue(0 * STAGE, 0);
-    issue(1 * STAGE, 1);
-    issue(2 * STAGE, 2);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));     // half chunk 0 has landed (this wave's part)
-    __builtin_amdgcn_s_barrier();
-    issue(3 * STAGE, 3);
-    read_frags(0, 0, 0);
-    DMA_CLK(0);
-    int h = 0;
-    for (; h + NS < nh; h += NS) {
+    } else {
+        auto mstep = [&](int cur_off, int nxt_off) {
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(1, cur_off, 1);
+            mma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of this stage have returned
+            __builtin_amdgcn_s_barrier();
+            read_frags(0, nxt_off, 0);
+            mma(1);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        __builtin_amdgcn_s_barrier();                          // half chunk 0 has landed
+        read_frags(0, 0, 0);
+        DMA_CLK(0);
+        int h = 0;
+        for (; h + NS < nh; h += NS) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, h + s);
+            for (int s = 0; s < NS; ++s) mstep(s * STAGE, ((s + 1) % NS) * STAGE);
+        }
+        for (; h + 1 < nh; ++h) mstep((h % NS) * STAGE, ((h + 1) % NS) * STAGE);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1, (h % NS) * STAGE, 1);
+        mma(0);
+        mma(1);
     }
-    for (; h + 1 < nh; ++h) step((h % NS) * STAGE, ((h + 1) % NS) * STAGE, h);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(1, (h % NS) * STAGE, 1);
-    mma(0);
-    mma(1);
     DMA_CLK(1);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
     __syncthreads();
@@ -344,7 +398,7 @@ __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
     {
         const float vP = ssP + __shfl_xor(ssP, 32, 64), vR = ssR + __shfl_xor(ssR, 32, 64);
         // (waves that sum the same block write the same bits: same pieces, same order)
-        if (half == 0) {
+        if (half == 0 && !loader) {
             const int rP = bP * 32 + l32, rR = bR * 32 + l32;
             scale[rP] = (t_tok[rP] >= 0 && vP > 0.f) ? 1.0f / sqrtf(vP) : 0.f;    // a zero row normalises to zero
             scale[rR] = (t_tok[rR] >= 0 && vR > 0.f) ? 1.0f / sqrtf(vR) : 0.f;
@@ -353,6 +407,7 @@ __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
     }
     uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
     const int sblk[3] = {bP, bP, bS}, tblk[3] = {bQ, bR, bR};
+    if (loader) return;
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
         if (a == 2 && !tri) break;                             // (wave-uniform)
@@ -456,7 +511,7 @@ __device__ inline void full_selection_finish(UpdateParams u, float* gamma, int* 
 }
 
 template <bool NORMS>
-__global__ __launch_bounds__(256) void k_gram_dma(GramParams p, int big_mode, int* meta, UpdateParams upd, float* gamma_out) {
+__global__ __launch_bounds__(NORMS ? 2 * DmaGeom::THREADS : DmaGeom::THREADS) void k_gram_dma(GramParams p, int big_mode, int* meta, UpdateParams upd, float* gamma_out) {
     extern __shared__ __align__(16) char lds[];
     __shared__ long long s_next;
     __shared__ int s_last, s_scan[32];

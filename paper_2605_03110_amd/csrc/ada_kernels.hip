@@ -1014,7 +1014,7 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* meta, int mode, hipStre
         mode = last_mode;
     }
     ProfScope ps(ADA_K_GRAM_FULL, st);
-    hipLaunchKernelGGL(k_gram_dma<NORMS>, dim3(G, groups), dim3(DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, meta, u,
+    hipLaunchKernelGGL(k_gram_dma<NORMS>, dim3(G, groups), dim3((NORMS ? 2 : 1) * DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, meta, u,
                        gamma_out);
     return hipGetLastError();
 }
