@@ -38,48 +38,34 @@ struct DmaGeom {
 #define DMA_CLK_ANY(i) do { } while (0)
 #endif
 
-// One (2 WA) x (2 WB) tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side; the four waves
-// are a 2 x 2 grid of WA x WB blocks.
-// NORMS: the rows' sums of squares (Section 2.1) come from the fragments in hand instead of a pass of their own: a
-// 32-row block is held by two waves, each wave sums the blocks at its even local positions, and the local order of a
-// wave's blocks is permuted (block a ^ parity) so that those positions cover every block and the K loop stays
-// straight-line code (a side with one block per wave is summed by both of its waves).
-// The NORMS tiles (few MFMAs per load) run with eight waves: a wave that issues a load waits for room in the memory
-// pipeline, and with one wave per SIMD those waits add to the MFMA time instead of hiding behind it.  Waves 4 .. 7 do
-// nothing but issue the loads (and count them in); waves 0 .. 3 multiply and never touch memory inside the K loop.
-// Both kinds meet at the same barriers: one when half chunk 0 has landed, one per step, one after the loop.
-template <int WA, int WB, bool NORMS>
+// One WM*2 x WM*2 tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side; the rows' inverse norms
+// come from p.inv_norm.
+template <int WM>
 __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool need_order, char* lds) {
     using G = DmaGeom;
-    constexpr int BS = 2 * WA, BT = 2 * WB, ROWS = BS + BT;
-    constexpr int NA = WA / 32, NB = WB / 32, LPT = ROWS / 64, NS = G::NS, HC = G::HC;
+    constexpr int BT = 2 * WM, ROWS = 2 * BT, NB = WM / 32, LPT = ROWS / 64, NS = G::NS, HC = G::HC;
     constexpr int STAGE = ROWS * 64;
-    static_assert(ROWS % 64 == 0 && STAGE <= G::STAGE && 2 * (BS + BT) * 4 <= G::META, "ring and tables fit");
     int* s_tok = reinterpret_cast<int*>(lds);
-    int* t_tok = s_tok + BS;
+    int* t_tok = s_tok + BT;
     float* s_scale = reinterpret_cast<float*>(t_tok + BT);
-    float* t_scale = s_scale + BS;
+    float* t_scale = s_scale + BT;
     char* ring = lds + G::META;
 
-    constexpr bool SPLIT = NORMS;                               // loader waves beside the multiplying ones
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool loader = SPLIT && wave8 >= 4;
-    const int wave = wave8 & 3;                                // place among the waves of its kind
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int ws = wave >> 1, wt = wave & 1;
     DMA_CLK(4);
     const int T = p.T;
     const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
 
-    for (int i = tid; i < BS + BT; i += (SPLIT ? 2 : 1) * G::THREADS) {
-        const bool isS = i < BS;
-        const int tok = isS ? s0 + i : t0 + (i - BS);
+    for (int i = tid; i < ROWS; i += G::THREADS) {
+        const bool isS = i < BT;
+        const int tok = isS ? s0 + i : t0 + (i - BT);
         const bool ok = tok < T;
-        float sc = 0.f;
-        if constexpr (!NORMS) sc = ok ? p.inv_norm[ok ? tok : 0] : 0.f;
+        const float sc = ok ? p.inv_norm[ok ? tok : 0] : 0.f;
         if (isS) { s_tok[i] = ok ? tok : INT_MAX; s_scale[i] = sc; }
-        else { t_tok[i - BS] = ok ? tok : -1; t_scale[i - BS] = sc; }
+        else { t_tok[i - BT] = ok ? tok : -1; t_scale[i - BT] = sc; }
     }
 
     // Stage layout: rows of 64 bytes = 4 pieces; piece c of row r sits at slot c ^ ((r >> 2) & 3).  Sixteen lanes that
@@ -90,7 +76,7 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
         const int row = (j * 4 + wave) * 16 + (lane >> 2);
-        const int tok = min(row < BS ? s0 + row : t0 + (row - BS), T - 1);
+        const int tok = min(row < BT ? s0 + row : t0 + (row - BT), T - 1);
         rowp[j] = X + (size_t)tok * (size_t)p.ld + (((lane & 3) ^ ((lane >> 4) & 3)) << 3);
     }
     const int nh = p.d / HC;
@@ -104,9 +90,9 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         }
     };
 
-    f32x16 acc[NA][NB];
+    f32x16 acc[NB][NB];
 #pragma unroll
-    for (int a = 0; a < NA; ++a)
+    for (int a = 0; a < NB; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -115,49 +101,21 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
     // lane part of a fragment address for k-step ks of a half chunk: row l32 of a 32-row block, piece 2 ks + half
     const int lo0 = l32 * 64 + (((0 + half) ^ ((l32 >> 2) & 3)) << 4);
     const int lo1 = l32 * 64 + (((2 + half) ^ ((l32 >> 2) & 3)) << 4);
-    // local block a of this wave is block ablk(a) of its NB "against" blocks, likewise bblk for the tested blocks
-    // (identity without NORMS)
-    const int pa = (NORMS && NA > 1) ? wt : 0, pb = (NORMS && NB > 1) ? ws : 0;
-    const char* abase = ring + (ws * WA) * 64;
-    const char* bbase = ring + (BS + wt * WB) * 64;
-    const char* aptr[2][NA];
-    const char* bptr[2][NB];
-#pragma unroll
-    for (int a = 0; a < NA; ++a) { aptr[0][a] = abase + (a ^ pa) * 2048 + lo0; aptr[1][a] = abase + (a ^ pa) * 2048 + lo1; }
-#pragma unroll
-    for (int b = 0; b < NB; ++b) { bptr[0][b] = bbase + (b ^ pb) * 2048 + lo0; bptr[1][b] = bbase + (b ^ pb) * 2048 + lo1; }
-    u32x4 fa[2][NA], fb[2][NB];
+    const char* abase = ring + (ws * WM) * 64;
+    const char* bbase = ring + (BT + wt * WM) * 64;
+    u32x4 fa[2][NB], fb[2][NB];
     auto read_frags = [&](int set, int stage_off, int ks) {
-        if constexpr (NORMS) {
+        const int lo = ks ? lo1 : lo0;
 #pragma unroll
-            for (int a = 0; a < NA; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(aptr[ks][a] + stage_off);
+        for (int a = 0; a < NB; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(abase + stage_off + a * 2048 + lo);
 #pragma unroll
-            for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bptr[ks][b] + stage_off);
-        } else {
-            const int lo = ks ? lo1 : lo0;
-#pragma unroll
-            for (int a = 0; a < NA; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(abase + stage_off + a * 2048 + lo);
-#pragma unroll
-            for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bbase + stage_off + b * 2048 + lo);
-        }
+        for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bbase + stage_off + b * 2048 + lo);
     };
-    constexpr int DA = (NA + 1) / 2, DB = (NB + 1) / 2;       // blocks a wave sums on each side
-    float ssa[DA], ssb[DB];
-#pragma unroll
-    for (int i = 0; i < DA; ++i) ssa[i] = 0.f;
-#pragma unroll
-    for (int i = 0; i < DB; ++i) ssb[i] = 0.f;
     auto mma = [&](int set) {
 #pragma unroll
-        for (int a = 0; a < NA; ++a)
+        for (int a = 0; a < NB; ++a)
 #pragma unroll
             for (int b = 0; b < NB; ++b) Mfma<uint16_t>::run(acc[a][b], fa[set][a], fb[set][b]);
-        if constexpr (NORMS) {
-#pragma unroll
-            for (int i = 0; i < NA; i += 2) ssa[i >> 1] += piece_sumsq_fast<uint16_t>(fa[set][i]);
-#pragma unroll
-            for (int i = 0; i < NB; i += 2) ssb[i >> 1] += piece_sumsq_fast<uint16_t>(fb[set][i]);
-        }
     };
 
     // Half step h multiplies half chunk h (two k-steps of 16).  With one wave per SIMD nothing else hides latency, so
@@ -174,96 +132,247 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         read_frags(0, nxt_off, 0);
         issue(cur_off, h + 4);
         mma(1);
-        __builtin_amdgcn_sched_group_barrier(0x100, NA + NB, 0); // the LDS reads first
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * NB, 0);  // the LDS reads first
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
-            if (j < NA * NB) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // then one MFMA ...
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // then one MFMA ...
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // ... per global load
         }
-        if constexpr (NA * NB > LPT) __builtin_amdgcn_sched_group_barrier(0x008, NA * NB - LPT, 0);
+        if constexpr (NB * NB > LPT) __builtin_amdgcn_sched_group_barrier(0x008, NB * NB - LPT, 0);
     };
+    issue(0 * STAGE, 0);
+    issue(1 * STAGE, 1);
+    issue(2 * STAGE, 2);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));     // half chunk 0 has landed (this wave's part)
+    __builtin_amdgcn_s_barrier();
+    issue(3 * STAGE, 3);
+    read_frags(0, 0, 0);
+    DMA_CLK(0);
+    int h = 0;
+    for (; h + NS < nh; h += NS) {                             // every step here has a successor: no branches inside
+#pragma unroll
+        for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, h + s);
+    }
+    for (; h + 1 < nh; ++h) step((h % NS) * STAGE, ((h + 1) % NS) * STAGE, h);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(1, (h % NS) * STAGE, 1);                        // last half chunk
+    mma(0);
+    mma(1);
+    DMA_CLK(1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
+    __syncthreads();
+    DMA_CLK(2);
+
+    uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int nl = wt * WM + b * 32 + l32;
+        const int ttok = t_tok[nl];
+        float m = 0.f;
+#pragma unroll
+        for (int a = 0; a < NB; ++a)
+            m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WM + a * 32, half, need_order, ttok));
+        publish_max(m, t_scale[nl], ttok, half, gamma_bits);
+        if (p.hits) {                                              // greedy covering: one bit per pair s < t as well
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+                publish_hits(acc[a][b], s_scale, s_tok, ws * WM + a * 32, half, need_order, ttok, t_scale[nl], p.thr,
+                             p.hits, T, s0 + ws * WM + a * 32);
+        }
+    }
+    DMA_CLK(3);
+}
+
+// ---- the one-launch form (T <= 4096, d a multiple of 64): tiles with few MFMAs per load ----------------------------
+// Eight waves: a wave that issues a load waits for room in the memory pipeline, and with one wave per SIMD those waits
+// add to the MFMA time instead of hiding behind it.  So waves 4 .. 7 do nothing but issue the loads (and count them
+// in), and waves 0 .. 3, a 2 x 2 grid of WA x WB blocks, multiply and never touch memory inside the K loop.  Rows are
+// staged in whole 128-byte chunks (one cache line per row and stage; the swizzle of lds_off), four stages, ONE barrier
+// per chunk of four k-steps, which both kinds of wave meet: a loader when its part of the next chunk has landed, a
+// multiplier when its reads of the current one have returned.
+// The rows' sums of squares (Section 2.1) come from the fragments in hand instead of a pass of their own: a 32-row
+// block is held by two waves, each wave sums the blocks at its even local positions, and the local order of a wave's
+// blocks is permuted (block a ^ parity) so that those positions cover every block and the K loop stays straight-line
+// code (a side with one block per wave is summed by both of its waves, which write the same bits).
+struct SplitGeom {
+    static constexpr int THREADS = 512, NS = 4, EPC = 64;      // elements per chunk (128 bytes of bf16)
+};
+
+// the loader waves' K loop: LPT instructions of 1 KB (8 rows x 128 bytes) per wave and chunk; row(j) = (4 j + wave) 8 + lane / 8
+template <int LPT, int STAGE, typename TokOf>
+__device__ inline void split_loader(const GramParams& p, char* ring, int wave, int lane, TokOf tok_of) {
+    constexpr int NS = SplitGeom::NS, EPC = SplitGeom::EPC;
+    static_assert((NS - 1) * LPT < 64, "the loads in flight can be counted");
+    const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
+    const int r8 = lane >> 3;
+    const int pcd = (lane & 7) ^ lds_swz(wave * 8 + r8);       // (32 j leaves bits 0..3 of the row alone)
+    const uint16_t* rowp[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) rowp[j] = X + (size_t)tok_of((j * 4 + wave) * 8 + r8) * (size_t)p.ld + pcd * 8;
+    const int nk = p.d / EPC;
+    auto issue = [&](int stage_off, int k) {
+        const int chunk = min(k, nk - 1);                      // surplus issues repeat the last chunk into a dead stage
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            char* dst = ring + stage_off + (j * 4 + wave) * 1024;               // wave-uniform
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + chunk * EPC),
+                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+        }
+    };
+    issue(0 * STAGE, 0);
+    issue(1 * STAGE, 1);
+    issue(2 * STAGE, 2);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));     // chunk 0 has landed (this wave's part)
+    __builtin_amdgcn_s_barrier();
+    issue(3 * STAGE, 3);
+    for (int k = 0; k + 1 < nk; ++k) {                         // the barrier of step k: k + 1 has landed, k is free
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));
+        __builtin_amdgcn_s_barrier();
+        issue((k % NS) * STAGE, k + NS);
+    }
+}
+
+// the multiplying waves' K loop around read(set, stage_off, ks) and mma(set): fragments of k-step ks + 1 are read
+// while k-step ks multiplies; the barrier sits before the last k-step of a chunk
+template <int STAGE, typename Read, typename Mma>
+__device__ inline void split_multiplier(int nk, Read read, Mma mma) {
+    constexpr int NS = SplitGeom::NS;
+    auto cstep = [&](int cur_off, int nxt_off) {
+        __builtin_amdgcn_sched_barrier(0);
+        read(1, cur_off, 1);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read(0, cur_off, 2);
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read(1, cur_off, 3);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));     // my reads of this stage have returned
+        __builtin_amdgcn_s_barrier();
+        read(0, nxt_off, 0);
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    __builtin_amdgcn_s_barrier();                              // chunk 0 has landed
+    read(0, 0, 0);
+    int k = 0;
+    for (; k + NS < nk; k += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) cstep(s * STAGE, ((s + 1) % NS) * STAGE);
+    }
+    for (; k + 1 < nk; ++k) cstep((k % NS) * STAGE, ((k + 1) % NS) * STAGE);
+    const int last_off = (k % NS) * STAGE;                     // last chunk
+    __builtin_amdgcn_sched_barrier(0);
+    read(1, last_off, 1);
+    mma(0);
+    read(0, last_off, 2);
+    mma(1);
+    read(1, last_off, 3);
+    mma(0);
+    mma(1);
+}
+
+// One (2 WA) x (2 WB) tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side.
+template <int WA, int WB>
+__device__ inline void gram_tile_split(const GramParams& p, int s0, int t0, bool need_order, char* lds) {
+    using G = DmaGeom;
+    constexpr int BS = 2 * WA, BT = 2 * WB, ROWS = BS + BT, NA = WA / 32, NB = WB / 32;
+    constexpr int LPT = ROWS / 32, STAGE = ROWS * 128;
+    static_assert(ROWS % 32 == 0 && SplitGeom::NS * STAGE <= G::NS * G::STAGE && 2 * (BS + BT) * 4 <= G::META,
+                  "ring and tables fit");
+    int* s_tok = reinterpret_cast<int*>(lds);
+    int* t_tok = s_tok + BS;
+    float* s_scale = reinterpret_cast<float*>(t_tok + BT);
+    float* t_scale = s_scale + BS;
+    char* ring = lds + G::META;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave8 >= 4;
+    const int wave = wave8 & 3;                                // place among the waves of its kind
+    const int l32 = lane & 31, half = lane >> 5;
+    const int ws = wave >> 1, wt = wave & 1;
+    DMA_CLK(4);
+    const int T = p.T;
+    for (int i = tid; i < BS + BT; i += SplitGeom::THREADS) {
+        const bool isS = i < BS;
+        const int tok = isS ? s0 + i : t0 + (i - BS);
+        const bool ok = tok < T;
+        if (isS) { s_tok[i] = ok ? tok : INT_MAX; s_scale[i] = 0.f; }
+        else { t_tok[i - BS] = ok ? tok : -1; t_scale[i - BS] = 0.f; }
+    }
+    f32x16 acc[NA][NB];
+    // local block a of this wave is block a ^ pa of its NA "against" blocks, likewise b ^ pb for the tested blocks
+    const int pa = NA > 1 ? wt : 0, pb = NB > 1 ? ws : 0;
+    constexpr int DA = (NA + 1) / 2, DB = (NB + 1) / 2;       // blocks a wave sums on each side
+    float ssa[DA], ssb[DB];
     if (loader) {
-        issue(0 * STAGE, 0);
-        issue(1 * STAGE, 1);
-        issue(2 * STAGE, 2);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT)); // half chunk 0 has landed (this wave's part)
-        __builtin_amdgcn_s_barrier();
-        issue(3 * STAGE, 3);
-        for (int h = 0; h + 1 < nh; ++h) {                     // the barrier of step h: h + 1 has landed, h is free
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));
-            __builtin_amdgcn_s_barrier();
-            issue((h % NS) * STAGE, h + NS);
-        }
-    } else if constexpr (SPLIT) {
-        auto mstep = [&](int cur_off, int nxt_off) {
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(1, cur_off, 1);
-            mma(0);
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of this stage have returned
-            __builtin_amdgcn_s_barrier();
-            read_frags(0, nxt_off, 0);
-            mma(1);
-            __builtin_amdgcn_sched_barrier(0);
-        };
-        __builtin_amdgcn_s_barrier();                          // half chunk 0 has landed
-        read_frags(0, 0, 0);
-        DMA_CLK(0);
-        int h = 0;
-        for (; h + NS < nh; h += NS) {
-#pragma unroll
-            for (int s = 0; s < NS; ++s) mstep(s * STAGE, ((s + 1) % NS) * STAGE);
-        }
-        for (; h + 1 < nh; ++h) mstep((h % NS) * STAGE, ((h + 1) % NS) * STAGE);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, (h % NS) * STAGE, 1);                    // last half chunk
-        mma(0);
-        mma(1);
+        // rows past the end re-read row T - 1 (and are never published)
+        split_loader<LPT, STAGE>(p, ring, wave, lane, [&](int row) { return min(row < BS ? s0 + row : t0 + (row - BS), T - 1); });
     } else {
-        issue(0 * STAGE, 0);
-        issue(1 * STAGE, 1);
-        issue(2 * STAGE, 2);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT)); // half chunk 0 has landed (this wave's part)
-        __builtin_amdgcn_s_barrier();
-        issue(3 * STAGE, 3);
-        read_frags(0, 0, 0);
-        DMA_CLK(0);
-        int h = 0;
-        for (; h + NS < nh; h += NS) {                         // every step here has a successor: no branches inside
 #pragma unroll
-            for (int s = 0; s < NS; ++s) step(s * STAGE, ((s + 1) % NS) * STAGE, h + s);
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DA; ++i) ssa[i] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DB; ++i) ssb[i] = 0.f;
+        // fragment addresses: row l32 of a 32-row block, piece 2 ks + half of the chunk (k-step ks of four)
+        const char* aptr[4][NA];
+        const char* bptr[4][NB];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+            for (int a = 0; a < NA; ++a) aptr[ks][a] = ring + lds_off(ws * WA + (a ^ pa) * 32 + l32, 2 * ks + half);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) bptr[ks][b] = ring + lds_off(BS + wt * WB + (b ^ pb) * 32 + l32, 2 * ks + half);
         }
-        for (; h + 1 < nh; ++h) step((h % NS) * STAGE, ((h + 1) % NS) * STAGE, h);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, (h % NS) * STAGE, 1);                    // last half chunk
-        mma(0);
-        mma(1);
+        u32x4 fa[2][NA], fb[2][NB];
+        DMA_CLK(0);
+        split_multiplier<STAGE>(p.d / SplitGeom::EPC,
+            [&](int set, int stage_off, int ks) {
+#pragma unroll
+                for (int a = 0; a < NA; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(aptr[ks][a] + stage_off);
+#pragma unroll
+                for (int b = 0; b < NB; ++b) fb[set][b] = *reinterpret_cast<const u32x4*>(bptr[ks][b] + stage_off);
+            },
+            [&](int set) {
+#pragma unroll
+                for (int a = 0; a < NA; ++a)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) Mfma<uint16_t>::run(acc[a][b], fa[set][a], fb[set][b]);
+#pragma unroll
+                for (int i = 0; i < NA; i += 2) ssa[i >> 1] += piece_sumsq_fast<uint16_t>(fa[set][i]);
+#pragma unroll
+                for (int i = 0; i < NB; i += 2) ssb[i >> 1] += piece_sumsq_fast<uint16_t>(fb[set][i]);
+            });
     }
     DMA_CLK(1);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
     __syncthreads();
     DMA_CLK(2);
-    if constexpr (NORMS) {
+    if (!loader) {
         // the two lane halves hold different k pieces; rows that do not exist keep scale 0
-        if (!loader) {
 #pragma unroll
-            for (int i = 0; i < DA; ++i) {
-                const float va = ssa[i] + __shfl_xor(ssa[i], 32, 64);
-                const int ra = ws * WA + ((2 * i) ^ pa) * 32 + l32;
-                if (half == 0) s_scale[ra] = (s_tok[ra] != INT_MAX && va > 0.f) ? 1.0f / sqrtf(va) : 0.f;   // a zero row normalises to zero
-            }
-#pragma unroll
-            for (int i = 0; i < DB; ++i) {
-                const float vb = ssb[i] + __shfl_xor(ssb[i], 32, 64);
-                const int rb = wt * WB + ((2 * i) ^ pb) * 32 + l32;
-                if (half == 0) t_scale[rb] = (t_tok[rb] >= 0 && vb > 0.f) ? 1.0f / sqrtf(vb) : 0.f;
-            }
+        for (int i = 0; i < DA; ++i) {
+            const float va = ssa[i] + __shfl_xor(ssa[i], 32, 64);
+            const int ra = ws * WA + ((2 * i) ^ pa) * 32 + l32;
+            if (half == 0) s_scale[ra] = (s_tok[ra] != INT_MAX && va > 0.f) ? 1.0f / sqrtf(va) : 0.f;   // a zero row normalises to zero
         }
-        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+            const float vb = ssb[i] + __shfl_xor(ssb[i], 32, 64);
+            const int rb = wt * WB + ((2 * i) ^ pb) * 32 + l32;
+            if (half == 0) t_scale[rb] = (t_tok[rb] >= 0 && vb > 0.f) ? 1.0f / sqrtf(vb) : 0.f;
+        }
     }
-
-    uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
+    __syncthreads();
     if (loader) return;                                        // (no barrier follows inside the tile)
+    uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int nl = wt * WB + (b ^ pb) * 32 + l32;
@@ -273,25 +382,18 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
         for (int a = 0; a < NA; ++a)
             m = fmaxf(m, block_max(acc[a][b], s_scale, s_tok, ws * WA + (a ^ pa) * 32, half, need_order, ttok));
         publish_max(m, t_scale[nl], ttok, half, gamma_bits);
-        if (p.hits) {                                              // greedy covering: one bit per pair s < t as well
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-                publish_hits(acc[a][b], s_scale, s_tok, ws * WA + (a ^ pa) * 32, half, need_order, ttok, t_scale[nl], p.thr,
-                             p.hits, T, s0 + ws * WA + (a ^ pa) * 32);
-        }
     }
     DMA_CLK(3);
 }
 
-// A 128-token block ON the diagonal, for the one-launch form (sums of squares from the fragments): its rows are staged
-// once, and of its sixteen 32 x 32 blocks only the ten with "against" block <= tested block are multiplied, three per
-// wave and k-step instead of four: wave 0 holds (0,0), (0,1), (1,1), wave 1 holds (2,2), (2,3), (3,3), wave 2 holds
-// (0,2), (0,3) and wave 3 holds (1,2), (1,3).  Written as one code path: four fragments P, Q, R, S per wave and the
-// products P x Q, P x R, S x R (the third is idle work in waves 2 and 3).  Same ring, waits, barriers and split into
-// multiplying waves (0 .. 3) and loader waves (4 .. 7) as gram_tile_dma's.
+// A 128-token block ON the diagonal: its rows are staged once, and of its sixteen 32 x 32 blocks only the ten with
+// "against" block <= tested block are multiplied, three per wave and k-step instead of four: wave 0 holds (0,0), (0,1),
+// (1,1), wave 1 holds (2,2), (2,3), (3,3), wave 2 holds (0,2), (0,3) and wave 3 holds (1,2), (1,3).  Written as one code
+// path: four fragments P, Q, R, S per wave and the products P x Q, P x R, S x R (the third is idle work in waves 2
+// and 3).
 __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
     using G = DmaGeom;
-    constexpr int ROWS = 128, LPT = ROWS / 64, NS = G::NS, HC = G::HC, STAGE = ROWS * 64;
+    constexpr int ROWS = 128, LPT = ROWS / 32, STAGE = ROWS * 128;
     int* s_tok = reinterpret_cast<int*>(lds);                  // INT_MAX past the end (never "earlier")
     int* t_tok = s_tok + ROWS;                                 // -1 past the end (never published)
     float* scale = reinterpret_cast<float*>(t_tok + ROWS);
@@ -306,108 +408,59 @@ __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
     const int bP = tri ? 2 * wave : wave - 2, bQ = tri ? bP : 2, bR = tri ? bP + 1 : 3, bS = tri ? bP + 1 : bP;
     DMA_CLK(4);
     const int T = p.T;
-    const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
-    for (int i = tid; i < ROWS; i += 2 * G::THREADS) {
+    for (int i = tid; i < ROWS; i += SplitGeom::THREADS) {
         const bool ok = t0 + i < T;
         s_tok[i] = ok ? t0 + i : INT_MAX;
         t_tok[i] = ok ? t0 + i : -1;
         scale[i] = 0.f;
     }
-    const uint16_t* rowp[LPT];                                 // (stage layout and lane roles: see gram_tile_dma)
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) {
-        const int tok = min(t0 + (j * 4 + wave) * 16 + (lane >> 2), T - 1);
-        rowp[j] = X + (size_t)tok * (size_t)p.ld + (((lane & 3) ^ ((lane >> 4) & 3)) << 3);
-    }
-    const int nh = p.d / HC;
-    auto issue = [&](int stage_off, int h) {
-        const int hc = min(h, nh - 1);
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            char* dst = ring + stage_off + (j * 4 + wave) * 1024;
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + hc * HC),
-                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
-        }
-    };
     f32x16 acc[3];
-#pragma unroll
-    for (int a = 0; a < 3; ++a)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
-    const int lo0 = l32 * 64 + (((0 + half) ^ ((l32 >> 2) & 3)) << 4);
-    const int lo1 = l32 * 64 + (((2 + half) ^ ((l32 >> 2) & 3)) << 4);
-    const int blk[4] = {bP, bQ, bR, bS};
-    const char* fptr[2][4];
-#pragma unroll
-    for (int f = 0; f < 4; ++f) { fptr[0][f] = ring + blk[f] * 2048 + lo0; fptr[1][f] = ring + blk[f] * 2048 + lo1; }
-    u32x4 fr[2][4];
-    auto read_frags = [&](int set, int stage_off, int ks) {
-#pragma unroll
-        for (int f = 0; f < 4; ++f) fr[set][f] = *reinterpret_cast<const u32x4*>(fptr[ks][f] + stage_off);
-    };
     float ssP = 0.f, ssR = 0.f;                                // waves 0 and 1 cover the four blocks; 2 and 3 repeat two
-    auto mma = [&](int set) {
-        Mfma<uint16_t>::run(acc[0], fr[set][0], fr[set][1]);
-        Mfma<uint16_t>::run(acc[1], fr[set][0], fr[set][2]);
-        Mfma<uint16_t>::run(acc[2], fr[set][3], fr[set][2]);
-        ssP += piece_sumsq_fast<uint16_t>(fr[set][0]);
-        ssR += piece_sumsq_fast<uint16_t>(fr[set][2]);
-    };
     if (loader) {
-        issue(0 * STAGE, 0);
-        issue(1 * STAGE, 1);
-        issue(2 * STAGE, 2);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT)); // half chunk 0 has landed (this wave's part)
-        __builtin_amdgcn_s_barrier();
-        issue(3 * STAGE, 3);
-        for (int h = 0; h + 1 < nh; ++h) {                     // the barrier of step h: h + 1 has landed, h is free
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));
-            __builtin_amdgcn_s_barrier();
-            issue((h % NS) * STAGE, h + NS);
-        }
+        split_loader<LPT, STAGE>(p, ring, wave, lane, [&](int row) { return min(t0 + row, T - 1); });
     } else {
-        auto mstep = [&](int cur_off, int nxt_off) {
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(1, cur_off, 1);
-            mma(0);
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of this stage have returned
-            __builtin_amdgcn_s_barrier();
-            read_frags(0, nxt_off, 0);
-            mma(1);
-            __builtin_amdgcn_sched_barrier(0);
-        };
-        __builtin_amdgcn_s_barrier();                          // half chunk 0 has landed
-        read_frags(0, 0, 0);
-        DMA_CLK(0);
-        int h = 0;
-        for (; h + NS < nh; h += NS) {
 #pragma unroll
-            for (int s = 0; s < NS; ++s) mstep(s * STAGE, ((s + 1) % NS) * STAGE);
-        }
-        for (; h + 1 < nh; ++h) mstep((h % NS) * STAGE, ((h + 1) % NS) * STAGE);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, (h % NS) * STAGE, 1);
-        mma(0);
-        mma(1);
+        for (int a = 0; a < 3; ++a)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+        const int blk[4] = {bP, bQ, bR, bS};
+        const char* fptr[4][4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int f = 0; f < 4; ++f) fptr[ks][f] = ring + lds_off(blk[f] * 32 + l32, 2 * ks + half);
+        u32x4 fr[2][4];
+        DMA_CLK(0);
+        split_multiplier<STAGE>(p.d / SplitGeom::EPC,
+            [&](int set, int stage_off, int ks) {
+#pragma unroll
+                for (int f = 0; f < 4; ++f) fr[set][f] = *reinterpret_cast<const u32x4*>(fptr[ks][f] + stage_off);
+            },
+            [&](int set) {
+                Mfma<uint16_t>::run(acc[0], fr[set][0], fr[set][1]);
+                Mfma<uint16_t>::run(acc[1], fr[set][0], fr[set][2]);
+                Mfma<uint16_t>::run(acc[2], fr[set][3], fr[set][2]);
+                ssP += piece_sumsq_fast<uint16_t>(fr[set][0]);
+                ssR += piece_sumsq_fast<uint16_t>(fr[set][2]);
+            });
     }
     DMA_CLK(1);
     __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));           // surplus loads land before the ring is reused
     __syncthreads();
     DMA_CLK(2);
-    {
+    if (!loader) {
         const float vP = ssP + __shfl_xor(ssP, 32, 64), vR = ssR + __shfl_xor(ssR, 32, 64);
         // (waves that sum the same block write the same bits: same pieces, same order)
-        if (half == 0 && !loader) {
+        if (half == 0) {
             const int rP = bP * 32 + l32, rR = bR * 32 + l32;
             scale[rP] = (t_tok[rP] >= 0 && vP > 0.f) ? 1.0f / sqrtf(vP) : 0.f;    // a zero row normalises to zero
             scale[rR] = (t_tok[rR] >= 0 && vR > 0.f) ? 1.0f / sqrtf(vR) : 0.f;
         }
-        __syncthreads();
     }
+    __syncthreads();
+    if (loader) return;
     uint32_t* gamma_bits = reinterpret_cast<uint32_t*>(p.gamma);
     const int sblk[3] = {bP, bP, bS}, tblk[3] = {bQ, bR, bR};
-    if (loader) return;
 #pragma unroll
     for (int a = 0; a < 3; ++a) {
         if (a == 2 && !tri) break;                             // (wave-uniform)
@@ -511,7 +564,7 @@ __device__ inline void full_selection_finish(UpdateParams u, float* gamma, int* 
 }
 
 template <bool NORMS>
-__global__ __launch_bounds__(NORMS ? 2 * DmaGeom::THREADS : DmaGeom::THREADS) void k_gram_dma(GramParams p, int big_mode, int* meta, UpdateParams upd, float* gamma_out) {
+__global__ __launch_bounds__(NORMS ? SplitGeom::THREADS : DmaGeom::THREADS) void k_gram_dma(GramParams p, int big_mode, int* meta, UpdateParams upd, float* gamma_out) {
     extern __shared__ __align__(16) char lds[];
     __shared__ long long s_next;
     __shared__ int s_last, s_scan[32];
@@ -532,7 +585,7 @@ __global__ __launch_bounds__(NORMS ? 2 * DmaGeom::THREADS : DmaGeom::THREADS) vo
                 if (u < U.n_big) {                             // tested 128-block tb >= 1 against the 64-blocks 0 .. 2 tb - 1
                     const int tb = tri_row(u >> 1) + 1;
                     const int sb = (int)(u - (long long)tb * (tb - 1));
-                    gram_tile_dma<32, 64, true>(p, sb * 64, tb * 128, false, lds);
+                    gram_tile_split<32, 64>(p, sb * 64, tb * 128, false, lds);
                 } else {
                     const int i = (int)(u - U.n_big);
                     gram_tile_diag(p, i * 128, lds);
@@ -540,21 +593,21 @@ __global__ __launch_bounds__(NORMS ? 2 * DmaGeom::THREADS : DmaGeom::THREADS) vo
             } else {
                 const int tb = tri_row(u);                     // 128-blocks: 0 <= sb <= tb
                 const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
-                gram_tile_dma<64, 64, true>(p, sb * 128, tb * 128, sb == tb, lds);
+                gram_tile_split<64, 64>(p, sb * 128, tb * 128, sb == tb, lds);
             }
         } else if (u < U.n_big) {
             const int tb = tri_row(u) + 1;                     // off-diagonal 256-blocks: 0 <= sb < tb
             const int sb = (int)(u - (long long)tb * (tb - 1) / 2);
-            gram_tile_dma<128, 128, false>(p, sb * 256, tb * 256, false, lds);
+            gram_tile_dma<128>(p, sb * 256, tb * 256, false, lds);
         } else if (big_mode) {
             const long long v = u - U.n_big;                   // diagonal 256-block i in three 128 x 128 units
             const int i = (int)(v / 3), k = (int)(v % 3);
             const int t0 = (2 * i + (k >= 1)) * 128, s0 = (2 * i + (k == 2)) * 128;
-            if (t0 < p.T) gram_tile_dma<64, 64, false>(p, s0, t0, k != 1, lds);
+            if (t0 < p.T) gram_tile_dma<64>(p, s0, t0, k != 1, lds);
         } else {
             const int tb = tri_row(u);                         // 128-blocks: 0 <= sb <= tb
             const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
-            gram_tile_dma<64, 64, false>(p, sb * 128, tb * 128, sb == tb, lds);
+            gram_tile_dma<64>(p, sb * 128, tb * 128, sb == tb, lds);
         }
         if (threadIdx.x == 0) s_next = nxt;
         __syncthreads();

@@ -1014,7 +1014,7 @@ hipError_t launch_gram_dma(const GramParams& p, int32_t* meta, int mode, hipStre
         mode = last_mode;
     }
     ProfScope ps(ADA_K_GRAM_FULL, st);
-    hipLaunchKernelGGL(k_gram_dma<NORMS>, dim3(G, groups), dim3((NORMS ? 2 : 1) * DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, meta, u,
+    hipLaunchKernelGGL(k_gram_dma<NORMS>, dim3(G, groups), dim3(NORMS ? SplitGeom::THREADS : DmaGeom::THREADS), DmaGeom::LDS, st, p, mode, meta, u,
                        gamma_out);
     return hipGetLastError();
 }
@@ -1154,7 +1154,7 @@ int run_full(const void* X, int T, int d, long long ld, int dtype, float tau, ui
             const bool can = d % DmaGeom::HC == 0 && go.x % 64 == 0;
             if (can && (path == "dma0" || path == "dma1" || path == "dma2" || (path.empty() && T >= 1536))) {
                 const int mode = path.empty() ? -1 : path == "dma1" ? 1 : path == "dma2" ? 2 : 0;
-                if (finish_in_kernel) {
+                if (finish_in_kernel && d % SplitGeom::EPC == 0) {
                     // ONE launch: the norms come from the tiles' own fragments, and the row maxima are accumulated in a
                     // workspace array that is zero between calls (the workgroup that finishes hands them over and
                     // clears it again), so nothing has to be computed or cleared ahead of the tiles.
