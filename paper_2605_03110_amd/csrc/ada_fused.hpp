@@ -955,6 +955,223 @@ __device__ inline void fused_tile_ring(const FusedParams& p, int r, int s0, int 
     }
 }
 
+// ---- loader waves and multiplying waves (bf16 rows in whole aligned 128-byte chunks) -----------------------------
+// A wave that issues a load waits for room in the memory pipeline; where few MFMAs stand against each load, those
+// waits add to the MFMA time instead of hiding behind it.  The tiles below therefore run with eight waves: waves
+// 4 .. 7 do nothing but issue the loads of the coming chunks (and count them in), waves 0 .. 3 multiply and never
+// touch memory inside the K loop.  A ring of NS stages of whole 128-byte chunks (one cache line per row and stage, the
+// swizzle of lds_off), ONE barrier per chunk of four k-steps, which both kinds of wave meet: a loader when its part of
+// the next chunk has landed, a multiplier when its reads of the current one have returned.
+constexpr int SPLIT_EPC = 64;                                 // elements per chunk
+
+// The loader waves' K loop: LPT instructions of 1 KB (8 rows x 128 bytes) per wave and chunk; instruction j of loader
+// wave w fills rows 8 (4 j + w) .. + 7 of the stage, lane l row l / 8 of them; tok_of(j, row): the row of X to fetch.
+template <int NS, int LPT, int STAGE, typename TokOf>
+__device__ inline void split_loader(const uint16_t* X, long long ld, int d, char* ring, int wave, int lane, TokOf tok_of) {
+    static_assert(NS >= 3 && (NS - 1) * LPT < 64, "the loads in flight can be counted");
+    const int r8 = lane >> 3;
+    const int pcd = (lane & 7) ^ lds_swz(wave * 8 + r8);       // (32 j leaves bits 0..3 of the row alone)
+    const uint16_t* rowp[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) rowp[j] = X + (size_t)tok_of(j, (j * 4 + wave) * 8 + r8) * (size_t)ld + pcd * 8;
+    const int nk = d / SPLIT_EPC;
+    auto issue = [&](int stage_off, int k) {
+        const int chunk = min(k, nk - 1);                      // surplus issues repeat the last chunk into a dead stage
+#pragma unroll
+        for (int j = 0; j < LPT; ++j) {
+            char* dst = ring + stage_off + (j * 4 + wave) * 1024;               // wave-uniform
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + chunk * SPLIT_EPC),
+                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(s * STAGE, s);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * LPT));   // chunk 0 has landed (this wave's part)
+    __builtin_amdgcn_s_barrier();
+    issue((NS - 1) * STAGE, NS - 1);
+    for (int k = 0; k + 1 < nk; ++k) {                         // the barrier of step k: k + 1 has landed, k is free
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * LPT));
+        __builtin_amdgcn_s_barrier();
+        issue((k % NS) * STAGE, k + NS);
+    }
+}
+
+// The multiplying waves' K loop around read(set, stage_off, ks) and mma(set): the fragments of k-step ks + 1 are read
+// while k-step ks multiplies; the barrier sits before the last k-step of a chunk.
+template <int NS, int STAGE, typename Read, typename Mma>
+__device__ inline void split_multiplier(int nk, Read read, Mma mma) {
+    auto cstep = [&](int cur_off, int nxt_off) {
+        __builtin_amdgcn_sched_barrier(0);
+        read(1, cur_off, 1);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        read(0, cur_off, 2);
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read(1, cur_off, 3);
+        mma(0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));     // my reads of this stage have returned
+        __builtin_amdgcn_s_barrier();
+        read(0, nxt_off, 0);
+        mma(1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    __builtin_amdgcn_s_barrier();                              // chunk 0 has landed
+    read(0, 0, 0);
+    int k = 0;
+    for (; k + NS < nk; k += NS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) cstep(s * STAGE, ((s + 1) % NS) * STAGE);
+    }
+    for (; k + 1 < nk; ++k) cstep((k % NS) * STAGE, ((k + 1) % NS) * STAGE);
+    const int last_off = (k % NS) * STAGE;                     // last chunk
+    __builtin_amdgcn_sched_barrier(0);
+    read(1, last_off, 1);
+    mma(0);
+    read(0, last_off, 2);
+    mma(1);
+    read(1, last_off, 3);
+    mma(0);
+    mma(1);
+}
+
+// One step's tile on that scheme: 128 NT tested tokens (MFMA N side) against 64 NR inherited representatives (M side);
+// the multiplying waves are a 2 (representatives) x 2 (tokens) grid, each holding NR x 2 NT blocks of 32 x 32 over ALL of
+// K.  Operand requests per Gram entry fall as 1 / tokens + 1 / representatives, which is why the tile is as large as the
+// step's tile count allows.  Sums of squares (Section 2.1) come from the fragments in hand: a 32-row block is held by
+// two waves, each wave sums the blocks at its even local positions, and the local order of a wave's blocks is permuted
+// (block a ^ parity) so that those positions cover every block and the K loop stays straight-line code.
+template <int NT, int NR>
+__device__ inline void fused_tile_split(const FusedParams& p, int r, int s0, int t0, char* lds) {
+    using G = FusedGeom<2, true>;
+    constexpr int BR = 64 * NR, BT = 128 * NT, ROWS = BR + BT, STAGE = ROWS * 128;
+    constexpr int NS = 4 * STAGE <= G::BODY ? 4 : 3;
+    constexpr int LPT = ROWS / 32, NA = NR, NB = 2 * NT;
+    static_assert(NS * STAGE <= G::RINGMAX, "ring does not fit");
+    static_assert(BR <= 256 && BT <= 256 && G::THREADS == 512, "metadata area; four loader and four multiplying waves");
+    int* s_tok = reinterpret_cast<int*>(lds + G::OFF_BIG);        // [BR] token id of each representative row (INT_MAX: none)
+    int* repf = s_tok + 256;                                      // [BT] tested token is inherited
+    float* ssq = reinterpret_cast<float*>(repf + 256);            // [ROWS] sums of squares
+    float* scale = ssq + 512;                                     // [ROWS] 1 / norm (0 for rows that do not exist)
+    char* ring = lds + G::META;
+
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave8 >= 4;
+    const int wave = wave8 & 3;                                   // place among the waves of its kind
+    const int wr = wave >> 1, wt = wave & 1;
+    const int T = p.T;
+
+    // the loaders' representative rows go through the list: every entry is requested before anything waits
+    int ptok[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+        const int row = (j * 4 + wave) * 8 + (lane >> 3);
+        const int li = s0 + min(row, BR - 1);
+        ptok[j] = loader ? list_at(p, li < r ? li : r - 1) : 0;
+    }
+    for (int i = tid; i < BR; i += G::THREADS) {
+        const int li = s0 + i;
+        const bool ok = li < r;
+        int tok = list_at(p, ok ? li : r - 1);
+        tok = min(max(tok, 0), T - 1);
+        s_tok[i] = ok ? tok : INT_MAX;
+    }
+    for (int i = tid; i < BT; i += G::THREADS) repf[i] = 0;
+    __syncthreads();
+
+    f32x16 acc[NA][NB];
+    // local block a of this wave is block a ^ pa of its NA representative blocks, likewise b ^ pb for its token blocks
+    const int pa = NA > 1 ? wt : 0, pb = wr;
+    constexpr int DA = (NA + 1) / 2, DB = NB / 2;                // blocks a wave sums on each side
+    float ssa[DA], ssb[DB];
+    if (loader) {
+        split_loader<NS, LPT, STAGE>(reinterpret_cast<const uint16_t*>(p.X), p.ld, p.d, ring, wave, lane,
+            [&](int j, int row) { return row < BR ? min(max(ptok[j], 0), T - 1) : min(t0 + row - BR, T - 1); });
+    } else {
+        if (!p.assign_mode) {                                     // which tested tokens are inherited (read in the epilogue)
+            for (int j = tid; j < r; j += G::THREADS / 2) {
+                const unsigned q = (unsigned)(list_at(p, j) - t0);
+                if (q < (unsigned)BT) repf[q] = 1;
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DA; ++i) ssa[i] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DB; ++i) ssb[i] = 0.f;
+        // Fragment addresses: row l32 of a 32-row block, piece 2 ks + half of the chunk (k-step ks of four).  Within a
+        // stage the offset of (local block, k-step) is one base per side XOR a constant: a block is 4096 bytes, the
+        // local order flips block bits (a ^ pa), and the swizzled slot (2 ks + half) ^ swz is (half ^ swz) ^ 2 ks; so
+        // two registers hold what 4 (NA + NB) pointers would.
+        static_assert((NA & (NA - 1)) == 0 && (NB & (NB - 1)) == 0 && BR % (32 * NB) == 0, "block bits do not carry");
+        const uint32_t abase = (uint32_t)lds_off((wr * NA + pa) * 32 + l32, half);
+        const uint32_t bbase = (uint32_t)lds_off(BR + (wt * NB + pb) * 32 + l32, half);
+        u32x4 fa[2][NA], fb[2][NB];
+        split_multiplier<NS, STAGE>(p.d / SPLIT_EPC,
+            [&](int set, int stage_off, int ks) {
+                uint32_t ab = abase, bb = bbase;               // (opaque: the XORs are redone here, not kept in 24 registers)
+                asm volatile("" : "+v"(ab), "+v"(bb));
+#pragma unroll
+                for (int a = 0; a < NA; ++a)
+                    fa[set][a] = *reinterpret_cast<const u32x4*>(ring + stage_off + (ab ^ (uint32_t)((a << 12) | (ks << 5))));
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    fb[set][b] = *reinterpret_cast<const u32x4*>(ring + stage_off + (bb ^ (uint32_t)((b << 12) | (ks << 5))));
+            },
+            [&](int set) {
+#pragma unroll
+                for (int a = 0; a < NA; ++a)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) Mfma<uint16_t>::run(acc[a][b], fa[set][a], fb[set][b]);
+#pragma unroll
+                for (int i = 0; i < NA; i += 2) ssa[i >> 1] += piece_sumsq_fast<uint16_t>(fa[set][i]);   // Section 2.1
+#pragma unroll
+                for (int i = 0; i < NB; i += 2) ssb[i >> 1] += piece_sumsq_fast<uint16_t>(fb[set][i]);
+            });
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));             // surplus loads land before the ring is reused
+    if (!loader) {
+        // the two lane halves hold different k pieces (a block summed by two waves gets the same bits from both)
+#pragma unroll
+        for (int i = 0; i < DA; ++i) {
+            const float v = ssa[i] + __shfl_xor(ssa[i], 32, 64);
+            if (half == 0) ssq[(wr * NA + ((2 * i) ^ pa)) * 32 + l32] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+            const float v = ssb[i] + __shfl_xor(ssb[i], 32, 64);
+            if (half == 0) ssq[BR + (wt * NB + ((2 * i) ^ pb)) * 32 + l32] = v;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < ROWS; i += G::THREADS) {
+        const float sum = ssq[i];
+        float sc = sum > 0.f ? 1.0f / sqrtf(sum) : 0.f;          // a zero row normalises to zero: all its cosines are 0
+        if (i < BR ? (s_tok[i] == INT_MAX) : (t0 + i - BR >= T)) sc = 0.f;
+        scale[i] = sc;
+    }
+    __syncthreads();
+    if (loader) return;                                           // (no barrier follows inside the tile)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int nl = (wt * NB + (b ^ pb)) * 32 + l32;
+        const int ordered = (repf[nl] != 0 ? 3 : 0) | (p.earlier_only ? 1 : 0);
+        const float tsc = scale[BR + nl];
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+            const int ablk = wr * NA + (a ^ pa);
+            finish_block(p, acc[a][b], s_tok + ablk * 32, scale + ablk * 32, tsc, ordered, t0 + nl, (s0 >> 5) + ablk, half);
+        }
+    }
+}
+
 // exclusive prefix sum of one 64-bit value per thread over the workgroup (three 21-bit counters ride in one scan)
 __device__ inline unsigned long long block_exclusive_scan64(unsigned long long v, unsigned long long* total,
                                                             unsigned long long* wave_tot /* >= 17 words of LDS */) {
@@ -1403,9 +1620,11 @@ __device__ inline void fused_step_tiles(const FusedParams& p, int r, char* lds, 
         const int tb = (int)(tile / nbS), sb = (int)(tile - (unsigned)tb * nbS);
         if constexpr (ALIGNED && KG == 2 && DMA) {
             if constexpr (sizeof(In) == 2) {
+                // (measured both ways: loader waves gain 10% at 128 x 128; at 128 x 256 the eight multiplying waves of
+                // the ring tile are 3% ahead for one sequence and level for stacked ones)
                 if (shape == 3) fused_tile_ring<2, 2>(p, r, sb * 128, tb * 256, lds);
-                else if (shape == 2) fused_tile_ring<1, 2>(p, r, sb * 128, tb * 128, lds);
-                else if (shape == 1) fused_tile_wide<In, 2>(p, r, sb * 64, tb * 128, lds);
+                else if (shape == 2) fused_tile_split<1, 2>(p, r, sb * 128, tb * 128, lds);
+                else if (shape == 1) fused_tile_wide<In, 2>(p, r, sb * 64, tb * 128, lds);   // (loader waves: no gain here)
                 else fused_tile<In, ALIGNED, KG, DMA>(p, r, sb * 64, tb * 64, sb, lds);
             } else {
                 if (shape == 2) fused_tile_wide<In, 4>(p, r, sb * 128, tb * 128, lds);

@@ -184,94 +184,15 @@ __device__ inline void gram_tile_dma(const GramParams& p, int s0, int t0, bool n
 }
 
 // ---- the one-launch form (T <= 4096, d a multiple of 64): tiles with few MFMAs per load ----------------------------
-// Eight waves: a wave that issues a load waits for room in the memory pipeline, and with one wave per SIMD those waits
-// add to the MFMA time instead of hiding behind it.  So waves 4 .. 7 do nothing but issue the loads (and count them
-// in), and waves 0 .. 3, a 2 x 2 grid of WA x WB blocks, multiply and never touch memory inside the K loop.  Rows are
-// staged in whole 128-byte chunks (one cache line per row and stage; the swizzle of lds_off), four stages, ONE barrier
-// per chunk of four k-steps, which both kinds of wave meet: a loader when its part of the next chunk has landed, a
-// multiplier when its reads of the current one have returned.
+// Eight waves, four loaders and four multipliers in a 2 x 2 grid of WA x WB blocks (split_loader / split_multiplier, the
+// scheme of the cascade step's large tiles), four stages of whole 128-byte chunks.
 // The rows' sums of squares (Section 2.1) come from the fragments in hand instead of a pass of their own: a 32-row
 // block is held by two waves, each wave sums the blocks at its even local positions, and the local order of a wave's
 // blocks is permuted (block a ^ parity) so that those positions cover every block and the K loop stays straight-line
 // code (a side with one block per wave is summed by both of its waves, which write the same bits).
 struct SplitGeom {
-    static constexpr int THREADS = 512, NS = 4, EPC = 64;      // elements per chunk (128 bytes of bf16)
+    static constexpr int THREADS = 512, NS = 4, EPC = SPLIT_EPC;
 };
-
-// the loader waves' K loop: LPT instructions of 1 KB (8 rows x 128 bytes) per wave and chunk; row(j) = (4 j + wave) 8 + lane / 8
-template <int LPT, int STAGE, typename TokOf>
-__device__ inline void split_loader(const GramParams& p, char* ring, int wave, int lane, TokOf tok_of) {
-    constexpr int NS = SplitGeom::NS, EPC = SplitGeom::EPC;
-    static_assert((NS - 1) * LPT < 64, "the loads in flight can be counted");
-    const uint16_t* X = reinterpret_cast<const uint16_t*>(p.X);
-    const int r8 = lane >> 3;
-    const int pcd = (lane & 7) ^ lds_swz(wave * 8 + r8);       // (32 j leaves bits 0..3 of the row alone)
-    const uint16_t* rowp[LPT];
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) rowp[j] = X + (size_t)tok_of((j * 4 + wave) * 8 + r8) * (size_t)p.ld + pcd * 8;
-    const int nk = p.d / EPC;
-    auto issue = [&](int stage_off, int k) {
-        const int chunk = min(k, nk - 1);                      // surplus issues repeat the last chunk into a dead stage
-#pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            char* dst = ring + stage_off + (j * 4 + wave) * 1024;               // wave-uniform
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rowp[j] + chunk * EPC),
-                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
-        }
-    };
-    issue(0 * STAGE, 0);
-    issue(1 * STAGE, 1);
-    issue(2 * STAGE, 2);
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));     // chunk 0 has landed (this wave's part)
-    __builtin_amdgcn_s_barrier();
-    issue(3 * STAGE, 3);
-    for (int k = 0; k + 1 < nk; ++k) {                         // the barrier of step k: k + 1 has landed, k is free
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(2 * LPT));
-        __builtin_amdgcn_s_barrier();
-        issue((k % NS) * STAGE, k + NS);
-    }
-}
-
-// the multiplying waves' K loop around read(set, stage_off, ks) and mma(set): fragments of k-step ks + 1 are read
-// while k-step ks multiplies; the barrier sits before the last k-step of a chunk
-template <int STAGE, typename Read, typename Mma>
-__device__ inline void split_multiplier(int nk, Read read, Mma mma) {
-    constexpr int NS = SplitGeom::NS;
-    auto cstep = [&](int cur_off, int nxt_off) {
-        __builtin_amdgcn_sched_barrier(0);
-        read(1, cur_off, 1);
-        mma(0);
-        __builtin_amdgcn_sched_barrier(0);
-        read(0, cur_off, 2);
-        mma(1);
-        __builtin_amdgcn_sched_barrier(0);
-        read(1, cur_off, 3);
-        mma(0);
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));     // my reads of this stage have returned
-        __builtin_amdgcn_s_barrier();
-        read(0, nxt_off, 0);
-        mma(1);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    __builtin_amdgcn_s_barrier();                              // chunk 0 has landed
-    read(0, 0, 0);
-    int k = 0;
-    for (; k + NS < nk; k += NS) {
-#pragma unroll
-        for (int s = 0; s < NS; ++s) cstep(s * STAGE, ((s + 1) % NS) * STAGE);
-    }
-    for (; k + 1 < nk; ++k) cstep((k % NS) * STAGE, ((k + 1) % NS) * STAGE);
-    const int last_off = (k % NS) * STAGE;                     // last chunk
-    __builtin_amdgcn_sched_barrier(0);
-    read(1, last_off, 1);
-    mma(0);
-    read(0, last_off, 2);
-    mma(1);
-    read(1, last_off, 3);
-    mma(0);
-    mma(1);
-}
 
 // One (2 WA) x (2 WB) tile: "against" rows s0.. on the MFMA M side, tested rows t0.. on the N side.
 template <int WA, int WB>
@@ -309,7 +230,8 @@ __device__ inline void gram_tile_split(const GramParams& p, int s0, int t0, bool
     float ssa[DA], ssb[DB];
     if (loader) {
         // rows past the end re-read row T - 1 (and are never published)
-        split_loader<LPT, STAGE>(p, ring, wave, lane, [&](int row) { return min(row < BS ? s0 + row : t0 + (row - BS), T - 1); });
+        split_loader<SplitGeom::NS, LPT, STAGE>(reinterpret_cast<const uint16_t*>(p.X), p.ld, p.d, ring, wave, lane,
+            [&](int, int row) { return min(row < BS ? s0 + row : t0 + (row - BS), T - 1); });
     } else {
 #pragma unroll
         for (int a = 0; a < NA; ++a)
@@ -333,7 +255,7 @@ __device__ inline void gram_tile_split(const GramParams& p, int s0, int t0, bool
         }
         u32x4 fa[2][NA], fb[2][NB];
         DMA_CLK(0);
-        split_multiplier<STAGE>(p.d / SplitGeom::EPC,
+        split_multiplier<SplitGeom::NS, STAGE>(p.d / SplitGeom::EPC,
             [&](int set, int stage_off, int ks) {
 #pragma unroll
                 for (int a = 0; a < NA; ++a) fa[set][a] = *reinterpret_cast<const u32x4*>(aptr[ks][a] + stage_off);
@@ -417,7 +339,8 @@ __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
     f32x16 acc[3];
     float ssP = 0.f, ssR = 0.f;                                // waves 0 and 1 cover the four blocks; 2 and 3 repeat two
     if (loader) {
-        split_loader<LPT, STAGE>(p, ring, wave, lane, [&](int row) { return min(t0 + row, T - 1); });
+        split_loader<SplitGeom::NS, LPT, STAGE>(reinterpret_cast<const uint16_t*>(p.X), p.ld, p.d, ring, wave, lane,
+            [&](int, int row) { return min(t0 + row, T - 1); });
     } else {
 #pragma unroll
         for (int a = 0; a < 3; ++a)
@@ -431,7 +354,7 @@ __device__ inline void gram_tile_diag(const GramParams& p, int t0, char* lds) {
             for (int f = 0; f < 4; ++f) fptr[ks][f] = ring + lds_off(blk[f] * 32 + l32, 2 * ks + half);
         u32x4 fr[2][4];
         DMA_CLK(0);
-        split_multiplier<STAGE>(p.d / SplitGeom::EPC,
+        split_multiplier<SplitGeom::NS, STAGE>(p.d / SplitGeom::EPC,
             [&](int set, int stage_off, int ks) {
 #pragma unroll
                 for (int f = 0; f < 4; ++f) fr[set][f] = *reinterpret_cast<const u32x4*>(fptr[ks][f] + stage_off);
