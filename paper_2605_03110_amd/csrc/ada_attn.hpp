@@ -858,12 +858,19 @@ __global__ __launch_bounds__(512) void k_attn_rep3(AttnParams p) {
             for (int e = 0; e < 16; ++e) acc_s[e] = 0.f;
             uint32_t kb_ = k_base, qb_ = q_base, vb_ = v_base;
             asm volatile("" : "+v"(kb_), "+v"(qb_), "+v"(vb_));   // (opaque: keeps the XORs below out of registers)
+            // (fragments are read two k-steps ahead of the MFMA that takes them: sixteen dependent MFMAs each waiting
+            //  for an LDS round trip were the longest part of a block)
+            u32x4 fkr[3], fqr[3];
+            auto rd = [&](int ks) {
+                fkr[ks % 3] = *reinterpret_cast<const u32x4*>(kcur + (kb_ ^ (uint32_t)(ks << 5)));
+                if (ks >= QREG) fqr[ks % 3] = *reinterpret_cast<const u32x4*>(qbuf + (qb_ ^ (uint32_t)(ks << 5)));
+            };
+            rd(0);
+            if (KS > 1) rd(1);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 fk = *reinterpret_cast<const u32x4*>(kcur + (kb_ ^ (uint32_t)(ks << 5)));
-                const u32x4 fq = ks < QREG ? qf[ks < QREG ? ks : 0]
-                                           : *reinterpret_cast<const u32x4*>(qbuf + (qb_ ^ (uint32_t)(ks << 5)));
-                Mfma<In>::run(acc_s, fk, fq);
+                if (ks + 2 < KS) rd(ks + 2);
+                Mfma<In>::run(acc_s, fkr[ks % 3], ks < QREG ? qf[ks < QREG ? ks : 0] : fqr[ks % 3]);
             }
             // ---- weights of this lane's query (register e is key 32 kh + (e & 3) + 4 half + 8 (e >> 2)), in base 2:
             // t = s * scale * log2(e), weight = 2^(t - m).  m is a reference, not the exact running maximum: it moves only
