@@ -396,7 +396,7 @@ int ada_profile_mfma_probe(int workgroups, int iters, float* sink, void* stream)
  *   ADA_KGROUPS=1|2               K-groups of the 64 x 64 one-launch cascade tile
  *   ADA_CASCADE_TILE=64|64x128|128|256x128   tile shape of the one-launch cascade step
  *   ADA_NO_DMA=1                  operands through registers instead of straight into LDS
- *   ADA_ATTN=lds|regs4            the first attention kernel / the four-wave form of the register kernel
+ *   ADA_ATTN=lds                  the first attention kernel
  *   ADA_SPIN_LIMIT=n              bound of the resident pass's wait between layers (polls)
  */
 

@@ -389,7 +389,7 @@ __global__ __launch_bounds__(256) void k_attn_rep(AttnParams p) {
 //   Wave w serves the 32 queries of block w % 2 against the 32 keys of half w / 2 of every key block, with a running
 //   maximum, sum and O^T (all d_h columns) of its own; the two waves of a query block are merged once, after the last
 //   key block (the usual rescaling to the common maximum).  Nothing is exchanged inside the loop, and a lane handles
-//   16 scores per block.  Two barriers per key block remain (K / V^T staged; everybody done with them).
+//   16 scores per block.  Two barriers per key block remain (see below).
 //   Weights are powers of 2 against a reference that only moves when a block's maximum passes it by more than 10
 //   (the accumulated rows are rescaled on few blocks, and stay in the accumulation registers otherwise).
 //   K rows go global -> LDS directly into one of two stages; token indices are read once per block (lane = row) and
@@ -414,315 +414,19 @@ template <int DH> struct AttnGeom2 {
     static constexpr int LDS = OFF_LIST + 257 * 4;
 };
 
-template <int DH>
-__global__ __launch_bounds__(256) void k_attn_rep2(AttnParams p) {
-    using In = uint16_t;
-    using G = AttnGeom2<DH>;
-    constexpr int EPP = 8, PPR = G::PPR, NB = DH / 32, KS = DH / 16, NP = PPR / 4;
-    extern __shared__ __align__(16) char lds[];
-    char* qbuf = lds + G::OFF_Q;
-    char* kbuf = lds + G::OFF_K;
-    char* vtbuf = lds + G::OFF_VT;
-    int* qtok = reinterpret_cast<int*>(lds + G::OFF_ROW);
-    int* ktok = qtok + 64;
-    float* mrow = reinterpret_cast<float*>(ktok + 64);     // [2][64] running maxima and sums of the two key halves
-    float* lrow = mrow + 128;
-    int* list = reinterpret_cast<int*>(lds + G::OFF_LIST);                 // the takers' counter
-    int* takers = reinterpret_cast<int*>(lds + G::OFF_TAKERS);            // up to 2048 (token, row) pairs
-
-    const int r = p.r_dev ? *p.r_dev : p.r_host;
-    if (attn_status(p, r) != ADA_OK) return;               // k_attn_pos rejected the set or the assignment
-    const AttnWho who = attn_who(p.H);
-    const int h = who.h;
-    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int qb = wave & 1, kh = wave >> 1;
-    ATTN_CLK(0);
-    for (int q0 = who.qblk * 64; q0 < r; q0 += gridDim.x * 64) {
-    __syncthreads();                                       // a previous query block's hand-over is done with the LDS
-    const In* Qh = reinterpret_cast<const In*>(p.Q) + (size_t)h * DH;
-    const In* Kh = reinterpret_cast<const In*>(p.K) + (size_t)h * DH;
-    const In* Vh = reinterpret_cast<const In*>(p.V) + (size_t)h * DH;
-    // every wave keeps the 64 query tokens and the 64 key tokens of a block in one register (lane = row) and hands
-    // them out with lane reads: no index goes through memory twice, and nothing in the loop waits on an index load
-    const int qtokv = min(max(p.idx[min(q0 + lane, r - 1)], 0), p.T - 1);
-    int tok_next = min(max(p.idx[min(lane, r - 1)], 0), p.T - 1), tok_cur = 0;
-    {
-        u32x4 qreg[NP];
-#pragma unroll
-        for (int j = 0; j < NP; ++j) {
-            const int i = tid + 256 * j, row = i / PPR, pc = i % PPR;
-            qreg[j] = *reinterpret_cast<const u32x4*>(Qh + (size_t)__shfl(qtokv, row, 64) * (size_t)p.ld + pc * EPP);
-        }
-#pragma unroll
-        for (int j = 0; j < NP; ++j) {
-            const int i = tid + 256 * j, row = i / PPR, pc = i % PPR;
-            *reinterpret_cast<u32x4*>(qbuf + attn_off(row, pc, PPR)) = qreg[j];
-        }
-    }
-    u32x4 vreg[NP];
-    // K goes global -> LDS directly, 1 KB (64 / PPR rows) per wave instruction; the 16-byte slots of a row are permuted
-    // on the global side, so that the LDS image is the swizzled one the operand reads expect.
-    // V: thread (wave, lane) takes keys 16 wave + 2 (lane / 8) + {0, 1} and, for j / 2 = line, columns 64 line + 8 (lane % 8) ..+7
-    const int vkey = 16 * wave + 2 * (lane >> 3), vp8 = lane & 7;
-    auto ids = [&](int kb) { tok_next = min(max(p.idx[min(kb * 64 + lane, r - 1)], 0), p.T - 1); };
-    auto fetch = [&](int stage) {                          // the block whose tokens are in tok_next
-        tok_cur = tok_next;
-#pragma unroll
-        for (int j = 0; j < NP; ++j) {
-            const int krow = (j * 4 + wave) * (64 / PPR) + lane / PPR, slot = lane % PPR;
-            const int kpc = slot ^ (PPR >= 16 ? (krow & 15) : lds_swz(krow));
-            const In* src = Kh + (size_t)__shfl(tok_cur, krow, 64) * (size_t)p.ld + kpc * EPP;
-            char* dst = kbuf + stage * G::KSTAGE + (j * 4 + wave) * 1024;           // wave-uniform
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
-                                             (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
-        }
-        const size_t vt0 = (size_t)__shfl(tok_cur, vkey, 64) * (size_t)p.ld;
-        const size_t vt1 = (size_t)__shfl(tok_cur, vkey + 1, 64) * (size_t)p.ld;
-#pragma unroll
-        for (int j = 0; j < NP; ++j)
-            vreg[j] = *reinterpret_cast<const u32x4*>(Vh + ((j & 1) ? vt1 : vt0) + ((j >> 1) * 8 + vp8) * EPP);
-    };
-    auto stash = [&]() {
-        // V^T with the keys of every group of 16 in the order the weights' registers have: 0-3, 8-11, 4-7, 12-15
-        const int o = vkey & 15;
-        const int pos = (vkey & ~15) | ((o & 3) | ((o & 4) << 1) | ((o & 8) >> 1));          // even: this key and the next
-#pragma unroll
-        for (int j = 0; j < NP; j += 2)
-#pragma unroll
-            for (int e = 0; e < EPP; ++e) {
-                const int c = ((j >> 1) * 8 + vp8) * EPP + e;
-                const uint32_t two = (uint32_t)attn_elem<In>(vreg[j], e) | ((uint32_t)attn_elem<In>(vreg[j + 1], e) << 16);
-                *reinterpret_cast<uint32_t*>(vtbuf + attn_vt_off(c, pos >> 3) + (pos & 7) * 2) = two;
-            }
-    };
-
-    float m_run = -INFINITY, l_run = 0.f;                  // of query qb * 32 + l32 over THIS wave's keys (both lane halves alike)
-    f32x16 acc_o[NB];                                      // O^T blocks: rows = output columns 32 i + ..., lane = query
-#pragma unroll
-    for (int i = 0; i < NB; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc_o[i][e] = 0.f;
-    const int my_q = qb * 32 + l32;
-    const float sc2 = p.scale * 1.44269504088896340736f;
-
-    const int nkb_all = (r + 63) / 64;
-    const int nkb = p.causal ? min(nkb_all, q0 / 64 + 1) : nkb_all;
-    fetch(0);
-    ids(1);
-    ATTN_CLK(1);
-    // The query operands of the first eight k-steps stay in registers (this lane's query row); the rest is read from
-    // LDS in every block: the score product is bound by LDS reads, and the register file has no room for more.
-    constexpr int QREG = KS < 8 ? KS : 8;
-    u32x4 qf[QREG];
-    for (int kb = 0; kb < nkb; ++kb) {
-        // the previous block's products are done with V^T and with the K stage the next fetch writes; this block's K
-        // has landed in LDS and its V in registers (the barrier's fence waits for both)
-        __syncthreads();
-        if (kb == 1) ATTN_CLK(2);
-        if (p.causal && wave == 0) ktok[lane] = tok_cur;   // the tokens of the block being staged
-        stash();
-        __syncthreads();
-        if (kb == 1) ATTN_CLK(3);
-        if (kb + 1 < nkb) { fetch((kb + 1) & 1); ids(kb + 2); }                   // in flight behind this block's products
-        if (kb == 0) {                                     // (Q was staged before the first pair of barriers)
-#pragma unroll
-            for (int ks = 0; ks < QREG; ++ks)
-                qf[ks] = *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
-        }
-        const char* kcur = kbuf + (kb & 1) * G::KSTAGE;
-        // ---- S^T = K Q^T: this wave's 32 keys (half kh of the block) against its 32 queries
-        f32x16 acc_s;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc_s[e] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const u32x4 fk = *reinterpret_cast<const u32x4*>(kcur + attn_off(kh * 32 + l32, 2 * ks + half, PPR));
-            const u32x4 fq = ks < QREG ? qf[ks < QREG ? ks : 0]
-                                       : *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
-            Mfma<In>::run(acc_s, fk, fq);
-        }
-        // ---- weights of this lane's query (register e is key 32 kh + (e & 3) + 4 half + 8 (e >> 2)), in base 2:
-        // t = s * scale * log2(e), weight = 2^(t - m).  m is a reference, not the exact running maximum: it moves only
-        // when a block's maximum passes it by more than 10, so weights stay below 2^10 and the accumulated rows are
-        // rescaled on few blocks (the quotient sum(w v) / sum(w) does not depend on the reference).
-        if (p.causal || kb * 64 + 64 > r) {                // uniform: only then can a key be masked
-            const int qt = __shfl(qtokv, my_q, 64);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                i32x4 kt4 = {INT_MIN, INT_MIN, INT_MIN, INT_MIN};                 // without the mask no key is "later"
-                if (p.causal) kt4 = *reinterpret_cast<const i32x4*>(ktok + kh * 32 + 8 * q + 4 * half);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int kk = kb * 64 + kh * 32 + 8 * q + 4 * half + e;
-                    if ((kk >= r) | (kt4[e] > qt)) acc_s[4 * q + e] = -INFINITY;
-                }
-            }
-        }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            acc_s[e] *= sc2;
-            mx = fmaxf(mx, acc_s[e]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));            // the other half of the keys
-        const bool grow = mx > m_run + 10.f;               // (false while both are -inf)
-        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-            const float m_new = grow ? mx : m_run;
-            const float a = grow ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;   // 0 when the old reference is -inf
-            l_run *= a;
-            m_run = m_new;
-            if (kb > 0) {                                  // (the rows are still zero on the first block)
-#pragma unroll
-                for (int i = 0; i < NB; ++i)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) acc_o[i][e] *= a;
-            }
-        }
-        const float m_use = m_run == -INFINITY ? 0.f : m_run;                     // all keys masked so far: weights 0
-        float sum = 0.f;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float pv = __builtin_amdgcn_exp2f(acc_s[e] - m_use);
-            acc_s[e] = pv;
-            sum += pv;
-        }
-        sum += __shfl_xor(sum, 32, 64);
-        l_run += sum;
-        // ---- O^T += V^T P^T: the weights of k-step j (16 keys) are registers 8 j .. 8 j + 7; each weight is split
-        // into a bf16 head and a bf16 remainder (hardware round-to-nearest-even pairs), two products per step
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            u32x4 hi, lo;
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const attn_f32x2 pv = {acc_s[8 * j + 2 * w], acc_s[8 * j + 2 * w + 1]};
-                const uint32_t hw = __builtin_bit_cast(uint32_t, __builtin_convertvector(pv, attn_bf16x2));
-                const attn_f32x2 rem = {pv[0] - __uint_as_float(hw << 16), pv[1] - __uint_as_float(hw & 0xFFFF0000u)};
-                hi[w] = hw;
-                lo[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rem, attn_bf16x2));
-            }
-#pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const u32x4 fv = *reinterpret_cast<const u32x4*>(vtbuf + attn_vt_off(32 * i + l32, 4 * kh + 2 * j + half));
-                Mfma<In>::run(acc_o[i], fv, hi);
-                Mfma<In>::run(acc_o[i], fv, lo);
-            }
-        }
-    }
-    ATTN_CLK(6);
-    int rel[8];                                            // hand-over: positions of 2048 tokens, relative to this block
-    auto load_rel = [&](int tb) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int t = tb + u * 256 + tid;
-            rel[u] = t < p.T ? p.pos[t] - q0 : -1;
-        }
-    };
-    load_rel(0);                                           // in flight behind the merge
-    // ---- the two waves of a query block hold sums over different keys: exchange (m, l), bring both to the common
-    // maximum and the common denominator, and add the second wave's rows onto the first's in the output block
-    if (half == 0) { mrow[kh * 64 + my_q] = m_run; lrow[kh * 64 + my_q] = l_run; }
-    __syncthreads();                                       // also: everybody is done with Q, K, V^T (O is laid over them)
-    float* obuf = reinterpret_cast<float*>(lds);           // [64][OS]
-    {
-        const float m_o = mrow[(kh ^ 1) * 64 + my_q], l_o = lrow[(kh ^ 1) * 64 + my_q];
-        const float m_all = fmaxf(m_run, m_o);
-        const float w_me = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - m_all);
-        const float w_o = m_o == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_o - m_all);
-        const float l_all = l_run * w_me + l_o * w_o;
-        const float f = l_all > 0.f ? w_me / l_all : 0.f;
-        // each wave hands the half of the columns it does not finish to its partner through the output block itself
-        // (disjoint places), then adds its own share onto what it received: every place has one writer at a time
-        auto give = [&](auto khc) {                        // (register blocks are addressed with constants only)
-            constexpr int KH = decltype(khc)::value;
-#pragma unroll
-            for (int i = 0; i < NB / 2; ++i) {
-                const int blk = (1 - KH) * (NB / 2) + i;   // given away
-#pragma unroll
-                for (int q = 0; q < 4; ++q)                // registers 4 q .. 4 q + 3 are four consecutive columns
-                    *reinterpret_cast<float4*>(obuf + my_q * G::OS + 32 * blk + 8 * q + 4 * half) =
-                        float4{acc_o[blk][4 * q] * f, acc_o[blk][4 * q + 1] * f, acc_o[blk][4 * q + 2] * f,
-                               acc_o[blk][4 * q + 3] * f};
-            }
-        };
-        auto finish = [&](auto khc) {
-            constexpr int KH = decltype(khc)::value;
-#pragma unroll
-            for (int i = 0; i < NB / 2; ++i) {
-                const int blk = KH * (NB / 2) + i;         // finished here
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float4* at = reinterpret_cast<float4*>(obuf + my_q * G::OS + 32 * blk + 8 * q + 4 * half);
-                    const float4 o = *at;
-                    *at = float4{o.x + acc_o[blk][4 * q] * f, o.y + acc_o[blk][4 * q + 1] * f,
-                                 o.z + acc_o[blk][4 * q + 2] * f, o.w + acc_o[blk][4 * q + 3] * f};
-                }
-            }
-        };
-        if (kh == 0) give(std::integral_constant<int, 0>{}); else give(std::integral_constant<int, 1>{});
-        __syncthreads();
-        if (kh == 0) finish(std::integral_constant<int, 0>{}); else finish(std::integral_constant<int, 1>{});
-    }
-    __syncthreads();
-    ATTN_CLK(4);
-    // ---- hand-over: every token whose representative sits in this block takes that row.  The positions of 2048
-    // tokens are read in one trip to memory and the takers collected in one list; a wave then copies a whole row
-    // (d_h floats) per store instruction.
-    float* outh = p.out + (size_t)h * DH;
-    for (int tb = 0; tb < p.T; tb += 8 * 256) {
-        if (tb > 0) load_rel(tb);                          // (the first 2048 were asked for before the merge)
-        if (tid == 0) list[0] = 0;
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if ((unsigned)rel[u] < 64u) takers[atomicAdd(&list[0], 1)] = ((tb + u * 256 + tid) << 6) | rel[u];
-        __syncthreads();
-        ATTN_CLK(5);
-        const int n = list[0];
-        constexpr int LPR = DH / 4, RPI = 64 / LPR;        // lanes per row (a float4 each), rows per instruction
-        const int sub = lane / LPR, c4 = (lane % LPR) * 4;
-        // a wave's share of the list (entries wave * RPI + sub + 4 RPI k) is read 64 entries at a time, one per lane,
-        // and handed to the lane groups by lane reads; eight rows are in flight per lane group
-        constexpr int KPB = 64 / RPI;                      // steps k per batch
-        const int steps = (n - wave * RPI + 4 * RPI - 1) / (4 * RPI);             // k with a first entry below n
-        for (int k0 = 0; k0 < steps; k0 += KPB) {
-            const int mine = takers[min(wave * RPI + (lane % RPI) + 4 * RPI * (k0 + lane / RPI), n - 1)];
-            const int kend = min(KPB, steps - k0);
-            for (int kk = 0; kk < kend; kk += 8) {
-                int ent[8];
-                float4 v4[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) ent[u] = __shfl(mine, min(kk + u, KPB - 1) * RPI + sub, 64);
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    v4[u] = *reinterpret_cast<const float4*>(obuf + (ent[u] & 63) * G::OS + c4);
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (kk + u < kend && wave * RPI + sub + 4 * RPI * (k0 + kk + u) < n)
-                        *reinterpret_cast<float4*>(outh + (size_t)(ent[u] >> 6) * (size_t)p.ld_out + c4) = v4[u];
-            }
-        }
-        __syncthreads();
-    }
-    }
-    ATTN_CLK(7);
-}
-
-// The same kernel with EIGHT waves: waves 0 .. 3 multiply as above and never touch memory inside the key-block loop;
-// waves 4 .. 7 fetch (K rows straight into LDS, V rows through their registers and transposed into LDS, the token
-// indices of the coming blocks).  A wave that issues a load waits for room in the memory pipeline, and with one wave per
-// SIMD that wait (a microsecond per key block here) and the staging of V added to the time of the products.  Two
-// barriers per key block kb, met by all eight waves:
+// EIGHT waves: waves 0 .. 3 multiply as described and never touch memory inside the key-block loop; waves 4 .. 7 fetch
+// (K rows straight into LDS, V rows through their registers and transposed into LDS, the token indices of the coming
+// blocks).  A wave that issues a load waits for room in the memory pipeline; when the four multiplying waves fetched
+// for themselves (one wave per SIMD), that wait -- a microsecond per key block here -- and the staging of V added to the
+// time of the products (41.7 against 32.2 us at 16 heads x 256, r = 434).  With half the register file per wave, the
+// operand addresses inside the loop are one base per buffer XOR a constant.  Two barriers per key block kb, met by all
+// eight waves:
 //   A(kb): K(kb) has landed in its stage and V(kb) in the loaders' registers; the multipliers have left V^T(kb - 1).
 //          Then the loaders write V^T(kb) and ask for V(kb + 1); the multipliers form the scores and weights of kb.
 //   B(kb): V^T(kb) is written; the multipliers have left K(kb).  Then the loaders ask for K(kb + 2) into the stage just
 //          left and for the indices of block kb + 3; the multipliers add weights x V^T(kb) to their rows.
-#ifndef ATTN3_QREG
-#define ATTN3_QREG 4
-#endif
 template <int DH>
-__global__ __launch_bounds__(512) void k_attn_rep3(AttnParams p) {
+__global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
     using In = uint16_t;
     using G = AttnGeom2<DH>;
     constexpr int EPP = 8, PPR = G::PPR, NB = DH / 32, KS = DH / 16, NP = PPR / 4;
@@ -837,7 +541,7 @@ __global__ __launch_bounds__(512) void k_attn_rep3(AttnParams p) {
         const float sc2 = p.scale * 1.44269504088896340736f;
         // The query operands of the first k-steps stay in registers (this lane's query row), as many as the register
         // file has room for beside the rows; the rest is read from LDS in every block.
-        constexpr int QREG = KS <= 8 ? KS : ATTN3_QREG;
+        constexpr int QREG = KS <= 8 ? KS : 4;
         u32x4 qf[QREG];
 #pragma unroll
         for (int ks = 0; ks < QREG; ++ks)

@@ -1059,19 +1059,15 @@ hipError_t dispatch(int dtype, const void* X, long long ld, int d, F&& f) {
     return al ? f(Variant<float, true>{}) : f(Variant<float, false>{});
 }
 
-// bf16: the kernels that keep scores and weights in registers (eight waves: four multiply, four fetch; or the
-// four-wave form, kept behind a development switch)
+// bf16: the kernel that keeps scores and weights in registers (eight waves: four multiply, four fetch)
 template <int DH>
-hipError_t launch_attn_regs(const AttnParams& p, hipStream_t st, bool four_waves) {
+hipError_t launch_attn_regs(const AttnParams& p, hipStream_t st) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     constexpr int lds = AttnGeom2<DH>::LDS;
     std::call_once(once, [] {
         attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_rep2<DH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_rep3<DH>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     });
     if (attr_err != hipSuccess) return attr_err;
     ProfScope ps(ADA_K_ATTN, st);
@@ -1080,21 +1076,20 @@ hipError_t launch_attn_regs(const AttnParams& p, hipStream_t st, bool four_waves
         const int fit = (device_cus() + p.H - 1) / p.H;
         gx = gx < fit ? gx : fit;
     }
-    if (four_waves) hipLaunchKernelGGL((k_attn_rep2<DH>), dim3(gx, p.H), dim3(256), lds, st, p);
-    else hipLaunchKernelGGL((k_attn_rep3<DH>), dim3(gx, p.H), dim3(512), lds, st, p);
+    hipLaunchKernelGGL((k_attn_rep2<DH>), dim3(gx, p.H), dim3(512), lds, st, p);
     return hipGetLastError();
 }
 
 template <typename In, int DH>
 hipError_t launch_attn(const AttnParams& p, hipStream_t st) {
     if constexpr (sizeof(In) == 2) {
-        static const int which = [] {                     // development switch: ADA_ATTN=lds keeps the first kernel,
-            const char* e = dev_switch("ADA_ATTN");        // ADA_ATTN=regs4 the four-wave form of the second
-            return !e ? 0 : std::string(e) == "lds" ? 1 : std::string(e) == "regs4" ? 2 : 0;
+        static const bool first_kernel = [] {             // development switch: ADA_ATTN=lds keeps the first kernel
+            const char* e = dev_switch("ADA_ATTN");
+            return e && std::string(e) == "lds";
         }();
         // its hand-over stores 16 bytes per lane
         const bool out16 = (uintptr_t)p.out % 16 == 0 && p.ld_out % 4 == 0;
-        if (which != 1 && out16) return launch_attn_regs<DH>(p, st, which == 2);
+        if (!first_kernel && out16) return launch_attn_regs<DH>(p, st);
     }
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
