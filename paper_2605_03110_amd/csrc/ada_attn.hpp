@@ -541,7 +541,7 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
         const float sc2 = p.scale * 1.44269504088896340736f;
         // The query operands of the first k-steps stay in registers (this lane's query row), as many as the register
         // file has room for beside the rows; the rest is read from LDS in every block.
-        constexpr int QREG = KS <= 8 ? KS : 4;
+        constexpr int QREG = KS <= 8 ? KS : 2;
         u32x4 qf[QREG];
 #pragma unroll
         for (int ks = 0; ks < QREG; ++ks)
