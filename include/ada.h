@@ -263,8 +263,10 @@ int ada_cascade_step_grouped(const ada_groups* groups, const void* X, int T, int
                              void* ws, size_t ws_bytes, void* stream, unsigned flags);
 
 /*
- * The full selection (Definition "Gram threshold") of every group, in the launches one problem takes (norms and
- * Gram tiles; the set update is the tiles' last workgroup up to T = 4096 and a third launch beyond).
+ * The full selection (Definition "Gram threshold") of every group, in the launches one problem takes (up to T = 4096
+ * one: the Gram tiles sum the norms from their own operands and their last workgroup updates the set; beyond that, or
+ * for rows that are not bf16 in whole aligned 128-byte chunks, a norm launch, the tiles and, beyond T = 4096, an
+ * update launch).
  *   mask    [G][T] uint8, or NULL
  *   idx     group g's representatives at idx + g * list_gstride, ascending     (required)
  *   counts  group g's {r, r, 0, 0} at counts + g * counts_gstride               (required)
