@@ -351,6 +351,16 @@ int ada_cascade_layers_adaptive(const void* const* X_layers, int L, int T, int d
 int ada_plan_tile_shape(int r, int T, int d, int workgroups);
 
 /*
+ * How ada_select_full cuts the lower triangle of the T x T Gram into work units when it runs its direct-to-LDS kernel
+ * (bf16 rows in whole aligned 64-byte pieces, T >= 1536, no greedy covering) on `workgroups` workgroups (the CU count
+ * for one problem): 0 = 128 x 128 units everywhere; 1 = 256 x 256 units off the diagonal, 128 x 128 on it (T > 4096);
+ * 2 = 64 x 128 units off the diagonal of 128-blocks and one unit per diagonal block (T <= 4096, d a multiple of 64,
+ * where 128 x 128 units would leave CUs idle); -1 for arguments outside that kernel's range.
+ * Host only (no device is touched): the choice the launch makes.
+ */
+int ada_plan_full_units(int T, int d, int workgroups);
+
+/*
  * |A n B| and |A u B| of two representative sets given as uint8 masks [T] (device), for the
  * Jaccard index of eq. (3).  out: device int32 [2] = {intersection, union}.
  */

@@ -27,7 +27,7 @@ FLAG_GREEDY_COVER = 16
 OK = 0
 
 SYMBOLS = ("ada_status_string", "ada_workspace_bytes", "ada_workspace_init", "ada_select_full", "ada_cascade_step",
-           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped", "ada_pipeline_layers", "ada_cascade_layers_adaptive", "ada_plan_tile_shape",
+           "ada_cascade_layers", "ada_cascade_layers_batched", "ada_cascade_step_grouped", "ada_cascade_layers_grouped", "ada_select_full_grouped", "ada_pipeline_layers", "ada_cascade_layers_adaptive", "ada_plan_tile_shape", "ada_plan_full_units",
            "ada_set_overlap", "ada_cascade_report", "ada_profile_enable",
            "ada_profile_collect", "ada_profile_copy_probe", "ada_profile_mfma_probe", "ada_assign_nearest",
            "ada_attention_compressed", "ada_cascade_step_static")
@@ -121,6 +121,8 @@ def lib():
                                                   ctypes.POINTER(AdaTauControl), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, u32]
         L.ada_plan_tile_shape.restype = i32
         L.ada_plan_tile_shape.argtypes = [i32, i32, i32, i32]
+        L.ada_plan_full_units.restype = i32
+        L.ada_plan_full_units.argtypes = [i32, i32, i32]
         L.ada_select_full_grouped.restype = i32
         L.ada_select_full_grouped.argtypes = [ctypes.POINTER(AdaGroups), vp, i32, i32, i64, i32, f32, vp, vp, vp, vp, sz, vp, u32]
         L.ada_cascade_layers_grouped.restype = i32
@@ -600,6 +602,12 @@ def ada_plan_tile_shape(r: int, T: int, d: int, workgroups: int) -> int:
     """Tile shape of a one-launch cascade step of this size (0 = 64 x 64, 1 = 64 x 128, 2 = 128 x 128; -1: bad
     arguments); host-side evaluation of the kernel's own choice."""
     return int(lib().ada_plan_tile_shape(int(r), int(T), int(d), int(workgroups)))
+
+
+def ada_plan_full_units(T: int, d: int, workgroups: int) -> int:
+    """How the full selection's direct-to-LDS kernel cuts the triangle into units (0, 1, 2; -1 outside its range).
+    Host only."""
+    return int(lib().ada_plan_full_units(int(T), int(d), int(workgroups)))
 
 
 def ada_set_overlap(mask_a: torch.Tensor, mask_b: torch.Tensor, *, stream=None) -> torch.Tensor:

@@ -1939,6 +1939,13 @@ int ada_plan_tile_shape(int r, int T, int d, int workgroups) {
     return cascade_tile_shape(r, T, d, workgroups, workgroups);
 }
 
+int ada_plan_full_units(int T, int d, int workgroups) {
+    if (T < 1536 || T > ADA_MAX_T || d < 1 || d % DmaGeom::HC != 0 || workgroups < 8) return -1;
+    const int G = workgroups / 8 * 8;
+    if (T <= 4096 && d % SplitGeom::EPC == 0) return dma_makespan_norms(T, 2, G) < dma_makespan_norms(T, 0, G) ? 2 : 0;
+    return dma_makespan(T, 1, G) < dma_makespan(T, 0, G) ? 1 : 0;
+}
+
 int ada_set_overlap(const uint8_t* mask_a, const uint8_t* mask_b, int T, int32_t* out, void* stream) {
     if (!mask_a || !mask_b || !out) return ADA_ERR_NULL;
     if (T < 1 || T > ADA_MAX_T) return ADA_ERR_SHAPE;

@@ -963,6 +963,7 @@ def test_config2_and_3_all_layers(ci, full_every):
     say("%s, all %d layers" % (w.name, w.L))
     xs_cpu = wl.layer_list(w)
     xs = [x.to(DEV) for x in xs_cpu]
+    assert pa.ada_plan_full_units(w.T, w.d, CUS) == 2            # T = 2048: 64 x 128 units and the diagonal units, one launch
     full = pa.fetch(pa.ada_select_full(xs[0], w.tau))
     parity.check_full(xs_cpu[0], w.tau, full, w.name + " layer 0")
     prev = full["idx"]
@@ -1057,6 +1058,7 @@ def test_config4_full_selection_compared_completely(config4_batch, layer):
     the oracle, at layer 0 and at layer 8 (the layers at which the configuration runs the full selection)."""
     w, n_layers, seqs_cpu, xg, _ = config4_batch
     say("%s sequence 0 layer %d: complete full selection" % (w.name, layer))
+    assert pa.ada_plan_full_units(w.T, w.d, CUS) == 1            # 256 x 256 units and the unit queue
     got = pa.fetch(pa.ada_select_full(xg[layer][0], w.tau))
     info = parity.check_full(seqs_cpu[0][layer], w.tau, got, "%s full layer %d" % (w.name, layer))
     say("gamma error %.3g, %d tokens in the band" % (info["gamma_err"], info["n_band"]))

@@ -218,3 +218,18 @@ def test_tile_shape_plan_follows_tiles_per_workgroup(ada):
     assert plan(0, 8, 8, 8) == -1 and plan(9, 8, 8, 8) == -1 and plan(4, 8, 0, 8) == -1 and plan(4, 8, 8, 0) == -1
     for r, T, d, wg in [(300, 4096, 1024, 256), (2000, 4096, 4096, 256), (5000, 16384, 512, 128)]:
         assert plan(r, T, d, wg) in (0, 1, 2, 3)
+
+
+def test_full_selection_unit_plan(ada):
+    """How the full selection's direct-to-LDS kernel cuts the triangle (host-side evaluation of the launch's own
+    choice): halved units where 128 x 128 units leave CUs idle, 128 x 128 units where they fill the chip in whole
+    rounds, 256 x 256 units beyond the one-launch form's range."""
+    plan = ada.lib().ada_plan_full_units
+    assert plan(2048, 4096, 256) == 2               # 240 + 16 = 256 units on 256 CUs instead of 136 of 128 x 128
+    assert plan(1536, 4096, 256) == 2               # 144 instead of 78
+    assert plan(2560, 4096, 256) == 0               # 210 units of 128 x 128 in one round; halved ones would take two
+    assert plan(4096, 4096, 256) == 0
+    assert plan(2048, 4096 + 32, 256) in (0, 1)     # rows in half chunks: not the one-launch form
+    assert plan(8192, 4096, 256) == 1               # 496 units of 256 x 256 and the diagonal in 128 x 128 units
+    assert plan(1535, 4096, 256) == -1 and plan(2048, 48, 256) == -1 and plan(2048, 4096, 4) == -1
+    assert plan(1 << 30, 4096, 256) == -1
