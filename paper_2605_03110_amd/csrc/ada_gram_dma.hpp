@@ -407,6 +407,35 @@ struct DmaUnits {
     }
 };
 
+// Mode 2: unit u -> tested 128-block tb >= 1 against the 64-block sb < 2 tb, or (sb < 0) the diagonal block tb.  The order
+// goes patch by patch -- four 128-blocks of tested rows against eight 64-blocks, 32 units -- so that the contiguous
+// range of units an XCD starts with needs about a thousand rows instead of most of the matrix (every XCD has an L2 of
+// its own): first the patches on the diagonal (their 64 x 128 units and their diagonal units), then the others.
+struct DmaUnit2 { int tb, sb; };
+__device__ inline DmaUnit2 dma_unit2(int u, int nb) {
+    const int P = (nb + 3) >> 2;
+    int acc = 0;
+    for (int g = 0; g < P; ++g) {
+        const int t_lo = 4 * g, n_t = min(4, nb - t_lo), n_rect = n_t * (n_t - 1), cnt = n_rect + n_t;
+        if (u < acc + cnt) {
+            const int w = u - acc;
+            if (w >= n_rect) return {t_lo + (w - n_rect), -1};
+            const int tl = w < 2 ? 1 : w < 6 ? 2 : 3;          // rows 1, 2, 3 of the patch hold 2, 4, 6 units
+            return {t_lo + tl, 8 * g + (w - tl * (tl - 1))};
+        }
+        acc += cnt;
+    }
+    for (int gt = 1; gt < P; ++gt) {
+        const int t_lo = 4 * gt, n_t = min(4, nb - t_lo), row = n_t * 8;
+        if (u < acc + gt * row) {
+            const int w = u - acc, gs = w / row, v = w - gs * row;
+            return {t_lo + (v >> 3), 8 * gs + (v & 7)};
+        }
+        acc += gt * row;
+    }
+    return {0, -1};                                            // (not reached for u < nb * nb)
+}
+
 // largest n with n (n + 1) / 2 <= v
 __device__ inline int tri_row(long long v) {
     int n = (int)((sqrtf(8.f * (float)v + 1.f) - 1.f) * 0.5f);
@@ -505,14 +534,9 @@ __global__ __launch_bounds__(NORMS ? SplitGeom::THREADS : DmaGeom::THREADS) void
         if (threadIdx.x == 0) nxt = U.n_units > G ? (long long)G + atomicAdd(queue, 1) : U.n_units;
         if constexpr (NORMS) {                                 // (launched with mode 0 or 2)
             if (big_mode == 2) {
-                if (u < U.n_big) {                             // tested 128-block tb >= 1 against the 64-blocks 0 .. 2 tb - 1
-                    const int tb = tri_row(u >> 1) + 1;
-                    const int sb = (int)(u - (long long)tb * (tb - 1));
-                    gram_tile_split<32, 64>(p, sb * 64, tb * 128, false, lds);
-                } else {
-                    const int i = (int)(u - U.n_big);
-                    gram_tile_diag(p, i * 128, lds);
-                }
+                const DmaUnit2 w = dma_unit2((int)u, (p.T + 127) >> 7);
+                if (w.sb >= 0) gram_tile_split<32, 64>(p, w.sb * 64, w.tb * 128, false, lds);
+                else gram_tile_diag(p, w.tb * 128, lds);
             } else {
                 const int tb = tri_row(u);                     // 128-blocks: 0 <= sb <= tb
                 const int sb = (int)(u - (long long)tb * (tb + 1) / 2);
