@@ -460,22 +460,8 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
     const int qtokv = min(max(p.idx[min(q0 + lane, r - 1)], 0), p.T - 1);
     int tok_cur = 0, tok_n1 = 0, tok_n2 = 0;               // loaders: the tokens of key blocks kb, kb + 1, kb + 2 (lane = row)
     if (loader) { tok_cur = ids(0); tok_n1 = ids(1); tok_n2 = ids(2); }
-    {
-        u32x4 qreg[NP / 2];
-#pragma unroll
-        for (int j = 0; j < NP / 2; ++j) {
-            const int i = tid + 512 * j, row = i / PPR, pc = i % PPR;
-            qreg[j] = *reinterpret_cast<const u32x4*>(Qh + (size_t)__shfl(qtokv, row, 64) * (size_t)p.ld + pc * EPP);
-        }
-#pragma unroll
-        for (int j = 0; j < NP / 2; ++j) {
-            const int i = tid + 512 * j, row = i / PPR, pc = i % PPR;
-            *reinterpret_cast<u32x4*>(qbuf + attn_off(row, pc, PPR)) = qreg[j];
-        }
-    }
     const int nkb_all = (r + 63) / 64;
     const int nkb = p.causal ? min(nkb_all, q0 / 64 + 1) : nkb_all;
-    __syncthreads();                                       // Q is staged (and nothing of the loaders is in flight yet)
 
     float m_run = -INFINITY, l_run = 0.f;                  // of query qb * 32 + l32 over THIS wave's keys (both lane halves alike)
     f32x16 acc_o[NB];                                      // O^T blocks: rows = output columns 32 i + ..., lane = query
@@ -534,6 +520,21 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
             fetch_k(kb & 1, tok_n1);                           // K(kb + 2) into the stage the multipliers have just left
         }
     } else {
+        // Q goes through the multiplying waves' registers into LDS while the loaders fetch the first key blocks; barrier
+        // A(0) is also the one behind which Q is staged
+        {
+            u32x4 qreg[NP];
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {
+                const int i = tid + 256 * j, row = i / PPR, pc = i % PPR;
+                qreg[j] = *reinterpret_cast<const u32x4*>(Qh + (size_t)__shfl(qtokv, row, 64) * (size_t)p.ld + pc * EPP);
+            }
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {
+                const int i = tid + 256 * j, row = i / PPR, pc = i % PPR;
+                *reinterpret_cast<u32x4*>(qbuf + attn_off(row, pc, PPR)) = qreg[j];
+            }
+        }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
@@ -543,18 +544,22 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
         // file has room for beside the rows; the rest is read from LDS in every block.
         constexpr int QREG = KS <= 8 ? KS : 2;
         u32x4 qf[QREG];
-#pragma unroll
-        for (int ks = 0; ks < QREG; ++ks)
-            qf[ks] = *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
         // Operand addresses inside the loop: one base per buffer XOR a constant (the slot of k-step ks is
         // (half ^ swizzle) ^ 2 ks; a V^T row block i flips one more slot bit), recomputed where they are used: the
         // 48 addresses would not fit beside the rows in the half register file a wave has here.
         const uint32_t k_base = (uint32_t)attn_off(kh * 32 + l32, half, PPR);
         const uint32_t q_base = (uint32_t)attn_off(my_q, half, PPR);
         const uint32_t v_base = (uint32_t)attn_vt_off(l32, 4 * kh + half);
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));     // my share of Q is written
+        __builtin_amdgcn_s_barrier();                          // A(0): Q is staged as well
+#pragma unroll
+        for (int ks = 0; ks < QREG; ++ks)
+            qf[ks] = *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
         for (int kb = 0; kb < nkb; ++kb) {
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of V^T(kb - 1) have returned
-            __builtin_amdgcn_s_barrier();                      // A(kb)
+            if (kb > 0) {
+                __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of V^T(kb - 1) have returned
+                __builtin_amdgcn_s_barrier();                      // A(kb)
+            }
             const char* kcur = kbuf + (kb & 1) * G::KSTAGE;
             // ---- S^T = K Q^T: this wave's 32 keys (half kh of the block) against its 32 queries
             f32x16 acc_s;
