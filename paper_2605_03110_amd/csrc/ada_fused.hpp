@@ -84,11 +84,11 @@ struct FusedParams {
     // cascade step with a gamma output: Algorithm 1's gamma^cross is the maximum over the VALID representatives, which are
     // known only after all products.  The tiles therefore also keep, per non-inherited token, the arg max over all
     // inherited representatives (p.best, keyed by list position); the workgroup that updates the set lists the tokens
-    // whose nearest representative was removed (fix_list, fix_count[0]) and leaves every representative's validity
-    // (valid_out, by list position) for the pass that recomputes those few tokens' maxima (k_gamma_cross_fix).
+    // whose nearest representative was removed (fix_list), clears their gamma and leaves the list's length, the set size
+    // and a status in the workspace's scalars (fix_meta: META_NONREP, META_R, META_STATUS) for the launch that recomputes
+    // those tokens' maxima against the valid representatives: the cross-Gram tiles of the step's other form, on that list.
     int32_t* fix_list;
-    int32_t* fix_count;
-    uint8_t* valid_out;
+    int32_t* fix_meta;
 };
 
 // Section 8.1's rule as read here: the turnover eta = (adds + removes) / r of the step just made (eq. (8)) moves tau
@@ -1237,10 +1237,11 @@ __device__ inline void block_rank3(const bool (&f)[3][U], int (&below)[3], int (
 // across the workgroup, independent of each other and branch-free (indices are clamped, results masked): a whole batch
 // is in flight before the first use.
 
-// Algorithm 1 step 8 for callers that ask for gamma: once validity is known (vmask: one bit per list position), leave it
-// for the recomputation pass and list the non-inherited tokens whose nearest inherited representative was removed --
-// their maximum over the VALID representatives is not the one the tiles accumulated.  The arg-max keys are cleared
-// on the way (the table is zero between calls).  ok == false: a rejected step, only the clearing is done.
+// Algorithm 1 step 8 for callers that ask for gamma: once validity is known (vmask: one bit per list position), list the
+// non-inherited tokens whose nearest inherited representative was removed -- their maximum over the VALID
+// representatives is not the one the tiles accumulated -- and clear their gamma for the recomputation.  The arg-max
+// keys are cleared on the way (the table is zero between calls).  ok == false: a rejected step, only the clearing is
+// done and the list is empty.
 template <int THREADS>
 __device__ inline void gamma_fix_collect(const FusedParams& p, int r, const uint32_t* vmask, bool ok) {
     if (!p.fix_list) return;                             // uniform
@@ -1248,18 +1249,33 @@ __device__ inline void gamma_fix_collect(const FusedParams& p, int r, const uint
     const int tid = threadIdx.x;
     if (tid == 0) s_fix = 0;
     __syncthreads();
-    if (ok)
-        for (int j = tid; j < r; j += THREADS) p.valid_out[j] = (uint8_t)((vmask[j >> 5] >> (j & 31)) & 1u);
-    for (int t = tid; t < p.T; t += THREADS) {
-        const unsigned long long key = p.best[t];
-        if (key == 0ull) continue;
-        p.best[t] = 0ull;
-        if (!ok) continue;
-        const int pos = min(max(INT_MAX - (int)(uint32_t)key, 0), r - 1);
-        if (!((vmask[pos >> 5] >> (pos & 31)) & 1u)) p.fix_list[atomicAdd(&s_fix, 1)] = t;
+    for (int base = 0; base < p.T; base += 8 * THREADS) {                   // eight keys per thread in flight per trip
+        unsigned long long key[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = base + i * THREADS + tid;
+            key[i] = p.best[min(t, p.T - 1)];
+            if (t >= p.T) key[i] = 0ull;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = base + i * THREADS + tid;
+            if (key[i] == 0ull) continue;
+            p.best[t] = 0ull;
+            if (!ok) continue;
+            const int pos = min(max(INT_MAX - (int)(uint32_t)key[i], 0), r - 1);
+            if (!((vmask[pos >> 5] >> (pos & 31)) & 1u)) {
+                p.fix_list[atomicAdd(&s_fix, 1)] = t;
+                p.gamma[t] = 0.f;                        // empty max: the recomputation accumulates into it
+            }
+        }
     }
     __syncthreads();
-    if (tid == 0) *p.fix_count = s_fix;
+    if (tid == 0) {
+        p.fix_meta[META_R] = ok ? r : 0;
+        p.fix_meta[META_NONREP] = s_fix;
+        p.fix_meta[META_STATUS] = ADA_OK;
+    }
 }
 
 // Algorithm 1 steps 5, 9, 10 from the first-hit records.  For every token the tiles left, next to its hit words, the

@@ -42,7 +42,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 enum { MODE_FULL = 0, MODE_REP = 1, MODE_CROSS = 2 };
 // meta: 8 words of scalars, then (from word META_TICKET + 64 on, one per 128-byte line) the per-XCD ticket counters
 constexpr size_t META_BYTES = 2048;
-enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_FIX = 3, META_TICKET = 4, META_QUEUE = 5 /* and 6 */, META_EPOCH = 7, META_WORDS = 8 };
+enum { META_R = 0, META_NONREP = 1, META_STATUS = 2, META_SPARE = 3, META_TICKET = 4, META_QUEUE = 5 /* and 6 */, META_EPOCH = 7, META_WORDS = 8 };
 
 // The one-launch cascade step keeps one hit word per token and per 32 inherited representatives; beyond this T
 // the table would dominate the workspace and the two-launch path is used instead.
@@ -1279,75 +1279,10 @@ int launch_fused_any(const FusedParams& p, int dtype, int prof_class, hipStream_
     return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
 
-// Algorithm 1 step 8 after the one-launch step, for callers that ask for gamma: the tiles accumulated every token's
-// maximum over ALL inherited representatives, because validity (step 5) is known only after the products.  For the
-// tokens whose nearest representative turned out removed (listed by the set update) the maximum over the VALID
-// representatives is recomputed here, one workgroup per token: every wave takes every fourth representative, the lanes
-// share a row's elements, products and sums in fp32 as in the tiles.  A few dozen tokens per step at most.
-struct GammaFixParams {
-    const void* X;
-    long long ld;
-    int T, d;
-    const int32_t* prev_idx;
-    const int32_t* r_dev;
-    int r_host;
-    const uint8_t* valid;        // by list position
-    const int32_t* fix_list;
-    const int32_t* fix_count;
-    const int32_t* counts;       // the step's counts: nothing is done for a rejected step
-    int earlier_only;
-    float* gamma;
-};
-
-template <typename In, bool ALIGNED>
-__global__ __launch_bounds__(256) void k_gamma_cross_fix(GammaFixParams p) {
-    constexpr int EPP = 16 / (int)sizeof(In);
-    __shared__ float s_red[4];
-    if (p.counts[3] != ADA_OK) return;
-    const int r = p.r_dev ? *p.r_dev : p.r_host;
-    const int n = *p.fix_count;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const In* X = reinterpret_cast<const In*>(p.X);
-    const int np = (p.d + EPP - 1) / EPP;
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const int t = p.fix_list[i];
-        const In* xt = X + (size_t)t * (size_t)p.ld;
-        float tt = 0.f;                                          // ||x_t||^2: every wave sums all of it
-        for (int pi = lane; pi < np; pi += 64) tt += piece_sumsq<In>(load_piece<In, ALIGNED>(xt, pi * EPP, p.d));
-        tt = wave_sum(tt);
-        const float tsc = tt > 0.f ? 1.0f / sqrtf(tt) : 0.f;
-        float m = 0.f;
-        for (int j = wave; j < r; j += 4) {
-            if (!p.valid[j]) continue;                           // wave-uniform
-            const int s = min(max(p.prev_idx[j], 0), p.T - 1);
-            if (p.earlier_only && !(s < t)) continue;
-            const In* xs = X + (size_t)s * (size_t)p.ld;
-            float dot = 0.f, ss = 0.f;
-            for (int pi = lane; pi < np; pi += 64) {
-                union { u32x4 v; In e[EPP]; } a, b;
-                a.v = load_piece<In, ALIGNED>(xs, pi * EPP, p.d);
-                b.v = load_piece<In, ALIGNED>(xt, pi * EPP, p.d);
-#pragma unroll
-                for (int e = 0; e < EPP; ++e) {
-                    const float fs = to_f32<In>(a.e[e]);
-                    dot = fmaf(fs, to_f32<In>(b.e[e]), dot);
-                    ss = fmaf(fs, fs, ss);
-                }
-            }
-            dot = wave_sum(dot);
-            ss = wave_sum(ss);
-            const float ssc = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-            m = fmaxf(m, (fabsf(dot) * ssc) * tsc);
-        }
-        if (lane == 0) s_red[wave] = m;
-        __syncthreads();
-        if (threadIdx.x == 0) p.gamma[t] = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-        __syncthreads();
-    }
-}
-
 // Algorithm 1 in one launch (ada_fused.hpp).  gamma, if given, receives for an inherited token gamma^rep and for any
-// other token gamma^cross; the latter costs a second, small launch for the tokens whose nearest representative was removed.
+// other token gamma^cross.  The tiles accumulate a token's maximum over ALL inherited representatives; for the tokens
+// whose nearest one turned out removed (listed by the workgroup that updates the set) the maximum over the VALID ones is
+// recomputed by the cross-Gram tiles of the step's other form on that list: a norm launch and a tile launch more.
 int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, float tau, const int32_t* prev_idx, int r,
                       const int32_t* r_dev, int32_t* idx, int32_t* adds, int32_t* removes, int32_t* counts,
                       uint64_t* gram_ops, float* gamma, void* ws, hipStream_t st, unsigned flags,
@@ -1360,8 +1295,8 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
                      w.meta + META_TICKET, idx, adds, removes, counts,
                      reinterpret_cast<unsigned long long*>(gram_ops), 0, nullptr, nullptr, nullptr, 0, cascade_tile_pick()};
     p.first = w.first;
-    if (gamma && !(grp && grp->G > 1)) {                          // Algorithm 1's gamma^cross: see k_gamma_cross_fix
-        p.best = w.best; p.fix_list = w.nonrep_idx; p.fix_count = w.meta + META_FIX; p.valid_out = w.is_rep;
+    if (gamma && !(grp && grp->G > 1)) {                          // Algorithm 1's gamma^cross: see above
+        p.best = w.best; p.fix_list = w.nonrep_idx; p.fix_meta = w.meta;
     }
     if (ctl) {                                                   // Section 8.1: threshold carried on the device
         p.tau_in = tau_in; p.thr_in = thr_in; p.tau_out = tau_out; p.thr_out = thr_out;
@@ -1377,13 +1312,16 @@ int run_cascade_fused(const void* X, int T, int d, long long ld, int dtype, floa
     }
     const int rc = launch_fused_any(p, dtype, ADA_K_CASCADE_FUSED, st);
     if (rc != ADA_OK || !p.fix_list) return rc;
-    const GammaFixParams gp = {X, ld, T, d, prev_idx, r_dev, r, w.is_rep, w.nonrep_idx, w.meta + META_FIX, counts,
-                               (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0, gamma};
+    // (a rejected step leaves an empty list; the validity of a representative is read off its own gamma^rep < threshold,
+    //  as in the step's other form)
+    GramParams cross = {X, ld, T, d, prev_idx, w.nonrep_idx, w.meta, w.inv_norm, gamma, threshold_of(tau), MODE_CROSS,
+                        (flags & ADA_FLAG_CROSS_EARLIER_ONLY) ? 1 : 0};
+    const PrepParams norms_only = {nullptr, nullptr, 0, 0};
     const hipError_t e = dispatch(dtype, X, ld, d, [&](auto v) {
         using V = decltype(v);
-        ProfScope ps(ADA_K_UPDATE, st);
-        hipLaunchKernelGGL((k_gamma_cross_fix<typename V::In, V::aligned>), dim3(128), dim3(256), 0, st, gp);
-        return hipGetLastError();
+        hipError_t e1 = launch_norm_prep<typename V::In, V::aligned>(X, ld, T, d, w.gamma, w, norms_only, st);
+        if (e1 != hipSuccess) return e1;
+        return launch_gram_any<typename V::In, V::aligned>(cross, r, T - 1 > 0 ? T - 1 : 1, false, st);
     });
     return e == hipSuccess ? ADA_OK : ADA_ERR_DEVICE;
 }
