@@ -1249,26 +1249,24 @@ __device__ inline void gamma_fix_collect(const FusedParams& p, int r, const uint
     const int tid = threadIdx.x;
     if (tid == 0) s_fix = 0;
     __syncthreads();
-    for (int base = 0; base < p.T; base += 8 * THREADS) {                   // eight keys per thread in flight per trip
-        unsigned long long key[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int t = base + i * THREADS + tid;
-            key[i] = p.best[min(t, p.T - 1)];
-            if (t >= p.T) key[i] = 0ull;
+    auto one = [&](int t, unsigned long long key) {
+        if (t >= p.T || key == 0ull) return;
+        p.best[t] = 0ull;
+        if (!ok) return;
+        const int pos = min(max(INT_MAX - (int)(uint32_t)key, 0), r - 1);
+        if (!((vmask[pos >> 5] >> (pos & 31)) & 1u)) {
+            p.fix_list[atomicAdd(&s_fix, 1)] = t;
+            p.gamma[t] = 0.f;                            // empty max: the recomputation accumulates into it
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int t = base + i * THREADS + tid;
-            if (key[i] == 0ull) continue;
-            p.best[t] = 0ull;
-            if (!ok) continue;
-            const int pos = min(max(INT_MAX - (int)(uint32_t)key[i], 0), r - 1);
-            if (!((vmask[pos >> 5] >> (pos & 31)) & 1u)) {
-                p.fix_list[atomicAdd(&s_fix, 1)] = t;
-                p.gamma[t] = 0.f;                        // empty max: the recomputation accumulates into it
-            }
-        }
+    };
+    for (int base = tid; base < p.T; base += 4 * THREADS) {                 // four keys per thread in flight per trip
+        const int t0 = base, t1 = base + THREADS, t2 = base + 2 * THREADS, t3 = base + 3 * THREADS;
+        const unsigned long long k0 = p.best[min(t0, p.T - 1)], k1 = p.best[min(t1, p.T - 1)];
+        const unsigned long long k2 = p.best[min(t2, p.T - 1)], k3 = p.best[min(t3, p.T - 1)];
+        one(t0, k0);
+        one(t1, k1);
+        one(t2, k2);
+        one(t3, k3);
     }
     __syncthreads();
     if (tid == 0) {
