@@ -53,17 +53,55 @@ class AdaError(RuntimeError):
         super().__init__("%s: %s" % (where, status_string(status)))
 
 
+# Private (scratch) memory the hot kernels may use, in bytes per lane: a private array or a spill that lands in one of
+# them costs every launch microseconds (k_cascade_fused once lost 10 us per step to a 64-byte array in its last
+# workgroup's code), so the build refuses it instead of letting a benchmark find out.
+SCRATCH_BUDGET = {
+    "k_cascade_fusedItLb1ELi2ELb1E": 64,       # bf16, aligned rows, two K-groups, direct-to-LDS: the cascade step
+    "k_gram_dmaILb1E": 0,                      # one-launch full selection
+    "k_gram_dmaILb0E": 0,                      # full Gram beyond T = 4096
+    "k_attn_rep2ILi256E": 64,                  # attention on the representative set, d_h = 256
+}
+
+
+def kernel_resources(remarks: str) -> Dict[str, Dict[str, int]]:
+    """{mangled kernel name: {VGPRs, AGPRs, ScratchSize, ...}} from hipcc's -Rpass-analysis=kernel-resource-usage."""
+    out: Dict[str, Dict[str, int]] = {}
+    cur = None
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            cur = line.split("Function Name:")[1].split("[")[0].strip()
+            out[cur] = {}
+        elif cur and "remark:" in line and ":" in line.split("remark:")[1]:
+            key, _, val = line.split("remark:")[1].partition(":")
+            val = val.split("[")[0].strip()
+            if val.isdigit():
+                out[cur][key.strip().split(" [")[0]] = int(val)
+    return out
+
+
 def build_library(verbose: bool = False) -> str:
-    """Compile the HIP sources for gfx950 into libada.so next to this file."""
+    """Compile the HIP sources for gfx950 into libada.so next to this file; fails if a hot kernel needs more private
+    memory than SCRATCH_BUDGET allows."""
     tmp = LIB_PATH + ".tmp.%d" % os.getpid()
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Rpass-analysis=kernel-resource-usage"]
     cmd += [os.path.join(SRC_DIR, s) for s in SOURCES] + ["-o", tmp]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
     if verbose:
         print(res.stderr)
+    usage = kernel_resources(res.stderr)
+    for tag, budget in SCRATCH_BUDGET.items():
+        hits = {k: v for k, v in usage.items() if tag in k}
+        if not hits:
+            os.remove(tmp)
+            raise RuntimeError("no resource report for kernel *%s*: has it been renamed?" % tag)
+        for k, v in hits.items():
+            if v.get("ScratchSize", 0) > budget:
+                os.remove(tmp)
+                raise RuntimeError("%s uses %d bytes of private memory per lane (budget %d)" % (k, v["ScratchSize"], budget))
     os.replace(tmp, LIB_PATH)
     return LIB_PATH
 

@@ -233,3 +233,22 @@ def test_full_selection_unit_plan(ada):
     assert plan(8192, 4096, 256) == 1               # 496 units of 256 x 256 and the diagonal in 128 x 128 units
     assert plan(1535, 4096, 256) == -1 and plan(2048, 48, 256) == -1 and plan(2048, 4096, 4) == -1
     assert plan(1 << 30, 4096, 256) == -1
+
+
+def test_build_reads_the_compilers_resource_report(ada):
+    """The build refuses a hot kernel that needs more private (scratch) memory than its budget; here only the reading of
+    the compiler's remarks is checked (the build itself runs them on every compile)."""
+    remarks = (
+        "a.hpp:10:1: remark: Function Name: _ZN1x15k_cascade_fusedItLb1ELi2ELb1EEEv [-Rpass-analysis=kernel-resource-usage]\n"
+        "   10 | __global__ void k() {\n      | ^\n"
+        "a.hpp:10:1: remark:     TotalSGPRs: 104 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hpp:10:1: remark:     VGPRs: 239 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hpp:10:1: remark:     ScratchSize [bytes/lane]: 20 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hpp:10:1: remark:     Dynamic Stack: False [-Rpass-analysis=kernel-resource-usage]\n"
+        "b.hpp:20:1: remark: Function Name: _ZN1x10k_gram_dmaILb1EEEv [-Rpass-analysis=kernel-resource-usage]\n"
+        "b.hpp:20:1: remark:     VGPRs: 169 [-Rpass-analysis=kernel-resource-usage]\n"
+        "b.hpp:20:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n")
+    got = ada.kernel_resources(remarks)
+    assert got["_ZN1x15k_cascade_fusedItLb1ELi2ELb1EEEv"] == {"TotalSGPRs": 104, "VGPRs": 239, "ScratchSize": 20}
+    assert got["_ZN1x10k_gram_dmaILb1EEEv"] == {"VGPRs": 169, "ScratchSize": 0}
+    assert all(isinstance(v, int) and v >= 0 for v in ada.SCRATCH_BUDGET.values())
