@@ -450,6 +450,7 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
     const bool loader = wave8 >= 4;
     const int wave = wave8 & 3;                            // place among the waves of its kind
     const int qb = wave & 1, kh = wave >> 1;
+    ATTN_CLK(0);
     for (int q0 = who.qblk * 64; q0 < r; q0 += gridDim.x * 64) {
     __syncthreads();                                       // a previous query block's hand-over is done with the LDS
     const In* Qh = reinterpret_cast<const In*>(p.Q) + (size_t)h * DH;
@@ -552,6 +553,7 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
         const uint32_t v_base = (uint32_t)attn_vt_off(l32, 4 * kh + half);
         __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63));     // my share of Q is written
         __builtin_amdgcn_s_barrier();                          // A(0): Q is staged as well
+        ATTN_CLK(1);
 #pragma unroll
         for (int ks = 0; ks < QREG; ++ks)
             qf[ks] = *reinterpret_cast<const u32x4*>(qbuf + attn_off(my_q, 2 * ks + half, PPR));
@@ -559,6 +561,7 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
             if (kb > 0) {
                 __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of V^T(kb - 1) have returned
                 __builtin_amdgcn_s_barrier();                      // A(kb)
+                if (kb == 1) ATTN_CLK(2);
             }
             const char* kcur = kbuf + (kb & 1) * G::KSTAGE;
             // ---- S^T = K Q^T: this wave's 32 keys (half kh of the block) against its 32 queries
@@ -630,6 +633,7 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
             l_run += sum;
             __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(63)); // my reads of K(kb) (and of the key tokens) have returned
             __builtin_amdgcn_s_barrier();                      // B(kb)
+            if (kb == 1) ATTN_CLK(3);
             // ---- O^T += V^T P^T: the weights of k-step j (16 keys) are registers 8 j .. 8 j + 7; each weight is split
             // into a bf16 head and a bf16 remainder (hardware round-to-nearest-even pairs), two products per step
 #pragma unroll
@@ -652,6 +656,7 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
             }
         }
     }
+    ATTN_CLK(6);
     int rel[4];                                            // hand-over: positions of 2048 tokens, relative to this block
     auto load_rel = [&](int tb) {
 #pragma unroll
@@ -707,6 +712,7 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
     __syncthreads();
     if (!loader) { if (kh == 0) finish(std::integral_constant<int, 0>{}); else finish(std::integral_constant<int, 1>{}); }
     __syncthreads();
+    ATTN_CLK(4);
     // ---- hand-over: every token whose representative sits in this block takes that row.  The positions of 2048
     // tokens are read in one trip to memory and the takers collected in one list; a wave then copies a whole row
     // (d_h floats) per store instruction.
@@ -746,4 +752,5 @@ __global__ __launch_bounds__(512) void k_attn_rep2(AttnParams p) {
         __syncthreads();
     }
     }
+    ATTN_CLK(7);
 }
